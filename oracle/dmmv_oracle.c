@@ -1,0 +1,46 @@
+/*
+ * CPU oracle for the single-move descent on the Discrete Min-Max Violation problem
+ * (min over x in D^n of ||A x - b||_inf).
+ *
+ * TEST INFRASTRUCTURE ONLY: this library exists to check the GPU library and to be
+ * timed as a baseline.  It shares no source, header or table with the GPU code and is
+ * never called by it.  Plain scalar C, one fused multiply-add per (row, move) pair,
+ * compiled without floating-point contraction so that only the explicit fma() calls
+ * fuse.
+ *
+ * Pins (see tests): objective and best move against brute-force enumeration, the
+ * score table against fresh recomputation of ||A x' - b||_inf, maintained residual
+ * against recomputation, monotone objective, Chebyshev LP lower bound, the
+ * Subset-Sum (m = 1, D = {0,1}) and A = I closed forms, sparse against dense.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define REAL double
+#define SFX(x) x##_f64
+#define FMA fma
+#define FABS fabs
+#include "dmmv_oracle_impl.inc"
+#undef REAL
+#undef SFX
+#undef FMA
+#undef FABS
+
+#define REAL float
+#define SFX(x) x##_f32
+#define FMA fmaf
+#define FABS fabsf
+#include "dmmv_oracle_impl.inc"
+#undef REAL
+#undef SFX
+#undef FMA
+#undef FABS
+
+#ifdef _OPENMP
+#include <omp.h>
+int oracle_num_threads(void) { return omp_get_max_threads(); }
+#else
+int oracle_num_threads(void) { return 1; }
+#endif

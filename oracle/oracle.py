@@ -1,0 +1,301 @@
+"""numpy front end of the CPU oracle (ctypes over oracle/liboracle.so).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the benchmark's
+cpu_baseline leg.  The GPU library never imports or calls anything here.
+
+All functions take host numpy arrays.  x is passed as values of D and converted to the
+index vector the C code uses; a value that is not in D raises ValueError.
+"""
+from __future__ import annotations
+
+import ctypes as C
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+
+from . import build as _build
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(_build.build())
+        _lib.oracle_num_threads.restype = C.c_int
+        for s in ("f32", "f64"):
+            real = C.c_float if s == "f32" else C.c_double
+            getattr(_lib, f"oracle_max_abs_{s}").restype = real
+            getattr(_lib, f"oracle_apply_move_dense_{s}").restype = real
+            getattr(_lib, f"oracle_apply_move_csc_{s}").restype = real
+            getattr(_lib, f"oracle_solve_dense_{s}").restype = C.c_int32
+            getattr(_lib, f"oracle_solve_csr_{s}").restype = C.c_int32
+    return _lib
+
+
+def num_threads() -> int:
+    return int(lib().oracle_num_threads())
+
+
+def _sfx(dtype) -> str:
+    dtype = np.dtype(dtype)
+    if dtype == np.float32:
+        return "f32"
+    if dtype == np.float64:
+        return "f64"
+    raise TypeError(f"unsupported dtype {dtype}")
+
+
+def _real(dtype):
+    return C.c_float if np.dtype(dtype) == np.float32 else C.c_double
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _fn(name: str, dtype):
+    return getattr(lib(), f"{name}_{_sfx(dtype)}")
+
+
+def values_to_index(x: np.ndarray, D: np.ndarray) -> np.ndarray:
+    """Index of every x value in the ascending set D (exact match required)."""
+    D = np.asarray(D)
+    x = np.asarray(x, dtype=D.dtype)
+    if D.ndim != 1 or D.size < 2 or np.any(np.diff(D) <= 0) or not np.all(np.isfinite(D)):
+        raise ValueError("D must be finite, strictly ascending, with at least two values")
+    k = np.searchsorted(D, x)
+    k = np.clip(k, 0, D.size - 1)
+    if np.any(D[k] != x):
+        raise ValueError("x has a value that is not in D")
+    return np.ascontiguousarray(k.astype(np.int32))
+
+
+def _dense(A: np.ndarray, dtype):
+    A = np.asfortranarray(A, dtype=dtype)
+    m, n = A.shape
+    return A, m, n, max(m, 1)
+
+
+def _mask(var_mask, n):
+    if var_mask is None:
+        return None
+    vm = np.ascontiguousarray(var_mask, dtype=np.uint8)
+    assert vm.shape == (n,)
+    return vm
+
+
+# ----------------------------------------------------------------------------- dense
+def residual_dense(A, b, D, x, scale=1.0):
+    dt = np.asarray(D).dtype
+    A, m, n, lda = _dense(A, dt)
+    D = np.ascontiguousarray(D)
+    k = values_to_index(x, D)
+    b = np.ascontiguousarray(b, dtype=dt)
+    r = np.empty(m, dtype=dt)
+    _fn("oracle_residual_dense", dt)(C.c_int64(m), C.c_int64(n), _p(A), C.c_int64(lda), _p(D),
+                                     _p(k), _real(dt)(scale), _p(b), _p(r))
+    return r
+
+
+def max_abs(r):
+    r = np.ascontiguousarray(r)
+    return r.dtype.type(_fn("oracle_max_abs", r.dtype)(C.c_int64(r.size), _p(r)))
+
+
+def eval_moves_dense(A, D, x, r, scale=1.0, radius=0, var_mask=None):
+    dt = np.asarray(D).dtype
+    A, m, n, lda = _dense(A, dt)
+    D = np.ascontiguousarray(D)
+    k = values_to_index(x, D)
+    r = np.ascontiguousarray(r, dtype=dt)
+    vm = _mask(var_mask, n)
+    scores = np.empty(n * D.size, dtype=dt)
+    _fn("oracle_eval_moves_dense", dt)(C.c_int64(m), C.c_int64(n), C.c_int32(D.size), _p(A),
+                                       C.c_int64(lda), _p(D), _p(k), _real(dt)(scale), _p(r),
+                                       C.c_int32(radius), _p(vm), _p(scores))
+    return scores
+
+
+def argmin_move(scores):
+    scores = np.ascontiguousarray(scores)
+    c = C.c_int64(-1)
+    s = _real(scores.dtype)(0)
+    _fn("oracle_argmin_move", scores.dtype)(C.c_int64(scores.size), _p(scores), C.byref(c),
+                                            C.byref(s))
+    return int(c.value), scores.dtype.type(s.value)
+
+
+def apply_move_dense(A, D, x, r, j, k, scale=1.0):
+    """Returns (x_new, r_new, t_new) after x_j <- D[k]."""
+    dt = np.asarray(D).dtype
+    A, m, n, lda = _dense(A, dt)
+    D = np.ascontiguousarray(D)
+    kidx = values_to_index(x, D)
+    diff = dt.type(D[k] - D[kidx[j]])
+    delta = dt.type(dt.type(scale) * diff)
+    r = np.array(r, dtype=dt, copy=True)
+    col = np.ascontiguousarray(A[:, j])
+    t = _fn("oracle_apply_move_dense", dt)(C.c_int64(m), _p(col), _real(dt)(delta), _p(r))
+    xn = np.array(x, dtype=dt, copy=True)
+    xn[j] = D[k]
+    return xn, r, dt.type(t)
+
+
+@dataclass
+class SolveResult:
+    x: np.ndarray
+    t: float
+    iters_done: int
+    r: Optional[np.ndarray]
+    trace_j: np.ndarray
+    trace_k: np.ndarray
+    trace_t: np.ndarray
+
+
+def solve_dense(A, b, D, x0, iters, scale=1.0, radius=0, var_mask=None) -> SolveResult:
+    dt = np.asarray(D).dtype
+    A, m, n, lda = _dense(A, dt)
+    D = np.ascontiguousarray(D)
+    k = values_to_index(x0, D)
+    b = np.ascontiguousarray(b, dtype=dt)
+    vm = _mask(var_mask, n)
+    t = _real(dt)(0)
+    r = np.empty(m, dtype=dt)
+    tj = np.full(max(iters, 1), -1, dtype=np.int32)
+    tk = np.full(max(iters, 1), -1, dtype=np.int32)
+    tt = np.zeros(max(iters, 1), dtype=dt)
+    done = _fn("oracle_solve_dense", dt)(
+        C.c_int64(m), C.c_int64(n), C.c_int32(D.size), _p(A), C.c_int64(lda), _p(b), _p(D),
+        _real(dt)(scale), _p(k), C.c_int32(iters), C.c_int32(radius), _p(vm), C.byref(t), _p(r),
+        _p(tj), _p(tk), _p(tt))
+    return SolveResult(D[k], dt.type(t.value), int(done), r, tj[:done], tk[:done], tt[:done])
+
+
+# ----------------------------------------------------------------------------- sparse
+def _csr(rowptr, col, val, dt):
+    return (np.ascontiguousarray(rowptr, dtype=np.int64), np.ascontiguousarray(col, dtype=np.int32),
+            np.ascontiguousarray(val, dtype=dt))
+
+
+def csr_to_csc(m, n, rowptr, col, val):
+    dt = np.asarray(val).dtype
+    rowptr, col, val = _csr(rowptr, col, val, dt)
+    nnz = int(rowptr[m])
+    colptr = np.empty(n + 1, dtype=np.int64)
+    rowidx = np.empty(max(nnz, 1), dtype=np.int32)
+    cval = np.empty(max(nnz, 1), dtype=dt)
+    _fn("oracle_csr_to_csc", dt)(C.c_int64(m), C.c_int64(n), _p(rowptr), _p(col), _p(val),
+                                 _p(colptr), _p(rowidx), _p(cval))
+    return colptr, rowidx[:nnz], cval[:nnz]
+
+
+def residual_csr(m, rowptr, col, val, b, D, x):
+    dt = np.asarray(D).dtype
+    rowptr, col, val = _csr(rowptr, col, val, dt)
+    D = np.ascontiguousarray(D)
+    k = values_to_index(x, D)
+    b = np.ascontiguousarray(b, dtype=dt)
+    r = np.empty(m, dtype=dt)
+    _fn("oracle_residual_csr", dt)(C.c_int64(m), _p(rowptr), _p(col), _p(val), _p(D), _p(k),
+                                   _p(b), _p(r))
+    return r
+
+
+def eval_moves_csr(m, n, rowptr, col, val, D, x, r, radius=0, var_mask=None, method="sorted",
+                   columns=None):
+    """Score table of a CSR instance.  method="plain" scans all rows per column (the
+    definition), "sorted" walks rows by decreasing |r|.  columns=(j0, j1) restricts the
+    plain method to a column range (the rest of the table is NaN)."""
+    dt = np.asarray(D).dtype
+    colptr, rowidx, cval = csr_to_csc(m, n, rowptr, col, np.asarray(val, dtype=dt))
+    rowidx = np.ascontiguousarray(rowidx)
+    cval = np.ascontiguousarray(cval)
+    D = np.ascontiguousarray(D)
+    k = values_to_index(x, D)
+    r = np.ascontiguousarray(r, dtype=dt)
+    vm = _mask(var_mask, n)
+    scores = np.full(n * D.size, np.nan, dtype=dt)
+    if method == "plain":
+        j0, j1 = (0, n) if columns is None else columns
+        _fn("oracle_eval_moves_csc_plain", dt)(
+            C.c_int64(m), C.c_int64(n), C.c_int32(D.size), _p(colptr), _p(rowidx), _p(cval),
+            _p(D), _p(k), _p(r), C.c_int32(radius), _p(vm), C.c_int64(j0), C.c_int64(j1),
+            _p(scores))
+    else:
+        _fn("oracle_eval_moves_csc_sorted", dt)(
+            C.c_int64(m), C.c_int64(n), C.c_int32(D.size), _p(colptr), _p(rowidx), _p(cval),
+            _p(D), _p(k), _p(r), C.c_int32(radius), _p(vm), _p(scores))
+    return scores
+
+
+def apply_move_csr(m, n, rowptr, col, val, D, x, r, j, k):
+    dt = np.asarray(D).dtype
+    colptr, rowidx, cval = csr_to_csc(m, n, rowptr, col, np.asarray(val, dtype=dt))
+    rowidx = np.ascontiguousarray(rowidx)
+    cval = np.ascontiguousarray(cval)
+    D = np.ascontiguousarray(D)
+    kidx = values_to_index(x, D)
+    delta = dt.type(dt.type(1) * dt.type(D[k] - D[kidx[j]]))
+    r = np.array(r, dtype=dt, copy=True)
+    t = _fn("oracle_apply_move_csc", dt)(C.c_int64(m), _p(colptr), _p(rowidx), _p(cval),
+                                         C.c_int64(j), _real(dt)(delta), _p(r))
+    xn = np.array(x, dtype=dt, copy=True)
+    xn[j] = D[k]
+    return xn, r, dt.type(t)
+
+
+def solve_csr(m, n, rowptr, col, val, b, D, x0, iters, radius=0, var_mask=None) -> SolveResult:
+    dt = np.asarray(D).dtype
+    rowptr, col, val = _csr(rowptr, col, val, dt)
+    D = np.ascontiguousarray(D)
+    k = values_to_index(x0, D)
+    b = np.ascontiguousarray(b, dtype=dt)
+    vm = _mask(var_mask, n)
+    t = _real(dt)(0)
+    r = np.empty(m, dtype=dt)
+    tj = np.full(max(iters, 1), -1, dtype=np.int32)
+    tk = np.full(max(iters, 1), -1, dtype=np.int32)
+    tt = np.zeros(max(iters, 1), dtype=dt)
+    done = _fn("oracle_solve_csr", dt)(
+        C.c_int64(m), C.c_int64(n), C.c_int32(D.size), _p(rowptr), _p(col), _p(val), _p(b), _p(D),
+        _p(k), C.c_int32(iters), C.c_int32(radius), _p(vm), C.byref(t), _p(r), _p(tj), _p(tk),
+        _p(tt))
+    return SolveResult(D[k], dt.type(t.value), int(done), r, tj[:done], tk[:done], tt[:done])
+
+
+# ----------------------------------------------------------------------------- batched
+@dataclass
+class BatchedResult:
+    x: np.ndarray            # [R][n]
+    t: np.ndarray            # [R]
+    iters_done: np.ndarray   # [R]
+    trace_j: np.ndarray      # [R][iters] (-1 beyond iters_done)
+    trace_k: np.ndarray
+    trace_t: np.ndarray
+
+
+def solve_batched(X, B, D, scale, x0, iters, radius=0) -> BatchedResult:
+    dt = np.asarray(D).dtype
+    X, m, n, ldx = _dense(X, dt)
+    D = np.ascontiguousarray(D)
+    B = np.ascontiguousarray(B, dtype=dt)
+    R = B.shape[0]
+    assert B.shape == (R, m)
+    scale = np.ascontiguousarray(scale, dtype=dt)
+    assert scale.shape == (R,)
+    k = np.ascontiguousarray(
+        np.stack([values_to_index(x0[q], D) for q in range(R)]) if R else
+        np.zeros((0, n), np.int32))
+    t = np.zeros(R, dtype=dt)
+    done = np.zeros(R, dtype=np.int32)
+    it = max(iters, 1)
+    tj = np.full((R, it), -1, dtype=np.int32)
+    tk = np.full((R, it), -1, dtype=np.int32)
+    tt = np.zeros((R, it), dtype=dt)
+    _fn("oracle_solve_batched", dt)(
+        C.c_int64(m), C.c_int64(n), C.c_int32(D.size), C.c_int64(R), _p(X), C.c_int64(ldx),
+        _p(B), _p(D), _p(scale), _p(k), C.c_int32(iters), C.c_int32(radius), _p(t), _p(done),
+        _p(tj), _p(tk), _p(tt))
+    return BatchedResult(D[k], t, done, tj, tk, tt)
