@@ -1,0 +1,177 @@
+/*
+ * libdmmv - GPU (gfx950) hot path of the AMVM heuristic for the Discrete Min-Max
+ * Violation problem (arXiv 2508.13437):
+ *
+ *     choose x in D^n (D a finite set of reals) to minimise  t = max_i |A_i x - b_i| .
+ *
+ * The library keeps the residual r = A x - b on the device, scores every
+ * single-coordinate move x_j -> D[k] as max_i |r_i + (D[k] - x_j) A_ij|, finds the best
+ * move with a lowest-index tie-break, and applies it as a rank-1 residual update.  These
+ * are the GPU-parallel boxes of the paper's Figure 1 (bulk candidate evaluation followed
+ * by a global minimum reduction, section "GPU Acceleration"; greedy repair, Appendix B.3;
+ * 1-OPT local search, section "Search Operators"), with the residual identity of
+ * Appendix A restricted to one changed coordinate.
+ *
+ * Three storage kinds are supported by one handle type:
+ *   dense    A column-major m x n                      (R = 1)
+ *   sparse   A in CSR (a CSC copy is built at create)  (R = 1)
+ *   batched  R independent instances sharing a dense A = X; instance q has its own
+ *            target b_q, scale s_q and x_q; its variables take the values s_q * D[k]
+ *            (one output row of a quantised linear layer, paper section
+ *            "Quantization without outlier separation as DMMV").
+ *
+ * Conventions
+ *   - Plain C ABI.  Pointers are DEVICE pointers unless marked HOST.  The caller owns every
+ *     buffer it passes; the library borrows problem buffers until dmmv_destroy and never
+ *     frees them.  The library allocates no device memory: its device state lives in the
+ *     workspace the caller provides (size from dmmv_workspace_bytes, 256-byte aligned).
+ *   - dtype selects float (DMMV_F32) or double (DMMV_F64) for A, b, D, scale, x, r and
+ *     scores alike.
+ *   - x is exchanged as VALUES of D (not indices), layout [R][n].  r is [R][m].  The score
+ *     table is [R][n*nd]; flat candidate index c = j*nd + k (k = position in ascending D).
+ *   - All work is enqueued on the stream given at create.  Calls return after enqueueing
+ *     unless stated otherwise; results in device buffers are ordered on that stream.
+ *   - Every call returns a dmmv_status; dmmv_last_error() gives a message for the last
+ *     failure on the calling thread.  No exceptions or aborts cross the ABI.
+ *   - Arithmetic contract (what makes results reproducible bit for bit):
+ *       step      delta = s * (D[k] - D[k_j])                 (two roundings; s = 1 unscaled)
+ *       pair      | fma(delta, A_ij, r_i) |                   (one fused multiply-add)
+ *       residual  acc = 0; for j ascending (CSR: stored order): acc = fma(A_ij, D[k_j], acc);
+ *                 r_i = fma(acc, s, -b_i)
+ *     max and arg-min are exact.  Inputs must be finite.
+ */
+#ifndef DMMV_H
+#define DMMV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dmmv_ctx* dmmv_handle;
+
+typedef enum { DMMV_F32 = 0, DMMV_F64 = 1 } dmmv_dtype;
+
+typedef enum {
+    DMMV_OK = 0,
+    DMMV_ERR_NULL = -1,        /* a required pointer is NULL                               */
+    DMMV_ERR_SHAPE = -2,       /* negative size, lda < m, CSR with duplicate / out-of-range  */
+    DMMV_ERR_DTYPE = -3,       /* dtype not F32 / F64                                       */
+    DMMV_ERR_DOMAIN = -4,      /* D not finite / not strictly ascending / nd < 2; x not in D */
+    DMMV_ERR_WORKSPACE = -5,   /* workspace NULL, misaligned or too small                    */
+    DMMV_ERR_HIP = -6,         /* a HIP runtime call failed                                  */
+    DMMV_ERR_STATE = -7,       /* call order: x not set, residual not computed, ...          */
+    DMMV_ERR_UNSUPPORTED = -8  /* combination not implemented (message says which)           */
+} dmmv_status;
+
+/* A move: variable j takes the value D[k].  j = -1 means "no move". */
+typedef struct { int32_t j, k; } dmmv_move;
+
+/* Problem description (paper, "Mathematical Problem Statement": A, b, value set V = D). */
+typedef struct {
+    int32_t dtype;               /* dmmv_dtype                                              */
+    int32_t nd;                  /* |D|, 2 <= nd <= 65535                                   */
+    int64_t m, n;                /* rows (constraints), variables                           */
+    const void* D;               /* HOST [nd], strictly ascending, copied at create         */
+    const void* A_dense;         /* column-major m x n with leading dimension lda, or NULL  */
+    int64_t lda;
+    const int64_t* csr_rowptr;   /* [m+1], or NULL.  Exactly one of A_dense / csr_* is set  */
+    const int32_t* csr_col;      /* [nnz] column of each entry, any order inside a row      */
+    const void* csr_val;         /* [nnz]                                                   */
+    int64_t nnz;
+    const void* b;               /* [R][m]                                                  */
+    int64_t R;                   /* instances sharing A (R > 1 or scale != NULL => batched) */
+    const void* scale;           /* HOST [R] positive scales, or NULL (all 1, R must be 1)  */
+} dmmv_problem;
+
+/* Neighbourhood and loop options. */
+typedef struct {
+    int32_t radius;          /* 0: every value of D is a candidate (default);
+                                q > 0: only values at most q levels from the current one
+                                (the paper's 1-OPT and greedy repair use q = 1)             */
+    int32_t keep_going;      /* dmmv_solve: 0 = an instance stops at the first iteration whose
+                                best move is not a strict improvement; 1 = keep scoring all
+                                moves every iteration although nothing can be applied
+                                (fixed-work mode for throughput measurement)                */
+    int32_t poll_every;      /* dmmv_solve: every poll_every iterations the host waits for the
+                                stream and stops enqueueing once every instance has stopped;
+                                0 = never wait inside the loop                              */
+    int32_t reserved;
+    const uint8_t* var_mask; /* [R][n] nonzero = variable may move (greedy repair works on the
+                                unassigned variables only); NULL = all                      */
+} dmmv_options;
+
+/* Bytes of device workspace dmmv_create needs for this problem (0 on invalid input, with
+ * dmmv_last_error set).  HOST computation, no GPU call. */
+size_t dmmv_workspace_bytes(const dmmv_problem* problem, const dmmv_options* options);
+
+/* Validate, copy D and scale, build the internal layouts (CSC copy of a CSR matrix;
+ * row-major copy of X and instance-interleaved copies of b for a batch).  `options` may be
+ * NULL (defaults).  hip_stream is a hipStream_t (NULL = the default stream).  Waits for
+ * the stream before returning so that layout errors (DMMV_ERR_SHAPE) can be reported. */
+dmmv_status dmmv_create(dmmv_handle* out, const dmmv_problem* problem, const dmmv_options* options,
+                        void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Releases the host-side handle.  Device buffers belong to the caller. */
+dmmv_status dmmv_destroy(dmmv_handle h);
+
+/* Set the current point from values x [R][n] (each must equal an entry of D exactly;
+ * waits for the stream to report DMMV_ERR_DOMAIN).  Invalidates the residual. */
+dmmv_status dmmv_set_x(dmmv_handle h, const void* x_values);
+
+/* Overwrite the maintained residual with r [R][m] and recompute t = max |r|
+ * (for starting from a residual computed elsewhere). */
+dmmv_status dmmv_set_residual(dmmv_handle h, const void* r);
+
+/* r = A x - b for the current x, in the fixed order of the arithmetic contract; also sets
+ * t = max_i |r_i|.  r_out [R][m] may be NULL (internal state only).
+ * Paper: residual s = Ax - b and objective t = ||s||_inf, "Materials and Methods". */
+dmmv_status dmmv_residual(dmmv_handle h, void* r_out);
+
+/* Score table of the current state: scores_out[q][j*nd + k] = max_i |fma(delta, A_ij, r_i)|.
+ * The null move k = k_j scores exactly t.  Candidates outside the neighbourhood (radius,
+ * var_mask) get +infinity.  Sparse matrices: the maximum still runs over all m rows (rows
+ * without an entry in column j contribute |r_i|).
+ * Paper: Appendix B.3 step 3, Appendix A component form, "evaluate all candidates in bulk". */
+dmmv_status dmmv_eval_moves(dmmv_handle h, void* scores_out);
+
+/* Best move per instance: smallest score, lowest flat index among equal scores.
+ * scores [R][n*nd] is a table to reduce, or NULL to score the current state without
+ * writing a table (fused evaluation + reduction).  best [R] and best_score [R] receive the
+ * result (best.j = -1 only if n = 0).  The move is reported whether or not it improves.
+ * Paper: "choose minima via global reductions", "tensor-wide argmin". */
+dmmv_status dmmv_argmin_move(dmmv_handle h, const void* scores, dmmv_move* best, void* best_score);
+
+/* Apply moves [R] (entries with j = -1 are skipped): x_j <- D[k],
+ * r_i <- fma(delta, A_ij, r_i) for all rows (sparse: the rows of column j), t <- max |r|.
+ * Paper: Appendix A boxed identity; Algorithm 2 residual update line. */
+dmmv_status dmmv_apply_move(dmmv_handle h, const dmmv_move* moves);
+
+/* Copy out the current x values [R][n], residual [R][m] and max violation [R]
+ * (any may be NULL). */
+dmmv_status dmmv_get_state(dmmv_handle h, void* x_values, void* r, void* max_violation);
+
+/* The descent: set x = x0, compute r, then up to `iters` times { score all moves, take the
+ * best, stop the instance unless it strictly lowers t, apply it }.
+ *   x_out [R][n], max_violation_out [R], iters_done [R] (moves applied)   - any may be NULL
+ *   trace [R][iters] applied moves in order (j = -1 past the end), trace_t [R][iters]
+ *   the max violation after each                                            - may be NULL
+ * Waits for the stream before returning.
+ * Paper: Algorithm 1 local-search step restricted to single-coordinate moves; strict
+ * improvement as in Proposition 1 / Algorithm 2. */
+dmmv_status dmmv_solve(dmmv_handle h, const void* x0, int32_t iters, void* x_out,
+                       void* max_violation_out, int32_t* iters_done, dmmv_move* trace,
+                       void* trace_t);
+
+/* Message of the last failure on this thread (static storage, HOST). */
+const char* dmmv_last_error(void);
+
+/* Library version string (HOST). */
+const char* dmmv_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DMMV_H */

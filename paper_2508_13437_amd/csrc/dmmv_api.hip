@@ -1,0 +1,695 @@
+// C ABI of libdmmv: validation, workspace layout, call sequencing, and the small kernels
+// shared by the three storage kinds (value<->index conversion, selection of the best move
+// from partial records, arg-min of a given table, max |r|).
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+
+#include "dmmv_common.h"
+
+namespace dmmv {
+
+// ----------------------------------------------------------------------------------------
+// errors
+// ----------------------------------------------------------------------------------------
+static thread_local char g_err[512] = "";
+
+dmmv_status fail(dmmv_status st, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+// ----------------------------------------------------------------------------------------
+// workspace layout
+// ----------------------------------------------------------------------------------------
+namespace {
+struct Bump {
+    char* base;
+    size_t off = 0;
+    template <class P>
+    void take(P** out, size_t bytes) {
+        off = (off + 255) / 256 * 256;
+        if (out) *out = base ? reinterpret_cast<P*>(base + off) : nullptr;
+        off += bytes;
+    }
+};
+
+}  // namespace
+
+int64_t dense_num_partials(const dmmv_problem& p) {
+    return p.n * ceil_div(p.nd, dense_ktile(p.nd));
+}
+int32_t batched_chunk_cols(const dmmv_problem& p) {
+    // enough (instance group, chunk) blocks to fill 256 CUs several times over
+    int64_t groups = ceil_div(p.R, 64);
+    int64_t want_chunks = ceil_div(2048, groups);
+    int64_t cols = ceil_div(p.n, want_chunks);
+    cols = ceil_div(cols, 32) * 32;
+    if (cols < 32) cols = 32;
+    return (int32_t)cols;
+}
+
+size_t workspace_layout(const dmmv_problem& p, const dmmv_options& o, Ctx* c, char* base) {
+    (void)o;
+    Ctx dummy;
+    if (!c) c = &dummy;
+    const size_t esz = p.dtype == DMMV_F64 ? 8 : 4;
+    const bool sparse = p.csr_rowptr != nullptr;
+    const bool batched = !sparse && (p.R > 1 || p.scale != nullptr);
+    const size_t state_sz = p.dtype == DMMV_F64 ? sizeof(InstState<double>) : sizeof(InstState<float>);
+    const size_t part_sz = p.dtype == DMMV_F64 ? sizeof(Partial<double>) : sizeof(Partial<float>);
+    Bump b{base};
+    b.take(&c->flags, FLAG_COUNT * sizeof(int32_t));
+    b.take(&c->D_dev, (size_t)p.nd * esz);
+    b.take(&c->scale_dev, (size_t)p.R * esz);
+    b.take(&c->state, (size_t)p.R * state_sz);
+    b.take(&c->kidx, (size_t)p.n * p.R * sizeof(int32_t));
+    b.take(&c->r, (size_t)p.m * p.R * esz);
+    c->red_elems = 1024;
+    b.take(&c->red, (size_t)c->red_elems * esz);
+    if (sparse) {
+        c->n_partials = ceil_div(p.n, CSC_COLS_PER_BLOCK);
+        b.take(&c->partials, (size_t)(c->n_partials > 0 ? c->n_partials : 1) * part_sz);
+        b.take(&c->colptr, (size_t)(p.n + 1) * sizeof(int64_t));
+        b.take(&c->fillpos, (size_t)(p.n + 1) * sizeof(int64_t));
+        b.take(&c->rowidx, (size_t)p.nnz * sizeof(int32_t));
+        b.take(&c->cval, (size_t)p.nnz * esz);
+        b.take(&c->rowidx_tmp, (size_t)p.nnz * sizeof(int32_t));
+        b.take(&c->cval_tmp, (size_t)p.nnz * esz);
+        c->topk_groups = ceil_div(p.m > 0 ? p.m : 1, TOPK_GROUP);
+        b.take(&c->topk_val, (size_t)TOPK * esz);
+        b.take(&c->topk_row, (size_t)TOPK * sizeof(int32_t));
+        b.take(&c->topk_sval, (size_t)c->topk_groups * TOPK * esz);
+        b.take(&c->topk_srow, (size_t)c->topk_groups * TOPK * sizeof(int32_t));
+    } else if (batched) {
+        c->chunk_cols = batched_chunk_cols(p);
+        c->n_partials = ceil_div(p.n, c->chunk_cols);
+        b.take(&c->partials, (size_t)(c->n_partials > 0 ? c->n_partials : 1) * p.R * part_sz);
+        b.take(&c->Xt, (size_t)p.m * p.n * esz);
+        b.take(&c->Bt, (size_t)p.m * p.R * esz);
+    } else {
+        c->n_partials = dense_num_partials(p);
+        b.take(&c->partials, (size_t)(c->n_partials > 0 ? c->n_partials : 1) * part_sz);
+    }
+    return (b.off + 255) / 256 * 256;
+}
+
+// ----------------------------------------------------------------------------------------
+// validation (host)
+// ----------------------------------------------------------------------------------------
+static dmmv_status validate_problem(const dmmv_problem* p) {
+    if (!p) return fail(DMMV_ERR_NULL, "problem is NULL");
+    if (p->dtype != DMMV_F32 && p->dtype != DMMV_F64) return fail(DMMV_ERR_DTYPE, "dtype %d is not DMMV_F32/DMMV_F64", p->dtype);
+    if (p->m < 0 || p->n < 0 || p->R < 1) return fail(DMMV_ERR_SHAPE, "need m >= 0, n >= 0, R >= 1 (m=%lld n=%lld R=%lld)", (long long)p->m, (long long)p->n, (long long)p->R);
+    if (p->m > INT32_MAX - 1 || p->n > INT32_MAX - 1) return fail(DMMV_ERR_SHAPE, "m and n must fit in 31 bits");
+    if (p->nd < 2 || p->nd > 65535) return fail(DMMV_ERR_DOMAIN, "need 2 <= nd <= 65535 (nd=%d)", p->nd);
+    if (!p->D) return fail(DMMV_ERR_NULL, "D is NULL");
+    for (int32_t k = 0; k < p->nd; ++k) {
+        double v = p->dtype == DMMV_F64 ? ((const double*)p->D)[k] : (double)((const float*)p->D)[k];
+        if (!isfinite(v)) return fail(DMMV_ERR_DOMAIN, "D[%d] is not finite", k);
+        if (k > 0) {
+            double u = p->dtype == DMMV_F64 ? ((const double*)p->D)[k - 1] : (double)((const float*)p->D)[k - 1];
+            if (!(u < v)) return fail(DMMV_ERR_DOMAIN, "D is not strictly ascending at index %d", k);
+        }
+    }
+    const bool dense = p->A_dense != nullptr;
+    const bool sparse = p->csr_rowptr != nullptr;
+    if (dense == sparse && (p->m > 0 && p->n > 0)) return fail(DMMV_ERR_NULL, "exactly one of A_dense and csr_rowptr must be set");
+    if (dense && p->lda < (p->m > 1 ? p->m : 1)) return fail(DMMV_ERR_SHAPE, "lda=%lld < max(m,1)", (long long)p->lda);
+    if (sparse) {
+        if (p->nnz < 0 || p->nnz > INT32_MAX - 1) return fail(DMMV_ERR_SHAPE, "nnz must be in [0, 2^31-2]");
+        if (p->nnz > 0 && (!p->csr_col || !p->csr_val)) return fail(DMMV_ERR_NULL, "csr_col / csr_val is NULL");
+        if (p->R != 1 || p->scale) return fail(DMMV_ERR_UNSUPPORTED, "sparse matrices support a single unscaled instance (R = 1, scale = NULL)");
+    }
+    if (p->m > 0 && !p->b) return fail(DMMV_ERR_NULL, "b is NULL");
+    if (p->scale) {
+        for (int64_t q = 0; q < p->R; ++q) {
+            double v = p->dtype == DMMV_F64 ? ((const double*)p->scale)[q] : (double)((const float*)p->scale)[q];
+            if (!isfinite(v) || !(v > 0)) return fail(DMMV_ERR_DOMAIN, "scale[%lld] must be finite and positive", (long long)q);
+        }
+    } else if (p->R != 1) {
+        return fail(DMMV_ERR_NULL, "scale is NULL but R = %lld", (long long)p->R);
+    }
+    return DMMV_OK;
+}
+
+// ----------------------------------------------------------------------------------------
+// shared kernels
+// ----------------------------------------------------------------------------------------
+template <class T>
+__global__ void k_init_state(InstState<T>* st, int64_t R) {
+    int64_t q = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    if (q >= R) return;
+    InstState<T> s;
+    s.t = (T)0; s.best_s = (T)0; s.delta = (T)0;
+    s.apply_j = -1; s.apply_k = -1; s.done = 0; s.moves = 0;
+    st[q] = s;
+}
+
+__global__ void k_zero_flags(int32_t* flags) {
+    if (threadIdx.x < FLAG_COUNT) flags[threadIdx.x] = 0;
+}
+
+// x values -> index into D (binary search, exact match required), single instance
+template <class T>
+__global__ void k_values_to_index(const T* __restrict__ x, const T* __restrict__ D, int32_t nd,
+                                  int64_t n, int32_t* __restrict__ kidx, int32_t* flags) {
+    int64_t j = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    if (j >= n) return;
+    T v = x[j];
+    int32_t lo = 0, hi = nd - 1;
+    while (lo < hi) {
+        int32_t mid = (lo + hi) >> 1;
+        if (D[mid] < v) lo = mid + 1; else hi = mid;
+    }
+    if (!(D[lo] == v)) { atomicOr(&flags[FLAG_ERROR], ERRBIT_X_NOT_IN_D); lo = 0; }
+    kidx[j] = lo;
+}
+
+template <class T>
+__global__ void k_index_to_values(const int32_t* __restrict__ kidx, const T* __restrict__ D,
+                                  int64_t n, T* __restrict__ x) {
+    int64_t j = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    if (j < n) x[j] = D[kidx[j]];
+}
+
+// stage 1 of max |r|: one partial per block
+template <class T>
+__global__ void k_maxabs_partial(const T* __restrict__ r, int64_t m, T* __restrict__ red) {
+    __shared__ T sh[16];
+    T v = (T)0;
+    for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < m;
+         i += (int64_t)gridDim.x * blockDim.x)
+        v = dmmv_max(v, dmmv_abs(r[i]));
+    v = wave_max(v);
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        T w = (T)0;
+        for (int q = 0; q < (int)(blockDim.x >> 6); ++q) w = dmmv_max(w, sh[q]);
+        red[blockIdx.x] = w;
+    }
+}
+
+template <class T>
+__global__ void k_maxabs_final(const T* __restrict__ red, int nred, InstState<T>* st) {
+    T v = (T)0;
+    for (int q = threadIdx.x; q < nred; q += blockDim.x) v = dmmv_max(v, red[q]);
+    v = wave_max(v);
+    __shared__ T sh[16];
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        T w = (T)0;
+        for (int q = 0; q < (int)(blockDim.x >> 6); ++q) w = dmmv_max(w, sh[q]);
+        st[0].t = w;
+    }
+}
+
+// Selection for a single instance: reduce the partial records of the fused evaluation to the
+// best move, decide whether it is a strict improvement and stage it for the apply kernel.
+template <class T>
+__global__ void k_select_single(const Partial<T>* __restrict__ part, int64_t n_part,
+                                InstState<T>* st, const T* __restrict__ D,
+                                const int32_t* __restrict__ kidx, int32_t nd, int32_t keep_going,
+                                dmmv_move* best_out, T* best_score_out) {
+    __shared__ T sh_s[16];
+    __shared__ int64_t sh_c[16];
+    if (st[0].done && !best_out) return;
+    T s = (T)0;
+    int64_t c = -1;
+    for (int64_t q = threadIdx.x; q < n_part; q += blockDim.x) {
+        Partial<T> p = part[q];
+        if (rec_less(p.s, p.c, s, c)) { s = p.s; c = p.c; }
+    }
+    block_argmin(s, c, sh_s, sh_c);
+    if (threadIdx.x == 0) {
+        InstState<T> z = st[0];
+        int32_t j = -1, k = -1;
+        if (c >= 0) { j = (int32_t)(c / nd); k = (int32_t)(c % nd); }
+        const bool improving = c >= 0 && s < z.t;
+        z.best_s = s;
+        z.apply_j = improving ? j : -1;
+        z.apply_k = improving ? k : -1;
+        z.delta = improving ? step_of(D[k], D[kidx[j]], (T)1) : (T)0;
+        if (!improving && !keep_going) z.done = 1;
+        st[0] = z;
+        if (best_out) { best_out[0].j = j; best_out[0].k = k; }
+        if (best_score_out) best_score_out[0] = c >= 0 ? s : Limits<T>::inf();
+    }
+}
+
+// Same for a batch: one lane per instance, partial records laid out [chunk][R].
+template <class T>
+__global__ void k_select_batched(const Partial<T>* __restrict__ part, int64_t n_part, int64_t R,
+                                 InstState<T>* st, const T* __restrict__ D,
+                                 const T* __restrict__ scale, const int32_t* __restrict__ kidx,
+                                 int32_t nd, int32_t keep_going, dmmv_move* best_out,
+                                 T* best_score_out) {
+    int64_t q = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    if (q >= R) return;
+    InstState<T> z = st[q];
+    if (z.done && !best_out) return;
+    T s = (T)0;
+    int64_t c = -1;
+    for (int64_t ch = 0; ch < n_part; ++ch) {
+        Partial<T> p = part[ch * R + q];
+        if (rec_less(p.s, p.c, s, c)) { s = p.s; c = p.c; }
+    }
+    int32_t j = -1, k = -1;
+    if (c >= 0) { j = (int32_t)(c / nd); k = (int32_t)(c % nd); }
+    const bool improving = c >= 0 && s < z.t;
+    z.best_s = s;
+    z.apply_j = improving ? j : -1;
+    z.apply_k = improving ? k : -1;
+    z.delta = improving ? step_of(D[k], D[kidx[(int64_t)j * R + q]], scale[q]) : (T)0;
+    if (!improving && !keep_going) z.done = 1;
+    st[q] = z;
+    if (best_out) { best_out[q].j = j; best_out[q].k = k; }
+    if (best_score_out) best_score_out[q] = c >= 0 ? s : Limits<T>::inf();
+}
+
+// Arg-min of a caller-supplied table, one block per instance.
+template <class T>
+__global__ void k_argmin_table(const T* __restrict__ scores, int64_t ntab, int32_t nd,
+                               dmmv_move* best_out, T* best_score_out) {
+    __shared__ T sh_s[16];
+    __shared__ int64_t sh_c[16];
+    const int64_t q = blockIdx.x;
+    const T* tab = scores + q * ntab;
+    T s = (T)0;
+    int64_t c = -1;
+    for (int64_t i = threadIdx.x; i < ntab; i += blockDim.x) {
+        T v = tab[i];
+        if (rec_less(v, i, s, c)) { s = v; c = i; }
+    }
+    block_argmin(s, c, sh_s, sh_c);
+    if (threadIdx.x == 0) {
+        if (best_out) {
+            best_out[q].j = c >= 0 ? (int32_t)(c / nd) : -1;
+            best_out[q].k = c >= 0 ? (int32_t)(c % nd) : -1;
+        }
+        if (best_score_out) best_score_out[q] = c >= 0 ? s : Limits<T>::inf();
+    }
+}
+
+// Stage caller-supplied moves for the apply kernels (dmmv_apply_move).
+template <class T>
+__global__ void k_stage_moves(const dmmv_move* __restrict__ moves, int64_t R, int64_t n,
+                              int32_t nd, InstState<T>* st, const T* __restrict__ D,
+                              const T* __restrict__ scale, const int32_t* __restrict__ kidx,
+                              int32_t* flags) {
+    int64_t q = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    if (q >= R) return;
+    dmmv_move mv = moves[q];
+    InstState<T> z = st[q];
+    z.apply_j = -1; z.apply_k = -1; z.delta = (T)0;
+    if (mv.j >= 0) {
+        if (mv.j >= n || mv.k < 0 || mv.k >= nd) {
+            atomicOr(&flags[FLAG_ERROR], ERRBIT_MOVE_RANGE);
+        } else {
+            z.apply_j = mv.j; z.apply_k = mv.k;
+            z.delta = step_of(D[mv.k], D[kidx[(int64_t)mv.j * R + q]], scale ? scale[q] : (T)1);
+        }
+    }
+    st[q] = z;
+}
+
+template <class T>
+__global__ void k_count_active(const InstState<T>* __restrict__ st, int64_t R, int32_t* flags) {
+    int64_t q = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    if (q < R && !st[q].done) atomicAdd(&flags[FLAG_ACTIVE], 1);
+}
+
+// a stopped instance is skipped by the fused evaluation; standalone queries clear the mark
+template <class T>
+__global__ void k_clear_done(InstState<T>* st, int64_t R) {
+    int64_t q = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    if (q < R) st[q].done = 0;
+}
+
+template <class T>
+__global__ void k_reset_loop(InstState<T>* st, int64_t R) {
+    int64_t q = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    if (q < R) { st[q].done = 0; st[q].moves = 0; st[q].apply_j = -1; }
+}
+
+template <class T>
+__global__ void k_fill_trace(dmmv_move* trace, T* trace_t, int64_t count) {
+    int64_t q = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    if (q >= count) return;
+    if (trace) { trace[q].j = -1; trace[q].k = -1; }
+    if (trace_t) trace_t[q] = (T)0;
+}
+
+template <class T>
+__global__ void k_export_state(const InstState<T>* __restrict__ st, int64_t R, T* t_out,
+                               int32_t* moves_out) {
+    int64_t q = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    if (q >= R) return;
+    if (t_out) t_out[q] = st[q].t;
+    if (moves_out) moves_out[q] = st[q].moves;
+}
+
+static inline dim3 grid1(int64_t n, int block) { return dim3((unsigned)(n > 0 ? ceil_div(n, block) : 1)); }
+
+template <class T>
+static dmmv_status maxabs_single(Ctx* c) {
+    const int nblk = (int)(c->p.m > 0 ? (ceil_div(c->p.m, 1024) < c->red_elems ? ceil_div(c->p.m, 1024) : c->red_elems) : 1);
+    hipLaunchKernelGGL(k_maxabs_partial<T>, dim3(nblk), dim3(256), 0, c->stream, (const T*)c->r, c->p.m, (T*)c->red);
+    hipLaunchKernelGGL(k_maxabs_final<T>, dim3(1), dim3(256), 0, c->stream, (const T*)c->red, nblk, (InstState<T>*)c->state);
+    DMMV_LAUNCH_CHECK();
+    return DMMV_OK;
+}
+
+// t = max |r| into the state, whatever the kind
+static dmmv_status refresh_t(Ctx* c) {
+    if (c->kind == KIND_BATCHED) return batched_maxabs(c);
+    if (c->kind == KIND_CSC) return csc_refresh_topk(c);
+    return c->p.dtype == DMMV_F64 ? maxabs_single<double>(c) : maxabs_single<float>(c);
+}
+
+template <class T>
+static dmmv_status select_t(Ctx* c, dmmv_move* best_out, void* best_score_out) {
+    if (c->kind == KIND_BATCHED) {
+        hipLaunchKernelGGL(k_select_batched<T>, grid1(c->p.R, 256), dim3(256), 0, c->stream,
+                           (const Partial<T>*)c->partials, c->p.n > 0 ? c->n_partials : 0, c->p.R,
+                           (InstState<T>*)c->state, (const T*)c->D_dev, (const T*)c->scale_dev,
+                           (const int32_t*)c->kidx, c->p.nd, c->o.keep_going, best_out,
+                           (T*)best_score_out);
+    } else {
+        hipLaunchKernelGGL(k_select_single<T>, dim3(1), dim3(1024), 0, c->stream,
+                           (const Partial<T>*)c->partials, c->p.n > 0 ? c->n_partials : 0,
+                           (InstState<T>*)c->state, (const T*)c->D_dev, (const int32_t*)c->kidx,
+                           c->p.nd, c->o.keep_going, best_out, (T*)best_score_out);
+    }
+    DMMV_LAUNCH_CHECK();
+    return DMMV_OK;
+}
+static dmmv_status launch_select(Ctx* c, dmmv_move* best_out, void* best_score_out) {
+    return c->p.dtype == DMMV_F64 ? select_t<double>(c, best_out, best_score_out)
+                                  : select_t<float>(c, best_out, best_score_out);
+}
+
+static dmmv_status eval_any(Ctx* c, void* scores_out, bool want_partials) {
+    if (c->p.n == 0) return DMMV_OK;
+    switch (c->kind) {
+        case KIND_DENSE: return dense_eval(c, scores_out, want_partials);
+        case KIND_CSC:
+            if (!c->topk_valid) DMMV_TRY(csc_refresh_topk(c));
+            return csc_eval(c, scores_out, want_partials);
+        default: return batched_eval(c, scores_out, want_partials);
+    }
+}
+
+static dmmv_status apply_any(Ctx* c, bool t_from_score, int32_t iters, dmmv_move* trace, void* trace_t) {
+    c->topk_valid = false;
+    switch (c->kind) {
+        case KIND_DENSE: return dense_apply(c, t_from_score, iters, trace, trace_t);
+        case KIND_CSC: return csc_apply(c, t_from_score, iters, trace, trace_t);
+        default: return batched_apply(c, t_from_score, iters, trace, trace_t);
+    }
+}
+
+static dmmv_status residual_any(Ctx* c) {
+    switch (c->kind) {
+        case KIND_DENSE: DMMV_TRY(dense_residual(c)); break;
+        case KIND_CSC: DMMV_TRY(csc_residual(c)); break;
+        default: DMMV_TRY(batched_residual(c)); break;
+    }
+    c->topk_valid = false;
+    DMMV_TRY(refresh_t(c));
+    if (c->kind == KIND_CSC) c->topk_valid = true;
+    c->r_valid = true;
+    return DMMV_OK;
+}
+
+// read and clear the device error flag (waits for the stream)
+static dmmv_status check_device_errors(Ctx* c) {
+    int32_t host_flag = 0;
+    DMMV_HIP_CHECK(hipMemcpyAsync(&host_flag, &c->flags[FLAG_ERROR], sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
+    DMMV_HIP_CHECK(hipStreamSynchronize(c->stream));
+    if (host_flag) {
+        hipLaunchKernelGGL(k_zero_flags, dim3(1), dim3(64), 0, c->stream, c->flags);
+        DMMV_HIP_CHECK(hipStreamSynchronize(c->stream));
+        if (host_flag & ERRBIT_X_NOT_IN_D) return fail(DMMV_ERR_DOMAIN, "x has a value that is not an element of D");
+        if (host_flag & ERRBIT_CSR_RANGE) return fail(DMMV_ERR_SHAPE, "CSR column index out of range or row pointers not ascending");
+        if (host_flag & ERRBIT_CSR_DUP) return fail(DMMV_ERR_SHAPE, "CSR matrix stores the same (row, column) entry twice");
+        if (host_flag & ERRBIT_MOVE_RANGE) return fail(DMMV_ERR_SHAPE, "move with j >= n or k outside [0, nd)");
+        return fail(DMMV_ERR_STATE, "device error flag %d", host_flag);
+    }
+    return DMMV_OK;
+}
+
+template <class T>
+static dmmv_status set_x_single(Ctx* c, const void* x) {
+    hipLaunchKernelGGL(k_values_to_index<T>, grid1(c->p.n, 256), dim3(256), 0, c->stream,
+                       (const T*)x, (const T*)c->D_dev, c->p.nd, c->p.n, c->kidx, c->flags);
+    DMMV_LAUNCH_CHECK();
+    return DMMV_OK;
+}
+
+template <class T>
+static dmmv_status solve_t(dmmv_ctx* c, const void* x0, int32_t iters, void* x_out, void* t_out,
+                           int32_t* iters_done, dmmv_move* trace, void* trace_t) {
+    const int64_t R = c->p.R;
+    if (x0 || c->p.n == 0) DMMV_TRY(dmmv_set_x(c, x0));
+    if (!c->x_set) return fail(DMMV_ERR_STATE, "dmmv_solve: no starting point (x0 is NULL and dmmv_set_x was never called)");
+    hipLaunchKernelGGL(k_reset_loop<T>, grid1(R, 256), dim3(256), 0, c->stream, (InstState<T>*)c->state, R);
+    DMMV_TRY(residual_any(c));
+    if (iters > 0 && (trace || trace_t))
+        hipLaunchKernelGGL(k_fill_trace<T>, grid1(R * (int64_t)iters, 256), dim3(256), 0, c->stream, trace, (T*)trace_t, R * (int64_t)iters);
+    const int32_t poll = c->o.keep_going ? 0 : c->o.poll_every;
+    for (int32_t it = 0; it < iters; ++it) {
+        DMMV_TRY(eval_any(c, nullptr, true));
+        DMMV_TRY(launch_select(c, nullptr, nullptr));
+        DMMV_TRY(apply_any(c, true, iters, trace, trace_t));
+        if (c->kind == KIND_CSC) { DMMV_TRY(csc_refresh_topk(c)); c->topk_valid = true; }
+        if (poll > 0 && (it + 1) % poll == 0 && it + 1 < iters) {
+            int32_t active = 0;
+            hipLaunchKernelGGL(k_zero_flags, dim3(1), dim3(64), 0, c->stream, c->flags);
+            hipLaunchKernelGGL(k_count_active<T>, grid1(R, 256), dim3(256), 0, c->stream, (const InstState<T>*)c->state, R, c->flags);
+            DMMV_HIP_CHECK(hipMemcpyAsync(&active, &c->flags[FLAG_ACTIVE], sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
+            DMMV_HIP_CHECK(hipStreamSynchronize(c->stream));
+            if (active == 0) break;
+        }
+    }
+    hipLaunchKernelGGL(k_export_state<T>, grid1(R, 256), dim3(256), 0, c->stream, (const InstState<T>*)c->state, R, (T*)t_out, iters_done);
+    DMMV_LAUNCH_CHECK();
+    if (x_out) DMMV_TRY(dmmv_get_state(c, x_out, nullptr, nullptr));
+    DMMV_HIP_CHECK(hipStreamSynchronize(c->stream));
+    return DMMV_OK;
+}
+
+}  // namespace dmmv
+
+// ========================================================================================
+// C ABI
+// ========================================================================================
+using namespace dmmv;
+
+extern "C" {
+
+const char* dmmv_last_error(void) { return g_err; }
+const char* dmmv_version(void) { return "libdmmv 0.1 (gfx950)"; }
+
+size_t dmmv_workspace_bytes(const dmmv_problem* problem, const dmmv_options* options) {
+    if (validate_problem(problem) != DMMV_OK) return 0;
+    dmmv_options o{};
+    if (options) o = *options;
+    return workspace_layout(*problem, o, nullptr, nullptr);
+}
+
+dmmv_status dmmv_create(dmmv_handle* out, const dmmv_problem* problem, const dmmv_options* options,
+                        void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!out) return fail(DMMV_ERR_NULL, "out handle pointer is NULL");
+    *out = nullptr;
+    DMMV_TRY(validate_problem(problem));
+    dmmv_options o{};
+    o.poll_every = 64;
+    if (options) o = *options;
+    if (o.radius < 0 || o.poll_every < 0) return fail(DMMV_ERR_SHAPE, "options: radius and poll_every must be >= 0");
+    const size_t need = workspace_layout(*problem, o, nullptr, nullptr);
+    if (!workspace) return fail(DMMV_ERR_WORKSPACE, "workspace is NULL (%zu bytes needed)", need);
+    if (((uintptr_t)workspace & 255) != 0) return fail(DMMV_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+    if (workspace_bytes < need) return fail(DMMV_ERR_WORKSPACE, "workspace too small: %zu bytes given, %zu needed", workspace_bytes, need);
+
+    dmmv_ctx* c = new (std::nothrow) dmmv_ctx();
+    if (!c) return fail(DMMV_ERR_STATE, "out of host memory");
+    c->p = *problem;
+    c->o = o;
+    c->stream = (hipStream_t)hip_stream;
+    c->esz = problem->dtype == DMMV_F64 ? 8 : 4;
+    const bool sparse = problem->csr_rowptr != nullptr;
+    c->kind = sparse ? KIND_CSC : ((problem->R > 1 || problem->scale) ? KIND_BATCHED : KIND_DENSE);
+    c->x_set = c->r_valid = c->topk_valid = false;
+    workspace_layout(*problem, o, c, (char*)workspace);
+    c->p.D = nullptr;       // host arrays are copied below and not referenced afterwards
+    c->p.scale = nullptr;
+
+    dmmv_status st = [&]() -> dmmv_status {
+        hipLaunchKernelGGL(k_zero_flags, dim3(1), dim3(64), 0, c->stream, c->flags);
+        DMMV_HIP_CHECK(hipMemcpyAsync(c->D_dev, problem->D, (size_t)problem->nd * c->esz, hipMemcpyHostToDevice, c->stream));
+        if (problem->scale) {
+            DMMV_HIP_CHECK(hipMemcpyAsync(c->scale_dev, problem->scale, (size_t)problem->R * c->esz, hipMemcpyHostToDevice, c->stream));
+        } else if (problem->dtype == DMMV_F64) {
+            const double one = 1.0;
+            DMMV_HIP_CHECK(hipMemcpyAsync(c->scale_dev, &one, sizeof(one), hipMemcpyHostToDevice, c->stream));
+        } else {
+            const float one = 1.0f;
+            DMMV_HIP_CHECK(hipMemcpyAsync(c->scale_dev, &one, sizeof(one), hipMemcpyHostToDevice, c->stream));
+        }
+        // the host copies above read caller memory: finish them before returning
+        if (problem->dtype == DMMV_F64)
+            hipLaunchKernelGGL(k_init_state<double>, grid1(problem->R, 256), dim3(256), 0, c->stream, (InstState<double>*)c->state, problem->R);
+        else
+            hipLaunchKernelGGL(k_init_state<float>, grid1(problem->R, 256), dim3(256), 0, c->stream, (InstState<float>*)c->state, problem->R);
+        DMMV_LAUNCH_CHECK();
+        if (c->kind == KIND_CSC) DMMV_TRY(csc_build(c));
+        if (c->kind == KIND_BATCHED) DMMV_TRY(batched_build(c));
+        return check_device_errors(c);
+    }();
+    if (st != DMMV_OK) { delete c; return st; }
+    *out = c;
+    return DMMV_OK;
+}
+
+dmmv_status dmmv_destroy(dmmv_handle h) {
+    if (!h) return fail(DMMV_ERR_NULL, "handle is NULL");
+    (void)hipStreamSynchronize(h->stream);
+    delete h;
+    return DMMV_OK;
+}
+
+dmmv_status dmmv_set_x(dmmv_handle h, const void* x_values) {
+    if (!h) return fail(DMMV_ERR_NULL, "handle is NULL");
+    if (!x_values && h->p.n > 0) return fail(DMMV_ERR_NULL, "x_values is NULL");
+    h->x_set = false;
+    h->r_valid = false;
+    if (h->p.n > 0) {
+        if (h->kind == KIND_BATCHED) DMMV_TRY(batched_set_x(h, x_values));
+        else if (h->p.dtype == DMMV_F64) DMMV_TRY(set_x_single<double>(h, x_values));
+        else DMMV_TRY(set_x_single<float>(h, x_values));
+    }
+    DMMV_TRY(check_device_errors(h));
+    h->x_set = true;
+    return DMMV_OK;
+}
+
+dmmv_status dmmv_set_residual(dmmv_handle h, const void* r) {
+    if (!h) return fail(DMMV_ERR_NULL, "handle is NULL");
+    if (!r && h->p.m > 0) return fail(DMMV_ERR_NULL, "r is NULL");
+    if (!h->x_set) return fail(DMMV_ERR_STATE, "dmmv_set_residual before dmmv_set_x");
+    if (h->p.m > 0) {
+        if (h->kind == KIND_BATCHED) DMMV_TRY(batched_set_r(h, r));
+        else DMMV_HIP_CHECK(hipMemcpyAsync(h->r, r, (size_t)h->p.m * h->esz, hipMemcpyDeviceToDevice, h->stream));
+    }
+    h->topk_valid = false;
+    DMMV_TRY(refresh_t(h));
+    if (h->kind == KIND_CSC) h->topk_valid = true;
+    h->r_valid = true;
+    return DMMV_OK;
+}
+
+dmmv_status dmmv_residual(dmmv_handle h, void* r_out) {
+    if (!h) return fail(DMMV_ERR_NULL, "handle is NULL");
+    if (!h->x_set) return fail(DMMV_ERR_STATE, "dmmv_residual before dmmv_set_x");
+    DMMV_TRY(residual_any(h));
+    if (r_out) DMMV_TRY(dmmv_get_state(h, nullptr, r_out, nullptr));
+    return DMMV_OK;
+}
+
+dmmv_status dmmv_eval_moves(dmmv_handle h, void* scores_out) {
+    if (!h) return fail(DMMV_ERR_NULL, "handle is NULL");
+    if (!scores_out && h->p.n > 0) return fail(DMMV_ERR_NULL, "scores_out is NULL");
+    if (!h->r_valid) return fail(DMMV_ERR_STATE, "dmmv_eval_moves needs a residual (call dmmv_residual or dmmv_set_residual)");
+    return eval_any(h, scores_out, false);
+}
+
+dmmv_status dmmv_argmin_move(dmmv_handle h, const void* scores, dmmv_move* best, void* best_score) {
+    if (!h) return fail(DMMV_ERR_NULL, "handle is NULL");
+    if (!best && !best_score) return fail(DMMV_ERR_NULL, "best and best_score are both NULL");
+    if (scores) {
+        const int64_t ntab = h->p.n * (int64_t)h->p.nd;
+        if (h->p.dtype == DMMV_F64)
+            hipLaunchKernelGGL(k_argmin_table<double>, dim3((unsigned)h->p.R), dim3(1024), 0, h->stream, (const double*)scores, ntab, h->p.nd, best, (double*)best_score);
+        else
+            hipLaunchKernelGGL(k_argmin_table<float>, dim3((unsigned)h->p.R), dim3(1024), 0, h->stream, (const float*)scores, ntab, h->p.nd, best, (float*)best_score);
+        DMMV_LAUNCH_CHECK();
+        return DMMV_OK;
+    }
+    if (!h->r_valid) return fail(DMMV_ERR_STATE, "dmmv_argmin_move(scores = NULL) needs a residual");
+    const int32_t keep = h->o.keep_going;
+    h->o.keep_going = 1;   // a standalone query must not stop the instance
+    if (h->p.dtype == DMMV_F64)
+        hipLaunchKernelGGL(k_clear_done<double>, grid1(h->p.R, 256), dim3(256), 0, h->stream, (InstState<double>*)h->state, h->p.R);
+    else
+        hipLaunchKernelGGL(k_clear_done<float>, grid1(h->p.R, 256), dim3(256), 0, h->stream, (InstState<float>*)h->state, h->p.R);
+    dmmv_status st = eval_any(h, nullptr, true);
+    if (st == DMMV_OK) st = launch_select(h, best, best_score);
+    h->o.keep_going = keep;
+    return st;
+}
+
+dmmv_status dmmv_apply_move(dmmv_handle h, const dmmv_move* moves) {
+    if (!h) return fail(DMMV_ERR_NULL, "handle is NULL");
+    if (!moves) return fail(DMMV_ERR_NULL, "moves is NULL");
+    if (!h->r_valid) return fail(DMMV_ERR_STATE, "dmmv_apply_move needs a residual");
+    const int64_t R = h->p.R;
+    const bool batched = h->kind == KIND_BATCHED;
+    if (h->p.dtype == DMMV_F64)
+        hipLaunchKernelGGL(k_stage_moves<double>, grid1(R, 256), dim3(256), 0, h->stream, moves, R, h->p.n, h->p.nd, (InstState<double>*)h->state, (const double*)h->D_dev, batched ? (const double*)h->scale_dev : nullptr, (const int32_t*)h->kidx, h->flags);
+    else
+        hipLaunchKernelGGL(k_stage_moves<float>, grid1(R, 256), dim3(256), 0, h->stream, moves, R, h->p.n, h->p.nd, (InstState<float>*)h->state, (const float*)h->D_dev, batched ? (const float*)h->scale_dev : nullptr, (const int32_t*)h->kidx, h->flags);
+    DMMV_LAUNCH_CHECK();
+    DMMV_TRY(check_device_errors(h));
+    DMMV_TRY(apply_any(h, false, 0, nullptr, nullptr));
+    DMMV_TRY(refresh_t(h));
+    if (h->kind == KIND_CSC) h->topk_valid = true;
+    return DMMV_OK;
+}
+
+dmmv_status dmmv_get_state(dmmv_handle h, void* x_values, void* r, void* max_violation) {
+    if (!h) return fail(DMMV_ERR_NULL, "handle is NULL");
+    const int64_t R = h->p.R;
+    if (x_values && h->p.n > 0) {
+        if (!h->x_set) return fail(DMMV_ERR_STATE, "dmmv_get_state: x was never set");
+        if (h->kind == KIND_BATCHED) DMMV_TRY(batched_get_x(h, x_values));
+        else if (h->p.dtype == DMMV_F64)
+            hipLaunchKernelGGL(k_index_to_values<double>, grid1(h->p.n, 256), dim3(256), 0, h->stream, (const int32_t*)h->kidx, (const double*)h->D_dev, h->p.n, (double*)x_values);
+        else
+            hipLaunchKernelGGL(k_index_to_values<float>, grid1(h->p.n, 256), dim3(256), 0, h->stream, (const int32_t*)h->kidx, (const float*)h->D_dev, h->p.n, (float*)x_values);
+    }
+    if (r && h->p.m > 0) {
+        if (!h->r_valid) return fail(DMMV_ERR_STATE, "dmmv_get_state: no residual yet");
+        if (h->kind == KIND_BATCHED) DMMV_TRY(batched_get_r(h, r));
+        else DMMV_HIP_CHECK(hipMemcpyAsync(r, h->r, (size_t)h->p.m * h->esz, hipMemcpyDeviceToDevice, h->stream));
+    }
+    if (max_violation) {
+        if (!h->r_valid) return fail(DMMV_ERR_STATE, "dmmv_get_state: no residual yet");
+        if (h->p.dtype == DMMV_F64)
+            hipLaunchKernelGGL(k_export_state<double>, grid1(R, 256), dim3(256), 0, h->stream, (const InstState<double>*)h->state, R, (double*)max_violation, (int32_t*)nullptr);
+        else
+            hipLaunchKernelGGL(k_export_state<float>, grid1(R, 256), dim3(256), 0, h->stream, (const InstState<float>*)h->state, R, (float*)max_violation, (int32_t*)nullptr);
+    }
+    DMMV_LAUNCH_CHECK();
+    return DMMV_OK;
+}
+
+dmmv_status dmmv_solve(dmmv_handle h, const void* x0, int32_t iters, void* x_out,
+                       void* max_violation_out, int32_t* iters_done, dmmv_move* trace,
+                       void* trace_t) {
+    if (!h) return fail(DMMV_ERR_NULL, "handle is NULL");
+    if (iters < 0) return fail(DMMV_ERR_SHAPE, "iters must be >= 0");
+    return h->p.dtype == DMMV_F64
+               ? solve_t<double>(h, x0, iters, x_out, max_violation_out, iters_done, trace, trace_t)
+               : solve_t<float>(h, x0, iters, x_out, max_violation_out, iters_done, trace, trace_t);
+}
+
+}  // extern "C"

@@ -1,0 +1,261 @@
+// Shared internals of libdmmv: context layout, error plumbing, wave64 reductions.
+// gfx950 (CDNA4) only: 64-wide wavefronts, DPP row operations, LDS.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/dmmv.h"
+
+namespace dmmv {
+
+// ----------------------------------------------------------------------------------------
+// error plumbing (host)
+// ----------------------------------------------------------------------------------------
+dmmv_status fail(dmmv_status st, const char* fmt, ...);
+
+#define DMMV_HIP_CHECK(expr)                                                              \
+    do {                                                                                  \
+        hipError_t e__ = (expr);                                                          \
+        if (e__ != hipSuccess)                                                            \
+            return ::dmmv::fail(DMMV_ERR_HIP, "%s failed: %s (%s:%d)", #expr,             \
+                                hipGetErrorString(e__), __FILE__, __LINE__);              \
+    } while (0)
+
+#define DMMV_LAUNCH_CHECK() DMMV_HIP_CHECK(hipGetLastError())
+
+#define DMMV_TRY(expr)                        \
+    do {                                      \
+        dmmv_status s__ = (expr);             \
+        if (s__ != DMMV_OK) return s__;       \
+    } while (0)
+
+// ----------------------------------------------------------------------------------------
+// context
+// ----------------------------------------------------------------------------------------
+enum Kind { KIND_DENSE = 0, KIND_CSC = 1, KIND_BATCHED = 2 };
+
+constexpr int TOPK = 32;          // rows of largest |r| tracked by the sparse path
+constexpr int TOPK_GROUP = 2048;  // rows per stage-1 group of the top-K selection
+
+// Per-instance loop state kept on the device.
+template <class T>
+struct alignas(16) InstState {
+    T t;             // current max violation
+    T best_s;        // score of the best move found by the last selection
+    T delta;         // step of the move to apply
+    int32_t apply_j; // variable of the move to apply, -1 = nothing to apply
+    int32_t apply_k;
+    int32_t done;    // 1: stopped (best move was not a strict improvement)
+    int32_t moves;   // moves applied so far
+};
+
+// One partial arg-min record: score and flat candidate index (c < 0: empty).
+template <class T>
+struct alignas(16) Partial {
+    T s;
+    int64_t c;
+};
+
+// device flag slots
+enum { FLAG_ERROR = 0, FLAG_ACTIVE = 1, FLAG_COUNT = 8 };
+// error bits set by kernels
+enum { ERRBIT_X_NOT_IN_D = 1, ERRBIT_CSR_RANGE = 2, ERRBIT_CSR_DUP = 4, ERRBIT_MOVE_RANGE = 8 };
+
+struct Ctx {
+    dmmv_problem p;
+    dmmv_options o;
+    hipStream_t stream;
+    Kind kind;
+    size_t esz;
+    bool x_set, r_valid, topk_valid;
+
+    // ---- carved from the caller's workspace (device) ----
+    void* D_dev;          // T[nd]
+    void* scale_dev;      // T[R]
+    int32_t* kidx;        // dense/sparse: [n]; batched: [n][R] (instances contiguous)
+    void* r;              // dense/sparse: T[m]; batched: T[m][R]
+    void* state;          // InstState<T>[R]
+    void* partials;       // Partial<T>: single [n_partials]; batched [n_partials][R]
+    int64_t n_partials;
+    int32_t* flags;       // [FLAG_COUNT]
+    void* red;            // T[red_elems] partial maxima of the max-|r| reduction
+    int64_t red_elems;
+
+    // sparse
+    int64_t* colptr;      // [n+1]
+    int32_t* rowidx;      // [nnz] rows ascending inside a column
+    void* cval;           // T[nnz]
+    int64_t* fillpos;     // [n] build scratch
+    int32_t* rowidx_tmp;  // [nnz] build scratch
+    void* cval_tmp;       // T[nnz] build scratch
+    void* topk_val;       // T[TOPK] largest |r|, descending (ties: lower row first)
+    int32_t* topk_row;    // [TOPK]
+    void* topk_sval;      // T[groups*TOPK] stage-1 candidates
+    int32_t* topk_srow;   // [groups*TOPK]
+    int64_t topk_groups;
+
+    // batched
+    void* Xt;             // T[m][n] row-major copy of X
+    void* Bt;             // T[m][R]
+    int32_t chunk_cols;   // columns per chunk of the fused evaluation (n_partials chunks)
+};
+
+}  // namespace dmmv
+
+// the opaque handle of the C ABI is the context itself
+struct dmmv_ctx : public dmmv::Ctx {};
+
+namespace dmmv {
+
+// Lays the device buffers out in a workspace starting at `base` (may be NULL: size only).
+// Returns the bytes needed.  Fills the pointer fields of *c when c != NULL.
+size_t workspace_layout(const dmmv_problem& p, const dmmv_options& o, Ctx* c, char* base);
+
+static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// values of D scored per workgroup by the dense evaluation kernel
+static inline int dense_ktile(int32_t nd) { return nd >= 16 ? 16 : (nd >= 8 ? 8 : 4); }
+// columns per workgroup of the sparse evaluation kernel
+constexpr int CSC_COLS_PER_BLOCK = 16;
+
+// ----------------------------------------------------------------------------------------
+// per-path entry points (all enqueue on c->stream)
+// ----------------------------------------------------------------------------------------
+dmmv_status dense_residual(Ctx* c);
+dmmv_status dense_eval(Ctx* c, void* scores_out, bool want_partials);
+dmmv_status dense_apply(Ctx* c, bool t_from_score, int32_t iters, dmmv_move* trace, void* trace_t);
+
+dmmv_status csc_build(Ctx* c);
+dmmv_status csc_residual(Ctx* c);
+dmmv_status csc_refresh_topk(Ctx* c);   // also sets state.t = largest |r|
+dmmv_status csc_eval(Ctx* c, void* scores_out, bool want_partials);
+dmmv_status csc_apply(Ctx* c, bool t_from_score, int32_t iters, dmmv_move* trace, void* trace_t);
+
+dmmv_status batched_build(Ctx* c);
+dmmv_status batched_residual(Ctx* c);
+dmmv_status batched_eval(Ctx* c, void* scores_out, bool want_partials);
+dmmv_status batched_apply(Ctx* c, bool t_from_score, int32_t iters, dmmv_move* trace, void* trace_t);
+dmmv_status batched_set_x(Ctx* c, const void* x_values);
+dmmv_status batched_get_x(Ctx* c, void* x_values);
+dmmv_status batched_set_r(Ctx* c, const void* r);
+dmmv_status batched_get_r(Ctx* c, void* r);
+dmmv_status batched_maxabs(Ctx* c);     // state[q].t = max_i |r[i][q]|
+
+// ----------------------------------------------------------------------------------------
+// device helpers
+// ----------------------------------------------------------------------------------------
+#ifdef __HIPCC__
+
+template <class T> struct Limits;
+template <> struct Limits<float> {
+    __device__ static float inf() { return __builtin_huge_valf(); }
+};
+template <> struct Limits<double> {
+    __device__ static double inf() { return __builtin_huge_val(); }
+};
+
+__device__ __forceinline__ float dmmv_fma(float a, float b, float c) { return __builtin_fmaf(a, b, c); }
+__device__ __forceinline__ double dmmv_fma(double a, double b, double c) { return __builtin_fma(a, b, c); }
+__device__ __forceinline__ float dmmv_abs(float a) { return __builtin_fabsf(a); }
+__device__ __forceinline__ double dmmv_abs(double a) { return __builtin_fabs(a); }
+__device__ __forceinline__ float dmmv_max(float a, float b) { return __builtin_fmaxf(a, b); }
+__device__ __forceinline__ double dmmv_max(double a, double b) { return __builtin_fmax(a, b); }
+
+// step of the move (k_cur -> k): sc * (D[k] - D[k_cur]), two roundings
+template <class T>
+__device__ __forceinline__ T step_of(T dk, T dcur, T sc) {
+    T diff = dk - dcur;
+    return sc * diff;
+}
+
+// DPP controls (GFX9 encoding)
+constexpr int DPP_QUAD_XOR1 = 0xB1;        // quad_perm [1,0,3,2]
+constexpr int DPP_QUAD_XOR2 = 0x4E;        // quad_perm [2,3,0,1]
+constexpr int DPP_ROW_HALF_MIRROR = 0x141;
+constexpr int DPP_ROW_MIRROR = 0x140;
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+template <int CTRL>
+__device__ __forceinline__ double dpp_mov(double v) {
+    int lo = __double2loint(v), hi = __double2hiint(v);
+    lo = __builtin_amdgcn_update_dpp(0, lo, CTRL, 0xF, 0xF, true);
+    hi = __builtin_amdgcn_update_dpp(0, hi, CTRL, 0xF, 0xF, true);
+    return __hiloint2double(hi, lo);
+}
+
+// Maximum over the 64 lanes of a wavefront, result in every lane.  max is idempotent, so a
+// butterfly of DPP permutations inside each row of 16 lanes (quad xor 1, quad xor 2, half-row
+// mirror, row mirror) followed by two cross-row exchanges is enough.  All 64 lanes must be
+// active.
+template <class T>
+__device__ __forceinline__ T wave_max(T v) {
+    v = dmmv_max(v, dpp_mov<DPP_QUAD_XOR1>(v));
+    v = dmmv_max(v, dpp_mov<DPP_QUAD_XOR2>(v));
+    v = dmmv_max(v, dpp_mov<DPP_ROW_HALF_MIRROR>(v));
+    v = dmmv_max(v, dpp_mov<DPP_ROW_MIRROR>(v));
+    v = dmmv_max(v, __shfl_xor(v, 16, 64));
+    v = dmmv_max(v, __shfl_xor(v, 32, 64));
+    return v;
+}
+
+__device__ __forceinline__ uint32_t wave_or(uint32_t v) {
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) v |= (uint32_t)__shfl_xor((int)v, off, 64);
+    return v;
+}
+
+// Lexicographic minimum of (score, index) over the wavefront, result in every lane.
+// Records with c < 0 are empty and lose against everything.
+template <class T>
+__device__ __forceinline__ bool rec_less(T s1, int64_t c1, T s2, int64_t c2) {
+    if (c1 < 0) return false;
+    if (c2 < 0) return true;
+    return (s1 < s2) || (s1 == s2 && c1 < c2);
+}
+
+template <class T>
+__device__ __forceinline__ void wave_argmin(T& s, int64_t& c) {
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        T os = __shfl_xor(s, off, 64);
+        int64_t oc = __shfl_xor(c, off, 64);
+        bool take = rec_less(os, oc, s, c);
+        s = take ? os : s;
+        c = take ? oc : c;
+    }
+}
+
+// Block-wide version; result valid in thread 0.  sh_s/sh_c hold blockDim.x/64 entries.
+template <class T>
+__device__ __forceinline__ void block_argmin(T& s, int64_t& c, T* sh_s, int64_t* sh_c) {
+    wave_argmin(s, c);
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+    if (lane == 0) { sh_s[w] = s; sh_c[w] = c; }
+    __syncthreads();
+    if (w == 0) {
+        T ls = lane < nw ? sh_s[lane] : (T)0;
+        int64_t lc = lane < nw ? sh_c[lane] : (int64_t)-1;
+        wave_argmin(ls, lc);
+        s = ls; c = lc;
+    }
+}
+
+// Is candidate k of a variable currently at k_cur inside the neighbourhood?
+__device__ __forceinline__ bool cand_allowed(int32_t kcur, int32_t k, int32_t radius, bool var_ok) {
+    if (k == kcur) return true;
+    if (!var_ok) return false;
+    if (radius > 0) {
+        int32_t d = k > kcur ? k - kcur : kcur - k;
+        if (d > radius) return false;
+    }
+    return true;
+}
+
+#endif  // __HIPCC__
+
+}  // namespace dmmv

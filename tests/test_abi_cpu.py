@@ -1,0 +1,114 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, sizes workspaces and rejects invalid problems before touching the device."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def mod():
+    from paper_2508_13437_amd import dmmv
+    if not os.path.exists(dmmv.LIB_PATH):
+        from paper_2508_13437_amd import build
+        build.build(force=True)
+    return dmmv
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "dmmv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dmmv_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(mod):
+    lib = mod.load()
+    names = declared_functions()
+    assert {"dmmv_residual", "dmmv_eval_moves", "dmmv_argmin_move", "dmmv_apply_move",
+            "dmmv_solve"} <= set(names)
+    for name in names:
+        assert hasattr(lib, name), name
+    assert set(names) == set(mod.EXPORTS)
+
+
+def _problem(mod, dtype=np.float64, m=10, n=5, D=(0.0, 1.0, 2.0), R=1, scale=None, sparse=False):
+    p = mod.Problem()
+    p.dtype = mod.DMMV_F64 if dtype == np.float64 else mod.DMMV_F32
+    Dh = np.asarray(D, dtype=dtype)
+    p.nd, p.m, p.n, p.R = len(Dh), m, n, R
+    p.D = Dh.ctypes.data_as(C.c_void_p)
+    p.b = 4096
+    if sparse:
+        p.csr_rowptr, p.csr_col, p.csr_val, p.nnz = 4096, 4096, 4096, 3 * m
+    else:
+        p.A_dense, p.lda = 4096, max(m, 1)
+    keep = [Dh]
+    if scale is not None:
+        sh = np.asarray(scale, dtype=dtype)
+        p.scale = sh.ctypes.data_as(C.c_void_p)
+        keep.append(sh)
+    return p, keep
+
+
+def test_workspace_sizes_and_validation(mod):
+    lib = mod.load()
+    o = mod.Options()
+    p, keep = _problem(mod)
+    base = lib.dmmv_workspace_bytes(C.byref(p), C.byref(o))
+    assert base > 0 and base % 256 == 0
+    p2, keep2 = _problem(mod, m=1000, n=500)
+    assert lib.dmmv_workspace_bytes(C.byref(p2), C.byref(o)) > base
+    ps, keeps = _problem(mod, dtype=np.float32, m=1000, n=500, sparse=True)
+    pb, keepb = _problem(mod, dtype=np.float32, m=100, n=50, R=3, scale=(1.0, 2.0, 0.5))
+    assert lib.dmmv_workspace_bytes(C.byref(ps), C.byref(o)) > 3000 * 8
+    assert lib.dmmv_workspace_bytes(C.byref(pb), C.byref(o)) >= 100 * 50 * 4 + 3 * 100 * 4
+    cases = [
+        (dict(D=(0.0,)), b"nd"), (dict(D=(0.0, 0.0)), b"ascending"),
+        (dict(D=(0.0, np.inf)), b"finite"), (dict(m=-1), b"m >= 0"),
+        (dict(R=2), b"scale"), (dict(R=2, scale=(1.0, -1.0)), b"positive"),
+    ]
+    for kw, needle in cases:
+        q, k = _problem(mod, **kw)
+        assert lib.dmmv_workspace_bytes(C.byref(q), C.byref(o)) == 0
+        assert needle in lib.dmmv_last_error(), (kw, lib.dmmv_last_error())
+    q, k = _problem(mod)
+    q.dtype = 7
+    assert lib.dmmv_workspace_bytes(C.byref(q), C.byref(o)) == 0
+    q, k = _problem(mod)
+    q.lda = 3
+    assert lib.dmmv_workspace_bytes(C.byref(q), C.byref(o)) == 0
+
+
+def test_create_rejects_bad_workspace_without_gpu(mod):
+    lib = mod.load()
+    o = mod.Options()
+    p, keep = _problem(mod)
+    h = C.c_void_p(None)
+    assert lib.dmmv_create(C.byref(h), C.byref(p), C.byref(o), None, 0, None) == -5
+    assert lib.dmmv_create(C.byref(h), C.byref(p), C.byref(o), C.c_void_p(4097), 1 << 20, None) == -5
+    assert lib.dmmv_create(C.byref(h), C.byref(p), C.byref(o), C.c_void_p(4096), 16, None) == -5
+    assert b"too small" in lib.dmmv_last_error()
+    assert lib.dmmv_create(None, C.byref(p), C.byref(o), C.c_void_p(4096), 1 << 20, None) == -1
+    assert lib.dmmv_destroy(None) == -1
+    assert lib.dmmv_solve(None, None, 1, None, None, None, None, None) == -1
+    assert mod.dmmv_version().startswith("libdmmv")
+
+
+def test_binding_fails_loudly_without_library(mod, monkeypatch):
+    monkeypatch.setattr(mod, "_lib", None)
+    monkeypatch.setattr(mod, "LIB_PATH", "/nonexistent/libdmmv.so")
+    with pytest.raises(RuntimeError):
+        mod.load()
+
+
+def test_product_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2508_13437_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower(), os.path.join(dirpath, f)

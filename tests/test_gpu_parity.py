@@ -1,0 +1,413 @@
+"""Parity of the HIP library (through its C ABI) against the CPU oracle, element by element.
+
+Bar: the arithmetic contract fixes every rounding (one fma per pair, fixed residual order),
+so score tables, move traces, final x and max violation must be bitwise equal, fp32 and fp64.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as orc
+from workloads import make_config, random_batched, random_dense, random_sparse
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def dmmv():
+    from paper_2508_13437_amd import dmmv as mod
+    return mod
+
+
+def T(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def N(t):
+    return t.detach().cpu().numpy()
+
+
+def oracle_solve(inst, iters, x0=None, **opt):
+    x0 = inst.x0 if x0 is None else x0
+    if inst.kind == "dense":
+        return orc.solve_dense(inst.A, inst.b, inst.D, x0, iters, **opt)
+    if inst.kind == "csr":
+        return orc.solve_csr(inst.m, inst.n, inst.csr_rowptr, inst.csr_col, inst.csr_val, inst.b,
+                             inst.D, x0, iters, **opt)
+    return orc.solve_batched(inst.A, inst.b, inst.D, inst.scale, x0, iters, **opt)
+
+
+def oracle_residual(inst, x):
+    if inst.kind == "dense":
+        return orc.residual_dense(inst.A, inst.b, inst.D, x)
+    return orc.residual_csr(inst.m, inst.csr_rowptr, inst.csr_col, inst.csr_val, inst.b, inst.D, x)
+
+
+def oracle_table(inst, x, r, **opt):
+    if inst.kind == "dense":
+        return orc.eval_moves_dense(inst.A, inst.D, x, r, **opt)
+    return orc.eval_moves_csr(inst.m, inst.n, inst.csr_rowptr, inst.csr_col, inst.csr_val, inst.D,
+                              x, r, method="plain", **opt)
+
+
+def check_single_trace(res, o, iters):
+    d = int(res.iters_done[0])
+    assert d == o.iters_done
+    tr = N(res.trace)[0]
+    assert np.array_equal(tr[:d, 0], o.trace_j) and np.array_equal(tr[:d, 1], o.trace_k)
+    assert np.all(tr[d:] == -1)
+    assert np.array_equal(N(res.trace_t)[0, :d], o.trace_t)
+    assert np.array_equal(N(res.x).reshape(-1), o.x)
+    assert N(res.max_violation)[0] == o.t
+
+
+def stepwise_check(inst, steps=4, **opt):
+    """Every entry point against the oracle, a few moves deep."""
+    m = dmmv()
+    vm = opt.get("var_mask")
+    hopt = dict(radius=opt.get("radius", 0))
+    if vm is not None:
+        hopt["var_mask"] = T(vm)
+    with m.from_instance(inst, DEV, **hopt) as h:
+        x = inst.x0.copy()
+        m.dmmv_set_x(h, T(x))
+        r_gpu = N(m.dmmv_residual(h))
+        r = oracle_residual(inst, x)
+        assert np.array_equal(r_gpu, r)
+        for _ in range(steps):
+            want = oracle_table(inst, x, r, **opt)
+            got = N(m.dmmv_eval_moves(h))
+            assert np.array_equal(got, want)
+            c, s = orc.argmin_move(want)
+            mv, ms = m.dmmv_argmin_move(h, T(want))
+            assert tuple(N(mv)[0]) == (c // inst.nd, c % inst.nd) and N(ms)[0] == s
+            mv2, ms2 = m.dmmv_argmin_move(h, None)          # fused evaluation + reduction
+            assert tuple(N(mv2)[0]) == (c // inst.nd, c % inst.nd) and N(ms2)[0] == s
+            xs, rs, ts = m.dmmv_get_state(h)
+            assert np.array_equal(N(xs), x) and np.array_equal(N(rs), r)
+            assert N(ts)[0] == orc.max_abs(r)
+            j, k = c // inst.nd, c % inst.nd
+            m.dmmv_apply_move(h, mv)
+            if inst.kind == "dense":
+                x, r, t = orc.apply_move_dense(inst.A, inst.D, x, r, j, k)
+            else:
+                x, r, t = orc.apply_move_csr(inst.m, inst.n, inst.csr_rowptr, inst.csr_col,
+                                             inst.csr_val, inst.D, x, r, j, k)
+            xs, rs, ts = m.dmmv_get_state(h)
+            assert np.array_equal(N(xs), x) and np.array_equal(N(rs), r) and N(ts)[0] == t
+
+
+# ------------------------------------------------------------------------------ dense
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("shape", [(1, 1, 2), (5, 3, 2), (63, 7, 3), (64, 9, 4), (65, 5, 5),
+                                   (257, 13, 9), (300, 40, 16), (1000, 6, 37), (130, 4, 200)])
+def test_dense_stepwise(shape, dtype):
+    mm, nn, nd = shape
+    stepwise_check(random_dense(10 + mm, mm, nn, nd, dtype=dtype), steps=3)
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("seed", range(4))
+def test_dense_integer_ties(seed, dtype):
+    """Small-integer data: exact ties are frequent, the lowest-index rule decides."""
+    inst = random_dense(50 + seed, 37, 11, 5, dtype=dtype, integer=True)
+    stepwise_check(inst, steps=4)
+    with dmmv().from_instance(inst, DEV) as h:
+        res = dmmv().dmmv_solve(h, T(inst.x0), 40, trace=True)
+    check_single_trace(res, oracle_solve(inst, 40), 40)
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_dense_solve_long_trace(dtype):
+    inst = random_dense(77, 700, 48, 16, dtype=dtype)
+    with dmmv().from_instance(inst, DEV, poll_every=7) as h:
+        res = dmmv().dmmv_solve(h, T(inst.x0), 150, trace=True)
+        o = oracle_solve(inst, 150)
+        assert o.iters_done >= 15
+        check_single_trace(res, o, 150)
+        x, r, t = dmmv().dmmv_get_state(h)
+        assert np.array_equal(N(r), o.r)
+        # the maintained t equals a fresh max |r| of the maintained residual
+        assert N(t)[0] == np.abs(o.r).max()
+        # resuming from the result does nothing more
+        assert o.iters_done < 150
+        res2 = dmmv().dmmv_solve(h, res.x, 10, trace=True)
+        assert int(res2.iters_done[0]) == 0 and N(res2.max_violation)[0] == o.t
+
+
+def test_dense_radius_and_mask():
+    inst = random_dense(91, 90, 17, 9, dtype=np.float64)
+    rng = np.random.default_rng(3)
+    vm = (rng.uniform(size=inst.n) < 0.5).astype(np.uint8)
+    for radius in (1, 2):
+        stepwise_check(inst, steps=2, radius=radius, var_mask=vm)
+        with dmmv().from_instance(inst, DEV, radius=radius, var_mask=T(vm)) as h:
+            res = dmmv().dmmv_solve(h, T(inst.x0), 30, trace=True)
+        check_single_trace(res, oracle_solve(inst, 30, radius=radius, var_mask=vm), 30)
+
+
+def test_dense_keep_going_reports_same_result():
+    inst = random_dense(5, 120, 10, 4, dtype=np.float64)
+    o = oracle_solve(inst, 60)
+    assert o.iters_done < 60
+    with dmmv().from_instance(inst, DEV, keep_going=True) as h:
+        res = dmmv().dmmv_solve(h, T(inst.x0), 60, trace=True)
+    check_single_trace(res, o, 60)
+
+
+def test_deterministic_repeat():
+    inst = random_dense(123, 500, 33, 16, dtype=np.float32)
+    outs = []
+    for _ in range(2):
+        with dmmv().from_instance(inst, DEV) as h:
+            res = dmmv().dmmv_solve(h, T(inst.x0), 50, trace=True)
+            outs.append((N(res.trace).copy(), N(res.trace_t).copy(), N(res.x).copy()))
+    for a, b in zip(outs[0], outs[1]):
+        assert np.array_equal(a, b)
+
+
+# ------------------------------------------------------------------------------ sparse
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("shape", [(1, 1, 2, 1.0), (20, 9, 3, 0.3), (33, 12, 3, 0.9),
+                                   (70, 40, 4, 0.1), (200, 150, 3, 0.05), (129, 31, 11, 0.2),
+                                   (2100, 64, 3, 0.02)])
+def test_sparse_stepwise(shape, dtype):
+    mm, nn, nd, dens = shape
+    stepwise_check(random_sparse(20 + mm, mm, nn, nd, density=dens, dtype=dtype), steps=3)
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_sparse_integer_ties_and_full_columns(seed):
+    """Dense-ish columns over few rows: columns that contain every listed top row force the
+    exact outside-the-column scan; integer data gives exact ties."""
+    inst = random_sparse(300 + seed, 45, 14, 3, density=0.85, dtype=np.float32, integer=True,
+                         explicit_zeros=True)
+    stepwise_check(inst, steps=4)
+    with dmmv().from_instance(inst, DEV) as h:
+        res = dmmv().dmmv_solve(h, T(inst.x0), 40, trace=True)
+    check_single_trace(res, oracle_solve(inst, 40), 40)
+
+
+def test_sparse_all_rows_in_one_column_beyond_list():
+    """m > list length and one column holding every row: no outside rows at all."""
+    mm, nn = 80, 3
+    rows = np.arange(mm)
+    rowptr = np.arange(mm + 1, dtype=np.int64)
+    col = np.zeros(mm, dtype=np.int32)
+    rng = np.random.default_rng(0)
+    inst = random_sparse(1, mm, nn, 3, density=0.0, dtype=np.float32)
+    inst.csr_rowptr, inst.csr_col = rowptr, col
+    inst.csr_val = rng.standard_normal(mm).astype(np.float32)
+    assert rows.size == inst.csr_val.size
+    stepwise_check(inst, steps=2)
+
+
+def test_sparse_solve_small_tomography():
+    inst = make_config(3, "small")
+    with dmmv().from_instance(inst, DEV) as h:
+        res = dmmv().dmmv_solve(h, T(inst.x0), inst.iters, trace=True)
+    o = oracle_solve(inst, inst.iters)
+    assert o.iters_done >= 10
+    check_single_trace(res, o, inst.iters)
+
+
+def test_sparse_unsorted_rows_and_errors():
+    m = dmmv()
+    inst = random_sparse(9, 30, 12, 3, density=0.4, dtype=np.float32)
+    # shuffle the entries inside each row: the result must not change (scores do not depend
+    # on the order; the residual follows the stored order, so compare tables for a given r)
+    rng = np.random.default_rng(1)
+    col, val = inst.csr_col.copy(), inst.csr_val.copy()
+    for i in range(inst.m):
+        a, b = inst.csr_rowptr[i], inst.csr_rowptr[i + 1]
+        p = rng.permutation(b - a)
+        col[a:b], val[a:b] = col[a:b][p], val[a:b][p]
+    r = oracle_residual(inst, inst.x0)
+    want = oracle_table(inst, inst.x0, r)
+    with m.Handle(D=inst.D, b=T(inst.b), csr=(T(inst.csr_rowptr), T(col), T(val)), m=inst.m,
+                  n=inst.n) as h:
+        m.dmmv_set_x(h, T(inst.x0))
+        m.dmmv_set_residual(h, T(r))
+        assert np.array_equal(N(m.dmmv_eval_moves(h)), want)
+    # duplicate entry
+    col2 = inst.csr_col.copy()
+    a, b = inst.csr_rowptr[0], inst.csr_rowptr[1]
+    row0 = next(i for i in range(inst.m) if inst.csr_rowptr[i + 1] - inst.csr_rowptr[i] >= 2)
+    a = inst.csr_rowptr[row0]
+    col2[a + 1] = col2[a]
+    with pytest.raises(m.DmmvError) as e:
+        m.Handle(D=inst.D, b=T(inst.b), csr=(T(inst.csr_rowptr), T(col2), T(inst.csr_val)),
+                 m=inst.m, n=inst.n)
+    assert e.value.status == -2
+    # column out of range
+    col3 = inst.csr_col.copy()
+    col3[0] = inst.n
+    with pytest.raises(m.DmmvError) as e:
+        m.Handle(D=inst.D, b=T(inst.b), csr=(T(inst.csr_rowptr), T(col3), T(inst.csr_val)),
+                 m=inst.m, n=inst.n)
+    assert e.value.status == -2
+
+
+# ------------------------------------------------------------------------------ batched
+def batched_check(inst, iters, **hopt):
+    m = dmmv()
+    o = oracle_solve(inst, iters, radius=hopt.get("radius", 0))
+    with m.from_instance(inst, DEV, **hopt) as h:
+        res = m.dmmv_solve(h, T(inst.x0), iters, trace=True)
+        assert np.array_equal(N(res.iters_done), o.iters_done)
+        tr = N(res.trace)
+        assert np.array_equal(tr[:, :, 0], o.trace_j) and np.array_equal(tr[:, :, 1], o.trace_k)
+        assert np.array_equal(N(res.trace_t), o.trace_t)
+        assert np.array_equal(N(res.x), o.x)
+        assert np.array_equal(N(res.max_violation), o.t)
+        # maintained residual vs fresh fp64 recomputation, and t == max |r|
+        x, r, t = m.dmmv_get_state(h)
+        r = N(r)
+        assert np.array_equal(np.abs(r).max(axis=1), N(t))
+        fresh = (inst.scale.astype(np.float64)[:, None] * o.x) @ inst.A.astype(np.float64).T - inst.b
+        scale_mag = np.abs(inst.b).max() + 1.0
+        assert np.abs(r - fresh).max() <= 1e-4 * scale_mag
+    return o
+
+
+@pytest.mark.parametrize("shape", [(1, 1, 1, 2), (17, 5, 3, 3), (64, 8, 64, 4), (100, 33, 65, 8),
+                                   (130, 70, 130, 16), (50, 19, 7, 21)])
+def test_batched_random(shape):
+    mm, nn, R, nd = shape
+    batched_check(random_batched(40 + mm, mm, nn, R, nd, dtype=np.float32), 12)
+
+
+def test_batched_f64_and_integer_ties():
+    batched_check(random_batched(8, 40, 12, 9, 5, dtype=np.float64), 10)
+    batched_check(random_batched(9, 30, 10, 70, 4, dtype=np.float32, integer=True), 15)
+
+
+def test_batched_stepwise_tables():
+    m = dmmv()
+    inst = random_batched(66, 75, 21, 67, 16, dtype=np.float32)
+    with m.from_instance(inst, DEV) as h:
+        m.dmmv_set_x(h, T(inst.x0))
+        r = N(m.dmmv_residual(h))
+        tab = N(m.dmmv_eval_moves(h))
+        mv, ms = m.dmmv_argmin_move(h, None)
+        mv_t, ms_t = m.dmmv_argmin_move(h, T(tab))
+        assert np.array_equal(N(mv), N(mv_t)) and np.array_equal(N(ms), N(ms_t))
+        for q in range(inst.R):
+            rq = orc.residual_dense(inst.A, inst.b[q], inst.D, inst.x0[q], scale=inst.scale[q])
+            assert np.array_equal(r[q], rq)
+            want = orc.eval_moves_dense(inst.A, inst.D, inst.x0[q], rq, scale=inst.scale[q])
+            assert np.array_equal(tab[q], want)
+            c, s = orc.argmin_move(want)
+            assert tuple(N(mv)[q]) == (c // inst.nd, c % inst.nd) and N(ms)[q] == s
+        # apply a different move per instance, some skipped
+        moves = N(mv).copy()
+        moves[::3, 0] = -1
+        m.dmmv_apply_move(h, T(moves))
+        x2, r2, t2 = m.dmmv_get_state(h)
+        for q in range(inst.R):
+            if moves[q, 0] < 0:
+                assert np.array_equal(N(r2)[q], r[q])
+                continue
+            xq, rq, tq = orc.apply_move_dense(inst.A, inst.D, inst.x0[q], r[q], moves[q, 0],
+                                              moves[q, 1], scale=inst.scale[q])
+            assert np.array_equal(N(r2)[q], rq) and N(t2)[q] == tq and np.array_equal(N(x2)[q], xq)
+
+
+def test_batched_radius():
+    batched_check(random_batched(12, 60, 14, 20, 8, dtype=np.float32), 10, radius=1)
+
+
+@pytest.mark.parametrize("idx", [4, 5])
+def test_batched_small_llm_configs(idx):
+    inst = make_config(idx, "small")
+    o = batched_check(inst, inst.iters)
+    assert o.iters_done.sum() > inst.R
+
+
+# ------------------------------------------------------------------------------ configs
+def test_config1_dense_toy_full():
+    inst = make_config(1)
+    with dmmv().from_instance(inst, DEV) as h:
+        res = dmmv().dmmv_solve(h, T(inst.x0), inst.iters, trace=True)
+        check_single_trace(res, oracle_solve(inst, inst.iters), inst.iters)
+        # a cold start gives a long trace on the same instance
+        rng = np.random.default_rng(0)
+        x0 = rng.choice(inst.D, size=inst.n)
+        res = dmmv().dmmv_solve(h, T(x0), inst.iters, trace=True)
+        o = oracle_solve(inst, inst.iters, x0=x0)
+        assert o.iters_done >= 10
+        check_single_trace(res, o, inst.iters)
+
+
+def test_config2_fir_small_and_full_prefix():
+    small = make_config(2, "small")
+    rng = np.random.default_rng(0)
+    x0 = rng.choice(small.D, size=small.n)
+    with dmmv().from_instance(small, DEV) as h:
+        res = dmmv().dmmv_solve(h, T(x0), small.iters, trace=True)
+    check_single_trace(res, oracle_solve(small, small.iters, x0=x0), small.iters)
+    inst = make_config(2)
+    with dmmv().from_instance(inst, DEV) as h:
+        res = dmmv().dmmv_solve(h, T(inst.x0), inst.iters, trace=True)
+        check_single_trace(res, oracle_solve(inst, inst.iters), inst.iters)
+        x0 = np.clip(inst.x0 + rng.integers(-40, 41, size=inst.n), inst.D[0], inst.D[-1])
+        res = dmmv().dmmv_solve(h, T(x0), 12, trace=True)
+        check_single_trace(res, oracle_solve(inst, 12, x0=x0), 12)
+
+
+# ------------------------------------------------------------------------------ edges / errors
+def test_empty_inputs():
+    m = dmmv()
+    D = np.array([0.0, 1.0])
+    # no variables
+    A = torch.zeros((5, 0), dtype=torch.float64, device=DEV)
+    b = T(np.arange(5, dtype=np.float64))
+    with m.Handle(A=A, b=b, D=D) as h:
+        res = m.dmmv_solve(h, torch.zeros(0, dtype=torch.float64, device=DEV), 5, trace=True)
+        assert int(res.iters_done[0]) == 0 and float(res.max_violation[0]) == 4.0
+        mv, ms = m.dmmv_argmin_move(h, None)
+        assert N(mv)[0, 0] == -1 and np.isinf(N(ms)[0])
+    # no rows
+    A = torch.zeros((0, 4), dtype=torch.float64, device=DEV)
+    with m.Handle(A=A, b=torch.zeros(0, dtype=torch.float64, device=DEV), D=D) as h:
+        x0 = T(np.array([0.0, 1.0, 1.0, 0.0]))
+        res = m.dmmv_solve(h, x0, 5, trace=True)
+        assert int(res.iters_done[0]) == 0 and float(res.max_violation[0]) == 0.0
+        m.dmmv_set_x(h, x0)
+        m.dmmv_residual(h)
+        assert np.all(N(m.dmmv_eval_moves(h)) == 0.0)
+    # zero iterations
+    inst = random_dense(1, 10, 4, 3)
+    with m.from_instance(inst, DEV) as h:
+        res = m.dmmv_solve(h, T(inst.x0), 0, trace=True)
+        assert int(res.iters_done[0]) == 0
+        assert float(res.max_violation[0]) == np.abs(oracle_residual(inst, inst.x0)).max()
+
+
+def test_error_paths():
+    m = dmmv()
+    inst = random_dense(2, 10, 4, 3)
+    with pytest.raises(m.DmmvError) as e:
+        m.Handle(A=T(inst.A), b=T(inst.b), D=inst.D[::-1].copy())
+    assert e.value.status == -4
+    with pytest.raises(m.DmmvError) as e:
+        m.Handle(A=T(inst.A), b=T(inst.b), D=inst.D[:1])
+    assert e.value.status == -4
+    with m.from_instance(inst, DEV) as h:
+        bad = inst.x0.copy()
+        bad[2] = 99.0
+        with pytest.raises(m.DmmvError) as e:
+            m.dmmv_set_x(h, T(bad))
+        assert e.value.status == -4
+        with pytest.raises(m.DmmvError) as e:
+            m.dmmv_eval_moves(h)            # no residual yet
+        assert e.value.status == -7
+        m.dmmv_set_x(h, T(inst.x0))
+        m.dmmv_residual(h)
+        with pytest.raises(m.DmmvError) as e:
+            m.dmmv_apply_move(h, T(np.array([[inst.n, 0]], dtype=np.int32)))
+        assert e.value.status == -2
+        # still usable afterwards
+        assert np.array_equal(N(m.dmmv_eval_moves(h)),
+                              oracle_table(inst, inst.x0, oracle_residual(inst, inst.x0)))
