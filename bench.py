@@ -1,0 +1,202 @@
+#!/usr/bin/env python3
+"""Benchmark of the DMMV single-move descent on one MI355X.
+
+One "step" is one full pass of the hot path over one workload: dmmv_solve from the
+configured starting point for the configured number of iterations (residual once, then per
+iteration: score every move, arg-min, apply).  The descent stalls at a local optimum long
+before the configured iteration count, so the timed solves run in fixed-work mode
+(keep_going): every iteration still scores all n*(|D|-1) moves of the current state and
+reduces them; iterations after the stall have no move left to apply.  Inputs are resident in
+HBM before the timed region starts.
+
+Prints ONE JSON line.  `value` = candidate moves evaluated per second over the whole timed
+region.  `roofline` describes the dominant kernel (the fused evaluation kernel that streams
+all of A), timed with HIP events on the library's stream.  `cpu_baseline` is the CPU oracle
+timed on a bounded sample of the same workload on this host.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0
+ALU_PEAK_TFLOPS = {"f32": 157.3, "f64": 78.6}
+FLOPS_PER_PAIR = 3          # multiply + add of the fma, and the max; |.| is an operand modifier
+
+
+def algorithmic_bytes_per_eval(inst) -> float:
+    """Bytes one evaluation launch must move ("Algorithmic bytes")."""
+    w = inst.dtype.itemsize
+    if inst.kind == "csr":
+        return inst.nnz * (w + 4) + (inst.n + 1) * 8 + inst.m * w + inst.n * 4
+    if inst.kind == "batched":
+        return inst.m * inst.n * w + inst.R * inst.m * w + inst.R * inst.n * 4
+    return inst.m * inst.n * w + inst.m * w + inst.n * 4
+
+
+def pairs_per_eval(inst) -> float:
+    """(row, move) pairs of one evaluation, non-null moves only."""
+    rows = inst.nnz / inst.n if inst.kind == "csr" else inst.m
+    return float(inst.R) * inst.n * (inst.nd - 1) * rows
+
+
+def roofline_for(inst, eval_ms: float) -> dict:
+    dt = "f64" if inst.dtype == np.float64 else "f32"
+    if inst.kind == "csr":
+        b = algorithmic_bytes_per_eval(inst)
+        ach = b / (eval_ms * 1e-3) / 1e9
+        return {"bound": "hbm", "kernel": "k_eval_csc", "achieved": ach, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None,
+                "algorithmic_bytes_per_launch": b, "avg_launch_ms": eval_ms}
+    flops = pairs_per_eval(inst) * FLOPS_PER_PAIR
+    ach = flops / (eval_ms * 1e-3) / 1e12
+    peak = ALU_PEAK_TFLOPS[dt]
+    return {"bound": "alu", "kernel": "k_eval_batched" if inst.kind == "batched" else "k_eval_dense",
+            "achieved": ach, "peak": peak, "unit": "TFLOP/s", "frac": ach / peak, "traffic": None,
+            "flops_per_launch": flops, "avg_launch_ms": eval_ms,
+            "hbm_GBs_algorithmic": algorithmic_bytes_per_eval(inst) / (eval_ms * 1e-3) / 1e9}
+
+
+def cpu_baseline(inst, budget_s: float) -> dict:
+    """The oracle as it stands, on a bounded sample of the workload."""
+    from oracle import oracle as orc
+
+    cores = len(os.sched_getaffinity(0))
+    if inst.kind == "batched":
+        # a few instances, a few iterations, all host threads (instances are independent)
+        threads = orc.num_threads()
+        rows = min(inst.R, max(threads, 16))
+        est_pair_rate = 4.0e8                       # pairs/s/thread, only to size the sample
+        per_row_iter = inst.m * inst.n * inst.nd
+        iters = int(max(1, min(inst.iters, budget_s * est_pair_rate * threads / (rows * per_row_iter))))
+        sel = np.linspace(0, inst.R - 1, rows).astype(np.int64)
+        t0 = time.perf_counter()
+        res = orc.solve_batched(inst.A, inst.b[sel], inst.D, inst.scale[sel], inst.x0[sel], iters)
+        dt = time.perf_counter() - t0
+        evals = int(np.minimum(res.iters_done + 1, iters).sum())
+        moves = evals * inst.n * (inst.nd - 1)
+        return {"value": moves / dt, "unit": "moves/s", "cores": threads, "kind": "oracle",
+                "sample": f"{rows} of {inst.R} instances x up to {iters} iterations "
+                          f"({evals} evaluations), {dt:.1f} s", "host_cores_visible": cores}
+    per_iter = inst.nnz * inst.nd
+    iters = int(max(1, min(inst.iters, budget_s * 2.5e8 / max(per_iter, 1))))
+    t0 = time.perf_counter()
+    if inst.kind == "csr":
+        res = orc.solve_csr(inst.m, inst.n, inst.csr_rowptr, inst.csr_col, inst.csr_val, inst.b,
+                            inst.D, inst.x0, iters)
+    else:
+        res = orc.solve_dense(inst.A, inst.b, inst.D, inst.x0, iters)
+    dt = time.perf_counter() - t0
+    evals = min(res.iters_done + 1, iters)
+    moves = evals * inst.n * (inst.nd - 1)
+    return {"value": moves / dt, "unit": "moves/s", "cores": 1, "kind": "oracle",
+            "sample": f"{evals} evaluations from the configured start (of {inst.iters}), {dt:.1f} s",
+            "host_cores_visible": cores}
+
+
+def run_config(idx: int, steps: int, warmup: int, iters_override, device: str, do_cpu: bool,
+               cpu_budget: float) -> dict:
+    import torch
+    from paper_2508_13437_amd import dmmv
+    from workloads import make_config
+
+    t_gen = time.perf_counter()
+    inst = make_config(idx)
+    t_gen = time.perf_counter() - t_gen
+    iters = int(iters_override) if iters_override else inst.iters
+    x0 = torch.from_numpy(np.ascontiguousarray(inst.x0)).to(device)
+    out = {}
+    # how far does the real descent get (normal mode, stops at the local optimum)?
+    with dmmv.from_instance(inst, device) as h:
+        res = dmmv.dmmv_solve(h, x0, iters)
+        improving = res.iters_done.cpu().numpy().astype(np.int64)
+        t_final = res.max_violation.cpu().numpy().astype(np.float64)
+    # timed: fixed-work mode
+    with dmmv.from_instance(inst, device, keep_going=True, poll_every=0) as h:
+        for _ in range(warmup):
+            dmmv.dmmv_solve(h, x0, iters)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            dmmv.dmmv_solve(h, x0, iters)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        reps = max(3, min(200, int(0.5 / max(dt / (steps * iters), 1e-6))))
+        eval_ms = dmmv.dmmv_time_eval(h, reps) / reps
+    moves = float(steps) * iters * inst.moves_per_iter()
+    out.update({
+        "workload": inst.name, "kind": inst.kind, "m": inst.m, "n": inst.n, "nd": inst.nd,
+        "R": inst.R, "nnz": inst.nnz, "iters_per_step": iters,
+        "moves_per_sec": moves / dt, "iters_per_sec": steps * iters / dt,
+        "instance_iters_per_sec": steps * iters * inst.R / dt,
+        "ms_per_step": dt / steps * 1e3, "us_per_iter": dt / (steps * iters) * 1e6,
+        "improving_moves_applied": int(improving.sum()),
+        "final_max_violation": float(t_final.max()),
+        "dtype": "f64" if inst.dtype == np.float64 else "f32",
+        "roofline": roofline_for(inst, eval_ms), "input_gen_s": round(t_gen, 2),
+    })
+    if do_cpu:
+        out["cpu_baseline"] = cpu_baseline(inst, cpu_budget)
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", type=int, default=3, help="headline workload (1..5)")
+    ap.add_argument("--iters", type=int, default=None, help="override iterations per step")
+    ap.add_argument("--others", type=str, default="",
+                    help="comma list of further configs to report in the same line, e.g. 1,2,4")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-budget", type=float, default=15.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    device = "cuda:0"
+    default_steps = {1: 20, 2: 10, 3: 5, 4: 1, 5: 1}
+    steps = args.steps if args.steps is not None else default_steps[args.config]
+    head = run_config(args.config, steps, args.warmup, args.iters, device,
+                      not args.no_cpu_baseline, args.cpu_budget)
+    line = {
+        "metric": "candidate_moves_evaluated_per_sec", "value": head["moves_per_sec"],
+        "unit": "moves/s", "n_gpus": 1, "steps": steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": head["dtype"], "data": "synthetic",
+        "config": {"workload": head["workload"], "m": head["m"], "n": head["n"], "nd": head["nd"],
+                   "R": head["R"], "nnz": head["nnz"], "iters_per_step": head["iters_per_step"],
+                   "mode": "fixed-work (keep_going): every iteration scores all moves"},
+        "iters_per_sec": head["iters_per_sec"], "us_per_iter": head["us_per_iter"],
+        "improving_moves_applied": head["improving_moves_applied"],
+        "final_max_violation": head["final_max_violation"],
+        "roofline": head["roofline"],
+    }
+    if "cpu_baseline" in head:
+        line["cpu_baseline"] = head["cpu_baseline"]
+    others = [int(v) for v in args.others.split(",") if v.strip()]
+    if others:
+        line["other_workloads"] = []
+        for idx in others:
+            o = run_config(idx, default_steps[idx], 1 if idx < 4 else 0, None, device, False, 0)
+            line["other_workloads"].append(o)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

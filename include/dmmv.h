@@ -165,6 +165,13 @@ dmmv_status dmmv_solve(dmmv_handle h, const void* x0, int32_t iters, void* x_out
                        void* max_violation_out, int32_t* iters_done, dmmv_move* trace,
                        void* trace_t);
 
+/* Measurement hook: enqueue the fused evaluation kernel of the descent (the kernel that
+ * streams all of A: the "evaluate all candidates in bulk" step of the paper's section
+ * "GPU Acceleration") `reps` times back to back between two HIP events on the handle's
+ * stream and return the elapsed time in milliseconds in *ms_out (HOST).  The state is not
+ * changed.  Needs a residual.  Waits for the stream. */
+dmmv_status dmmv_time_eval(dmmv_handle h, int32_t reps, float* ms_out);
+
 /* Message of the last failure on this thread (static storage, HOST). */
 const char* dmmv_last_error(void);
 

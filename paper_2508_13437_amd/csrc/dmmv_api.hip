@@ -692,4 +692,31 @@ dmmv_status dmmv_solve(dmmv_handle h, const void* x0, int32_t iters, void* x_out
                : solve_t<float>(h, x0, iters, x_out, max_violation_out, iters_done, trace, trace_t);
 }
 
+dmmv_status dmmv_time_eval(dmmv_handle h, int32_t reps, float* ms_out) {
+    if (!h) return fail(DMMV_ERR_NULL, "handle is NULL");
+    if (!ms_out) return fail(DMMV_ERR_NULL, "ms_out is NULL");
+    if (reps < 1) return fail(DMMV_ERR_SHAPE, "reps must be >= 1");
+    if (!h->r_valid) return fail(DMMV_ERR_STATE, "dmmv_time_eval needs a residual");
+    if (h->p.dtype == DMMV_F64)
+        hipLaunchKernelGGL(k_clear_done<double>, grid1(h->p.R, 256), dim3(256), 0, h->stream, (InstState<double>*)h->state, h->p.R);
+    else
+        hipLaunchKernelGGL(k_clear_done<float>, grid1(h->p.R, 256), dim3(256), 0, h->stream, (InstState<float>*)h->state, h->p.R);
+    if (h->kind == KIND_CSC && !h->topk_valid) { DMMV_TRY(csc_refresh_topk(h)); h->topk_valid = true; }
+    hipEvent_t e0, e1;
+    DMMV_HIP_CHECK(hipEventCreate(&e0));
+    DMMV_HIP_CHECK(hipEventCreate(&e1));
+    dmmv_status st = eval_any(h, nullptr, true);       // warm-up launch, not timed
+    if (st == DMMV_OK) {
+        (void)hipEventRecord(e0, h->stream);
+        for (int32_t q = 0; q < reps && st == DMMV_OK; ++q) st = eval_any(h, nullptr, true);
+        (void)hipEventRecord(e1, h->stream);
+        hipError_t e = hipEventSynchronize(e1);
+        if (e != hipSuccess) st = fail(DMMV_ERR_HIP, "hipEventSynchronize failed: %s", hipGetErrorString(e));
+        else (void)hipEventElapsedTime(ms_out, e0, e1);
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    return st;
+}
+
 }  // extern "C"

@@ -26,7 +26,8 @@ STATUS_NAMES = {0: "DMMV_OK", -1: "DMMV_ERR_NULL", -2: "DMMV_ERR_SHAPE", -3: "DM
 
 EXPORTS = ("dmmv_workspace_bytes", "dmmv_create", "dmmv_destroy", "dmmv_set_x",
            "dmmv_set_residual", "dmmv_residual", "dmmv_eval_moves", "dmmv_argmin_move",
-           "dmmv_apply_move", "dmmv_get_state", "dmmv_solve", "dmmv_last_error", "dmmv_version")
+           "dmmv_apply_move", "dmmv_get_state", "dmmv_solve", "dmmv_time_eval", "dmmv_last_error",
+           "dmmv_version")
 
 
 class DmmvError(RuntimeError):
@@ -75,6 +76,8 @@ def load() -> C.CDLL:
     lib.dmmv_solve.restype = C.c_int
     lib.dmmv_solve.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
                                C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.dmmv_time_eval.restype = C.c_int
+    lib.dmmv_time_eval.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_float)]
     lib.dmmv_last_error.restype = C.c_char_p
     lib.dmmv_version.restype = C.c_char_p
     _lib = lib
@@ -297,6 +300,13 @@ def dmmv_solve(h: Handle, x0: Optional[torch.Tensor], iters: int, trace: bool = 
     if trace and iters == 0:
         tr, tt = tr[:, :0], tt[:, :0]
     return SolveResult(x, t, done, tr, tt)
+
+
+def dmmv_time_eval(h: Handle, reps: int) -> float:
+    """Milliseconds for `reps` back-to-back launches of the fused evaluation kernel."""
+    ms = C.c_float(0.0)
+    _check(load().dmmv_time_eval(h._h, C.c_int32(reps), C.byref(ms)))
+    return float(ms.value)
 
 
 def dmmv_version() -> str:
