@@ -98,7 +98,9 @@ typedef struct {
     int32_t poll_every;      /* dmmv_solve: every poll_every iterations the host waits for the
                                 stream and stops enqueueing once every instance has stopped;
                                 0 = never wait inside the loop                              */
-    int32_t reserved;
+    int32_t sparse_partition_rows; /* sparse matrices: rows per LDS-resident partition of r;
+                                0 = automatic (as many as fit 128 KiB, at most 65536).  A tuning
+                                and testing knob: results do not depend on it              */
     const uint8_t* var_mask; /* [R][n] nonzero = variable may move (greedy repair works on the
                                 unassigned variables only); NULL = all                      */
 } dmmv_options;

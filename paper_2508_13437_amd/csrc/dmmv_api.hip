@@ -74,19 +74,33 @@ size_t workspace_layout(const dmmv_problem& p, const dmmv_options& o, Ctx* c, ch
     c->red_elems = 1024;
     b.take(&c->red, (size_t)c->red_elems * esz);
     if (sparse) {
-        c->n_partials = ceil_div(p.n, CSC_COLS_PER_BLOCK);
-        b.take(&c->partials, (size_t)(c->n_partials > 0 ? c->n_partials : 1) * part_sz);
-        b.take(&c->colptr, (size_t)(p.n + 1) * sizeof(int64_t));
-        b.take(&c->fillpos, (size_t)(p.n + 1) * sizeof(int64_t));
-        b.take(&c->rowidx, (size_t)p.nnz * sizeof(int32_t));
-        b.take(&c->cval, (size_t)p.nnz * esz);
-        b.take(&c->rowidx_tmp, (size_t)p.nnz * sizeof(int32_t));
-        b.take(&c->cval_tmp, (size_t)p.nnz * esz);
-        c->topk_groups = ceil_div(p.m > 0 ? p.m : 1, TOPK_GROUP);
-        b.take(&c->topk_val, (size_t)TOPK * esz);
-        b.take(&c->topk_row, (size_t)TOPK * sizeof(int32_t));
-        b.take(&c->topk_sval, (size_t)c->topk_groups * TOPK * esz);
-        b.take(&c->topk_srow, (size_t)c->topk_groups * TOPK * sizeof(int32_t));
+        // rows per partition: what fits the LDS budget, addressable by a 16-bit offset
+        int64_t mp = o.sparse_partition_rows > 0 ? o.sparse_partition_rows : (int64_t)(CSC_LDS_BYTES / esz);
+        if (mp > 65535) mp = 65535;          // offset mp itself marks a pad
+        if (mp * (int64_t)esz > CSC_LDS_BYTES) mp = CSC_LDS_BYTES / esz;
+        c->csc_mp = (int32_t)mp;
+        c->csc_P = (int32_t)(p.m > 0 ? ceil_div(p.m, mp) : 1);
+        int64_t gb = 512;                    // two workgroups per compute unit
+        if (gb > ceil_div(p.n, 16)) gb = ceil_div(p.n, 16);
+        if (gb < 1) gb = 1;
+        c->csc_gb = (int32_t)gb;
+        const int64_t nseg = (int64_t)c->csc_P * p.n;
+        c->csc_nnzp = p.nnz + 3 * nseg + 4;  // padding bound, plus spare entries for clamped loads
+        c->n_partials = gb;
+        b.take(&c->partials, (size_t)c->n_partials * part_sz);
+        b.take(&c->segptr, (size_t)(nseg + 1) * sizeof(int32_t));
+        b.take(&c->fillpos, (size_t)(nseg + 1) * sizeof(int32_t));
+        b.take(&c->row16, (size_t)c->csc_nnzp * sizeof(uint16_t));
+        b.take(&c->cval, (size_t)c->csc_nnzp * esz);
+        b.take(&c->row16_tmp, (size_t)c->csc_nnzp * sizeof(uint16_t));
+        b.take(&c->cval_tmp, (size_t)c->csc_nnzp * esz);
+        b.take(&c->blk_lo, (size_t)(gb + 1) * sizeof(int32_t));
+        b.take(&c->colmax, (size_t)p.n * p.nd * esz);
+        b.take(&c->colmask, (size_t)p.n * sizeof(uint32_t));
+        b.take(&c->res_val, (size_t)RES_CAP * esz);
+        b.take(&c->res_row, (size_t)RES_CAP * sizeof(int32_t));
+        b.take(&c->res_meta, 4 * sizeof(int32_t));
+        b.take(&c->res_floor, esz);
     } else if (batched) {
         c->chunk_cols = batched_chunk_cols(p);
         c->n_partials = ceil_div(p.n, c->chunk_cols);
@@ -126,6 +140,9 @@ static dmmv_status validate_problem(const dmmv_problem* p) {
         if (p->nnz < 0 || p->nnz > INT32_MAX - 1) return fail(DMMV_ERR_SHAPE, "nnz must be in [0, 2^31-2]");
         if (p->nnz > 0 && (!p->csr_col || !p->csr_val)) return fail(DMMV_ERR_NULL, "csr_col / csr_val is NULL");
         if (p->R != 1 || p->scale) return fail(DMMV_ERR_UNSUPPORTED, "sparse matrices support a single unscaled instance (R = 1, scale = NULL)");
+        // every (row partition, column) segment is padded to a multiple of four entries
+        const int64_t parts = p->m / 16384 + 1;
+        if (p->nnz + 3 * parts * p->n > INT32_MAX - 1) return fail(DMMV_ERR_UNSUPPORTED, "sparse matrix too large for 32-bit segment offsets");
     }
     if (p->m > 0 && !p->b) return fail(DMMV_ERR_NULL, "b is NULL");
     if (p->scale) {
@@ -369,9 +386,10 @@ static dmmv_status maxabs_single(Ctx* c) {
 }
 
 // t = max |r| into the state, whatever the kind
+// (sparse: also rebuilds the reservoir of the rows of largest |r|)
 static dmmv_status refresh_t(Ctx* c) {
     if (c->kind == KIND_BATCHED) return batched_maxabs(c);
-    if (c->kind == KIND_CSC) return csc_refresh_topk(c);
+    if (c->kind == KIND_CSC) DMMV_TRY(csc_reservoir(c));
     return c->p.dtype == DMMV_F64 ? maxabs_single<double>(c) : maxabs_single<float>(c);
 }
 
@@ -397,24 +415,29 @@ static dmmv_status launch_select(Ctx* c, dmmv_move* best_out, void* best_score_o
                                   : select_t<float>(c, best_out, best_score_out);
 }
 
-static dmmv_status eval_any(Ctx* c, void* scores_out, bool want_partials) {
+static dmmv_status eval_any(Ctx* c, void* scores_out, bool want_partials, bool honor_done) {
     if (c->p.n == 0) return DMMV_OK;
     switch (c->kind) {
         case KIND_DENSE: return dense_eval(c, scores_out, want_partials);
         case KIND_CSC:
-            if (!c->topk_valid) DMMV_TRY(csc_refresh_topk(c));
-            return csc_eval(c, scores_out, want_partials);
+            return csc_eval(c, scores_out, want_partials, honor_done);
         default: return batched_eval(c, scores_out, want_partials);
     }
 }
 
 static dmmv_status apply_any(Ctx* c, bool t_from_score, int32_t iters, dmmv_move* trace, void* trace_t) {
-    c->topk_valid = false;
     switch (c->kind) {
         case KIND_DENSE: return dense_apply(c, t_from_score, iters, trace, trace_t);
-        case KIND_CSC: return csc_apply(c, t_from_score, iters, trace, trace_t);
+        case KIND_CSC: return csc_apply(c);   // staged moves only; the loop uses csc_select_apply
         default: return batched_apply(c, t_from_score, iters, trace, trace_t);
     }
+}
+
+// one loop step after the evaluation: pick the best move and apply it if it improves
+static dmmv_status select_apply_any(Ctx* c, int32_t iters, dmmv_move* trace, void* trace_t) {
+    if (c->kind == KIND_CSC) return csc_select_apply(c, iters, trace, trace_t);
+    DMMV_TRY(launch_select(c, nullptr, nullptr));
+    return apply_any(c, true, iters, trace, trace_t);
 }
 
 static dmmv_status residual_any(Ctx* c) {
@@ -423,9 +446,7 @@ static dmmv_status residual_any(Ctx* c) {
         case KIND_CSC: DMMV_TRY(csc_residual(c)); break;
         default: DMMV_TRY(batched_residual(c)); break;
     }
-    c->topk_valid = false;
     DMMV_TRY(refresh_t(c));
-    if (c->kind == KIND_CSC) c->topk_valid = true;
     c->r_valid = true;
     return DMMV_OK;
 }
@@ -467,10 +488,8 @@ static dmmv_status solve_t(dmmv_ctx* c, const void* x0, int32_t iters, void* x_o
         hipLaunchKernelGGL(k_fill_trace<T>, grid1(R * (int64_t)iters, 256), dim3(256), 0, c->stream, trace, (T*)trace_t, R * (int64_t)iters);
     const int32_t poll = c->o.keep_going ? 0 : c->o.poll_every;
     for (int32_t it = 0; it < iters; ++it) {
-        DMMV_TRY(eval_any(c, nullptr, true));
-        DMMV_TRY(launch_select(c, nullptr, nullptr));
-        DMMV_TRY(apply_any(c, true, iters, trace, trace_t));
-        if (c->kind == KIND_CSC) { DMMV_TRY(csc_refresh_topk(c)); c->topk_valid = true; }
+        DMMV_TRY(eval_any(c, nullptr, true, true));
+        DMMV_TRY(select_apply_any(c, iters, trace, trace_t));
         if (poll > 0 && (it + 1) % poll == 0 && it + 1 < iters) {
             int32_t active = 0;
             hipLaunchKernelGGL(k_zero_flags, dim3(1), dim3(64), 0, c->stream, c->flags);
@@ -514,7 +533,8 @@ dmmv_status dmmv_create(dmmv_handle* out, const dmmv_problem* problem, const dmm
     dmmv_options o{};
     o.poll_every = 64;
     if (options) o = *options;
-    if (o.radius < 0 || o.poll_every < 0) return fail(DMMV_ERR_SHAPE, "options: radius and poll_every must be >= 0");
+    if (o.radius < 0 || o.poll_every < 0 || o.sparse_partition_rows < 0)
+        return fail(DMMV_ERR_SHAPE, "options: radius, poll_every and sparse_partition_rows must be >= 0");
     const size_t need = workspace_layout(*problem, o, nullptr, nullptr);
     if (!workspace) return fail(DMMV_ERR_WORKSPACE, "workspace is NULL (%zu bytes needed)", need);
     if (((uintptr_t)workspace & 255) != 0) return fail(DMMV_ERR_WORKSPACE, "workspace must be 256-byte aligned");
@@ -528,7 +548,7 @@ dmmv_status dmmv_create(dmmv_handle* out, const dmmv_problem* problem, const dmm
     c->esz = problem->dtype == DMMV_F64 ? 8 : 4;
     const bool sparse = problem->csr_rowptr != nullptr;
     c->kind = sparse ? KIND_CSC : ((problem->R > 1 || problem->scale) ? KIND_BATCHED : KIND_DENSE);
-    c->x_set = c->r_valid = c->topk_valid = false;
+    c->x_set = c->r_valid = false;
     workspace_layout(*problem, o, c, (char*)workspace);
     c->p.D = nullptr;       // host arrays are copied below and not referenced afterwards
     c->p.scale = nullptr;
@@ -590,9 +610,7 @@ dmmv_status dmmv_set_residual(dmmv_handle h, const void* r) {
         if (h->kind == KIND_BATCHED) DMMV_TRY(batched_set_r(h, r));
         else DMMV_HIP_CHECK(hipMemcpyAsync(h->r, r, (size_t)h->p.m * h->esz, hipMemcpyDeviceToDevice, h->stream));
     }
-    h->topk_valid = false;
     DMMV_TRY(refresh_t(h));
-    if (h->kind == KIND_CSC) h->topk_valid = true;
     h->r_valid = true;
     return DMMV_OK;
 }
@@ -609,7 +627,7 @@ dmmv_status dmmv_eval_moves(dmmv_handle h, void* scores_out) {
     if (!h) return fail(DMMV_ERR_NULL, "handle is NULL");
     if (!scores_out && h->p.n > 0) return fail(DMMV_ERR_NULL, "scores_out is NULL");
     if (!h->r_valid) return fail(DMMV_ERR_STATE, "dmmv_eval_moves needs a residual (call dmmv_residual or dmmv_set_residual)");
-    return eval_any(h, scores_out, false);
+    return eval_any(h, scores_out, false, false);
 }
 
 dmmv_status dmmv_argmin_move(dmmv_handle h, const void* scores, dmmv_move* best, void* best_score) {
@@ -631,7 +649,7 @@ dmmv_status dmmv_argmin_move(dmmv_handle h, const void* scores, dmmv_move* best,
         hipLaunchKernelGGL(k_clear_done<double>, grid1(h->p.R, 256), dim3(256), 0, h->stream, (InstState<double>*)h->state, h->p.R);
     else
         hipLaunchKernelGGL(k_clear_done<float>, grid1(h->p.R, 256), dim3(256), 0, h->stream, (InstState<float>*)h->state, h->p.R);
-    dmmv_status st = eval_any(h, nullptr, true);
+    dmmv_status st = eval_any(h, nullptr, true, false);
     if (st == DMMV_OK) st = launch_select(h, best, best_score);
     h->o.keep_going = keep;
     return st;
@@ -651,7 +669,6 @@ dmmv_status dmmv_apply_move(dmmv_handle h, const dmmv_move* moves) {
     DMMV_TRY(check_device_errors(h));
     DMMV_TRY(apply_any(h, false, 0, nullptr, nullptr));
     DMMV_TRY(refresh_t(h));
-    if (h->kind == KIND_CSC) h->topk_valid = true;
     return DMMV_OK;
 }
 
@@ -701,14 +718,14 @@ dmmv_status dmmv_time_eval(dmmv_handle h, int32_t reps, float* ms_out) {
         hipLaunchKernelGGL(k_clear_done<double>, grid1(h->p.R, 256), dim3(256), 0, h->stream, (InstState<double>*)h->state, h->p.R);
     else
         hipLaunchKernelGGL(k_clear_done<float>, grid1(h->p.R, 256), dim3(256), 0, h->stream, (InstState<float>*)h->state, h->p.R);
-    if (h->kind == KIND_CSC && !h->topk_valid) { DMMV_TRY(csc_refresh_topk(h)); h->topk_valid = true; }
     hipEvent_t e0, e1;
     DMMV_HIP_CHECK(hipEventCreate(&e0));
     DMMV_HIP_CHECK(hipEventCreate(&e1));
-    dmmv_status st = eval_any(h, nullptr, true);       // warm-up launch, not timed
+    auto once = [&]() { return eval_any(h, nullptr, true, false); };
+    dmmv_status st = h->p.n > 0 ? once() : DMMV_OK;       // warm-up launch, not timed
     if (st == DMMV_OK) {
         (void)hipEventRecord(e0, h->stream);
-        for (int32_t q = 0; q < reps && st == DMMV_OK; ++q) st = eval_any(h, nullptr, true);
+        for (int32_t q = 0; q < reps && st == DMMV_OK && h->p.n > 0; ++q) st = once();
         (void)hipEventRecord(e1, h->stream);
         hipError_t e = hipEventSynchronize(e1);
         if (e != hipSuccess) st = fail(DMMV_ERR_HIP, "hipEventSynchronize failed: %s", hipGetErrorString(e));

@@ -36,8 +36,10 @@ dmmv_status fail(dmmv_status st, const char* fmt, ...);
 // ----------------------------------------------------------------------------------------
 enum Kind { KIND_DENSE = 0, KIND_CSC = 1, KIND_BATCHED = 2 };
 
-constexpr int TOPK = 32;          // rows of largest |r| tracked by the sparse path
-constexpr int TOPK_GROUP = 2048;  // rows per stage-1 group of the top-K selection
+// sparse path: reservoir of the rows of largest |r|
+constexpr int RES_CAP = 128;      // capacity
+constexpr int RES_MIN = 16;       // rebuild when fewer entries remain
+constexpr int RES_FAST = 8;       // entries checked inline while streaming (one mask bit each)
 
 // Per-instance loop state kept on the device.
 template <class T>
@@ -69,7 +71,7 @@ struct Ctx {
     hipStream_t stream;
     Kind kind;
     size_t esz;
-    bool x_set, r_valid, topk_valid;
+    bool x_set, r_valid;
 
     // ---- carved from the caller's workspace (device) ----
     void* D_dev;          // T[nd]
@@ -83,18 +85,22 @@ struct Ctx {
     void* red;            // T[red_elems] partial maxima of the max-|r| reduction
     int64_t red_elems;
 
-    // sparse
-    int64_t* colptr;      // [n+1]
-    int32_t* rowidx;      // [nnz] rows ascending inside a column
-    void* cval;           // T[nnz]
-    int64_t* fillpos;     // [n] build scratch
-    int32_t* rowidx_tmp;  // [nnz] build scratch
-    void* cval_tmp;       // T[nnz] build scratch
-    void* topk_val;       // T[TOPK] largest |r|, descending (ties: lower row first)
-    int32_t* topk_row;    // [TOPK]
-    void* topk_sval;      // T[groups*TOPK] stage-1 candidates
-    int32_t* topk_srow;   // [groups*TOPK]
-    int64_t topk_groups;
+    // sparse: rows cut into csc_P partitions of csc_mp rows; segment s = p*n + j
+    int32_t csc_P, csc_mp, csc_gb;  // partitions, rows per partition, evaluation workgroups
+    int64_t csc_nnzp;     // stored entries including segment padding (upper bound)
+    int32_t* segptr;      // [P*n + 1] padded start of every segment
+    uint16_t* row16;      // [nnzp] row offset inside the partition (pad = csc_mp)
+    void* cval;           // T[nnzp]
+    int32_t* fillpos;     // [P*n + 1] build scratch: end of the real entries of a segment
+    uint16_t* row16_tmp;  // [nnzp] build scratch
+    void* cval_tmp;       // T[nnzp] build scratch
+    int32_t* blk_lo;      // [csc_gb + 1] first column of every evaluation workgroup
+    void* colmax;         // T[n*nd] per-column maxima carried across partitions
+    uint32_t* colmask;    // [n] reservoir rows met by the column
+    void* res_val;        // T[RES_CAP] reservoir: largest |r|, sorted
+    int32_t* res_row;     // [RES_CAP]
+    int32_t* res_meta;    // [4] count, floor row
+    void* res_floor;      // T[1] floor value
 
     // batched
     void* Xt;             // T[m][n] row-major copy of X
@@ -117,8 +123,13 @@ static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 // values of D scored per workgroup by the dense evaluation kernel
 static inline int dense_ktile(int32_t nd) { return nd >= 16 ? 16 : (nd >= 8 ? 8 : 4); }
-// columns per workgroup of the sparse evaluation kernel
-constexpr int CSC_COLS_PER_BLOCK = 16;
+// columns per workgroup of the sparse finalize kernel (one arg-min record each)
+constexpr int CSC_FIN_BLOCK = 256;
+// bytes of LDS a sparse evaluation workgroup may use for its partition of r
+// (64 KiB: two workgroups share a compute unit's 160 KiB, so one can stage while the other
+// streams)
+constexpr int CSC_LDS_BYTES = 64 * 1024;
+constexpr int CSC_MAX_PARTITIONS = 1024;
 
 // ----------------------------------------------------------------------------------------
 // per-path entry points (all enqueue on c->stream)
@@ -129,9 +140,10 @@ dmmv_status dense_apply(Ctx* c, bool t_from_score, int32_t iters, dmmv_move* tra
 
 dmmv_status csc_build(Ctx* c);
 dmmv_status csc_residual(Ctx* c);
-dmmv_status csc_refresh_topk(Ctx* c);   // also sets state.t = largest |r|
-dmmv_status csc_eval(Ctx* c, void* scores_out, bool want_partials);
-dmmv_status csc_apply(Ctx* c, bool t_from_score, int32_t iters, dmmv_move* trace, void* trace_t);
+dmmv_status csc_reservoir(Ctx* c);      // rebuild the reservoir of largest |r| from r
+dmmv_status csc_eval(Ctx* c, void* scores_out, bool want_partials, bool honor_done);
+dmmv_status csc_apply(Ctx* c);          // staged move only; caller refreshes t and the reservoir
+dmmv_status csc_select_apply(Ctx* c, int32_t iters, dmmv_move* trace, void* trace_t);
 
 dmmv_status batched_build(Ctx* c);
 dmmv_status batched_residual(Ctx* c);

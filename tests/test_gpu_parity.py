@@ -66,7 +66,10 @@ def stepwise_check(inst, steps=4, **opt):
     """Every entry point against the oracle, a few moves deep."""
     m = dmmv()
     vm = opt.get("var_mask")
-    hopt = dict(radius=opt.get("radius", 0))
+    hopt = dict(radius=opt.pop("radius", 0))
+    opt["radius"] = hopt["radius"]
+    if "sparse_partition_rows" in opt:
+        hopt["sparse_partition_rows"] = opt.pop("sparse_partition_rows")
     if vm is not None:
         hopt["var_mask"] = T(vm)
     with m.from_instance(inst, DEV, **hopt) as h:
@@ -177,6 +180,28 @@ def test_sparse_stepwise(shape, dtype):
     stepwise_check(random_sparse(20 + mm, mm, nn, nd, density=dens, dtype=dtype), steps=3)
 
 
+@pytest.mark.parametrize("rows", [1, 7, 64, 1000])
+def test_sparse_row_partitions(rows):
+    """Several LDS partitions of r (forced small): results must not depend on the cut."""
+    inst = random_sparse(555, 150, 60, 4, density=0.2, dtype=np.float32)
+    stepwise_check(inst, steps=3, sparse_partition_rows=rows)
+    inst = random_sparse(556, 90, 25, 3, density=0.5, dtype=np.float64, integer=True)
+    stepwise_check(inst, steps=3, sparse_partition_rows=rows)
+    with dmmv().from_instance(inst, DEV, sparse_partition_rows=rows) as h:
+        res = dmmv().dmmv_solve(h, T(inst.x0), 30, trace=True)
+    check_single_trace(res, oracle_solve(inst, 30), 30)
+
+
+def test_sparse_long_columns_and_many_groups():
+    """Columns longer than two wavefront loads, and more rows than one top-K group."""
+    inst = random_sparse(557, 5000, 20, 3, density=0.3, dtype=np.float32)
+    stepwise_check(inst, steps=2)
+    stepwise_check(inst, steps=2, sparse_partition_rows=700)
+    # more than 32 groups: the candidate list needs a reduction pass before the merge
+    inst = random_sparse(558, 70000, 12, 3, density=0.01, dtype=np.float32)
+    stepwise_check(inst, steps=2)
+
+
 @pytest.mark.parametrize("seed", range(3))
 def test_sparse_integer_ties_and_full_columns(seed):
     """Dense-ish columns over few rows: columns that contain every listed top row force the
@@ -201,6 +226,37 @@ def test_sparse_all_rows_in_one_column_beyond_list():
     inst.csr_val = rng.standard_normal(mm).astype(np.float32)
     assert rows.size == inst.csr_val.size
     stepwise_check(inst, steps=2)
+
+
+@pytest.mark.parametrize("density,nn", [(1.0, 5), (1.0, 100), (0.97, 70)])
+def test_sparse_columns_holding_all_large_rows(density, nn):
+    """More rows than the reservoir holds and columns that contain every reservoir row: the
+    outside maximum needs the walk past the inline list and the exact scan; with 100 such
+    columns the per-workgroup list of deferred columns overflows into the rescan path."""
+    inst = random_sparse(900 + nn, 333, nn, 3, density=density, dtype=np.float32)
+    stepwise_check(inst, steps=2)
+    stepwise_check(inst, steps=2, sparse_partition_rows=100)
+    with dmmv().from_instance(inst, DEV) as h:
+        res = dmmv().dmmv_solve(h, T(inst.x0), 25, trace=True)
+    check_single_trace(res, oracle_solve(inst, 25), 25)
+
+
+def test_sparse_long_descent_reservoir_maintenance():
+    """A few hundred moves on a matrix with far more rows than the reservoir: the sorted
+    reservoir is updated incrementally after every move, drained, rebuilt and truncated."""
+    inst = random_sparse(977, 6000, 400, 5, density=0.02, dtype=np.float32)
+    rng = np.random.default_rng(5)
+    x0 = rng.choice(inst.D, size=inst.n).astype(np.float32)
+    for rows in (0, 2500):
+        with dmmv().from_instance(inst, DEV, sparse_partition_rows=rows) as h:
+            res = dmmv().dmmv_solve(h, T(x0), 400, trace=True)
+            o = oracle_solve(inst, 400, x0=x0)
+            assert o.iters_done > 100
+            check_single_trace(res, o, 400)
+            x, r, t = dmmv().dmmv_get_state(h)
+            assert np.array_equal(N(r), o.r)
+            # the table of the final state still matches (reservoir consistent with r)
+            assert np.array_equal(N(dmmv().dmmv_eval_moves(h)), oracle_table(inst, o.x, o.r))
 
 
 def test_sparse_solve_small_tomography():
