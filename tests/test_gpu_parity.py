@@ -467,3 +467,70 @@ def test_error_paths():
         # still usable afterwards
         assert np.array_equal(N(m.dmmv_eval_moves(h)),
                               oracle_table(inst, inst.x0, oracle_residual(inst, inst.x0)))
+
+
+# ------------------------------------------------------------------------------ full-size configs
+def test_config3_tomography_full_prefix_and_sampled_scores():
+    """Full 65 340 x 65 536 projection matrix: the first moves of the descent, and sampled
+    columns of the score table against the definition (max over ALL rows)."""
+    m = dmmv()
+    inst = make_config(3)
+    iters = 40
+    with m.from_instance(inst, DEV) as h:
+        res = m.dmmv_solve(h, T(inst.x0), iters, trace=True)
+        o = oracle_solve(inst, iters)
+        assert o.iters_done == iters
+        check_single_trace(res, o, iters)
+        x, r, t = m.dmmv_get_state(h)
+        assert np.array_equal(N(r), o.r) and N(t)[0] == o.t
+        tab = N(m.dmmv_eval_moves(h)).reshape(inst.n, inst.nd)
+        # columns of the last moves (they hold the largest rows) plus a seeded sample
+        rng = np.random.default_rng(7)
+        cols = np.unique(np.concatenate([o.trace_j[-10:], rng.integers(0, inst.n, size=150)]))
+        for j in cols:
+            want = orc.eval_moves_csr(inst.m, inst.n, inst.csr_rowptr, inst.csr_col, inst.csr_val,
+                                      inst.D, o.x, o.r, method="plain",
+                                      columns=(int(j), int(j) + 1)).reshape(inst.n, inst.nd)[j]
+            assert np.array_equal(tab[j], want), j
+        # properties that hold for the whole table: null moves score t, nothing scores below
+        # the largest |r| over the rows a column cannot touch (at least the 2nd largest overall)
+        kidx = orc.values_to_index(o.x, inst.D)
+        assert np.all(tab[np.arange(inst.n), kidx] == o.t)
+        assert tab.min() >= 0
+
+
+@pytest.mark.parametrize("idx,iters,sample", [(4, 3, 16), (5, 2, 8)])
+def test_llm_configs_full_sampled_instances(idx, iters, sample):
+    """Full-size batched layer: every instance runs on the GPU; a seeded sample of instances
+    is replayed by the oracle and must match bitwise; all instances pass cheap checks."""
+    m = dmmv()
+    inst = make_config(idx)
+    with m.from_instance(inst, DEV) as h:
+        res = m.dmmv_solve(h, T(inst.x0), iters, trace=True)
+        x = N(res.x)
+        t = N(res.max_violation)
+        done = N(res.iters_done)
+        tr = N(res.trace)
+        tt = N(res.trace_t)
+        xs, r, ts = m.dmmv_get_state(h)
+        r = N(r)
+    rng = np.random.default_rng(idx)
+    sel = np.sort(rng.choice(inst.R, size=sample, replace=False))
+    o = orc.solve_batched(inst.A, inst.b[sel], inst.D, inst.scale[sel], inst.x0[sel], iters)
+    assert np.array_equal(done[sel], o.iters_done)
+    assert np.array_equal(tr[sel][:, :, 0], o.trace_j) and np.array_equal(tr[sel][:, :, 1], o.trace_k)
+    assert np.array_equal(tt[sel], o.trace_t)
+    assert np.array_equal(x[sel], o.x) and np.array_equal(t[sel], o.t)
+    # every instance: x in D, t == max |maintained r|, traces strictly decreasing
+    assert np.all(np.isin(x, inst.D))
+    assert np.array_equal(np.abs(r).max(axis=1), t)
+    for q in range(0, inst.R, 97):
+        d = done[q]
+        assert np.all(np.diff(tt[q, :d]) < 0)
+        assert np.all(tr[q, d:] == -1)
+    # sampled instances: maintained residual against a fresh fp64 recomputation
+    X64 = inst.A.astype(np.float64)
+    for q in sel[:4]:
+        fresh = X64 @ (inst.scale[q].astype(np.float64) * x[q]) - inst.b[q]
+        assert np.abs(r[q] - fresh).max() <= 1e-5 * max(1.0, np.abs(inst.b[q]).max())
+        assert abs(t[q] - np.abs(fresh).max()) <= 1e-5 * np.abs(fresh).max()
