@@ -9,8 +9,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libdmmv.so")
-SOURCES = ["dmmv_api.hip", "dmmv_dense.hip", "dmmv_sparse.hip", "dmmv_batched.hip"]
-HEADERS = [os.path.join(CSRC, "dmmv_common.h"),
+SOURCES = ["dmmv_api.hip", "dmmv_dense.hip", "dmmv_sparse.hip", "dmmv_sparse_eval.hip",
+           "dmmv_batched.hip"]
+HEADERS = [os.path.join(CSRC, "dmmv_common.h"), os.path.join(CSRC, "dmmv_sparse_common.h"),
            os.path.join(os.path.dirname(HERE), "include", "dmmv.h")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

@@ -86,7 +86,7 @@ struct Ctx {
     int64_t red_elems;
 
     // sparse: rows cut into csc_P partitions of csc_mp rows; segment s = p*n + j
-    int32_t csc_P, csc_mp, csc_gb;  // partitions, rows per partition, evaluation workgroups
+    int32_t csc_P, csc_mp, csc_gb;  // partitions, rows per partition, workgroups per partition
     int64_t csc_nnzp;     // stored entries including segment padding (upper bound)
     int32_t* segptr;      // [P*n + 1] padded start of every segment
     uint16_t* row16;      // [nnzp] row offset inside the partition (pad = csc_mp)
@@ -94,9 +94,9 @@ struct Ctx {
     int32_t* fillpos;     // [P*n + 1] build scratch: end of the real entries of a segment
     uint16_t* row16_tmp;  // [nnzp] build scratch
     void* cval_tmp;       // T[nnzp] build scratch
-    int32_t* blk_lo;      // [csc_gb + 1] first column of every evaluation workgroup
-    void* colmax;         // T[n*nd] per-column maxima carried across partitions
-    uint32_t* colmask;    // [n] reservoir rows met by the column
+    int32_t* blk_lo;      // [P][csc_gb + 1] first column of every evaluation workgroup
+    void* part_scores;    // T[P][n*nd] per-partition maxima over the touched rows
+    uint32_t* part_mask;  // [P][n] inline-checked reservoir rows met by the column
     void* res_val;        // T[RES_CAP] reservoir: largest |r|, sorted
     int32_t* res_row;     // [RES_CAP]
     int32_t* res_meta;    // [4] count, floor row
@@ -142,6 +142,7 @@ dmmv_status csc_build(Ctx* c);
 dmmv_status csc_residual(Ctx* c);
 dmmv_status csc_reservoir(Ctx* c);      // rebuild the reservoir of largest |r| from r
 dmmv_status csc_eval(Ctx* c, void* scores_out, bool want_partials, bool honor_done);
+dmmv_status csc_eval_stream_only(Ctx* c);   // just the kernel that streams the matrix
 dmmv_status csc_apply(Ctx* c);          // staged move only; caller refreshes t and the reservoir
 dmmv_status csc_select_apply(Ctx* c, int32_t iters, dmmv_move* trace, void* trace_t);
 

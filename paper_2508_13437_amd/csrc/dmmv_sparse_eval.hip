@@ -1,0 +1,369 @@
+// Sparse move evaluation: a streaming kernel and a finalize kernel.
+//
+// k_eval_stream.  grid = (workgroups per partition, partitions).  A workgroup stages ITS
+// partition of r in LDS once (64 KiB, so two workgroups share a compute unit: one stages while
+// the other streams) and owns a range of columns holding an equal share of the partition's
+// entries.  A row of 16 lanes takes one column segment, each lane four consecutive entries
+// per pass (one 8-byte load of row offsets, one 16-byte load of values, both coalesced and
+// unconditional with clamped addresses), gathers r from LDS, keeps KT running maxima and
+// reduces them over the 16 lanes with integer DPP max.  Every wavefront keeps DEPTH column
+// groups in flight: the loads of group g + DEPTH*8 go out right after group g is consumed.
+// Output: per partition, the maximum over the touched rows for every (column, value), and
+// the mask of the first RES_FAST reservoir rows the column meets in this partition.
+//
+// k_finalize_csc.  One thread per column: combine the partitions, add the maximum over the
+// rows OUTSIDE the column (first reservoir row the column does not contain; rare columns that
+// contain every inline-checked row walk the rest of the reservoir, then scan all rows),
+// apply the neighbourhood mask, write scores and one arg-min record per workgroup.
+#include "dmmv_sparse_common.h"
+
+namespace dmmv {
+
+constexpr int ST_BLOCK = 512;
+constexpr int ST_WAVES = ST_BLOCK / 64;
+constexpr int ST_DEPTH = 4;        // column groups a wavefront keeps in flight
+constexpr int ST_COLS = 1024;      // columns whose bounds / current values sit in LDS at once
+constexpr int FIN_BLOCK = CSC_FIN_BLOCK;
+
+// one pass (64 entries) of one group of four columns, as loaded
+template <class T>
+struct EntryRegs {
+    uint2 ix;
+    typename Vec4<T>::type av;
+    bool ok;
+};
+
+template <class T>
+__device__ __forceinline__ void load_entries(EntryRegs<T>& E, const uint16_t* __restrict__ row16,
+                                             const T* __restrict__ cval, int32_t e, int32_t s1,
+                                             int32_t emax) {
+    const int32_t ec = e < emax ? e : emax;       // four spare entries follow the arrays
+    E.ix = *reinterpret_cast<const uint2*>(row16 + ec);
+    E.av = *reinterpret_cast<const typename Vec4<T>::type*>(cval + ec);
+    E.ok = e < s1;
+}
+
+// lanes beyond their segment become pads (offset = partition size -> LDS slot holding 0)
+template <class T>
+__device__ __forceinline__ void mask_entries(EntryRegs<T>& E, uint32_t pad) {
+    const uint32_t pp = pad | (pad << 16);
+    E.ix.x = E.ok ? E.ix.x : pp;
+    E.ix.y = E.ok ? E.ix.y : pp;
+    E.av.x = E.ok ? E.av.x : (T)0;
+    E.av.y = E.ok ? E.av.y : (T)0;
+    E.av.z = E.ok ? E.av.z : (T)0;
+    E.av.w = E.ok ? E.av.w : (T)0;
+}
+
+// fold one pass into the lane's running maxima and reservoir mask
+template <class T, int KT>
+__device__ __forceinline__ void fold_pass(const EntryRegs<T>& E, const T* lds_r, const T (&delta)[KT],
+                                          T (&acc)[KT], uint32_t& mask, bool first_tile, T thr,
+                                          int32_t nfast, const int32_t* sh_rloc, uint32_t pad) {
+    const uint32_t i0 = E.ix.x & 0xFFFFu, i1 = E.ix.x >> 16, i2 = E.ix.y & 0xFFFFu, i3 = E.ix.y >> 16;
+    const T r0 = lds_r[i0], r1 = lds_r[i1], r2 = lds_r[i2], r3 = lds_r[i3];
+    if (first_tile) {
+        const T big = dmmv_max(dmmv_max(dmmv_abs(r0), dmmv_abs(r1)), dmmv_max(dmmv_abs(r2), dmmv_abs(r3)));
+        if (big >= thr) {      // uncommon: one of these rows may be among the listed ones
+            for (int32_t q = 0; q < nfast; ++q) {
+                const uint32_t l = (uint32_t)sh_rloc[q];     // offset in this partition or ~0
+                if (i0 == l || i1 == l || i2 == l || i3 == l) mask |= 1u << q;
+            }
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < KT; ++q) {
+        T a = acc[q];
+        a = dmmv_max(a, dmmv_abs(dmmv_fma(delta[q], E.av.x, r0)));
+        a = dmmv_max(a, dmmv_abs(dmmv_fma(delta[q], E.av.y, r1)));
+        a = dmmv_max(a, dmmv_abs(dmmv_fma(delta[q], E.av.z, r2)));
+        a = dmmv_max(a, dmmv_abs(dmmv_fma(delta[q], E.av.w, r3)));
+        acc[q] = a;
+    }
+}
+
+template <class T, int KT>
+__global__ __launch_bounds__(ST_BLOCK, 4) void k_eval_stream(   // 4 waves per SIMD: 2 workgroups per CU
+    int64_t m, int64_t n, int32_t nd, int32_t mp, const int32_t* __restrict__ segptr,
+    const uint16_t* __restrict__ row16, const T* __restrict__ cval,
+    const int32_t* __restrict__ blk_lo, const T* __restrict__ D, const int32_t* __restrict__ kidx,
+    const T* __restrict__ r, const T* __restrict__ res_val, const int32_t* __restrict__ res_row,
+    const int32_t* __restrict__ res_meta, const InstState<T>* __restrict__ st, int32_t honor_done,
+    T* __restrict__ part_scores, uint32_t* __restrict__ part_mask) {
+    extern __shared__ __align__(32) unsigned char smem[];
+    T* lds_r = reinterpret_cast<T*>(smem);                 // mp + 1 entries (slot mp = 0)
+    __shared__ int32_t sh_b[ST_COLS + 1];
+    __shared__ T sh_dcur[ST_COLS];
+    __shared__ int32_t sh_rloc[RES_FAST];
+    __shared__ int32_t sh_long;
+    if (honor_done && st[0].done) return;
+
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int sub = lane & 15;                 // position inside the row of 16 lanes
+    const int rowid = lane >> 4;               // which of the wavefront's 4 columns
+    const int32_t P = gridDim.y;
+    const int32_t p = blockIdx.y;
+    const int64_t j_lo = blk_lo[p * (gridDim.x + 1) + blockIdx.x];
+    const int64_t j_hi = blk_lo[p * (gridDim.x + 1) + blockIdx.x + 1];
+    const int64_t row0 = (int64_t)p * mp;
+    const int32_t rows_here = (int32_t)((m - row0) < mp ? (m - row0) : mp);
+    const uint32_t pad = (uint32_t)mp;
+    const int32_t emax = segptr[(int64_t)P * n];
+    const int32_t cnt = res_meta[RES_CNT];
+    const int32_t nfast = cnt < RES_FAST ? cnt : RES_FAST;
+    const T thr = nfast > 0 ? res_val[nfast - 1] : Limits<T>::inf();
+    if (threadIdx.x < RES_FAST) {
+        // offset of the q-th reservoir row inside this partition (no such offset otherwise)
+        int32_t loc = -1;
+        if ((int32_t)threadIdx.x < nfast) {
+            const int64_t d = (int64_t)res_row[threadIdx.x] - row0;
+            if (d >= 0 && d < (int64_t)rows_here) loc = (int32_t)d;
+        }
+        sh_rloc[threadIdx.x] = loc;
+    }
+    // stage this partition of r
+    if ((row0 & 3) == 0) {
+        const int32_t nvec = rows_here >> 2;
+        const typename Vec4<T>::type* __restrict__ src = reinterpret_cast<const typename Vec4<T>::type*>(r + row0);
+        typename Vec4<T>::type* dst = reinterpret_cast<typename Vec4<T>::type*>(lds_r);
+        for (int32_t i = threadIdx.x; i < nvec; i += ST_BLOCK) dst[i] = src[i];
+        for (int32_t i = (nvec << 2) + threadIdx.x; i < rows_here; i += ST_BLOCK) lds_r[i] = r[row0 + i];
+    } else {
+        for (int32_t i = threadIdx.x; i < rows_here; i += ST_BLOCK) lds_r[i] = r[row0 + i];
+    }
+    if (threadIdx.x == 0) lds_r[mp] = (T)0;
+
+    const int32_t* __restrict__ sp = segptr + (int64_t)p * n;
+    T* __restrict__ out = part_scores + (int64_t)p * (n * (int64_t)nd);
+    uint32_t* __restrict__ out_mask = part_mask + (int64_t)p * n;
+
+    for (int64_t c0 = j_lo; c0 < j_hi; c0 += ST_COLS) {
+        const int32_t nc = (int32_t)(j_hi - c0 < ST_COLS ? j_hi - c0 : ST_COLS);
+        const int32_t nq = (nc + 3) >> 2;
+        __syncthreads();                       // previous chunk consumed
+        if (threadIdx.x == 0) sh_long = 0;
+        __syncthreads();
+        for (int32_t t = threadIdx.x; t <= nc; t += ST_BLOCK) {
+            const int32_t b0 = sp[c0 + t];
+            sh_b[t] = b0;
+            if (t < nc) {
+                sh_dcur[t] = D[kidx[c0 + t]];
+                if (sp[c0 + t + 1] - b0 > 64) sh_long = 1;     // more than one pass somewhere
+            }
+        }
+        __syncthreads();                       // r, bounds and current values staged
+        const bool any_long = sh_long != 0;
+
+        for (int32_t k0 = 0; k0 < nd; k0 += KT) {
+            T dk[KT];
+#pragma unroll
+            for (int q = 0; q < KT; ++q) dk[q] = D[k0 + q < nd ? k0 + q : nd - 1];
+            EntryRegs<T> ent[ST_DEPTH];
+            int32_t qe[ST_DEPTH], qs1[ST_DEPTH];
+#pragma unroll
+            for (int u = 0; u < ST_DEPTH; ++u) {
+                const int32_t t = (w + u * ST_WAVES) * 4 + rowid;
+                const bool okc = t < nc;
+                qe[u] = (okc ? sh_b[t] : 0) + sub * SEG_ALIGN;
+                qs1[u] = okc ? sh_b[t + 1] : 0;
+                load_entries<T>(ent[u], row16, cval, qe[u], qs1[u], emax);
+            }
+            for (int32_t g0 = w; g0 < nq; g0 += ST_WAVES * ST_DEPTH) {
+#pragma unroll
+                for (int u = 0; u < ST_DEPTH; ++u) {
+                    const int32_t g = g0 + u * ST_WAVES;
+                    if (g < nq) {                              // uniform per wavefront
+                        const int32_t t = g * 4 + rowid;
+                        const bool col_ok = t < nc;
+                        const T dcur = sh_dcur[col_ok ? t : 0];
+                        T delta[KT], acc[KT];
+#pragma unroll
+                        for (int q = 0; q < KT; ++q) { delta[q] = step_of(dk[q], dcur, (T)1); acc[q] = (T)0; }
+                        uint32_t mask = 0;
+                        mask_entries<T>(ent[u], pad);
+                        fold_pass<T, KT>(ent[u], lds_r, delta, acc, mask, k0 == 0, thr, nfast, sh_rloc, pad);
+                        if (any_long) {                        // segments longer than one pass
+                            int32_t left = qs1[u] - (qe[u] - sub * SEG_ALIGN);
+                            left = max(left, __shfl_xor(left, 16, 64));
+                            left = max(left, __shfl_xor(left, 32, 64));
+                            const int32_t passes = __builtin_amdgcn_readfirstlane((left + 63) >> 6);
+                            for (int32_t ps = 1; ps < passes; ++ps) {
+                                EntryRegs<T> more;
+                                load_entries<T>(more, row16, cval, qe[u] + ps * 64, qs1[u], emax);
+                                mask_entries<T>(more, pad);
+                                fold_pass<T, KT>(more, lds_r, delta, acc, mask, k0 == 0, thr, nfast, sh_rloc, pad);
+                            }
+                        }
+#pragma unroll
+                        for (int q = 0; q < KT; ++q) acc[q] = row16_max_nonneg(acc[q]);
+                        if (k0 == 0) mask = row16_or(mask);
+                        if (sub == 0 && col_ok) {
+                            const int64_t j = c0 + t;
+#pragma unroll
+                            for (int q = 0; q < KT; ++q)
+                                if (k0 + q < nd) out[j * (int64_t)nd + k0 + q] = acc[q];
+                            if (k0 == 0) out_mask[j] = mask;
+                        }
+                    }
+                    // the group DEPTH*8 further on takes this slot
+                    {
+                        const int32_t t = (g + ST_WAVES * ST_DEPTH) * 4 + rowid;
+                        const bool okc = t < nc;
+                        qe[u] = (okc ? sh_b[t] : 0) + sub * SEG_ALIGN;
+                        qs1[u] = okc ? sh_b[t + 1] : 0;
+                        load_entries<T>(ent[u], row16, cval, qe[u], qs1[u], emax);
+                    }
+                }
+            }
+        }
+    }
+}
+
+// =========================================================================================
+// finalize
+// =========================================================================================
+template <class T>
+__global__ __launch_bounds__(FIN_BLOCK) void k_finalize_csc(
+    int64_t m, int64_t n, int32_t nd, int32_t mp, int32_t P, const int32_t* __restrict__ segptr,
+    const uint16_t* __restrict__ row16, const int32_t* __restrict__ kidx, const T* __restrict__ r,
+    const T* __restrict__ res_val, const int32_t* __restrict__ res_row,
+    const int32_t* __restrict__ res_meta, const T* __restrict__ part_scores,
+    const uint32_t* __restrict__ part_mask, int32_t radius, const uint8_t* __restrict__ var_mask,
+    const InstState<T>* __restrict__ st, int32_t honor_done, T* __restrict__ scores,
+    Partial<T>* __restrict__ part) {
+    __shared__ T sh_rv[RES_CAP];
+    __shared__ int32_t sh_rr[RES_CAP];
+    __shared__ T sh_s[FIN_BLOCK / 64];
+    __shared__ int64_t sh_c[FIN_BLOCK / 64];
+    if (honor_done && st[0].done) return;
+    const int32_t cnt = res_meta[RES_CNT];
+    if (threadIdx.x < RES_CAP) {
+        sh_rv[threadIdx.x] = threadIdx.x < cnt ? res_val[threadIdx.x] : (T)-1;
+        sh_rr[threadIdx.x] = threadIdx.x < cnt ? res_row[threadIdx.x] : -1;
+    }
+    __syncthreads();
+    const int32_t nfast = cnt < RES_FAST ? cnt : RES_FAST;
+    const uint32_t full = (1u << nfast) - 1u;              // RES_FAST < 32
+    const int lane = threadIdx.x & 63;
+    const int64_t j = blockIdx.x * (int64_t)FIN_BLOCK + threadIdx.x;
+    const bool live = j < n;
+
+    T outside = (T)0;
+    bool need_walk = false;
+    if (live) {
+        uint32_t cm = 0;
+        for (int32_t p = 0; p < P; ++p) cm |= part_mask[(int64_t)p * n + j];
+        const uint32_t missing = full & ~cm;
+        if (missing) outside = sh_rv[__builtin_ctz(missing)];
+        else if ((int64_t)nfast >= m) outside = (T)0;          // the column holds every row
+        else need_walk = true;
+    }
+    // rare: the column contains every inline-checked reservoir row; the whole wavefront helps
+    unsigned long long todo = __ballot(need_walk);
+    while (todo) {
+        const int src = __builtin_ctzll(todo);
+        todo &= todo - 1;
+        const int64_t jj = __shfl(j, src, 64);
+        // 1) the rest of the reservoir, in order: first entry whose row is not in the column
+        int32_t first = INT32_MAX;
+        for (int32_t base = RES_FAST; base < cnt && first == INT32_MAX; base += 64) {
+            const int32_t q = base + lane;
+            const bool absent = q < cnt && !column_has_row<T>(segptr, row16, n, mp, jj, sh_rr[q]);
+            const unsigned long long b = __ballot(absent);
+            if (b) first = base + __builtin_ctzll(b);
+        }
+        T o;
+        if (first != INT32_MAX) {
+            o = sh_rv[first];
+        } else if ((int64_t)cnt >= m) {
+            o = (T)0;
+        } else {
+            // 2) exact scan over all rows
+            o = (T)0;
+            for (int64_t i = lane; i < m; i += 64)
+                if (!column_has_row<T>(segptr, row16, n, mp, jj, (int32_t)i)) o = dmmv_max(o, dmmv_abs(r[i]));
+            o = wave_max(o);
+        }
+        if (lane == src) outside = o;
+    }
+
+    T bs = (T)0;
+    int64_t bc = -1;
+    if (live) {
+        const int32_t kcur = kidx[j];
+        const bool var_ok = var_mask ? var_mask[j] != 0 : true;
+        for (int32_t k = 0; k < nd; ++k) {
+            const int64_t cidx = j * (int64_t)nd + k;
+            T v = outside;
+            for (int32_t p = 0; p < P; ++p) v = dmmv_max(v, part_scores[(int64_t)p * (n * (int64_t)nd) + cidx]);
+            if (!cand_allowed(kcur, k, radius, var_ok)) v = Limits<T>::inf();
+            if (scores) scores[cidx] = v;
+            if (rec_less(v, cidx, bs, bc)) { bs = v; bc = cidx; }
+        }
+    }
+    if (part) {
+        block_argmin(bs, bc, sh_s, sh_c);
+        if (threadIdx.x == 0) { Partial<T> pr; pr.s = bs; pr.c = bc; part[blockIdx.x] = pr; }
+    }
+}
+
+// =========================================================================================
+// host dispatch
+// =========================================================================================
+template <class T, int KT>
+static dmmv_status stream_launch(Ctx* c, bool honor_done) {
+    if (c->csc_P > CSC_MAX_PARTITIONS)
+        return fail(DMMV_ERR_UNSUPPORTED, "sparse path: %d row partitions exceed the limit of %d (raise sparse_partition_rows)", c->csc_P, CSC_MAX_PARTITIONS);
+    const size_t lds = ((size_t)c->csc_mp + 1) * sizeof(T);
+    static bool attr_set = false;
+    if (!attr_set) {
+        DMMV_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_eval_stream<T, KT>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, CSC_LDS_BYTES + 256));
+        attr_set = true;
+    }
+    dim3 grid((unsigned)c->csc_gb, (unsigned)c->csc_P);
+    hipLaunchKernelGGL((k_eval_stream<T, KT>), grid, dim3(ST_BLOCK), lds, c->stream, c->p.m, c->p.n,
+                       c->p.nd, c->csc_mp, (const int32_t*)c->segptr, (const uint16_t*)c->row16,
+                       (const T*)c->cval, (const int32_t*)c->blk_lo, (const T*)c->D_dev,
+                       (const int32_t*)c->kidx, (const T*)c->r, (const T*)c->res_val,
+                       (const int32_t*)c->res_row, (const int32_t*)c->res_meta,
+                       (const InstState<T>*)c->state, (int32_t)honor_done, (T*)c->part_scores,
+                       c->part_mask);
+    DMMV_LAUNCH_CHECK();
+    return DMMV_OK;
+}
+
+template <class T>
+static dmmv_status stream_t(Ctx* c, bool honor_done) {
+    if (c->p.nd <= 2) return stream_launch<T, 2>(c, honor_done);
+    if (c->p.nd == 3) return stream_launch<T, 3>(c, honor_done);
+    if (c->p.nd <= 4) return stream_launch<T, 4>(c, honor_done);
+    return stream_launch<T, 8>(c, honor_done);
+}
+
+template <class T>
+static dmmv_status eval_t(Ctx* c, void* scores, bool want_partials, bool honor_done) {
+    DMMV_TRY(stream_t<T>(c, honor_done));
+    const unsigned blocks = (unsigned)ceil_div(c->p.n, FIN_BLOCK);
+    if ((int64_t)blocks != c->n_partials) return fail(DMMV_ERR_STATE, "sparse finalize grid does not match the partial-record buffer");
+    hipLaunchKernelGGL(k_finalize_csc<T>, dim3(blocks), dim3(FIN_BLOCK), 0, c->stream, c->p.m, c->p.n,
+                       c->p.nd, c->csc_mp, c->csc_P, (const int32_t*)c->segptr, (const uint16_t*)c->row16,
+                       (const int32_t*)c->kidx, (const T*)c->r, (const T*)c->res_val,
+                       (const int32_t*)c->res_row, (const int32_t*)c->res_meta,
+                       (const T*)c->part_scores, (const uint32_t*)c->part_mask, c->o.radius,
+                       c->o.var_mask, (const InstState<T>*)c->state, (int32_t)honor_done, (T*)scores,
+                       want_partials ? (Partial<T>*)c->partials : nullptr);
+    DMMV_LAUNCH_CHECK();
+    return DMMV_OK;
+}
+
+dmmv_status csc_eval(Ctx* c, void* scores_out, bool want_partials, bool honor_done) {
+    return c->p.dtype == DMMV_F64 ? eval_t<double>(c, scores_out, want_partials, honor_done)
+                                  : eval_t<float>(c, scores_out, want_partials, honor_done);
+}
+dmmv_status csc_eval_stream_only(Ctx* c) {
+    return c->p.dtype == DMMV_F64 ? stream_t<double>(c, false) : stream_t<float>(c, false);
+}
+
+}  // namespace dmmv
