@@ -31,6 +31,11 @@ import numpy as np  # noqa: E402
 HBM_PEAK_GBS = 8000.0
 ALU_PEAK_TFLOPS = {"f32": 157.3, "f64": 78.6}
 FLOPS_PER_PAIR = 3          # multiply + add of the fma, and the max; |.| is an operand modifier
+# HBM bytes per launch of the evaluation kernel, from rocprofv3 FETCH_SIZE + WRITE_SIZE runs
+# calibrated against a plain copy (summaries under profiles/hbm_traffic_*.md)
+MEASURED_TRAFFIC_BYTES = {
+    "tomography_256x256_180x363_csr_f32": 100.4e6,
+}
 
 
 def algorithmic_bytes_per_eval(inst) -> float:
@@ -54,8 +59,9 @@ def roofline_for(inst, eval_ms: float) -> dict:
     if inst.kind == "csr":
         b = algorithmic_bytes_per_eval(inst)
         ach = b / (eval_ms * 1e-3) / 1e9
-        return {"bound": "hbm", "kernel": "k_eval_csc", "achieved": ach, "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None,
+        return {"bound": "hbm", "kernel": "k_eval_stream", "achieved": ach, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+                "traffic": MEASURED_TRAFFIC_BYTES.get(inst.name),
                 "algorithmic_bytes_per_launch": b, "avg_launch_ms": eval_ms}
     flops = pairs_per_eval(inst) * FLOPS_PER_PAIR
     ach = flops / (eval_ms * 1e-3) / 1e12
@@ -149,6 +155,30 @@ def run_config(idx: int, steps: int, warmup: int, iters_override, device: str, d
     return out
 
 
+def traffic_probe(idx: int, device: str, reps: int) -> None:
+    """For `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` runs: launches the evaluation
+    kernel of workload idx `reps` times and one plain device-to-device copy of a known size
+    (256 MiB read + 256 MiB written) whose counter reading calibrates the counters' unit."""
+    import torch
+    from paper_2508_13437_amd import dmmv
+    from workloads import make_config
+
+    inst = make_config(idx)
+    x0 = torch.from_numpy(np.ascontiguousarray(inst.x0)).to(device)
+    src = torch.empty(256 << 20, dtype=torch.uint8, device=device).fill_(1)
+    dst = torch.empty_like(src)
+    with dmmv.from_instance(inst, device, keep_going=True, poll_every=0) as h:
+        dmmv.dmmv_set_x(h, x0)
+        dmmv.dmmv_residual(h)
+        ms = dmmv.dmmv_time_eval(h, reps)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+    print(json.dumps({"probe": inst.name, "eval_launches": reps + 1, "eval_avg_ms": ms / reps,
+                      "copy_bytes_read": int(src.numel()), "copy_bytes_written": int(src.numel()),
+                      "algorithmic_bytes_per_launch": algorithmic_bytes_per_eval(inst)}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -160,6 +190,9 @@ def main():
                     help="comma list of further configs to report in the same line, e.g. 1,2,4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget", type=float, default=15.0)
+    ap.add_argument("--traffic-probe", type=int, default=0, metavar="REPS",
+                    help="only launch the evaluation kernel REPS times plus a calibration copy "
+                         "(for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
@@ -170,6 +203,9 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
     device = "cuda:0"
+    if args.traffic_probe > 0:
+        traffic_probe(args.config, device, args.traffic_probe)
+        return
     default_steps = {1: 20, 2: 10, 3: 5, 4: 1, 5: 1}
     steps = args.steps if args.steps is not None else default_steps[args.config]
     head = run_config(args.config, steps, args.warmup, args.iters, device,

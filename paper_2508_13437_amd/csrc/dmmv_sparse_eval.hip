@@ -122,17 +122,7 @@ __global__ __launch_bounds__(ST_BLOCK, 4) void k_eval_stream(   // 4 waves per S
         }
         sh_rloc[threadIdx.x] = loc;
     }
-    // stage this partition of r
-    if ((row0 & 3) == 0) {
-        const int32_t nvec = rows_here >> 2;
-        const typename Vec4<T>::type* __restrict__ src = reinterpret_cast<const typename Vec4<T>::type*>(r + row0);
-        typename Vec4<T>::type* dst = reinterpret_cast<typename Vec4<T>::type*>(lds_r);
-        for (int32_t i = threadIdx.x; i < nvec; i += ST_BLOCK) dst[i] = src[i];
-        for (int32_t i = (nvec << 2) + threadIdx.x; i < rows_here; i += ST_BLOCK) lds_r[i] = r[row0 + i];
-    } else {
-        for (int32_t i = threadIdx.x; i < rows_here; i += ST_BLOCK) lds_r[i] = r[row0 + i];
-    }
-    if (threadIdx.x == 0) lds_r[mp] = (T)0;
+    bool r_staged = false;
 
     const int32_t* __restrict__ sp = segptr + (int64_t)p * n;
     T* __restrict__ out = part_scores + (int64_t)p * (n * (int64_t)nd);
@@ -152,7 +142,7 @@ __global__ __launch_bounds__(ST_BLOCK, 4) void k_eval_stream(   // 4 waves per S
                 if (sp[c0 + t + 1] - b0 > 64) sh_long = 1;     // more than one pass somewhere
             }
         }
-        __syncthreads();                       // r, bounds and current values staged
+        __syncthreads();                       // bounds and current values staged
         const bool any_long = sh_long != 0;
 
         for (int32_t k0 = 0; k0 < nd; k0 += KT) {
@@ -168,6 +158,21 @@ __global__ __launch_bounds__(ST_BLOCK, 4) void k_eval_stream(   // 4 waves per S
                 qe[u] = (okc ? sh_b[t] : 0) + sub * SEG_ALIGN;
                 qs1[u] = okc ? sh_b[t + 1] : 0;
                 load_entries<T>(ent[u], row16, cval, qe[u], qs1[u], emax);
+            }
+            if (!r_staged) {
+                // stage this partition of r while the first groups' entries are in flight
+                if ((row0 & 3) == 0) {
+                    const int32_t nvec = rows_here >> 2;
+                    const typename Vec4<T>::type* __restrict__ src = reinterpret_cast<const typename Vec4<T>::type*>(r + row0);
+                    typename Vec4<T>::type* dst = reinterpret_cast<typename Vec4<T>::type*>(lds_r);
+                    for (int32_t i = threadIdx.x; i < nvec; i += ST_BLOCK) dst[i] = src[i];
+                    for (int32_t i = (nvec << 2) + threadIdx.x; i < rows_here; i += ST_BLOCK) lds_r[i] = r[row0 + i];
+                } else {
+                    for (int32_t i = threadIdx.x; i < rows_here; i += ST_BLOCK) lds_r[i] = r[row0 + i];
+                }
+                if (threadIdx.x == 0) lds_r[mp] = (T)0;
+                r_staged = true;
+                __syncthreads();
             }
             for (int32_t g0 = w; g0 < nq; g0 += ST_WAVES * ST_DEPTH) {
 #pragma unroll
