@@ -42,9 +42,6 @@ struct Bump {
 
 }  // namespace
 
-int64_t dense_num_partials(const dmmv_problem& p) {
-    return p.n * ceil_div(p.nd, dense_ktile(p.nd));
-}
 int32_t batched_chunk_cols(const dmmv_problem& p) {
     // enough (instance group, chunk) blocks to fill 256 CUs several times over
     int64_t groups = ceil_div(p.R, 64);
@@ -418,7 +415,7 @@ static dmmv_status launch_select(Ctx* c, dmmv_move* best_out, void* best_score_o
 static dmmv_status eval_any(Ctx* c, void* scores_out, bool want_partials, bool honor_done) {
     if (c->p.n == 0) return DMMV_OK;
     switch (c->kind) {
-        case KIND_DENSE: return dense_eval(c, scores_out, want_partials);
+        case KIND_DENSE: return dense_eval(c, scores_out, want_partials, honor_done);
         case KIND_CSC:
             return csc_eval(c, scores_out, want_partials, honor_done);
         default: return batched_eval(c, scores_out, want_partials);
@@ -436,6 +433,7 @@ static dmmv_status apply_any(Ctx* c, bool t_from_score, int32_t iters, dmmv_move
 // one loop step after the evaluation: pick the best move and apply it if it improves
 static dmmv_status select_apply_any(Ctx* c, int32_t iters, dmmv_move* trace, void* trace_t) {
     if (c->kind == KIND_CSC) return csc_select_apply(c, iters, trace, trace_t);
+    if (c->kind == KIND_DENSE && dense_has_fused_select_apply(c)) return dense_select_apply(c, iters, trace, trace_t);
     DMMV_TRY(launch_select(c, nullptr, nullptr));
     return apply_any(c, true, iters, trace, trace_t);
 }

@@ -121,8 +121,6 @@ size_t workspace_layout(const dmmv_problem& p, const dmmv_options& o, Ctx* c, ch
 
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
-// values of D scored per workgroup by the dense evaluation kernel
-static inline int dense_ktile(int32_t nd) { return nd >= 16 ? 16 : (nd >= 8 ? 8 : 4); }
 // columns per workgroup of the sparse finalize kernel (one arg-min record each)
 constexpr int CSC_FIN_BLOCK = 256;
 // bytes of LDS a sparse evaluation workgroup may use for its partition of r
@@ -135,7 +133,10 @@ constexpr int CSC_MAX_PARTITIONS = 1024;
 // per-path entry points (all enqueue on c->stream)
 // ----------------------------------------------------------------------------------------
 dmmv_status dense_residual(Ctx* c);
-dmmv_status dense_eval(Ctx* c, void* scores_out, bool want_partials);
+int64_t dense_num_partials(const dmmv_problem& p);    // arg-min records one evaluation writes
+dmmv_status dense_eval(Ctx* c, void* scores_out, bool want_partials, bool honor_done);
+bool dense_has_fused_select_apply(const Ctx* c);
+dmmv_status dense_select_apply(Ctx* c, int32_t iters, dmmv_move* trace, void* trace_t);
 dmmv_status dense_apply(Ctx* c, bool t_from_score, int32_t iters, dmmv_move* trace, void* trace_t);
 
 dmmv_status csc_build(Ctx* c);

@@ -1,13 +1,22 @@
 // Dense single-instance path: A column-major m x n.
 //
-// Layout: a column of A is one variable's move direction, so lanes map to consecutive rows
-// and every load of A or r is a coalesced stream.  One workgroup scores one variable j for
-// a tile of KT values of D: each lane keeps KT running maxima in registers, reads A_ij and
-// r_i once per row, and the KT maxima are reduced over the wavefront with DPP row
-// operations and over the workgroup through LDS.
+// A column of A is one variable's move direction, so lanes map to consecutive rows and every
+// load of A or r is a coalesced stream.  A workgroup scores one variable j for up to 64 values
+// of D: it stages the column and r in LDS once (row chunks of up to 64 KiB), and each of its
+// wavefronts keeps KT = 16 running maxima per lane while striding over the staged rows.  The
+// 16 x 64 lane maxima of a wavefront are reduced through an LDS transpose (each lane folds a
+// quarter of one value's 64 entries, two DPP steps finish), so the reduction costs a few dozen
+// instructions per 16 x m pairs.  The wavefronts' best candidates become one arg-min record
+// per workgroup.
 #include "dmmv_common.h"
 
 namespace dmmv {
+
+constexpr int DE_KT = 16;                 // values of D per wavefront
+constexpr int DE_MAXW = 4;                // wavefronts (value tiles) per workgroup
+constexpr int DE_STAGE_BYTES = 64 * 1024; // LDS for one chunk of (column, r)
+constexpr int DE_SKEW = 65;               // row stride of the transpose scratch (bank skew)
+constexpr int64_t DE_FUSED_APPLY_ROWS = 32768;   // up to here one workgroup selects AND applies
 
 // ---- residual: r_i = fma(sum_j fma-chain, 1, -b_i), lanes over rows (coalesced) ----------
 template <class T>
@@ -22,58 +31,77 @@ __global__ void k_residual_dense(int64_t m, int64_t n, const T* __restrict__ A, 
 }
 
 // ---- evaluation ---------------------------------------------------------------------------
-// grid.x = variable j, grid.y = tile of KT values.  Writes the table entries of its tile
-// (scores != NULL) and one partial arg-min record (part != NULL).
-template <class T, int KT, int BLOCK>
-__global__ __launch_bounds__(BLOCK) void k_eval_dense(
-    int64_t m, int32_t nd, const T* __restrict__ A, int64_t lda, const T* __restrict__ D,
-    const int32_t* __restrict__ kidx, const T* __restrict__ r, int32_t radius,
-    const uint8_t* __restrict__ var_mask, const InstState<T>* __restrict__ st,
-    T* __restrict__ scores, Partial<T>* __restrict__ part) {
-    constexpr int NW = BLOCK / 64;
-    __shared__ T sh[NW][KT];
-    if (part && !scores && st[0].done) return;
+// grid.x = variable j, grid.y = group of blockDim.x/64 value tiles.  Writes the table entries
+// of its values (scores != NULL) and one partial arg-min record (part != NULL).
+template <class T>
+__global__ __launch_bounds__(64 * DE_MAXW) void k_eval_dense(
+    int64_t m, int32_t nd, int32_t rows_per_chunk, const T* __restrict__ A, int64_t lda,
+    const T* __restrict__ D, const int32_t* __restrict__ kidx, const T* __restrict__ r,
+    int32_t radius, const uint8_t* __restrict__ var_mask, const InstState<T>* __restrict__ st,
+    int32_t honor_done, T* __restrict__ scores, Partial<T>* __restrict__ part) {
+    constexpr int KT = DE_KT;
+    extern __shared__ __align__(16) unsigned char smem[];
+    T* lds_a = reinterpret_cast<T*>(smem);
+    T* lds_r = lds_a + rows_per_chunk;
+    __shared__ T sh_s[DE_MAXW];
+    __shared__ int64_t sh_c[DE_MAXW];
+    if (honor_done && st[0].done) return;
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int nw = blockDim.x >> 6;
     const int64_t j = blockIdx.x;
-    const int32_t k0 = blockIdx.y * KT;
+    const int32_t kbase = (blockIdx.y * nw + w) * KT;
     const int32_t kcur = kidx[j];
     const T dcur = D[kcur];
     T delta[KT], acc[KT];
 #pragma unroll
     for (int q = 0; q < KT; ++q) {
-        const int32_t k = k0 + q < nd ? k0 + q : nd - 1;
+        const int32_t k = kbase + q < nd ? kbase + q : nd - 1;
         delta[q] = step_of(D[k], dcur, (T)1);
         acc[q] = (T)0;
     }
     const T* __restrict__ col = A + lda * j;
-    for (int64_t i = threadIdx.x; i < m; i += BLOCK) {
-        const T a = col[i];
-        const T ri = r[i];
-#pragma unroll
-        for (int q = 0; q < KT; ++q) acc[q] = dmmv_max(acc[q], dmmv_abs(dmmv_fma(delta[q], a, ri)));
-    }
-#pragma unroll
-    for (int q = 0; q < KT; ++q) acc[q] = wave_max(acc[q]);
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    if (lane == 0) {
-#pragma unroll
-        for (int q = 0; q < KT; ++q) sh[w][q] = acc[q];
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const bool var_ok = var_mask ? var_mask[j] != 0 : true;
-        T bs = (T)0;
-        int64_t bc = -1;
-        for (int q = 0; q < KT; ++q) {
-            const int32_t k = k0 + q;
-            if (k >= nd) break;
-            T v = sh[0][q];
-            for (int ww = 1; ww < NW; ++ww) v = dmmv_max(v, sh[ww][q]);
-            if (!cand_allowed(kcur, k, radius, var_ok)) v = Limits<T>::inf();
-            const int64_t cidx = j * (int64_t)nd + k;
-            if (scores) scores[cidx] = v;
-            if (rec_less(v, cidx, bs, bc)) { bs = v; bc = cidx; }
+    for (int64_t c0 = 0; c0 < m; c0 += rows_per_chunk) {
+        const int32_t rc = (int32_t)(m - c0 < rows_per_chunk ? m - c0 : rows_per_chunk);
+        __syncthreads();
+        for (int32_t i = threadIdx.x; i < rc; i += blockDim.x) {
+            lds_a[i] = col[c0 + i];
+            lds_r[i] = r[c0 + i];
         }
-        if (part) {
+        __syncthreads();
+        for (int32_t i = lane; i < rc; i += 64) {
+            const T a = lds_a[i];
+            const T ri = lds_r[i];
+#pragma unroll
+            for (int q = 0; q < KT; ++q) acc[q] = dmmv_max(acc[q], dmmv_abs(dmmv_fma(delta[q], a, ri)));
+        }
+    }
+    __syncthreads();                              // staging area is free: reuse it as scratch
+    T* sc = reinterpret_cast<T*>(smem) + (size_t)w * KT * DE_SKEW;
+#pragma unroll
+    for (int q = 0; q < KT; ++q) sc[q * DE_SKEW + lane] = acc[q];
+    __syncthreads();
+    // lane folds a quarter (16 entries) of value q = lane / 4; two DPP steps join the quarters
+    const int q = lane >> 2, quarter = lane & 3;
+    T v = (T)0;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) v = dmmv_max(v, sc[q * DE_SKEW + quarter * 16 + e]);
+    v = dmmv_max(v, dpp_mov<DPP_QUAD_XOR1>(v));
+    v = dmmv_max(v, dpp_mov<DPP_QUAD_XOR2>(v));
+    const int32_t k = kbase + q;
+    T bs = (T)0;
+    int64_t bc = -1;
+    if (quarter == 0 && k < nd) {
+        const bool var_ok = var_mask ? var_mask[j] != 0 : true;
+        if (!cand_allowed(kcur, k, radius, var_ok)) v = Limits<T>::inf();
+        const int64_t cidx = j * (int64_t)nd + k;
+        if (scores) scores[cidx] = v;
+        bs = v;
+        bc = cidx;
+    }
+    if (part) {
+        block_argmin(bs, bc, sh_s, sh_c);
+        if (threadIdx.x == 0) {
             Partial<T> p; p.s = bs; p.c = bc;
             part[j * (int64_t)gridDim.y + blockIdx.y] = p;
         }
@@ -108,7 +136,63 @@ __global__ void k_apply_dense(int64_t m, const T* __restrict__ A, int64_t lda, T
     }
 }
 
+// ---- the loop's fused step for matrices of moderate height: one workgroup reduces the
+// arg-min records, decides, and applies the move to r and x --------------------------------
+template <class T>
+__global__ __launch_bounds__(1024) void k_select_apply_dense(
+    int64_t m, int32_t nd, const T* __restrict__ A, int64_t lda, const T* __restrict__ D,
+    T* __restrict__ r, int32_t* __restrict__ kidx, const Partial<T>* __restrict__ part,
+    int64_t n_part, InstState<T>* st, int32_t keep_going, int32_t iters, dmmv_move* trace,
+    T* trace_t) {
+    __shared__ T sh_s[16];
+    __shared__ int64_t sh_c[16];
+    __shared__ int32_t sh_j;
+    __shared__ T sh_delta;
+    if (st[0].done) return;
+    T s = (T)0;
+    int64_t c = -1;
+    for (int64_t q = threadIdx.x; q < n_part; q += blockDim.x) {
+        const Partial<T> pr = part[q];
+        if (rec_less(pr.s, pr.c, s, c)) { s = pr.s; c = pr.c; }
+    }
+    block_argmin(s, c, sh_s, sh_c);
+    if (threadIdx.x == 0) {
+        InstState<T> z = st[0];
+        int32_t j = -1, k = -1;
+        if (c >= 0) { j = (int32_t)(c / nd); k = (int32_t)(c % nd); }
+        const bool improving = c >= 0 && s < z.t;
+        z.best_s = s;
+        z.apply_j = -1; z.apply_k = -1; z.delta = (T)0;      // applied right here
+        sh_j = improving ? j : -1;
+        if (improving) {
+            sh_delta = step_of(D[k], D[kidx[j]], (T)1);
+            if (z.moves < iters) {
+                if (trace) { trace[z.moves].j = j; trace[z.moves].k = k; }
+                if (trace_t) trace_t[z.moves] = s;
+            }
+            z.t = s;
+            z.moves += 1;
+            kidx[j] = k;
+        } else if (!keep_going) {
+            z.done = 1;
+        }
+        st[0] = z;
+    }
+    __syncthreads();
+    const int32_t j = sh_j;
+    if (j < 0) return;
+    const T delta = sh_delta;
+    const T* __restrict__ col = A + lda * (int64_t)j;
+    for (int64_t i = threadIdx.x; i < m; i += blockDim.x) r[i] = dmmv_fma(delta, col[i], r[i]);
+}
+
 // ---- host dispatch ---------------------------------------------------------------------------
+int64_t dense_num_partials(const dmmv_problem& p) {
+    const int64_t tiles = ceil_div(p.nd, DE_KT);
+    const int64_t nw = tiles < DE_MAXW ? tiles : DE_MAXW;
+    return p.n * ceil_div(tiles, nw);
+}
+
 template <class T>
 static dmmv_status residual_t(Ctx* c) {
     if (c->p.m == 0) return DMMV_OK;
@@ -119,28 +203,32 @@ static dmmv_status residual_t(Ctx* c) {
     return DMMV_OK;
 }
 
-template <class T, int KT>
-static dmmv_status eval_launch(Ctx* c, void* scores, bool want_partials) {
-    constexpr int BLOCK = 256;
-    dim3 grid((unsigned)c->p.n, (unsigned)ceil_div(c->p.nd, KT));
+template <class T>
+static dmmv_status eval_t(Ctx* c, void* scores, bool want_partials, bool honor_done) {
+    const int64_t tiles = ceil_div(c->p.nd, DE_KT);
+    const int nw = (int)(tiles < DE_MAXW ? tiles : DE_MAXW);
+    dim3 grid((unsigned)c->p.n, (unsigned)ceil_div(tiles, nw));
     if ((int64_t)grid.x * grid.y != c->n_partials)
         return fail(DMMV_ERR_STATE, "dense evaluation grid does not match the partial-record buffer");
-    hipLaunchKernelGGL((k_eval_dense<T, KT, BLOCK>), grid, dim3(BLOCK), 0, c->stream, c->p.m,
-                       c->p.nd, (const T*)c->p.A_dense, c->p.lda, (const T*)c->D_dev,
+    if (grid.y > 65535) return fail(DMMV_ERR_UNSUPPORTED, "dense path: too many values of D for the launch grid");
+    int64_t rows = DE_STAGE_BYTES / (2 * (int64_t)sizeof(T));
+    if (rows > c->p.m) rows = c->p.m > 0 ? c->p.m : 1;
+    size_t lds = (size_t)rows * 2 * sizeof(T);
+    const size_t scratch = (size_t)nw * DE_KT * DE_SKEW * sizeof(T);
+    if (lds < scratch) lds = scratch;
+    static bool attr_set = false;
+    if (!attr_set) {
+        DMMV_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_eval_dense<T>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 72 * 1024));
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(k_eval_dense<T>, grid, dim3(64 * nw), lds, c->stream, c->p.m, c->p.nd,
+                       (int32_t)rows, (const T*)c->p.A_dense, c->p.lda, (const T*)c->D_dev,
                        (const int32_t*)c->kidx, (const T*)c->r, c->o.radius, c->o.var_mask,
-                       (const InstState<T>*)c->state, (T*)scores,
+                       (const InstState<T>*)c->state, (int32_t)honor_done, (T*)scores,
                        want_partials ? (Partial<T>*)c->partials : nullptr);
     DMMV_LAUNCH_CHECK();
     return DMMV_OK;
-}
-
-template <class T>
-static dmmv_status eval_t(Ctx* c, void* scores, bool want_partials) {
-    switch (dense_ktile(c->p.nd)) {
-        case 16: return eval_launch<T, 16>(c, scores, want_partials);
-        case 8: return eval_launch<T, 8>(c, scores, want_partials);
-        default: return eval_launch<T, 4>(c, scores, want_partials);
-    }
 }
 
 template <class T>
@@ -154,16 +242,31 @@ static dmmv_status apply_t(Ctx* c, bool t_from_score, int32_t iters, dmmv_move* 
     return DMMV_OK;
 }
 
+template <class T>
+static dmmv_status select_apply_t(Ctx* c, int32_t iters, dmmv_move* trace, void* trace_t) {
+    hipLaunchKernelGGL(k_select_apply_dense<T>, dim3(1), dim3(1024), 0, c->stream, c->p.m, c->p.nd,
+                       (const T*)c->p.A_dense, c->p.lda, (const T*)c->D_dev, (T*)c->r, c->kidx,
+                       (const Partial<T>*)c->partials, c->p.n > 0 ? c->n_partials : 0,
+                       (InstState<T>*)c->state, c->o.keep_going, iters, trace, (T*)trace_t);
+    DMMV_LAUNCH_CHECK();
+    return DMMV_OK;
+}
+
 dmmv_status dense_residual(Ctx* c) {
     return c->p.dtype == DMMV_F64 ? residual_t<double>(c) : residual_t<float>(c);
 }
-dmmv_status dense_eval(Ctx* c, void* scores_out, bool want_partials) {
-    return c->p.dtype == DMMV_F64 ? eval_t<double>(c, scores_out, want_partials)
-                                  : eval_t<float>(c, scores_out, want_partials);
+dmmv_status dense_eval(Ctx* c, void* scores_out, bool want_partials, bool honor_done) {
+    return c->p.dtype == DMMV_F64 ? eval_t<double>(c, scores_out, want_partials, honor_done)
+                                  : eval_t<float>(c, scores_out, want_partials, honor_done);
 }
 dmmv_status dense_apply(Ctx* c, bool t_from_score, int32_t iters, dmmv_move* trace, void* trace_t) {
     return c->p.dtype == DMMV_F64 ? apply_t<double>(c, t_from_score, iters, trace, trace_t)
                                   : apply_t<float>(c, t_from_score, iters, trace, trace_t);
+}
+bool dense_has_fused_select_apply(const Ctx* c) { return c->p.m <= DE_FUSED_APPLY_ROWS; }
+dmmv_status dense_select_apply(Ctx* c, int32_t iters, dmmv_move* trace, void* trace_t) {
+    return c->p.dtype == DMMV_F64 ? select_apply_t<double>(c, iters, trace, trace_t)
+                                  : select_apply_t<float>(c, iters, trace, trace_t);
 }
 
 }  // namespace dmmv

@@ -139,6 +139,18 @@ def test_dense_solve_long_trace(dtype):
         assert int(res2.iters_done[0]) == 0 and N(res2.max_violation)[0] == o.t
 
 
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_dense_tall_matrix_several_row_chunks(dtype):
+    """More rows than one staged chunk and than the fused select+apply handles."""
+    inst = random_dense(31, 40001, 3, 5, dtype=dtype)
+    stepwise_check(inst, steps=2)
+    with dmmv().from_instance(inst, DEV) as h:
+        res = dmmv().dmmv_solve(h, T(inst.x0), 12, trace=True)
+    check_single_trace(res, oracle_solve(inst, 12), 12)
+    inst = random_dense(32, 9000, 2, 70, dtype=dtype)      # several value tiles, two chunks (f64)
+    stepwise_check(inst, steps=2)
+
+
 def test_dense_radius_and_mask():
     inst = random_dense(91, 90, 17, 9, dtype=np.float64)
     rng = np.random.default_rng(3)
