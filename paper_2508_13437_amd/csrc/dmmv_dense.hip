@@ -2,8 +2,9 @@
 //
 // A column of A is one variable's move direction, so lanes map to consecutive rows and every
 // load of A or r is a coalesced stream.  A workgroup scores one variable j for up to 64 values
-// of D: it stages the column and r in LDS once (row chunks of up to 64 KiB), and each of its
-// wavefronts keeps KT = 16 running maxima per lane while striding over the staged rows.  The
+// of D: it streams the column and r through two LDS buffers (the next row chunk is in flight
+// in registers while the current one is scored), and each of its wavefronts keeps KT = 16
+// running maxima per lane while striding over the staged rows.  The
 // 16 x 64 lane maxima of a wavefront are reduced through an LDS transpose (each lane folds a
 // quarter of one value's 64 entries, two DPP steps finish), so the reduction costs a few dozen
 // instructions per 16 x m pairs.  The wavefronts' best candidates become one arg-min record
@@ -14,7 +15,7 @@ namespace dmmv {
 
 constexpr int DE_KT = 16;                 // values of D per wavefront
 constexpr int DE_MAXW = 4;                // wavefronts (value tiles) per workgroup
-constexpr int DE_STAGE_BYTES = 64 * 1024; // LDS for one chunk of (column, r)
+constexpr int DE_PF = 4;                  // rows each thread stages per chunk (chunk = PF * threads)
 constexpr int DE_SKEW = 65;               // row stride of the transpose scratch (bank skew)
 constexpr int64_t DE_FUSED_APPLY_ROWS = 32768;   // up to here one workgroup selects AND applies
 
@@ -31,26 +32,28 @@ __global__ void k_residual_dense(int64_t m, int64_t n, const T* __restrict__ A, 
 }
 
 // ---- evaluation ---------------------------------------------------------------------------
-// grid.x = variable j, grid.y = group of blockDim.x/64 value tiles.  Writes the table entries
+// grid.x = variable j, grid.y = group of NW value tiles (NW wavefronts per workgroup).  Writes the table entries
 // of its values (scores != NULL) and one partial arg-min record (part != NULL).
-template <class T>
-__global__ __launch_bounds__(64 * DE_MAXW) void k_eval_dense(
-    int64_t m, int32_t nd, int32_t rows_per_chunk, const T* __restrict__ A, int64_t lda,
+template <class T, int NW>
+__global__ __launch_bounds__(64 * NW) void k_eval_dense(
+    int64_t m, int32_t nd, const T* __restrict__ A, int64_t lda,
     const T* __restrict__ D, const int32_t* __restrict__ kidx, const T* __restrict__ r,
     int32_t radius, const uint8_t* __restrict__ var_mask, const InstState<T>* __restrict__ st,
     int32_t honor_done, T* __restrict__ scores, Partial<T>* __restrict__ part) {
     constexpr int KT = DE_KT;
+    constexpr int PF = DE_PF;
     extern __shared__ __align__(16) unsigned char smem[];
-    T* lds_a = reinterpret_cast<T*>(smem);
-    T* lds_r = lds_a + rows_per_chunk;
+    constexpr int THREADS = 64 * NW;
+    constexpr int rows_per_chunk = PF * THREADS;
+    // two buffers of (column chunk, r chunk), rows_per_chunk rows each
+    T* lds = reinterpret_cast<T*>(smem);
     __shared__ T sh_s[DE_MAXW];
     __shared__ int64_t sh_c[DE_MAXW];
     if (honor_done && st[0].done) return;
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int nw = blockDim.x >> 6;
     const int64_t j = blockIdx.x;
-    const int32_t kbase = (blockIdx.y * nw + w) * KT;
+    const int32_t kbase = (blockIdx.y * NW + w) * KT;
     const int32_t kcur = kidx[j];
     const T dcur = D[kcur];
     T delta[KT], acc[KT];
@@ -61,22 +64,52 @@ __global__ __launch_bounds__(64 * DE_MAXW) void k_eval_dense(
         acc[q] = (T)0;
     }
     const T* __restrict__ col = A + lda * j;
-    for (int64_t c0 = 0; c0 < m; c0 += rows_per_chunk) {
-        const int32_t rc = (int32_t)(m - c0 < rows_per_chunk ? m - c0 : rows_per_chunk);
-        __syncthreads();
-        for (int32_t i = threadIdx.x; i < rc; i += blockDim.x) {
-            lds_a[i] = col[c0 + i];
-            lds_r[i] = r[c0 + i];
+    const int64_t n_chunks = (m + rows_per_chunk - 1) / rows_per_chunk;
+    // Rows past m are staged as (a, r) = (0, 0): their |fma| is 0 and never raises a maximum.
+    // The loads are unconditional on clamped rows so that a whole chunk is in flight at once.
+    T pa[PF], pr[PF];
+    auto fetch = [&](int64_t c0) {
+#pragma unroll
+        for (int u = 0; u < PF; ++u) {
+            const int64_t i = c0 + u * THREADS + threadIdx.x;
+            const int64_t ic = i < m ? i : m - 1;
+            const T a = col[ic];
+            const T x = r[ic];
+            pa[u] = i < m ? a : (T)0;
+            pr[u] = i < m ? x : (T)0;
         }
-        __syncthreads();
-        for (int32_t i = lane; i < rc; i += 64) {
-            const T a = lds_a[i];
-            const T ri = lds_r[i];
+    };
+    auto stash = [&](int buf) {
+        T* la = lds + (size_t)buf * 2 * rows_per_chunk;
+        T* lr = la + rows_per_chunk;
+#pragma unroll
+        for (int u = 0; u < PF; ++u) {
+            la[u * THREADS + threadIdx.x] = pa[u];
+            lr[u * THREADS + threadIdx.x] = pr[u];
+        }
+    };
+    if (n_chunks > 0) {
+        fetch(0);
+        stash(0);
+    }
+    __syncthreads();
+    for (int64_t ch = 0; ch < n_chunks; ++ch) {
+        // rolling prefetch: the next chunk travels while this one is scored (the last pass
+        // re-reads row m-1, which is harmless and keeps the loop free of branches)
+        fetch((ch + 1) * rows_per_chunk);
+        const T* la = lds + (size_t)(ch & 1) * 2 * rows_per_chunk;
+        const T* lr = la + rows_per_chunk;
+#pragma unroll
+        for (int it = 0; it < PF * NW; ++it) {
+            const T a = la[it * 64 + lane];
+            const T ri = lr[it * 64 + lane];
 #pragma unroll
             for (int q = 0; q < KT; ++q) acc[q] = dmmv_max(acc[q], dmmv_abs(dmmv_fma(delta[q], a, ri)));
         }
+        stash((int)((ch + 1) & 1));
+        __syncthreads();
     }
-    __syncthreads();                              // staging area is free: reuse it as scratch
+    // staging area is free (every wavefront passed the loop's last barrier): reuse it as scratch
     T* sc = reinterpret_cast<T*>(smem) + (size_t)w * KT * DE_SKEW;
 #pragma unroll
     for (int q = 0; q < KT; ++q) sc[q * DE_SKEW + lane] = acc[q];
@@ -187,10 +220,11 @@ __global__ __launch_bounds__(1024) void k_select_apply_dense(
 }
 
 // ---- host dispatch ---------------------------------------------------------------------------
+static int dense_wavefronts(int64_t tiles) { return tiles <= 1 ? 1 : tiles == 2 ? 2 : DE_MAXW; }
+
 int64_t dense_num_partials(const dmmv_problem& p) {
     const int64_t tiles = ceil_div(p.nd, DE_KT);
-    const int64_t nw = tiles < DE_MAXW ? tiles : DE_MAXW;
-    return p.n * ceil_div(tiles, nw);
+    return p.n * ceil_div(tiles, dense_wavefronts(tiles));
 }
 
 template <class T>
@@ -206,27 +240,25 @@ static dmmv_status residual_t(Ctx* c) {
 template <class T>
 static dmmv_status eval_t(Ctx* c, void* scores, bool want_partials, bool honor_done) {
     const int64_t tiles = ceil_div(c->p.nd, DE_KT);
-    const int nw = (int)(tiles < DE_MAXW ? tiles : DE_MAXW);
+    const int nw = dense_wavefronts(tiles);
     dim3 grid((unsigned)c->p.n, (unsigned)ceil_div(tiles, nw));
     if ((int64_t)grid.x * grid.y != c->n_partials)
         return fail(DMMV_ERR_STATE, "dense evaluation grid does not match the partial-record buffer");
     if (grid.y > 65535) return fail(DMMV_ERR_UNSUPPORTED, "dense path: too many values of D for the launch grid");
-    int64_t rows = DE_STAGE_BYTES / (2 * (int64_t)sizeof(T));
-    if (rows > c->p.m) rows = c->p.m > 0 ? c->p.m : 1;
-    size_t lds = (size_t)rows * 2 * sizeof(T);
+    const int64_t rows = (int64_t)DE_PF * 64 * nw;           // two (column, r) buffers of this many rows
+    size_t lds = (size_t)rows * 4 * sizeof(T);
     const size_t scratch = (size_t)nw * DE_KT * DE_SKEW * sizeof(T);
-    if (lds < scratch) lds = scratch;
-    static bool attr_set = false;
-    if (!attr_set) {
-        DMMV_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_eval_dense<T>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 72 * 1024));
-        attr_set = true;
-    }
-    hipLaunchKernelGGL(k_eval_dense<T>, grid, dim3(64 * nw), lds, c->stream, c->p.m, c->p.nd,
-                       (int32_t)rows, (const T*)c->p.A_dense, c->p.lda, (const T*)c->D_dev,
-                       (const int32_t*)c->kidx, (const T*)c->r, c->o.radius, c->o.var_mask,
-                       (const InstState<T>*)c->state, (int32_t)honor_done, (T*)scores,
-                       want_partials ? (Partial<T>*)c->partials : nullptr);
+    if (lds < scratch) lds = scratch;                        // at most 33 KiB: no attribute needed
+    auto launch = [&](auto kernel) {
+        hipLaunchKernelGGL(kernel, grid, dim3(64 * nw), lds, c->stream, c->p.m, c->p.nd,
+                           (const T*)c->p.A_dense, c->p.lda, (const T*)c->D_dev,
+                           (const int32_t*)c->kidx, (const T*)c->r, c->o.radius, c->o.var_mask,
+                           (const InstState<T>*)c->state, (int32_t)honor_done, (T*)scores,
+                           want_partials ? (Partial<T>*)c->partials : nullptr);
+    };
+    if (nw == 1) launch(k_eval_dense<T, 1>);
+    else if (nw == 2) launch(k_eval_dense<T, 2>);
+    else launch(k_eval_dense<T, DE_MAXW>);
     DMMV_LAUNCH_CHECK();
     return DMMV_OK;
 }
