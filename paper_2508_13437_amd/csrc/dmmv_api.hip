@@ -43,9 +43,10 @@ struct Bump {
 }  // namespace
 
 int32_t batched_chunk_cols(const dmmv_problem& p) {
-    // enough (instance group, chunk) blocks to fill 256 CUs several times over
+    // 512 workgroups are resident at a time (2 per CU), each for the whole of its chunk: aim at
+    // some 30 rounds of them so that the last, partly filled round costs a few percent at most
     int64_t groups = ceil_div(p.R, 64);
-    int64_t want_chunks = ceil_div(2048, groups);
+    int64_t want_chunks = ceil_div(16384, groups);
     int64_t cols = ceil_div(p.n, want_chunks);
     cols = ceil_div(cols, 32) * 32;
     if (cols < 32) cols = 32;

@@ -112,12 +112,16 @@ __global__ void k_maxabs_batched(int64_t m, int64_t R, const T* __restrict__ r, 
     st[q].t = v;
 }
 
+#ifndef DMMV_BATCHED_RB
+#define DMMV_BATCHED_RB 8      // rows of X and r whose loads are in flight together
+#endif
+
 // ---- evaluation -----------------------------------------------------------------------------
 // grid.x = group of 64 instances, grid.y = chunk of `chunk_cols` variables.  A block has four
 // wavefronts; each takes tiles of TJ variables of the chunk in turn.  For nd > KT the values
 // of D are covered KT at a time.  Xt is the row-major copy of X, so the TJ entries of a row
 // are one scalar load.
-template <class T, int KT, int TJ>
+template <class T, int KT, int TJ, int RB = DMMV_BATCHED_RB>
 __global__ __launch_bounds__(256) void k_eval_batched(
     int64_t m, int64_t n, int64_t R, int32_t nd, int32_t chunk_cols, const T* __restrict__ Xt,
     const T* __restrict__ D, const int32_t* __restrict__ kidx, const T* __restrict__ scale,
@@ -164,8 +168,12 @@ __global__ __launch_bounds__(256) void k_eval_batched(
                         acc[u][v] = (T)0;
                     }
                 if (j0 + TJ <= n) {
+                    // RB rows per pass: all their loads (r in vector registers, the X tile in
+                    // scalar registers) are issued before the first row is scored, so one pass
+                    // of a wavefront computes for longer than the loads of the other resident
+                    // wavefront take.
                     const T* __restrict__ xrow = Xt + j0;
-#pragma unroll 2
+#pragma unroll RB
                     for (int64_t i = 0; i < m; ++i) {
                         const T ri = r[i * R + qc];
                         const T* __restrict__ xp = xrow + i * n;
@@ -195,12 +203,12 @@ __global__ __launch_bounds__(256) void k_eval_batched(
 #pragma unroll
                     for (int u = 0; u < TJ; ++u) {
                         const int64_t j = j0 + u;
-                        if (j >= jend) break;
+                        if (j >= jend) continue;                 // (no break: keeps acc in registers)
                         const bool var_ok = var_mask ? var_mask[q * n + j] != 0 : true;
 #pragma unroll
                         for (int v = 0; v < KT; ++v) {
                             const int32_t k = k0 + v;
-                            if (k >= nd) break;
+                            if (k >= nd) continue;
                             T val = acc[u][v];
                             if (!cand_allowed(kcur[u], k, radius, var_ok)) val = Limits<T>::inf();
                             const int64_t cidx = j * (int64_t)nd + k;
