@@ -186,8 +186,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", type=int, default=3, help="headline workload (1..5)")
     ap.add_argument("--iters", type=int, default=None, help="override iterations per step")
-    ap.add_argument("--others", type=str, default="",
-                    help="comma list of further configs to report in the same line, e.g. 1,2,4")
+    ap.add_argument("--others", type=str, default="1,2,4,5",
+                    help="comma list of further configs reported under other_workloads in the same "
+                         "line ('' for none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget", type=float, default=15.0)
     ap.add_argument("--traffic-probe", type=int, default=0, metavar="REPS",
@@ -225,7 +226,7 @@ def main():
     }
     if "cpu_baseline" in head:
         line["cpu_baseline"] = head["cpu_baseline"]
-    others = [int(v) for v in args.others.split(",") if v.strip()]
+    others = [int(v) for v in args.others.split(",") if v.strip() and int(v) != args.config]
     if others:
         line["other_workloads"] = []
         for idx in others:
