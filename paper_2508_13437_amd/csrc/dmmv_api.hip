@@ -83,7 +83,7 @@ size_t workspace_layout(const dmmv_problem& p, const dmmv_options& o, Ctx* c, ch
         if (gb < 1) gb = 1;
         c->csc_gb = (int32_t)gb;
         const int64_t nseg = (int64_t)c->csc_P * p.n;
-        c->csc_nnzp = p.nnz + 3 * nseg + 4;  // padding bound, plus spare entries for clamped loads
+        c->csc_nnzp = p.nnz + 4 * nseg + 4;  // padding bound (an empty segment holds four pads), plus spare entries
         c->n_partials = ceil_div(p.n, CSC_FIN_BLOCK);
         b.take(&c->partials, (size_t)(c->n_partials > 0 ? c->n_partials : 1) * part_sz);
         b.take(&c->segptr, (size_t)(nseg + 1) * sizeof(int32_t));
@@ -138,9 +138,10 @@ static dmmv_status validate_problem(const dmmv_problem* p) {
         if (p->nnz < 0 || p->nnz > INT32_MAX - 1) return fail(DMMV_ERR_SHAPE, "nnz must be in [0, 2^31-2]");
         if (p->nnz > 0 && (!p->csr_col || !p->csr_val)) return fail(DMMV_ERR_NULL, "csr_col / csr_val is NULL");
         if (p->R != 1 || p->scale) return fail(DMMV_ERR_UNSUPPORTED, "sparse matrices support a single unscaled instance (R = 1, scale = NULL)");
-        // every (row partition, column) segment is padded to a multiple of four entries
+        // every (row partition, column) segment is padded to a multiple of four entries and
+        // holds at least four
         const int64_t parts = p->m / 16384 + 1;
-        if (p->nnz + 3 * parts * p->n > INT32_MAX - 1) return fail(DMMV_ERR_UNSUPPORTED, "sparse matrix too large for 32-bit segment offsets");
+        if (p->nnz + 4 * parts * p->n > INT32_MAX - 1) return fail(DMMV_ERR_UNSUPPORTED, "sparse matrix too large for 32-bit segment offsets");
     }
     if (p->m > 0 && !p->b) return fail(DMMV_ERR_NULL, "b is NULL");
     if (p->scale) {

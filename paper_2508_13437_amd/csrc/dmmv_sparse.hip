@@ -55,7 +55,9 @@ __global__ void k_cscp_scan(int64_t count, int32_t* a, int32_t* fillpos) {
     for (int64_t base = 0; base < count; base += 1024) {
         const int64_t s = base + threadIdx.x;
         const int32_t len = s < count ? a[s + 1] : 0;
-        const int32_t v = (len + SEG_ALIGN - 1) / SEG_ALIGN * SEG_ALIGN;
+        // padded to whole groups of SEG_ALIGN, and never empty: the streaming kernel's lanes
+        // re-read a segment's last group when they have nothing of their own
+        const int32_t v = s < count ? (len > 0 ? (len + SEG_ALIGN - 1) / SEG_ALIGN * SEG_ALIGN : SEG_ALIGN) : 0;
         sh[threadIdx.x] = v;
         __syncthreads();
         for (int off = 1; off < 1024; off <<= 1) {

@@ -5,7 +5,7 @@
 // the other streams) and owns a range of columns holding an equal share of the partition's
 // entries.  A row of 16 lanes takes one column segment, each lane four consecutive entries
 // per pass (one 8-byte load of row offsets, one 16-byte load of values, both coalesced and
-// unconditional with clamped addresses), gathers r from LDS, keeps KT running maxima and
+// unconditional: a lane past its segment re-reads the segment's last four), gathers r from LDS, keeps KT running maxima and
 // reduces them over the 16 lanes with integer DPP max.  Every wavefront keeps DEPTH column
 // groups in flight: the loads of group g + DEPTH*8 go out right after group g is consumed.
 // Output: per partition, the maximum over the touched rows for every (column, value), and
@@ -30,36 +30,24 @@ template <class T>
 struct EntryRegs {
     uint2 ix;
     typename Vec4<T>::type av;
-    bool ok;
 };
 
+// Every segment holds at least one aligned group of four entries (pads included), so a lane
+// whose entries would lie past its segment reads the segment's last group again instead: a
+// repeated entry changes neither a maximum nor a mask, and no lane needs masking.
 template <class T>
 __device__ __forceinline__ void load_entries(EntryRegs<T>& E, const uint16_t* __restrict__ row16,
-                                             const T* __restrict__ cval, int32_t e, int32_t s1,
-                                             int32_t emax) {
-    const int32_t ec = e < emax ? e : emax;       // four spare entries follow the arrays
+                                             const T* __restrict__ cval, int32_t e, int32_t s1) {
+    const int32_t ec = e < s1 ? e : s1 - SEG_ALIGN;
     E.ix = *reinterpret_cast<const uint2*>(row16 + ec);
     E.av = *reinterpret_cast<const typename Vec4<T>::type*>(cval + ec);
-    E.ok = e < s1;
-}
-
-// lanes beyond their segment become pads (offset = partition size -> LDS slot holding 0)
-template <class T>
-__device__ __forceinline__ void mask_entries(EntryRegs<T>& E, uint32_t pad) {
-    const uint32_t pp = pad | (pad << 16);
-    E.ix.x = E.ok ? E.ix.x : pp;
-    E.ix.y = E.ok ? E.ix.y : pp;
-    E.av.x = E.ok ? E.av.x : (T)0;
-    E.av.y = E.ok ? E.av.y : (T)0;
-    E.av.z = E.ok ? E.av.z : (T)0;
-    E.av.w = E.ok ? E.av.w : (T)0;
 }
 
 // fold one pass into the lane's running maxima and reservoir mask
 template <class T, int KT>
 __device__ __forceinline__ void fold_pass(const EntryRegs<T>& E, const T* lds_r, const T (&delta)[KT],
                                           T (&acc)[KT], uint32_t& mask, bool first_tile, T thr,
-                                          int32_t nfast, const int32_t* sh_rloc, uint32_t pad) {
+                                          int32_t nfast, const int32_t* sh_rloc) {
     const uint32_t i0 = E.ix.x & 0xFFFFu, i1 = E.ix.x >> 16, i2 = E.ix.y & 0xFFFFu, i3 = E.ix.y >> 16;
     const T r0 = lds_r[i0], r1 = lds_r[i1], r2 = lds_r[i2], r3 = lds_r[i3];
     if (first_tile) {
@@ -95,7 +83,6 @@ __global__ __launch_bounds__(ST_BLOCK, 4) void k_eval_stream(   // 4 waves per S
     __shared__ int32_t sh_b[ST_COLS + 1];
     __shared__ T sh_dcur[ST_COLS];
     __shared__ int32_t sh_rloc[RES_FAST];
-    __shared__ int32_t sh_long;
     if (honor_done && st[0].done) return;
 
     const int lane = threadIdx.x & 63;
@@ -108,8 +95,6 @@ __global__ __launch_bounds__(ST_BLOCK, 4) void k_eval_stream(   // 4 waves per S
     const int64_t j_hi = blk_lo[p * (gridDim.x + 1) + blockIdx.x + 1];
     const int64_t row0 = (int64_t)p * mp;
     const int32_t rows_here = (int32_t)((m - row0) < mp ? (m - row0) : mp);
-    const uint32_t pad = (uint32_t)mp;
-    const int32_t emax = segptr[(int64_t)P * n];
     const int32_t cnt = res_meta[RES_CNT];
     const int32_t nfast = cnt < RES_FAST ? cnt : RES_FAST;
     const T thr = nfast > 0 ? res_val[nfast - 1] : Limits<T>::inf();
@@ -132,18 +117,11 @@ __global__ __launch_bounds__(ST_BLOCK, 4) void k_eval_stream(   // 4 waves per S
         const int32_t nc = (int32_t)(j_hi - c0 < ST_COLS ? j_hi - c0 : ST_COLS);
         const int32_t nq = (nc + 3) >> 2;
         __syncthreads();                       // previous chunk consumed
-        if (threadIdx.x == 0) sh_long = 0;
-        __syncthreads();
         for (int32_t t = threadIdx.x; t <= nc; t += ST_BLOCK) {
-            const int32_t b0 = sp[c0 + t];
-            sh_b[t] = b0;
-            if (t < nc) {
-                sh_dcur[t] = D[kidx[c0 + t]];
-                if (sp[c0 + t + 1] - b0 > 64) sh_long = 1;     // more than one pass somewhere
-            }
+            sh_b[t] = sp[c0 + t];
+            if (t < nc) sh_dcur[t] = D[kidx[c0 + t]];
         }
         __syncthreads();                       // bounds and current values staged
-        const bool any_long = sh_long != 0;
 
         for (int32_t k0 = 0; k0 < nd; k0 += KT) {
             T dk[KT];
@@ -156,8 +134,8 @@ __global__ __launch_bounds__(ST_BLOCK, 4) void k_eval_stream(   // 4 waves per S
                 const int32_t t = (w + u * ST_WAVES) * 4 + rowid;
                 const bool okc = t < nc;
                 qe[u] = (okc ? sh_b[t] : 0) + sub * SEG_ALIGN;
-                qs1[u] = okc ? sh_b[t + 1] : 0;
-                load_entries<T>(ent[u], row16, cval, qe[u], qs1[u], emax);
+                qs1[u] = okc ? sh_b[t + 1] : SEG_ALIGN;        // no column: entries 0..3, unused
+                load_entries<T>(ent[u], row16, cval, qe[u], qs1[u]);
             }
             if (!r_staged) {
                 // stage this partition of r while the first groups' entries are in flight
@@ -186,19 +164,13 @@ __global__ __launch_bounds__(ST_BLOCK, 4) void k_eval_stream(   // 4 waves per S
 #pragma unroll
                         for (int q = 0; q < KT; ++q) { delta[q] = step_of(dk[q], dcur, (T)1); acc[q] = (T)0; }
                         uint32_t mask = 0;
-                        mask_entries<T>(ent[u], pad);
-                        fold_pass<T, KT>(ent[u], lds_r, delta, acc, mask, k0 == 0, thr, nfast, sh_rloc, pad);
-                        if (any_long) {                        // segments longer than one pass
-                            int32_t left = qs1[u] - (qe[u] - sub * SEG_ALIGN);
-                            left = max(left, __shfl_xor(left, 16, 64));
-                            left = max(left, __shfl_xor(left, 32, 64));
-                            const int32_t passes = __builtin_amdgcn_readfirstlane((left + 63) >> 6);
-                            for (int32_t ps = 1; ps < passes; ++ps) {
-                                EntryRegs<T> more;
-                                load_entries<T>(more, row16, cval, qe[u] + ps * 64, qs1[u], emax);
-                                mask_entries<T>(more, pad);
-                                fold_pass<T, KT>(more, lds_r, delta, acc, mask, k0 == 0, thr, nfast, sh_rloc, pad);
-                            }
+                        fold_pass<T, KT>(ent[u], lds_r, delta, acc, mask, k0 == 0, thr, nfast, sh_rloc);
+                        // segments longer than one pass (rows of 16 lanes diverge here)
+                        const int32_t seg_end = qs1[u];
+                        for (int32_t e = qe[u] - sub * SEG_ALIGN + 64; e < seg_end; e += 64) {
+                            EntryRegs<T> more;
+                            load_entries<T>(more, row16, cval, e + sub * SEG_ALIGN, seg_end);
+                            fold_pass<T, KT>(more, lds_r, delta, acc, mask, k0 == 0, thr, nfast, sh_rloc);
                         }
 #pragma unroll
                         for (int q = 0; q < KT; ++q) acc[q] = row16_max_nonneg(acc[q]);
@@ -216,8 +188,8 @@ __global__ __launch_bounds__(ST_BLOCK, 4) void k_eval_stream(   // 4 waves per S
                         const int32_t t = (g + ST_WAVES * ST_DEPTH) * 4 + rowid;
                         const bool okc = t < nc;
                         qe[u] = (okc ? sh_b[t] : 0) + sub * SEG_ALIGN;
-                        qs1[u] = okc ? sh_b[t + 1] : 0;
-                        load_entries<T>(ent[u], row16, cval, qe[u], qs1[u], emax);
+                        qs1[u] = okc ? sh_b[t + 1] : SEG_ALIGN;
+                        load_entries<T>(ent[u], row16, cval, qe[u], qs1[u]);
                     }
                 }
             }
