@@ -53,6 +53,33 @@ __device__ __forceinline__ uint32_t row16_or(uint32_t v) {
     return v;
 }
 
+// maximum / OR over each aligned run of LANES lanes (4, 8 or 16), result in every lane
+template <int LANES>
+__device__ __forceinline__ float lanes_max_nonneg(float v) {
+    uint32_t u = __float_as_uint(v);
+    u = max(u, dpp_mov_u32<DPP_QUAD_XOR1>(u));
+    u = max(u, dpp_mov_u32<DPP_QUAD_XOR2>(u));
+    if (LANES >= 8) u = max(u, dpp_mov_u32<DPP_ROW_HALF_MIRROR>(u));
+    if (LANES >= 16) u = max(u, dpp_mov_u32<DPP_ROW_MIRROR>(u));
+    return __uint_as_float(u);
+}
+template <int LANES>
+__device__ __forceinline__ double lanes_max_nonneg(double v) {
+    v = dmmv_max(v, dpp_mov<DPP_QUAD_XOR1>(v));
+    v = dmmv_max(v, dpp_mov<DPP_QUAD_XOR2>(v));
+    if (LANES >= 8) v = dmmv_max(v, dpp_mov<DPP_ROW_HALF_MIRROR>(v));
+    if (LANES >= 16) v = dmmv_max(v, dpp_mov<DPP_ROW_MIRROR>(v));
+    return v;
+}
+template <int LANES>
+__device__ __forceinline__ uint32_t lanes_or(uint32_t v) {
+    v |= dpp_mov_u32<DPP_QUAD_XOR1>(v);
+    v |= dpp_mov_u32<DPP_QUAD_XOR2>(v);
+    if (LANES >= 8) v |= dpp_mov_u32<DPP_ROW_HALF_MIRROR>(v);
+    if (LANES >= 16) v |= dpp_mov_u32<DPP_ROW_MIRROR>(v);
+    return v;
+}
+
 template <class T> struct Vec4;
 template <> struct Vec4<float> { typedef float4 type; };
 template <> struct Vec4<double> { typedef double4 type; };

@@ -3,11 +3,12 @@
 // k_eval_stream.  grid = (workgroups per partition, partitions).  A workgroup stages ITS
 // partition of r in LDS once (64 KiB, so two workgroups share a compute unit: one stages while
 // the other streams) and owns a range of columns holding an equal share of the partition's
-// entries.  A row of 16 lanes takes one column segment, each lane four consecutive entries
-// per pass (one 8-byte load of row offsets, one 16-byte load of values, both coalesced and
-// unconditional: a lane past its segment re-reads the segment's last four), gathers r from LDS, keeps KT running maxima and
-// reduces them over the 16 lanes with integer DPP max.  Every wavefront keeps DEPTH column
-// groups in flight: the loads of group g + DEPTH*8 go out right after group g is consumed.
+// entries.  ST_LPC adjacent lanes take one column segment, 64 entries per pass: each lane
+// loads aligned groups of four consecutive entries (one 8-byte load of row offsets, one
+// 16-byte load of values, coalesced and unconditional: a lane past its segment re-reads the
+// segment's last group), gathers r from LDS, keeps KT running maxima and reduces them over
+// the column's lanes with integer DPP max.  Every wavefront keeps DEPTH column groups in
+// flight: the loads of group g + DEPTH*8 go out right after group g is consumed.
 // Output: per partition, the maximum over the touched rows for every (column, value), and
 // the mask of the first RES_FAST reservoir rows the column meets in this partition.
 //
@@ -21,15 +22,19 @@ namespace dmmv {
 
 constexpr int ST_BLOCK = 512;
 constexpr int ST_WAVES = ST_BLOCK / 64;
-constexpr int ST_DEPTH = 4;        // column groups a wavefront keeps in flight
+constexpr int ST_LPC = 8;          // lanes that share a column (4, 8 or 16)
+constexpr int ST_QPL = 16 / ST_LPC;    // aligned groups of four entries per lane per pass (64 entries per column)
+constexpr int ST_CPW = 64 / ST_LPC;    // columns a wavefront works on at a time
+constexpr int ST_DEPTH = 4 / ST_QPL > 1 ? 4 / ST_QPL : 2;   // column groups a wavefront keeps in flight
 constexpr int ST_COLS = 1024;      // columns whose bounds / current values sit in LDS at once
 constexpr int FIN_BLOCK = CSC_FIN_BLOCK;
 
-// one pass (64 entries) of one group of four columns, as loaded
+// one pass (64 entries per column) of one group of ST_CPW columns, as loaded: per lane ST_QPL
+// groups of four consecutive entries, 4 * ST_LPC entries apart
 template <class T>
 struct EntryRegs {
-    uint2 ix;
-    typename Vec4<T>::type av;
+    uint2 ix[ST_QPL];
+    typename Vec4<T>::type av[ST_QPL];
 };
 
 // Every segment holds at least one aligned group of four entries (pads included), so a lane
@@ -38,9 +43,13 @@ struct EntryRegs {
 template <class T>
 __device__ __forceinline__ void load_entries(EntryRegs<T>& E, const uint16_t* __restrict__ row16,
                                              const T* __restrict__ cval, int32_t e, int32_t s1) {
-    const int32_t ec = e < s1 ? e : s1 - SEG_ALIGN;
-    E.ix = *reinterpret_cast<const uint2*>(row16 + ec);
-    E.av = *reinterpret_cast<const typename Vec4<T>::type*>(cval + ec);
+#pragma unroll
+    for (int g = 0; g < ST_QPL; ++g) {
+        const int32_t eg = e + g * (SEG_ALIGN * ST_LPC);
+        const int32_t ec = eg < s1 ? eg : s1 - SEG_ALIGN;
+        E.ix[g] = *reinterpret_cast<const uint2*>(row16 + ec);
+        E.av[g] = *reinterpret_cast<const typename Vec4<T>::type*>(cval + ec);
+    }
 }
 
 // fold one pass into the lane's running maxima and reservoir mask
@@ -48,25 +57,28 @@ template <class T, int KT>
 __device__ __forceinline__ void fold_pass(const EntryRegs<T>& E, const T* lds_r, const T (&delta)[KT],
                                           T (&acc)[KT], uint32_t& mask, bool first_tile, T thr,
                                           int32_t nfast, const int32_t* sh_rloc) {
-    const uint32_t i0 = E.ix.x & 0xFFFFu, i1 = E.ix.x >> 16, i2 = E.ix.y & 0xFFFFu, i3 = E.ix.y >> 16;
-    const T r0 = lds_r[i0], r1 = lds_r[i1], r2 = lds_r[i2], r3 = lds_r[i3];
-    if (first_tile) {
-        const T big = dmmv_max(dmmv_max(dmmv_abs(r0), dmmv_abs(r1)), dmmv_max(dmmv_abs(r2), dmmv_abs(r3)));
-        if (big >= thr) {      // uncommon: one of these rows may be among the listed ones
-            for (int32_t q = 0; q < nfast; ++q) {
-                const uint32_t l = (uint32_t)sh_rloc[q];     // offset in this partition or ~0
-                if (i0 == l || i1 == l || i2 == l || i3 == l) mask |= 1u << q;
+#pragma unroll
+    for (int g = 0; g < ST_QPL; ++g) {
+        const uint32_t i0 = E.ix[g].x & 0xFFFFu, i1 = E.ix[g].x >> 16, i2 = E.ix[g].y & 0xFFFFu, i3 = E.ix[g].y >> 16;
+        const T r0 = lds_r[i0], r1 = lds_r[i1], r2 = lds_r[i2], r3 = lds_r[i3];
+        if (first_tile) {
+            const T big = dmmv_max(dmmv_max(dmmv_abs(r0), dmmv_abs(r1)), dmmv_max(dmmv_abs(r2), dmmv_abs(r3)));
+            if (big >= thr) {      // uncommon: one of these rows may be among the listed ones
+                for (int32_t q = 0; q < nfast; ++q) {
+                    const uint32_t l = (uint32_t)sh_rloc[q];     // offset in this partition or ~0
+                    if (i0 == l || i1 == l || i2 == l || i3 == l) mask |= 1u << q;
+                }
             }
         }
-    }
 #pragma unroll
-    for (int q = 0; q < KT; ++q) {
-        T a = acc[q];
-        a = dmmv_max(a, dmmv_abs(dmmv_fma(delta[q], E.av.x, r0)));
-        a = dmmv_max(a, dmmv_abs(dmmv_fma(delta[q], E.av.y, r1)));
-        a = dmmv_max(a, dmmv_abs(dmmv_fma(delta[q], E.av.z, r2)));
-        a = dmmv_max(a, dmmv_abs(dmmv_fma(delta[q], E.av.w, r3)));
-        acc[q] = a;
+        for (int q = 0; q < KT; ++q) {
+            T a = acc[q];
+            a = dmmv_max(a, dmmv_abs(dmmv_fma(delta[q], E.av[g].x, r0)));
+            a = dmmv_max(a, dmmv_abs(dmmv_fma(delta[q], E.av[g].y, r1)));
+            a = dmmv_max(a, dmmv_abs(dmmv_fma(delta[q], E.av[g].z, r2)));
+            a = dmmv_max(a, dmmv_abs(dmmv_fma(delta[q], E.av[g].w, r3)));
+            acc[q] = a;
+        }
     }
 }
 
@@ -87,9 +99,8 @@ __global__ __launch_bounds__(ST_BLOCK, 4) void k_eval_stream(   // 4 waves per S
 
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int sub = lane & 15;                 // position inside the row of 16 lanes
-    const int rowid = lane >> 4;               // which of the wavefront's 4 columns
-    const int32_t P = gridDim.y;
+    const int sub = lane & (ST_LPC - 1);       // position among the lanes of one column
+    const int rowid = lane / ST_LPC;           // which of the wavefront's columns
     const int32_t p = blockIdx.y;
     const int64_t j_lo = blk_lo[p * (gridDim.x + 1) + blockIdx.x];
     const int64_t j_hi = blk_lo[p * (gridDim.x + 1) + blockIdx.x + 1];
@@ -115,7 +126,7 @@ __global__ __launch_bounds__(ST_BLOCK, 4) void k_eval_stream(   // 4 waves per S
 
     for (int64_t c0 = j_lo; c0 < j_hi; c0 += ST_COLS) {
         const int32_t nc = (int32_t)(j_hi - c0 < ST_COLS ? j_hi - c0 : ST_COLS);
-        const int32_t nq = (nc + 3) >> 2;
+        const int32_t nq = (nc + ST_CPW - 1) / ST_CPW;
         __syncthreads();                       // previous chunk consumed
         for (int32_t t = threadIdx.x; t <= nc; t += ST_BLOCK) {
             sh_b[t] = sp[c0 + t];
@@ -131,7 +142,7 @@ __global__ __launch_bounds__(ST_BLOCK, 4) void k_eval_stream(   // 4 waves per S
             int32_t qe[ST_DEPTH], qs1[ST_DEPTH];
 #pragma unroll
             for (int u = 0; u < ST_DEPTH; ++u) {
-                const int32_t t = (w + u * ST_WAVES) * 4 + rowid;
+                const int32_t t = (w + u * ST_WAVES) * ST_CPW + rowid;
                 const bool okc = t < nc;
                 qe[u] = (okc ? sh_b[t] : 0) + sub * SEG_ALIGN;
                 qs1[u] = okc ? sh_b[t + 1] : SEG_ALIGN;        // no column: entries 0..3, unused
@@ -157,7 +168,7 @@ __global__ __launch_bounds__(ST_BLOCK, 4) void k_eval_stream(   // 4 waves per S
                 for (int u = 0; u < ST_DEPTH; ++u) {
                     const int32_t g = g0 + u * ST_WAVES;
                     if (g < nq) {                              // uniform per wavefront
-                        const int32_t t = g * 4 + rowid;
+                        const int32_t t = g * ST_CPW + rowid;
                         const bool col_ok = t < nc;
                         const T dcur = sh_dcur[col_ok ? t : 0];
                         T delta[KT], acc[KT];
@@ -165,16 +176,16 @@ __global__ __launch_bounds__(ST_BLOCK, 4) void k_eval_stream(   // 4 waves per S
                         for (int q = 0; q < KT; ++q) { delta[q] = step_of(dk[q], dcur, (T)1); acc[q] = (T)0; }
                         uint32_t mask = 0;
                         fold_pass<T, KT>(ent[u], lds_r, delta, acc, mask, k0 == 0, thr, nfast, sh_rloc);
-                        // segments longer than one pass (rows of 16 lanes diverge here)
+                        // segments longer than one pass (the columns of a wavefront diverge here)
                         const int32_t seg_end = qs1[u];
-                        for (int32_t e = qe[u] - sub * SEG_ALIGN + 64; e < seg_end; e += 64) {
+                        for (int32_t e = qe[u] + 64; e - sub * SEG_ALIGN < seg_end; e += 64) {
                             EntryRegs<T> more;
-                            load_entries<T>(more, row16, cval, e + sub * SEG_ALIGN, seg_end);
+                            load_entries<T>(more, row16, cval, e, seg_end);
                             fold_pass<T, KT>(more, lds_r, delta, acc, mask, k0 == 0, thr, nfast, sh_rloc);
                         }
 #pragma unroll
-                        for (int q = 0; q < KT; ++q) acc[q] = row16_max_nonneg(acc[q]);
-                        if (k0 == 0) mask = row16_or(mask);
+                        for (int q = 0; q < KT; ++q) acc[q] = lanes_max_nonneg<ST_LPC>(acc[q]);
+                        if (k0 == 0) mask = lanes_or<ST_LPC>(mask);
                         if (sub == 0 && col_ok) {
                             const int64_t j = c0 + t;
 #pragma unroll
@@ -183,9 +194,9 @@ __global__ __launch_bounds__(ST_BLOCK, 4) void k_eval_stream(   // 4 waves per S
                             if (k0 == 0) out_mask[j] = mask;
                         }
                     }
-                    // the group DEPTH*8 further on takes this slot
+                    // the group DEPTH * ST_WAVES further on takes this slot
                     {
-                        const int32_t t = (g + ST_WAVES * ST_DEPTH) * 4 + rowid;
+                        const int32_t t = (g + ST_WAVES * ST_DEPTH) * ST_CPW + rowid;
                         const bool okc = t < nc;
                         qe[u] = (okc ? sh_b[t] : 0) + sub * SEG_ALIGN;
                         qs1[u] = okc ? sh_b[t + 1] : SEG_ALIGN;
