@@ -94,7 +94,8 @@ def cpu_baseline(inst, budget_s: float) -> dict:
                 "sample": f"{rows} of {inst.R} instances x up to {iters} iterations "
                           f"({evals} evaluations), {dt:.1f} s", "host_cores_visible": cores}
     per_iter = inst.nnz * inst.nd
-    iters = int(max(1, min(inst.iters, budget_s * 2.5e8 / max(per_iter, 1))))
+    # the oracle scores about 1e9 pairs/s on one core; only used to size the sample
+    iters = int(max(1, min(inst.iters, budget_s * 1.0e9 / max(per_iter, 1))))
     t0 = time.perf_counter()
     if inst.kind == "csr":
         res = orc.solve_csr(inst.m, inst.n, inst.csr_rowptr, inst.csr_col, inst.csr_val, inst.b,
@@ -150,9 +151,38 @@ def run_config(idx: int, steps: int, warmup: int, iters_override, device: str, d
         "dtype": "f64" if inst.dtype == np.float64 else "f32",
         "roofline": roofline_for(inst, eval_ms), "input_gen_s": round(t_gen, 2),
     })
+    if inst.kind == "batched":
+        out["residual"] = residual_timing(inst, device, x0)
     if do_cpu:
         out["cpu_baseline"] = cpu_baseline(inst, cpu_budget)
     return out
+
+
+def residual_timing(inst, device: str, x0) -> dict:
+    """The one-off batched residual r = (X Q^T) diag(s) - B: the sequential-order VALU kernel
+    (bitwise reproducible, what dmmv_solve uses by default) and the matrix-core kernel
+    (options.residual_mfma), each timed over a few calls with events on the library's stream."""
+    import torch
+    from paper_2508_13437_amd import dmmv
+
+    res = {"flops": 2.0 * inst.m * inst.n * inst.R}
+    for key, opt in (("valu", {}), ("mfma", {"residual_mfma": True})):
+        with dmmv.from_instance(inst, device, **opt) as h:
+            dmmv.dmmv_set_x(h, x0)
+            dmmv.dmmv_residual(h)
+            reps = 3
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(h.stream)
+            for _ in range(reps):
+                dmmv.dmmv_residual(h)
+            e1.record(h.stream)
+            e1.synchronize()
+            ms = e0.elapsed_time(e1) / reps
+        res[key + "_ms"] = ms
+        res[key + "_TFLOPs"] = res["flops"] / (ms * 1e-3) / 1e12
+    res["note"] = ("ms per dmmv_residual call (kernel + max|r| + the copy of r out); mfma: bf16 planes of X "
+                   "(1 when X is bf16-valued, else 3) x bf16-exact codes, fp32 accumulate")
+    return res
 
 
 def traffic_probe(idx: int, device: str, reps: int) -> None:
@@ -224,6 +254,8 @@ def main():
         "final_max_violation": head["final_max_violation"],
         "roofline": head["roofline"],
     }
+    if "residual" in head:
+        line["residual"] = head["residual"]
     if "cpu_baseline" in head:
         line["cpu_baseline"] = head["cpu_baseline"]
     others = [int(v) for v in args.others.split(",") if v.strip() and int(v) != args.config]

@@ -99,10 +99,17 @@ typedef struct {
                                 stream and stops enqueueing once every instance has stopped;
                                 0 = never wait inside the loop                              */
     int32_t sparse_partition_rows; /* sparse matrices: rows per LDS-resident partition of r;
-                                0 = automatic (as many as fit 128 KiB, at most 65536).  A tuning
+                                0 = automatic (as many as fit 64 KiB, at most 65535).  A tuning
                                 and testing knob: results do not depend on it              */
     const uint8_t* var_mask; /* [R][n] nonzero = variable may move (greedy repair works on the
                                 unassigned variables only); NULL = all                      */
+    int32_t residual_mfma;   /* batched fp32 problems whose D is exact in bf16 (integer codes):
+                                1 = dmmv_residual / dmmv_solve compute r = (X Q^T) diag(s) - B on the
+                                matrix cores (X split into bf16 planes that sum to it exactly,
+                                products exact, fp32 accumulation in the instruction's order), so r
+                                agrees with the sequential-order kernel only to fp32 rounding of the
+                                sum; 0 (default) = sequential order, bitwise reproducible.
+                                dmmv_create fails with DMMV_ERR_UNSUPPORTED if 1 is not applicable */
 } dmmv_options;
 
 /* Bytes of device workspace dmmv_create needs for this problem (0 on invalid input, with

@@ -105,6 +105,11 @@ size_t workspace_layout(const dmmv_problem& p, const dmmv_options& o, Ctx* c, ch
         b.take(&c->partials, (size_t)(c->n_partials > 0 ? c->n_partials : 1) * p.R * part_sz);
         b.take(&c->Xt, (size_t)p.m * p.n * esz);
         b.take(&c->Bt, (size_t)p.m * p.R * esz);
+        if (o.residual_mfma) {
+            c->mfma_ldk = mfma_ldk(p.n);
+            b.take(&c->Xp, (size_t)3 * p.m * c->mfma_ldk * sizeof(uint16_t));
+            b.take(&c->Qt, (size_t)p.R * c->mfma_ldk * sizeof(uint16_t));
+        }
     } else {
         c->n_partials = dense_num_partials(p);
         b.take(&c->partials, (size_t)(c->n_partials > 0 ? c->n_partials : 1) * part_sz);
@@ -444,7 +449,10 @@ static dmmv_status residual_any(Ctx* c) {
     switch (c->kind) {
         case KIND_DENSE: DMMV_TRY(dense_residual(c)); break;
         case KIND_CSC: DMMV_TRY(csc_residual(c)); break;
-        default: DMMV_TRY(batched_residual(c)); break;
+        default:
+            if (c->o.residual_mfma) DMMV_TRY(batched_mfma_residual(c));
+            else DMMV_TRY(batched_residual(c));
+            break;
     }
     DMMV_TRY(refresh_t(c));
     c->r_valid = true;
@@ -535,6 +543,18 @@ dmmv_status dmmv_create(dmmv_handle* out, const dmmv_problem* problem, const dmm
     if (options) o = *options;
     if (o.radius < 0 || o.poll_every < 0 || o.sparse_partition_rows < 0)
         return fail(DMMV_ERR_SHAPE, "options: radius, poll_every and sparse_partition_rows must be >= 0");
+    if (o.residual_mfma) {
+        // the matrix-core residual needs fp32, the batched layout and codes that bf16 holds exactly
+        const bool is_batched = !problem->csr_rowptr && (problem->R > 1 || problem->scale);
+        if (problem->dtype != DMMV_F32 || !is_batched)
+            return fail(DMMV_ERR_UNSUPPORTED, "options.residual_mfma needs an fp32 batched problem (R > 1 or scale given)");
+        for (int32_t k = 0; k < problem->nd; ++k) {
+            uint32_t bits;
+            memcpy(&bits, (const float*)problem->D + k, sizeof(bits));
+            if (bits & 0xFFFFu)
+                return fail(DMMV_ERR_UNSUPPORTED, "options.residual_mfma: D[%d] is not exactly representable in bf16", k);
+        }
+    }
     const size_t need = workspace_layout(*problem, o, nullptr, nullptr);
     if (!workspace) return fail(DMMV_ERR_WORKSPACE, "workspace is NULL (%zu bytes needed)", need);
     if (((uintptr_t)workspace & 255) != 0) return fail(DMMV_ERR_WORKSPACE, "workspace must be 256-byte aligned");
@@ -573,6 +593,14 @@ dmmv_status dmmv_create(dmmv_handle* out, const dmmv_problem* problem, const dmm
         DMMV_LAUNCH_CHECK();
         if (c->kind == KIND_CSC) DMMV_TRY(csc_build(c));
         if (c->kind == KIND_BATCHED) DMMV_TRY(batched_build(c));
+        c->mfma_planes = 1;
+        if (o.residual_mfma) {
+            DMMV_TRY(batched_mfma_build(c));
+            int32_t lower = 0;
+            DMMV_HIP_CHECK(hipMemcpyAsync(&lower, &c->flags[FLAG_PLANES], sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
+            DMMV_HIP_CHECK(hipStreamSynchronize(c->stream));
+            c->mfma_planes |= lower & 6;
+        }
         return check_device_errors(c);
     }();
     if (st != DMMV_OK) { delete c; return st; }

@@ -61,7 +61,7 @@ struct alignas(16) Partial {
 };
 
 // device flag slots
-enum { FLAG_ERROR = 0, FLAG_ACTIVE = 1, FLAG_COUNT = 8 };
+enum { FLAG_ERROR = 0, FLAG_ACTIVE = 1, FLAG_PLANES = 2, FLAG_COUNT = 8 };
 // error bits set by kernels
 enum { ERRBIT_X_NOT_IN_D = 1, ERRBIT_CSR_RANGE = 2, ERRBIT_CSR_DUP = 4, ERRBIT_MOVE_RANGE = 8 };
 
@@ -106,6 +106,11 @@ struct Ctx {
     void* Xt;             // T[m][n] row-major copy of X
     void* Bt;             // T[m][R]
     int32_t chunk_cols;   // columns per chunk of the fused evaluation (n_partials chunks)
+    // batched residual on the matrix cores (options.residual_mfma)
+    void* Xp;             // bf16[3][m][mfma_ldk] planes whose sum is X
+    void* Qt;             // bf16[R][mfma_ldk] current codes D[k_j] per instance
+    int64_t mfma_ldk;     // n rounded up to the K step, zero-filled
+    int32_t mfma_planes;  // bit s set: plane s of Xp is not all zero (bit 0 always)
 };
 
 }  // namespace dmmv
@@ -132,6 +137,9 @@ constexpr int CSC_MAX_PARTITIONS = 1024;
 // ----------------------------------------------------------------------------------------
 // per-path entry points (all enqueue on c->stream)
 // ----------------------------------------------------------------------------------------
+int64_t mfma_ldk(int64_t n);
+dmmv_status batched_mfma_build(Ctx* c);
+dmmv_status batched_mfma_residual(Ctx* c);
 dmmv_status dense_residual(Ctx* c);
 int64_t dense_num_partials(const dmmv_problem& p);    // arg-min records one evaluation writes
 dmmv_status dense_eval(Ctx* c, void* scores_out, bool want_partials, bool honor_done);

@@ -546,3 +546,93 @@ def test_llm_configs_full_sampled_instances(idx, iters, sample):
         fresh = X64 @ (inst.scale[q].astype(np.float64) * x[q]) - inst.b[q]
         assert np.abs(r[q] - fresh).max() <= 1e-5 * max(1.0, np.abs(inst.b[q]).max())
         assert abs(t[q] - np.abs(fresh).max()) <= 1e-5 * np.abs(fresh).max()
+
+
+# ------------------------------------------------------------- batched residual on the matrix cores
+def mfma_residual_check(inst):
+    """r from the matrix-core path against the fp64 definition, element by element.  The
+    path's products are exact (bf16 planes of X times bf16-exact codes), so the error is
+    that of an fp32 accumulation of n terms in some order plus the final fma."""
+    m = dmmv()
+    X64 = inst.A.astype(np.float64)
+    with m.from_instance(inst, DEV, residual_mfma=True) as h:
+        m.dmmv_set_x(h, T(inst.x0))
+        r = N(m.dmmv_residual(h))
+        _, r_state, t = m.dmmv_get_state(h)
+        assert np.array_equal(N(r_state), r)
+        assert np.array_equal(np.abs(r).max(axis=1) if inst.m else np.zeros(inst.R, r.dtype), N(t))
+    ref = np.stack([orc.residual_dense(X64, inst.b[q].astype(np.float64), inst.D.astype(np.float64),
+                                       inst.x0[q].astype(np.float64), scale=float(inst.scale[q]))
+                    for q in range(inst.R)]) if inst.R else np.zeros((0, inst.m))
+    mag = (np.abs(inst.scale.astype(np.float64))[:, None] * np.abs(inst.x0.astype(np.float64))) @ np.abs(X64).T \
+        + np.abs(inst.b.astype(np.float64))
+    tol = (inst.n + 2) * 2.0 ** -24 * mag + 1e-30
+    err = np.abs(r.astype(np.float64) - ref)
+    assert np.all(err <= tol), float((err / tol).max())
+    return r
+
+
+@pytest.mark.parametrize("shape", [(1, 1, 1, 2), (17, 5, 3, 3), (64, 64, 64, 4), (100, 33, 65, 8),
+                                   (130, 70, 130, 16), (257, 129, 200, 16), (300, 200, 129, 8)])
+def test_batched_mfma_residual_random(shape):
+    mm, nn, R, nd = shape
+    print("mfma residual", shape, flush=True)
+    mfma_residual_check(random_batched(4000 + mm + nn, mm, nn, R, nd))
+
+
+def test_batched_mfma_residual_integer_data_is_exact():
+    # small integers: every partial sum is exact in fp32, so any summation order gives the
+    # sequential kernel's bits
+    inst = random_batched(4100, 96, 40, 70, 5, integer=True)
+    r = mfma_residual_check(inst)
+    m = dmmv()
+    with m.from_instance(inst, DEV) as h:
+        m.dmmv_set_x(h, T(inst.x0))
+        assert np.array_equal(N(m.dmmv_residual(h)), r)
+
+
+@pytest.mark.parametrize("idx", [4, 5])
+def test_batched_mfma_residual_small_llm_configs(idx):
+    # cfg 5 has bf16-valued X (one plane), cfg 4 needs all three
+    mfma_residual_check(make_config(idx, "small"))
+
+
+def test_batched_mfma_solve_is_consistent():
+    m = dmmv()
+    inst = make_config(4, "small")
+    iters = 12
+    with m.from_instance(inst, DEV, residual_mfma=True) as h:
+        res = m.dmmv_solve(h, T(inst.x0), iters, trace=True)
+        x, r, t = m.dmmv_get_state(h)
+        x, r, t = N(x), N(r), N(t)
+        assert np.array_equal(np.abs(r).max(axis=1), t)
+        assert np.array_equal(N(res.max_violation), t)
+        tt = N(res.trace_t)
+        for q in range(inst.R):
+            d = int(res.iters_done[q])
+            assert np.all(np.diff(tt[q, :d]) < 0)
+        fresh = (inst.scale.astype(np.float64)[:, None] * x) @ inst.A.astype(np.float64).T - inst.b
+        assert np.abs(r - fresh).max() <= 1e-4 * (np.abs(inst.b).max() + 1.0)
+    # the sequential-order path ends within 1e-5 relative of it (same descent up to near-ties)
+    with m.from_instance(inst, DEV) as h:
+        res0 = m.dmmv_solve(h, T(inst.x0), iters)
+        t0 = N(res0.max_violation)
+    assert np.median(np.abs(t - t0) / t0) <= 1e-5
+
+
+def test_batched_mfma_not_applicable_is_an_error():
+    m = dmmv()
+    inst = random_batched(4200, 20, 6, 4, 3)
+    D_bad = inst.D.copy()
+    D_bad[0] = np.float32(-1.0009765625) * 3                       # needs more than 8 significand bits
+    with pytest.raises(m.DmmvError) as e:
+        m.Handle(D=np.sort(D_bad), b=T(inst.b), A=T(inst.A.T).t(), scale=inst.scale, residual_mfma=True)
+    assert e.value.status == -8
+    d = random_dense(4201, 20, 6, 3, dtype=np.float32)
+    with pytest.raises(m.DmmvError) as e:
+        m.Handle(D=d.D, b=T(d.b), A=T(d.A.T).t(), residual_mfma=True)
+    assert e.value.status == -8
+    b64 = random_batched(4202, 20, 6, 4, 3, dtype=np.float64)
+    with pytest.raises(m.DmmvError) as e:
+        m.Handle(D=b64.D, b=T(b64.b), A=T(b64.A.T).t(), scale=b64.scale, residual_mfma=True)
+    assert e.value.status == -8
