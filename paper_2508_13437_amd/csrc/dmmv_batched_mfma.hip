@@ -4,8 +4,8 @@
 // then r[i][q] = fma(acc, s_q, -b[i][q]).  The codes D[k] are exact in bf16, and X is cut into
 // up to three bf16 planes whose sum is X exactly (8 + 8 + 8 significand bits, by truncation),
 // so every product the matrix cores form is exact in fp32 and only the fp32 accumulation rounds.
-// The summation order differs from the sequential kernel's, so this path is checked against the
-// oracle to a tolerance instead of bitwise, and is used only when the caller asks for it.
+// The summation order differs from the sequential kernel's, so its result agrees with that
+// kernel's only to the rounding of an fp32 sum, and it is used only when the caller asks for it.
 //
 // Layouts: Xp[plane][m][ldk] and Qt[R][ldk] in bf16, ldk = n rounded up to the K step and
 // zero-filled, so both operands of C = Xp * Qt^T are read along K.
