@@ -209,6 +209,24 @@ def traffic_probe(idx: int, device: str, reps: int) -> None:
                       "algorithmic_bytes_per_launch": algorithmic_bytes_per_eval(inst)}))
 
 
+def residual_probe(idx: int, device: str, reps: int) -> None:
+    """For `rocprofv3 --pmc` runs on the matrix-core residual: `reps` calls of dmmv_residual
+    with options.residual_mfma on batched workload idx, nothing else."""
+    import torch
+    from paper_2508_13437_amd import dmmv
+    from workloads import make_config
+
+    inst = make_config(idx)
+    x0 = torch.from_numpy(np.ascontiguousarray(inst.x0)).to(device)
+    with dmmv.from_instance(inst, device, residual_mfma=True) as h:
+        dmmv.dmmv_set_x(h, x0)
+        for _ in range(reps):
+            dmmv.dmmv_residual(h)
+        torch.cuda.synchronize()
+    print(json.dumps({"probe": inst.name, "residual_calls": reps,
+                      "useful_flops_per_call": 2.0 * inst.m * inst.n * inst.R}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -224,6 +242,8 @@ def main():
     ap.add_argument("--traffic-probe", type=int, default=0, metavar="REPS",
                     help="only launch the evaluation kernel REPS times plus a calibration copy "
                          "(for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs)")
+    ap.add_argument("--residual-probe", type=int, default=0, metavar="REPS",
+                    help="only run the matrix-core batched residual REPS times (for rocprofv3 --pmc runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
@@ -236,6 +256,9 @@ def main():
     device = "cuda:0"
     if args.traffic_probe > 0:
         traffic_probe(args.config, device, args.traffic_probe)
+        return
+    if args.residual_probe > 0:
+        residual_probe(args.config, device, args.residual_probe)
         return
     default_steps = {1: 20, 2: 10, 3: 5, 4: 1, 5: 1}
     steps = args.steps if args.steps is not None else default_steps[args.config]

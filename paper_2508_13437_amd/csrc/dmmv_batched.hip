@@ -102,14 +102,23 @@ __global__ __launch_bounds__(256) void k_residual_batched(
     }
 }
 
-// per-instance max |r|: lane = instance, serial over rows
+// per-instance max |r|: lane = instance, the 16 wavefronts of a workgroup share the rows
 template <class T>
-__global__ void k_maxabs_batched(int64_t m, int64_t R, const T* __restrict__ r, InstState<T>* st) {
-    const int64_t q = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
-    if (q >= R) return;
+__global__ __launch_bounds__(1024) void k_maxabs_batched(int64_t m, int64_t R, const T* __restrict__ r,
+                                                         InstState<T>* st) {
+    __shared__ T sh[16][64];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int64_t q = blockIdx.x * 64ll + lane;
     T v = (T)0;
-    for (int64_t i = 0; i < m; ++i) v = dmmv_max(v, dmmv_abs(r[i * R + q]));
-    st[q].t = v;
+    if (q < R)
+        for (int64_t i = w; i < m; i += 16) v = dmmv_max(v, dmmv_abs(r[i * R + q]));
+    sh[w][lane] = v;
+    __syncthreads();
+    if (w == 0 && q < R) {
+#pragma unroll
+        for (int ww = 1; ww < 16; ++ww) v = dmmv_max(v, sh[ww][lane]);
+        st[q].t = v;
+    }
 }
 
 #ifndef DMMV_BATCHED_RB
@@ -298,7 +307,7 @@ static dmmv_status residual_t(Ctx* c) {
 
 template <class T>
 static dmmv_status maxabs_t(Ctx* c) {
-    hipLaunchKernelGGL(k_maxabs_batched<T>, dim3((unsigned)ceil_div(c->p.R, 64)), dim3(64), 0, c->stream,
+    hipLaunchKernelGGL(k_maxabs_batched<T>, dim3((unsigned)ceil_div(c->p.R, 64)), dim3(1024), 0, c->stream,
                        c->p.m, c->p.R, (const T*)c->r, (InstState<T>*)c->state);
     DMMV_LAUNCH_CHECK();
     return DMMV_OK;
