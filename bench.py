@@ -34,7 +34,7 @@ FLOPS_PER_PAIR = 3          # multiply + add of the fma, and the max; |.| is an 
 # HBM bytes per launch of the evaluation kernel, from rocprofv3 FETCH_SIZE + WRITE_SIZE runs
 # calibrated against a plain copy (summaries under profiles/hbm_traffic_*.md)
 MEASURED_TRAFFIC_BYTES = {
-    "tomography_256x256_180x363_csr_f32": 100.4e6,
+    "tomography_256x256_180x363_csr_f32": 100.2e6,
 }
 
 
