@@ -12,17 +12,24 @@
  * score table against fresh recomputation of ||A x' - b||_inf, maintained residual
  * against recomputation, monotone objective, Chebyshev LP lower bound, the
  * Subset-Sum (m = 1, D = {0,1}) and A = I closed forms, sparse against dense.
+ * The ALNS outer loop (alns_*.inc) has pins of its own: published SplitMix64 outputs, the
+ * library exponential, the three bound equations of the worst-remove operator evaluated
+ * literally, draw frequencies, greedy repair against fresh recomputation, and the loop's
+ * invariants.
  */
 #include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
 
+#include "alns_common.inc"
+
 #define REAL double
 #define SFX(x) x##_f64
 #define FMA fma
 #define FABS fabs
 #include "dmmv_oracle_impl.inc"
+#include "alns_oracle_impl.inc"
 #undef REAL
 #undef SFX
 #undef FMA
@@ -33,6 +40,7 @@
 #define FMA fmaf
 #define FABS fabsf
 #include "dmmv_oracle_impl.inc"
+#include "alns_oracle_impl.inc"
 #undef REAL
 #undef SFX
 #undef FMA

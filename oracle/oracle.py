@@ -299,3 +299,135 @@ def solve_batched(X, B, D, scale, x0, iters, radius=0) -> BatchedResult:
         _p(B), _p(D), _p(scale), _p(k), C.c_int32(iters), C.c_int32(radius), _p(t), _p(done),
         _p(tj), _p(tk), _p(tt))
     return BatchedResult(D[k], t, done, tj, tk, tt)
+
+
+# ------------------------------------------------------------------------------ ALNS outer loop
+class AlnsParams(C.Structure):
+    """Parameter block of the ALNS loop (Algorithm 1; Appendix F for alpha and the destroy rate)."""
+    _fields_ = [("iters", C.c_int32), ("ls_moves", C.c_int32), ("ls_radius", C.c_int32),
+                ("destroy_count", C.c_int32), ("alpha", C.c_double), ("lambda_", C.c_double),
+                ("sigma1", C.c_double), ("sigma2", C.c_double), ("sigma3", C.c_double),
+                ("seed", C.c_uint64)]
+
+
+def alns_params(iters, ls_moves=8, ls_radius=1, destroy_count=0, alpha=0.3, lambda_=0.2,
+                sigma1=3.0, sigma2=2.0, sigma3=1.0, seed=1) -> AlnsParams:
+    return AlnsParams(int(iters), int(ls_moves), int(ls_radius), int(destroy_count), float(alpha),
+                      float(lambda_), float(sigma1), float(sigma2), float(sigma3), int(seed))
+
+
+@dataclass
+class AlnsResult:
+    x: np.ndarray            # best solution (values of D)
+    t_best: float
+    destroy: np.ndarray      # [iters] 0 random, 1 worst-remove
+    repair: np.ndarray       # [iters] 0 random, 1 greedy
+    moves: np.ndarray        # [iters] moves of the local search
+    accepted: np.ndarray     # [iters]
+    t: np.ndarray            # [iters] error after the local search
+    best: np.ndarray         # [iters] best error so far
+    weights: np.ndarray      # [4] final operator weights
+
+
+def alns_mix(z: int) -> int:
+    lib().oracle_alns_mix.restype = C.c_uint64
+    return int(lib().oracle_alns_mix(C.c_uint64(z & (2 ** 64 - 1))))
+
+
+def alns_rnd(seed: int, inst: int, it: int, stream: int, c: int) -> int:
+    lib().oracle_alns_rnd.restype = C.c_uint64
+    return int(lib().oracle_alns_rnd(C.c_uint64(seed), C.c_uint64(inst), C.c_uint64(it),
+                                     C.c_uint64(stream), C.c_uint64(c)))
+
+
+def alns_expneg(y: float) -> float:
+    lib().oracle_alns_expneg.restype = C.c_double
+    return float(lib().oracle_alns_expneg(C.c_double(y)))
+
+
+def full_csr(A):
+    """A dense matrix as CSR with EVERY entry stored (zeros included), columns ascending."""
+    A = np.asarray(A)
+    m, n = A.shape
+    rowptr = (np.arange(m + 1, dtype=np.int64) * n)
+    col = np.tile(np.arange(n, dtype=np.int32), m)
+    val = np.ascontiguousarray(A, dtype=A.dtype).reshape(-1).copy()
+    return rowptr, col, val
+
+
+def _csc_of(m, n, rowptr, col, val, dt):
+    nnz = int(rowptr[m])
+    colptr = np.empty(n + 1, dtype=np.int64)
+    rowidx = np.empty(max(nnz, 1), dtype=np.int32)
+    cval = np.empty(max(nnz, 1), dtype=dt)
+    _fn("oracle_csr_to_csc", dt)(C.c_int64(m), C.c_int64(n), _p(rowptr), _p(col), _p(val),
+                                 _p(colptr), _p(rowidx), _p(cval))
+    return colptr, rowidx, cval
+
+
+def alns_impact_weights(m, n, rowptr, col, val, r, alpha=0.3, scale=1.0) -> np.ndarray:
+    dt = np.asarray(val).dtype
+    rowptr = np.ascontiguousarray(rowptr, dtype=np.int64)
+    col = np.ascontiguousarray(col, dtype=np.int32)
+    val = np.ascontiguousarray(val)
+    colptr, rowidx, cval = _csc_of(m, n, rowptr, col, val, dt)
+    r = np.ascontiguousarray(r, dtype=dt)
+    w = np.empty(max(n, 1), dtype=np.uint64)
+    _fn("oracle_alns_impact_weights", dt)(C.c_int64(m), C.c_int64(n), _p(colptr), _p(rowidx), _p(cval),
+                                          _real(dt)(scale), _p(r), C.c_double(alpha), _p(w))
+    return w[:n]
+
+
+def alns_sample(n, weight, count, seed, inst, it) -> np.ndarray:
+    w = None if weight is None else np.ascontiguousarray(weight, dtype=np.uint64)
+    picked = np.full(max(n, 1), -1, dtype=np.int32)
+    lib().oracle_alns_sample(C.c_int64(n), _p(w), C.c_int64(count), C.c_uint64(seed), C.c_uint64(inst),
+                             C.c_uint64(it), _p(picked))
+    return picked[:min(count, n)]
+
+
+def alns_repair(m, n, rowptr, col, val, D, x, r, picked, greedy, seed, inst, it, scale=1.0):
+    """Returns (x, r) after reassigning the picked variables."""
+    dt = np.asarray(D).dtype
+    rowptr = np.ascontiguousarray(rowptr, dtype=np.int64)
+    col = np.ascontiguousarray(col, dtype=np.int32)
+    val = np.ascontiguousarray(val, dtype=dt)
+    colptr, rowidx, cval = _csc_of(m, n, rowptr, col, val, dt)
+    D = np.ascontiguousarray(D)
+    k = values_to_index(x, D)
+    r = np.ascontiguousarray(r, dtype=dt).copy()
+    picked = np.ascontiguousarray(picked, dtype=np.int32)
+    _fn("oracle_alns_repair", dt)(C.c_int64(m), C.c_int32(D.size), _p(colptr), _p(rowidx), _p(cval), _p(D),
+                                  _real(dt)(scale), _p(k), _p(r), C.c_int64(picked.size), _p(picked),
+                                  C.c_int32(int(greedy)), C.c_uint64(seed), C.c_uint64(inst), C.c_uint64(it))
+    return D[k], r
+
+
+def alns_csr(m, n, rowptr, col, val, b, D, x0, params: AlnsParams, inst=0, scale=1.0) -> AlnsResult:
+    dt = np.asarray(D).dtype
+    rowptr = np.ascontiguousarray(rowptr, dtype=np.int64)
+    col = np.ascontiguousarray(col, dtype=np.int32)
+    val = np.ascontiguousarray(val, dtype=dt)
+    b = np.ascontiguousarray(b, dtype=dt)
+    D = np.ascontiguousarray(D)
+    k = values_to_index(x0, D)
+    it = max(int(params.iters), 1)
+    tr = [np.zeros(it, dtype=np.int32) for _ in range(4)]
+    tr_t, tr_best = np.zeros(it, dtype=dt), np.zeros(it, dtype=dt)
+    w = np.zeros(4, dtype=np.float64)
+    f = _fn("oracle_alns", dt)
+    f.restype = _real(dt)
+    t_best = f(C.c_int64(m), C.c_int64(n), C.c_int32(D.size), _p(rowptr), _p(col), _p(val), _p(b), _p(D),
+               _real(dt)(scale), _p(k), C.byref(params), C.c_uint64(inst), _p(tr[0]), _p(tr[1]), _p(tr[2]),
+               _p(tr[3]), _p(tr_t), _p(tr_best), _p(w))
+    q = int(params.iters)
+    return AlnsResult(D[k], float(t_best), tr[0][:q], tr[1][:q], tr[2][:q], tr[3][:q], tr_t[:q],
+                      tr_best[:q], w)
+
+
+def alns_dense(A, b, D, x0, params: AlnsParams, inst=0, scale=1.0) -> AlnsResult:
+    """A dense matrix is the sparse case with every entry stored."""
+    dt = np.asarray(D).dtype
+    A = np.asarray(A, dtype=dt)
+    rowptr, col, val = full_csr(A)
+    return alns_csr(A.shape[0], A.shape[1], rowptr, col, val, b, D, x0, params, inst, scale)

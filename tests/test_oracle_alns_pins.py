@@ -1,0 +1,226 @@
+"""Pins of the ALNS part of the CPU oracle (Algorithm 1; Appendix B operators) against facts
+that do not come from the oracle: published generator outputs, the library exponential, the
+paper's bound equations evaluated literally, brute force, and invariants of the loop."""
+import itertools
+import json
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import oracle as orc
+from workloads import random_dense, random_sparse
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+M64 = 2 ** 64 - 1
+GOLDEN = 0x9E3779B97F4A7C15
+
+
+def test_mix_reproduces_published_splitmix64_outputs():
+    g = json.load(open(os.path.join(HERE, "golden", "splitmix64_seed1234567.json")))
+    state = g["seed"]
+    for want in g["outputs"]:
+        state = (state + GOLDEN) & M64
+        assert orc.alns_mix(state) == int(want)
+
+
+def test_rnd_is_a_chain_of_generator_steps_and_streams_differ():
+    # first link = first SplitMix64 output of the seed (instance 0)
+    seed = 1234567
+    z = orc.alns_mix((seed + GOLDEN) & M64)
+    for ctr in (3, 0, 5):                       # it, stream, c
+        z = orc.alns_mix((z + GOLDEN * (ctr + 1)) & M64)
+    assert orc.alns_rnd(seed, 0, 3, 0, 5) == z
+    vals = {orc.alns_rnd(9, q, it, s, c) for q in range(3) for it in range(3) for s in range(3) for c in range(3)}
+    assert len(vals) == 81
+
+
+def test_expneg_matches_the_library_exponential():
+    rng = np.random.default_rng(1)
+    ys = np.concatenate([np.linspace(0, 50, 2001), rng.uniform(0, 699.9, 2000), [0.0, 1e-300, 1e-12, 699.99]])
+    for y in ys:
+        got, want = orc.alns_expneg(float(y)), math.exp(-float(y))
+        assert abs(got - want) <= 4e-16 * want, (y, got, want)
+    assert orc.alns_expneg(0.0) == 1.0
+    assert orc.alns_expneg(700.0) == 0.0 and orc.alns_expneg(float("inf")) == 0.0
+    assert orc.alns_expneg(float("nan")) == 0.0
+
+
+def literal_impact(A, b, x, alpha):
+    """Appendix B.2 as printed: LB, UB, R, then the numerator of d_j and sum |s_k|."""
+    A = np.asarray(A, dtype=np.float64); b = np.asarray(b, dtype=np.float64); x = np.asarray(x, dtype=np.float64)
+    s = A @ x - b
+    t = np.abs(s).max()
+    m, n = A.shape
+    num = np.zeros(n)
+    Rs = np.zeros((m, n))
+    for j in range(n):
+        for k in range(m):
+            rest = A[k] @ x - A[k, j] * x[j]             # sum_{i != j} a_ki x_i
+            lb = (-t + b[k] - rest) / A[k, j]
+            ub = (t + b[k] - rest) / A[k, j]
+            R = min(ub - x[j], x[j] - lb) if A[k, j] > 0 else min(lb - x[j], x[j] - ub)
+            Rs[k, j] = R
+            num[j] += abs(s[k]) * math.exp(-alpha * R)
+    return s, t, Rs, num
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_impact_weights_follow_the_bound_equations(seed):
+    inst = random_dense(100 + seed, 14, 6, 5)
+    A = inst.A.astype(np.float64)
+    assert np.all(A != 0)
+    s, t, Rs, num = literal_impact(A, inst.b, inst.x0, 0.3)
+    # the collapse used by the oracle: R = (t - |s_k|) / |a_kj| >= 0
+    assert np.allclose(Rs, (t - np.abs(s))[:, None] / np.abs(A), rtol=1e-9, atol=1e-9)
+    rowptr, col, val = orc.full_csr(A)
+    r = orc.residual_dense(A, inst.b, inst.D, inst.x0)
+    w = orc.alns_impact_weights(inst.m, inst.n, rowptr, col, val, r, alpha=0.3).astype(np.float64)
+    e = math.frexp(t)[1]
+    scale = 2.0 ** (24 - e)
+    # fixed point with truncation: each of the m terms loses less than 1
+    assert np.all(np.abs((w - 1) - num * scale) <= inst.m + 1e-6 * num * scale)
+    # proportions are those of the paper's d_j
+    assert np.allclose((w - 1) / (w - 1).sum(), num / num.sum(), atol=1e-5)
+
+
+def test_impact_weight_ignores_rows_with_zero_coefficient_and_handles_zero_residual():
+    A = np.array([[1.0, 0.0], [0.0, 2.0], [1.0, 1.0]])
+    D = np.array([0.0, 1.0, 2.0]); x = np.array([1.0, 1.0]); b = A @ x
+    rowptr, col, val = orc.full_csr(A)
+    w = orc.alns_impact_weights(3, 2, rowptr, col, val, np.zeros(3), alpha=0.3)
+    assert np.array_equal(w, [1, 1])                       # t = 0: nothing to weigh
+    r = np.array([0.5, -0.25, 0.125])
+    w_full = orc.alns_impact_weights(3, 2, rowptr, col, val, r, alpha=0.3)
+    # dropping the explicit zeros from the storage changes nothing
+    keep = val != 0
+    rp = np.concatenate([[0], np.cumsum([keep[i * 2:(i + 1) * 2].sum() for i in range(3)])]).astype(np.int64)
+    w_sparse = orc.alns_impact_weights(3, 2, rp, col[keep], val[keep], r, alpha=0.3)
+    assert np.array_equal(w_full, w_sparse)
+
+
+def test_sample_distinct_ordered_and_proportional():
+    n = 50
+    p = orc.alns_sample(n, None, n, 3, 0, 0)
+    assert sorted(p.tolist()) == list(range(n))            # all of them: a permutation
+    p = orc.alns_sample(n, None, 7, 3, 0, 1)
+    assert len(set(p.tolist())) == 7 and p.min() >= 0 and p.max() < n
+    # the first draw is the first variable whose prefix sum exceeds rnd mod total
+    w = np.array([5, 1, 10, 4], dtype=np.uint64)
+    for it in range(20):
+        v = orc.alns_rnd(11, 2, it, 1, 0) % 20
+        want = int(np.searchsorted(np.cumsum(w.astype(np.int64)), v, side="right"))
+        assert orc.alns_sample(4, w, 1, 11, 2, it)[0] == want
+    # frequencies of single draws follow the weights
+    counts = np.zeros(4)
+    N = 6000
+    for it in range(N):
+        counts[orc.alns_sample(4, w, 1, 5, 0, it)[0]] += 1
+    expect = N * w.astype(np.float64) / 20
+    chi2 = ((counts - expect) ** 2 / expect).sum()
+    assert chi2 < 16.3                                     # 99.9 % point of chi-square with 3 dof
+
+
+def test_greedy_repair_is_the_better_of_the_two_neighbour_levels():
+    inst = random_dense(321, 18, 7, 6)
+    A = inst.A.astype(np.float64)
+    rowptr, col, val = orc.full_csr(A)
+    D = inst.D
+    x = inst.x0.copy()
+    x[0], x[1] = D[0], D[-1]                               # two variables at the ends of D
+    r = orc.residual_dense(A, inst.b, D, x)
+    picked = np.array([3, 0, 1, 5], dtype=np.int32)
+    x_new, r_new = orc.alns_repair(inst.m, inst.n, rowptr, col, val, D, x, r, picked, True, 1, 0, 0)
+    xs = x.copy()
+    for j in picked:
+        k = int(np.searchsorted(D, xs[j]))
+        cands = [kk for kk in (k - 1, k + 1) if 0 <= kk < D.size]
+        errs = []
+        for kk in cands:
+            y = xs.copy(); y[j] = D[kk]
+            errs.append(np.abs(A @ y - inst.b).max())
+        best = cands[int(np.argmin(errs))]                 # argmin takes the lower level on a tie
+        assert abs(errs[0] - errs[-1]) > 1e-9 or len(cands) == 1
+        xs[j] = D[best]
+    assert np.array_equal(x_new, xs)
+    assert np.allclose(r_new, A @ xs - inst.b, atol=1e-9)
+
+
+def test_random_repair_follows_the_generator_bit():
+    inst = random_dense(322, 10, 6, 5)
+    rowptr, col, val = orc.full_csr(inst.A)
+    D = inst.D
+    x = np.full(inst.n, D[2])
+    x[4] = D[0]
+    r = orc.residual_dense(inst.A, inst.b, D, x)
+    picked = np.array([2, 4, 0], dtype=np.int32)
+    x_new, r_new = orc.alns_repair(inst.m, inst.n, rowptr, col, val, D, x, r, picked, False, 77, 3, 9)
+    for pos, j in enumerate(picked):
+        up = orc.alns_rnd(77, 3, 9, 2, pos) & 1
+        k = int(np.searchsorted(D, x[j]))
+        want = k + 1 if (up or k == 0) else k - 1
+        assert x_new[j] == D[want]
+    assert np.allclose(r_new, inst.A @ x_new - inst.b, atol=1e-9)
+
+
+@pytest.mark.parametrize("kind,dtype", [("dense", np.float64), ("dense", np.float32), ("sparse", np.float32)])
+def test_alns_loop_invariants(kind, dtype):
+    if kind == "dense":
+        inst = random_dense(500, 40, 16, 5, dtype=dtype, integer=True)
+        rowptr, col, val = orc.full_csr(inst.A)
+        A = inst.A.astype(np.float64)
+    else:
+        inst = random_sparse(501, 60, 24, 4, 0.3, dtype=dtype, integer=True)
+        rowptr, col, val = inst.csr_rowptr, inst.csr_col, inst.csr_val
+        A = np.zeros((inst.m, inst.n))
+        for i in range(inst.m):
+            A[i, col[rowptr[i]:rowptr[i + 1]]] = val[rowptr[i]:rowptr[i + 1]]
+    prm = orc.alns_params(40, ls_moves=6, ls_radius=1, destroy_count=3, seed=5)
+    res = orc.alns_csr(inst.m, inst.n, rowptr, col, val, inst.b, inst.D, inst.x0, prm)
+    t0 = np.abs(A @ inst.x0.astype(np.float64) - inst.b).max()
+    # best error: never increases, starts no worse than x0, and belongs to the returned x
+    assert np.all(np.diff(res.best) <= 0) and res.best[0] <= t0
+    assert res.t_best == res.best[-1]
+    assert np.abs(A @ res.x.astype(np.float64) - inst.b).max() == res.t_best      # integer data: exact
+    assert np.all(np.isin(res.x, inst.D))
+    # acceptance: not worse than the current solution, whose error is the last accepted one
+    cur = t0
+    for it in range(40):
+        assert bool(res.accepted[it]) == (res.t[it] <= cur)
+        if res.accepted[it]:
+            cur = res.t[it]
+        assert 0 <= res.moves[it] <= 6 and res.destroy[it] in (0, 1) and res.repair[it] in (0, 1)
+    assert set(res.destroy.tolist()) == {0, 1} and set(res.repair.tolist()) == {0, 1}
+    assert np.all(res.weights > 0)
+    # same seed, same run; another seed, another run
+    again = orc.alns_csr(inst.m, inst.n, rowptr, col, val, inst.b, inst.D, inst.x0, prm)
+    assert np.array_equal(again.t, res.t) and np.array_equal(again.x, res.x)
+    other = orc.alns_csr(inst.m, inst.n, rowptr, col, val, inst.b, inst.D, inst.x0,
+                         orc.alns_params(40, ls_moves=6, ls_radius=1, destroy_count=3, seed=6))
+    assert not np.array_equal(other.t, res.t)
+
+
+def test_alns_zero_iterations_and_lower_bound_by_enumeration():
+    inst = random_dense(502, 9, 5, 3, integer=True)
+    rowptr, col, val = orc.full_csr(inst.A)
+    res0 = orc.alns_csr(inst.m, inst.n, rowptr, col, val, inst.b, inst.D, inst.x0, orc.alns_params(0))
+    assert np.array_equal(res0.x, inst.x0)
+    assert res0.t_best == np.abs(inst.A @ inst.x0 - inst.b).max()
+    opt = min(np.abs(inst.A @ np.array(x) - inst.b).max() for x in itertools.product(inst.D, repeat=inst.n))
+    res = orc.alns_csr(inst.m, inst.n, rowptr, col, val, inst.b, inst.D, inst.x0,
+                       orc.alns_params(60, ls_moves=10, ls_radius=0, destroy_count=2, seed=3))
+    assert res.t_best >= opt
+    assert res.t_best <= res0.t_best
+
+
+def test_alns_dense_entry_equals_full_storage_sparse_entry():
+    inst = random_dense(503, 25, 10, 4, dtype=np.float32)
+    prm = orc.alns_params(15, seed=21)
+    a = orc.alns_dense(inst.A, inst.b, inst.D, inst.x0, prm)
+    rowptr, col, val = orc.full_csr(inst.A)
+    b = orc.alns_csr(inst.m, inst.n, rowptr, col, val, inst.b, inst.D, inst.x0, prm)
+    assert np.array_equal(a.t, b.t) and np.array_equal(a.x, b.x)
+    # the first local search of a run that destroys nothing would be the plain descent:
+    # with the repaired variable moved, the descent still reaches a local optimum of the same kind
+    assert a.t_best <= np.abs(inst.A.astype(np.float64) @ inst.x0 - inst.b).max() * (1 + 1e-6)
