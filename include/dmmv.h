@@ -181,6 +181,46 @@ dmmv_status dmmv_solve(dmmv_handle h, const void* x0, int32_t iters, void* x_out
  * changed.  Needs a residual.  Waits for the stream. */
 dmmv_status dmmv_time_eval(dmmv_handle h, int32_t reps, float* ms_out);
 
+/* Parameters of the ALNS outer loop (Algorithm 1 of the paper).  What the paper leaves open is
+ * fixed as stated at each field. */
+typedef struct {
+    int32_t iters;           /* outer iterations: destroy, repair, local search, accept          */
+    int32_t ls_moves;        /* local search: at most this many moves of the single-move descent
+                                per outer iteration (it stops earlier at a local optimum)        */
+    int32_t ls_radius;       /* neighbourhood of the local search, as dmmv_options.radius
+                                (1 = the paper's 1-OPT move to a neighbouring level)              */
+    int32_t destroy_count;   /* variables unassigned per iteration; 0 = 0.5 % of n, at least 1
+                                (Appendix F)                                                     */
+    double alpha;            /* coefficient of the impact score of the worst-remove operator
+                                (Appendix B.2; Appendix F uses 0.3)                              */
+    double lambda;           /* reaction factor of the operator weights (Appendix F.2 names the
+                                roulette wheel, not its update): w <- (1-lambda) w + lambda psi,
+                                only after an accepted iteration, as in Algorithm 1              */
+    double sigma1, sigma2, sigma3; /* psi: new best / better than the current solution / accepted
+                                without improvement                                              */
+    uint64_t seed;           /* every random decision is a function of (seed, iteration, stream,
+                                counter): two runs with the same seed are identical              */
+} dmmv_alns_params;
+
+/* Algorithm 1 of the paper around the single-move descent, single dense or sparse instances
+ * (R = 1, no scale).  Per outer iteration: (1) one of two destroy operators and one of two
+ * repair operators are chosen by roulette wheel on their weights (Appendix F.2); (2) destroy:
+ * destroy_count distinct variables are drawn, uniformly (B.1) or with probability proportional
+ * to the impact score d_j (B.2; R_j^k = (t - |s_k|) / |a_kj|, accumulated in fixed point);
+ * (3) repair, in the order of the draws: each drawn variable moves to the level next below or
+ * next above its old one, chosen at random (B.1) or as the one with the smaller worst-case
+ * error, the lower on a tie (B.3), r following every reassignment; (4) local search;
+ * (5) the result replaces the current solution if it is not worse, and the best solution if
+ * it is strictly better; the weights of the two operators used are updated.
+ * x0 (DEVICE, [n], NULL = keep the current x) is the starting point.  Outputs (DEVICE, any
+ * may be NULL): x_best_out [n] values, t_best_out [1], trace [iters][4] int32 = destroy
+ * operator (0 random, 1 worst-remove), repair operator (0 random, 1 greedy), moves the local
+ * search made, accepted; trace_t [iters][2] = error after the local search, best error so
+ * far.  Afterwards the handle holds the current (last accepted) solution.  Waits for the
+ * stream.  DMMV_ERR_UNSUPPORTED for batched handles. */
+dmmv_status dmmv_alns(dmmv_handle h, const void* x0, const dmmv_alns_params* params, void* x_best_out,
+                      void* t_best_out, int32_t* trace, void* trace_t);
+
 /* Message of the last failure on this thread (static storage, HOST). */
 const char* dmmv_last_error(void);
 

@@ -1,0 +1,326 @@
+// ALNS outer loop of AMVM (Algorithm 1 of the paper) around the single-move descent:
+// destroy (random / worst-remove, Appendix B.1-B.2), repair (random / greedy, B.1, B.3),
+// local search, acceptance, adaptive operator weights (Appendix F.2).
+//
+// Everything is decided on the device; the host only enqueues a fixed sequence of kernels
+// per outer iteration.  Whatever a floating-point value decides is decided on integers or by
+// a fixed sequence of IEEE operations, so that an independent implementation can follow the
+// run move by move:
+//   - random numbers are a counter-based chain of SplitMix64 steps addressed by
+//     (seed, instance, outer iteration, stream, counter);
+//   - the impact score of the worst-remove operator is accumulated in fixed point
+//     (a sum of integers does not depend on the order of its terms) and becomes an integer
+//     sampling weight; exp is a fixed Horner polynomial after a fixed range reduction;
+//   - variables are drawn against integer prefix sums, a repeated draw is skipped.
+// This file holds what is independent of the matrix storage plus the dense kernels.
+#include "dmmv_alns_common.h"
+
+namespace dmmv {
+
+// ----------------------------------------------------------------------------------------
+// loop control
+// ----------------------------------------------------------------------------------------
+template <class T>
+__global__ void k_alns_init(AlnsState* S, const InstState<T>* st) {
+    if (threadIdx.x != 0) return;
+    for (int q = 0; q < 4; ++q) S->w[q] = 1.0;
+    S->t_cur = (double)st[0].t;
+    S->t_best = (double)st[0].t;
+    S->it = 0; S->d_op = 0; S->r_op = 0; S->accepted = 0; S->new_best = 0;
+}
+
+// operators of this outer iteration by roulette wheel
+__global__ void k_alns_begin(AlnsState* S, uint64_t seed, uint64_t inst, int32_t it) {
+    if (threadIdx.x != 0) return;
+    const double ud = alns_unit(alns_rnd(seed, inst, (uint64_t)it, 0, 0));
+    const double ur = alns_unit(alns_rnd(seed, inst, (uint64_t)it, 0, 1));
+    S->it = it;
+    S->d_op = (ud * (S->w[0] + S->w[1]) < S->w[0]) ? 0 : 1;
+    S->r_op = (ur * (S->w[2] + S->w[3]) < S->w[2]) ? 0 : 1;
+}
+
+// inclusive prefix sums of the weights (single workgroup); only for the worst-remove operator
+__global__ __launch_bounds__(1024) void k_alns_scan(int64_t n, const uint64_t* __restrict__ weight,
+                                                    uint64_t* __restrict__ prefix, const AlnsState* S) {
+    __shared__ uint64_t sh[1024];
+    __shared__ uint64_t carry;
+    if (S->d_op != 1) return;
+    if (threadIdx.x == 0) carry = 0;
+    __syncthreads();
+    for (int64_t base = 0; base < n; base += 1024) {
+        const int64_t j = base + threadIdx.x;
+        sh[threadIdx.x] = j < n ? weight[j] : 0;
+        __syncthreads();
+        for (int off = 1; off < 1024; off <<= 1) {
+            const uint64_t t = threadIdx.x >= off ? sh[threadIdx.x - off] : 0;
+            __syncthreads();
+            sh[threadIdx.x] += t;
+            __syncthreads();
+        }
+        const uint64_t incl = sh[threadIdx.x] + carry;
+        if (j < n) prefix[j] = incl;
+        __syncthreads();
+        if (threadIdx.x == 1023) carry = incl;
+        __syncthreads();
+    }
+}
+
+// Draw `count` distinct variables (single workgroup).  Draw c takes rnd(.., 1, c) mod total and
+// the first variable whose prefix sum exceeds it (all weights 1 for the random operator); a
+// variable drawn before is skipped.  1024 draws are made at a time: a draw is the first of its
+// variable exactly if it holds the largest stamp (iteration, -c) that variable has seen.
+__global__ __launch_bounds__(1024) void k_alns_sample(int64_t n, int32_t count,
+                                                      const uint64_t* __restrict__ prefix,
+                                                      unsigned long long* first,
+                                                      int32_t* __restrict__ picked, const AlnsState* S,
+                                                      uint64_t seed, uint64_t inst) {
+    __shared__ int32_t sh_cnt[16];
+    __shared__ int32_t sh_have;
+    const int32_t it = S->it;
+    const bool weighted = S->d_op == 1;
+    const uint64_t total = weighted ? prefix[n - 1] : (uint64_t)n;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    if (threadIdx.x == 0) sh_have = 0;
+    __syncthreads();
+    for (uint64_t base = 0;; base += 1024) {
+        const int32_t have = sh_have;
+        if (have >= count) break;
+        const uint64_t c = base + threadIdx.x;
+        const uint64_t v = alns_rnd(seed, inst, (uint64_t)it, 1, c) % total;
+        int64_t j;
+        if (weighted) {
+            int64_t lo = 0, hi = n - 1;
+            while (lo < hi) {
+                const int64_t mid = (lo + hi) / 2;
+                if (prefix[mid] > v) hi = mid; else lo = mid + 1;
+            }
+            j = lo;
+        } else {
+            j = (int64_t)v;
+        }
+        const unsigned long long stamp = ((unsigned long long)(it + 1) << 32) | (0xFFFFFFFFull - (c & 0xFFFFFFFFull));
+        atomicMax(&first[j], stamp);
+        __syncthreads();
+        const bool is_first = __hip_atomic_load(&first[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == stamp;
+        const unsigned long long bal = __ballot(is_first);
+        if (lane == 0) sh_cnt[w] = __popcll(bal);
+        __syncthreads();
+        int32_t before = 0, all = 0;
+        for (int q = 0; q < 16; ++q) { if (q < w) before += sh_cnt[q]; all += sh_cnt[q]; }
+        const int32_t pos = have + before + __popcll(bal & ((1ull << lane) - 1ull));
+        if (is_first && pos < count) picked[pos] = (int32_t)j;
+        __syncthreads();
+        if (threadIdx.x == 0) sh_have = have + all;
+        __syncthreads();
+    }
+}
+
+// acceptance, best solution, weights, trace (one thread)
+template <class T>
+__global__ void k_alns_end(AlnsState* S, InstState<T>* st, double lambda, double sigma1, double sigma2,
+                           double sigma3, int32_t* trace, T* trace_t) {
+    if (threadIdx.x != 0) return;
+    const double t = (double)st[0].t;
+    const int32_t it = S->it;
+    const int accepted = t <= S->t_cur;
+    int new_best = 0;
+    if (accepted) {
+        double psi = sigma3;
+        if (t < S->t_cur) psi = sigma2;
+        if (t < S->t_best) { psi = sigma1; S->t_best = t; new_best = 1; }
+        S->t_cur = t;
+        const double keep = 1.0 - lambda;
+        S->w[S->d_op] = keep * S->w[S->d_op] + lambda * psi;
+        S->w[2 + S->r_op] = keep * S->w[2 + S->r_op] + lambda * psi;
+    }
+    S->accepted = accepted;
+    S->new_best = new_best;
+    if (trace) {
+        trace[it * 4 + 0] = S->d_op; trace[it * 4 + 1] = S->r_op;
+        trace[it * 4 + 2] = st[0].moves; trace[it * 4 + 3] = accepted;
+    }
+    if (trace_t) { trace_t[it * 2 + 0] = st[0].t; trace_t[it * 2 + 1] = (T)S->t_best; }
+    if (!accepted) st[0].t = (T)S->t_cur;           // the copy kernel restores x and r
+}
+
+// accepted: current <- working (and best <- working for a new best); rejected: working <- current
+template <class T>
+__global__ void k_alns_copy(int64_t m, int64_t n, const AlnsState* S, int32_t* kidx, int32_t* kidx_cur,
+                            int32_t* kidx_best, T* r, T* r_cur) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const int64_t t0 = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    if (S->accepted) {
+        const bool nb = S->new_best != 0;
+        for (int64_t j = t0; j < n; j += stride) { const int32_t k = kidx[j]; kidx_cur[j] = k; if (nb) kidx_best[j] = k; }
+        for (int64_t i = t0; i < m; i += stride) r_cur[i] = r[i];
+    } else {
+        for (int64_t j = t0; j < n; j += stride) kidx[j] = kidx_cur[j];
+        for (int64_t i = t0; i < m; i += stride) r[i] = r_cur[i];
+    }
+}
+
+template <class T>
+__global__ void k_alns_snapshot(int64_t m, int64_t n, const int32_t* kidx, int32_t* kidx_cur,
+                                int32_t* kidx_best, const T* r, T* r_cur, unsigned long long* first) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const int64_t t0 = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    for (int64_t j = t0; j < n; j += stride) { kidx_cur[j] = kidx[j]; kidx_best[j] = kidx[j]; first[j] = 0; }
+    for (int64_t i = t0; i < m; i += stride) r_cur[i] = r[i];
+}
+
+template <class T>
+__global__ void k_alns_export(const AlnsState* S, T* t_best_out) {
+    if (threadIdx.x == 0 && t_best_out) t_best_out[0] = (T)S->t_best;
+}
+
+// ----------------------------------------------------------------------------------------
+// dense: impact weights and repair
+// ----------------------------------------------------------------------------------------
+// one workgroup per variable: weight_j = 1 + (sum over rows of the fixed-point terms >> shift)
+template <class T>
+__global__ __launch_bounds__(256) void k_alns_impact_dense(int64_t m, int64_t n, const T* __restrict__ A,
+                                                           int64_t lda, const T* __restrict__ r,
+                                                           const InstState<T>* st, double alpha,
+                                                           uint64_t* __restrict__ weight, const AlnsState* S) {
+    __shared__ uint64_t sh[4];
+    if (S->d_op != 1) return;
+    const int64_t j = blockIdx.x;
+    const double t = (double)st[0].t;
+    const double scale = alns_impact_scale(t);
+    uint64_t sum = 0;
+    if (scale != 0.0) {
+        const T* __restrict__ col = A + lda * j;
+        for (int64_t i = threadIdx.x; i < m; i += blockDim.x)
+            sum += alns_impact_term(__builtin_fabs((double)col[i]), __builtin_fabs((double)r[i]), t, alpha, scale);
+    }
+    sum = block_sum_u64(sum, sh);
+    if (threadIdx.x == 0) {
+        int shift = alns_bits(m) + 24 + alns_bits(n) - 62;
+        if (shift < 0) shift = 0;
+        weight[j] = 1 + (sum >> shift);
+    }
+}
+
+// single workgroup; thread i owns the rows i, i + 1024, ...; the picked variables are
+// reassigned one after the other, r follows each reassignment
+template <class T>
+__global__ __launch_bounds__(1024) void k_alns_repair_dense(int64_t m, int32_t nd, const T* __restrict__ A,
+                                                            int64_t lda, const T* __restrict__ D, T* r,
+                                                            int32_t* kidx, int32_t count,
+                                                            const int32_t* __restrict__ picked,
+                                                            InstState<T>* st, const AlnsState* S,
+                                                            uint64_t seed, uint64_t inst) {
+    __shared__ T sh[16];
+    const int32_t it = S->it;
+    const bool greedy = S->r_op == 1;
+    for (int32_t pos = 0; pos < count; ++pos) {
+        const int64_t j = picked[pos];
+        const int32_t kc = kidx[j];
+        const bool has_lo = kc > 0, has_hi = kc < nd - 1;
+        const T* __restrict__ col = A + lda * j;
+        int32_t knew;
+        if (has_lo && has_hi) {
+            if (greedy) {
+                const T dlo = step_of(D[kc - 1], D[kc], (T)1), dhi = step_of(D[kc + 1], D[kc], (T)1);
+                T elo = (T)0, ehi = (T)0;
+                for (int64_t i = threadIdx.x; i < m; i += blockDim.x) {
+                    const T a = col[i], ri = r[i];
+                    elo = dmmv_max(elo, dmmv_abs(dmmv_fma(dlo, a, ri)));
+                    ehi = dmmv_max(ehi, dmmv_abs(dmmv_fma(dhi, a, ri)));
+                }
+                elo = block_max(elo, sh);
+                ehi = block_max(ehi, sh);
+                knew = ehi < elo ? kc + 1 : kc - 1;
+            } else {
+                knew = (alns_rnd(seed, inst, (uint64_t)it, 2, (uint64_t)pos) & 1) ? kc + 1 : kc - 1;
+            }
+        } else {
+            knew = has_lo ? kc - 1 : kc + 1;
+        }
+        const T delta = step_of(D[knew], D[kc], (T)1);
+        for (int64_t i = threadIdx.x; i < m; i += blockDim.x) r[i] = dmmv_fma(delta, col[i], r[i]);
+        __syncthreads();                      // every thread has read kidx[j] of this step
+        if (threadIdx.x == 0) kidx[j] = knew;
+    }
+    T tmax = (T)0;
+    for (int64_t i = threadIdx.x; i < m; i += blockDim.x) tmax = dmmv_max(tmax, dmmv_abs(r[i]));
+    tmax = block_max(tmax, sh);
+    if (threadIdx.x == 0) { st[0].t = tmax; st[0].done = 0; st[0].moves = 0; }
+}
+
+// ----------------------------------------------------------------------------------------
+// host side: one outer iteration's kernels around the local search
+// ----------------------------------------------------------------------------------------
+template <class T>
+static dmmv_status start_t(Ctx* c) {
+    hipLaunchKernelGGL(k_alns_init<T>, dim3(1), dim3(64), 0, c->stream, (AlnsState*)c->alns_state,
+                       (const InstState<T>*)c->state);
+    hipLaunchKernelGGL(k_alns_snapshot<T>, dim3(256), dim3(256), 0, c->stream, c->p.m, c->p.n,
+                       (const int32_t*)c->kidx, c->alns_kidx_cur, c->alns_kidx_best, (const T*)c->r,
+                       (T*)c->alns_r_cur, (unsigned long long*)c->alns_first);
+    DMMV_LAUNCH_CHECK();
+    return DMMV_OK;
+}
+
+template <class T>
+static dmmv_status destroy_repair_t(Ctx* c, const dmmv_alns_params& prm, int32_t it, int32_t count) {
+    AlnsState* S = (AlnsState*)c->alns_state;
+    hipLaunchKernelGGL(k_alns_begin, dim3(1), dim3(64), 0, c->stream, S, prm.seed, (uint64_t)0, it);
+    if (c->kind == KIND_DENSE) {
+        hipLaunchKernelGGL(k_alns_impact_dense<T>, dim3((unsigned)c->p.n), dim3(256), 0, c->stream, c->p.m,
+                           c->p.n, (const T*)c->p.A_dense, c->p.lda, (const T*)c->r,
+                           (const InstState<T>*)c->state, prm.alpha, c->alns_weight, (const AlnsState*)S);
+    } else {
+        DMMV_TRY(csc_alns_impact(c, prm.alpha));
+    }
+    hipLaunchKernelGGL(k_alns_scan, dim3(1), dim3(1024), 0, c->stream, c->p.n, (const uint64_t*)c->alns_weight,
+                       c->alns_prefix, (const AlnsState*)S);
+    hipLaunchKernelGGL(k_alns_sample, dim3(1), dim3(1024), 0, c->stream, c->p.n, count,
+                       (const uint64_t*)c->alns_prefix, (unsigned long long*)c->alns_first, c->alns_picked,
+                       (const AlnsState*)S, prm.seed, (uint64_t)0);
+    if (c->kind == KIND_DENSE) {
+        hipLaunchKernelGGL(k_alns_repair_dense<T>, dim3(1), dim3(1024), 0, c->stream, c->p.m, c->p.nd,
+                           (const T*)c->p.A_dense, c->p.lda, (const T*)c->D_dev, (T*)c->r, c->kidx, count,
+                           (const int32_t*)c->alns_picked, (InstState<T>*)c->state, (const AlnsState*)S,
+                           prm.seed, (uint64_t)0);
+    } else {
+        DMMV_TRY(csc_alns_repair(c, count, prm.seed));
+    }
+    DMMV_LAUNCH_CHECK();
+    return DMMV_OK;
+}
+
+template <class T>
+static dmmv_status finish_iteration_t(Ctx* c, const dmmv_alns_params& prm, int32_t* trace, void* trace_t) {
+    AlnsState* S = (AlnsState*)c->alns_state;
+    hipLaunchKernelGGL(k_alns_end<T>, dim3(1), dim3(64), 0, c->stream, S, (InstState<T>*)c->state, prm.lambda,
+                       prm.sigma1, prm.sigma2, prm.sigma3, trace, (T*)trace_t);
+    hipLaunchKernelGGL(k_alns_copy<T>, dim3(256), dim3(256), 0, c->stream, c->p.m, c->p.n, (const AlnsState*)S,
+                       c->kidx, c->alns_kidx_cur, c->alns_kidx_best, (T*)c->r, (T*)c->alns_r_cur);
+    DMMV_LAUNCH_CHECK();
+    if (c->kind == KIND_CSC) DMMV_TRY(csc_alns_after_copy(c));
+    return DMMV_OK;
+}
+
+template <class T>
+static dmmv_status export_t(Ctx* c, void* t_best_out) {
+    hipLaunchKernelGGL(k_alns_export<T>, dim3(1), dim3(64), 0, c->stream, (const AlnsState*)c->alns_state,
+                       (T*)t_best_out);
+    DMMV_LAUNCH_CHECK();
+    return DMMV_OK;
+}
+
+dmmv_status alns_start(Ctx* c) { return c->p.dtype == DMMV_F64 ? start_t<double>(c) : start_t<float>(c); }
+dmmv_status alns_destroy_repair(Ctx* c, const dmmv_alns_params& prm, int32_t it, int32_t count) {
+    return c->p.dtype == DMMV_F64 ? destroy_repair_t<double>(c, prm, it, count)
+                                  : destroy_repair_t<float>(c, prm, it, count);
+}
+dmmv_status alns_finish_iteration(Ctx* c, const dmmv_alns_params& prm, int32_t* trace, void* trace_t) {
+    return c->p.dtype == DMMV_F64 ? finish_iteration_t<double>(c, prm, trace, trace_t)
+                                  : finish_iteration_t<float>(c, prm, trace, trace_t);
+}
+dmmv_status alns_export(Ctx* c, void* t_best_out) {
+    return c->p.dtype == DMMV_F64 ? export_t<double>(c, t_best_out) : export_t<float>(c, t_best_out);
+}
+
+}  // namespace dmmv

@@ -71,6 +71,18 @@ size_t workspace_layout(const dmmv_problem& p, const dmmv_options& o, Ctx* c, ch
     b.take(&c->r, (size_t)p.m * p.R * esz);
     c->red_elems = 1024;
     b.take(&c->red, (size_t)c->red_elems * esz);
+    if (!batched) {
+        // ALNS outer loop: current and best solution, sampling weights, draws
+        b.take(&c->alns_state, sizeof(AlnsState));
+        b.take(&c->alns_kidx_cur, (size_t)p.n * sizeof(int32_t));
+        b.take(&c->alns_kidx_best, (size_t)p.n * sizeof(int32_t));
+        b.take(&c->alns_r_cur, (size_t)p.m * esz);
+        b.take(&c->alns_weight, (size_t)p.n * sizeof(uint64_t));
+        b.take(&c->alns_prefix, (size_t)p.n * sizeof(uint64_t));
+        b.take(&c->alns_first, (size_t)p.n * sizeof(uint64_t));
+        b.take(&c->alns_picked, (size_t)p.n * sizeof(int32_t));
+        if (sparse) b.take(&c->alns_touched, (size_t)p.m);
+    }
     if (sparse) {
         // rows per partition: what fits the LDS budget, addressable by a 16-bit offset
         int64_t mp = o.sparse_partition_rows > 0 ? o.sparse_partition_rows : (int64_t)(CSC_LDS_BYTES / esz);
@@ -514,6 +526,53 @@ static dmmv_status solve_t(dmmv_ctx* c, const void* x0, int32_t iters, void* x_o
     return DMMV_OK;
 }
 
+// ---- ALNS outer loop (Algorithm 1): destroy + repair, local search, accept ---------------
+static dmmv_status alns_run(dmmv_ctx* c, const void* x0, const dmmv_alns_params& prm, void* x_best_out,
+                            void* t_best_out, int32_t* trace, void* trace_t) {
+    if (x0) DMMV_TRY(dmmv_set_x(c, x0));
+    if (!c->x_set) return fail(DMMV_ERR_STATE, "dmmv_alns: no starting point (x0 is NULL and dmmv_set_x was never called)");
+    DMMV_TRY(residual_any(c));
+    if (c->p.n == 0) {
+        DMMV_TRY(alns_start(c));
+        DMMV_TRY(alns_export(c, t_best_out));
+        DMMV_HIP_CHECK(hipStreamSynchronize(c->stream));
+        return DMMV_OK;
+    }
+    int64_t count = prm.destroy_count > 0 ? prm.destroy_count : (c->p.n * 5 + 999) / 1000;
+    if (count < 1) count = 1;
+    if (count > c->p.n) count = c->p.n;
+    // the local search runs with its own neighbourhood and always stops at a local optimum
+    const dmmv_options saved = c->o;
+    c->o.radius = prm.ls_radius;
+    c->o.keep_going = 0;
+    dmmv_status st = [&]() -> dmmv_status {
+        DMMV_TRY(alns_start(c));
+        for (int32_t it = 0; it < prm.iters; ++it) {
+            DMMV_TRY(alns_destroy_repair(c, prm, it, (int32_t)count));
+            for (int32_t mv = 0; mv < prm.ls_moves; ++mv) {
+                DMMV_TRY(eval_any(c, nullptr, true, true));
+                DMMV_TRY(select_apply_any(c, prm.ls_moves, nullptr, nullptr));
+            }
+            DMMV_TRY(alns_finish_iteration(c, prm, trace, trace_t));
+        }
+        DMMV_TRY(alns_export(c, t_best_out));
+        return DMMV_OK;
+    }();
+    c->o = saved;
+    DMMV_TRY(st);
+    if (x_best_out) {
+        if (c->p.dtype == DMMV_F64)
+            hipLaunchKernelGGL(k_index_to_values<double>, grid1(c->p.n, 256), dim3(256), 0, c->stream,
+                               (const int32_t*)c->alns_kidx_best, (const double*)c->D_dev, c->p.n, (double*)x_best_out);
+        else
+            hipLaunchKernelGGL(k_index_to_values<float>, grid1(c->p.n, 256), dim3(256), 0, c->stream,
+                               (const int32_t*)c->alns_kidx_best, (const float*)c->D_dev, c->p.n, (float*)x_best_out);
+        DMMV_LAUNCH_CHECK();
+    }
+    DMMV_HIP_CHECK(hipStreamSynchronize(c->stream));
+    return DMMV_OK;
+}
+
 }  // namespace dmmv
 
 // ========================================================================================
@@ -735,6 +794,19 @@ dmmv_status dmmv_solve(dmmv_handle h, const void* x0, int32_t iters, void* x_out
     return h->p.dtype == DMMV_F64
                ? solve_t<double>(h, x0, iters, x_out, max_violation_out, iters_done, trace, trace_t)
                : solve_t<float>(h, x0, iters, x_out, max_violation_out, iters_done, trace, trace_t);
+}
+
+dmmv_status dmmv_alns(dmmv_handle h, const void* x0, const dmmv_alns_params* params, void* x_best_out,
+                      void* t_best_out, int32_t* trace, void* trace_t) {
+    if (!h) return fail(DMMV_ERR_NULL, "handle is NULL");
+    if (!params) return fail(DMMV_ERR_NULL, "params is NULL");
+    if (h->kind == KIND_BATCHED) return fail(DMMV_ERR_UNSUPPORTED, "dmmv_alns: batched handles are not supported");
+    if (params->iters < 0 || params->ls_moves < 0 || params->ls_radius < 0 || params->destroy_count < 0)
+        return fail(DMMV_ERR_SHAPE, "dmmv_alns: iters, ls_moves, ls_radius and destroy_count must be >= 0");
+    if (!(params->alpha >= 0.0) || !(params->lambda >= 0.0 && params->lambda <= 1.0) ||
+        !(params->sigma1 >= 0.0) || !(params->sigma2 >= 0.0) || !(params->sigma3 >= 0.0))
+        return fail(DMMV_ERR_DOMAIN, "dmmv_alns: need alpha >= 0, 0 <= lambda <= 1, sigma >= 0");
+    return alns_run(h, x0, *params, x_best_out, t_best_out, trace, trace_t);
 }
 
 dmmv_status dmmv_time_eval(dmmv_handle h, int32_t reps, float* ms_out) {

@@ -53,6 +53,17 @@ struct alignas(16) InstState {
     int32_t moves;   // moves applied so far
 };
 
+// State of the ALNS outer loop kept on the device (single instance).
+struct alignas(16) AlnsState {
+    double w[4];        // operator weights: random destroy, worst-remove, random repair, greedy repair
+    double t_cur;       // error of the current (last accepted) solution
+    double t_best;      // error of the best solution so far
+    int32_t it;         // outer iteration in progress
+    int32_t d_op, r_op; // operators chosen for it
+    int32_t accepted;   // verdict of the iteration just finished
+    int32_t new_best;
+};
+
 // One partial arg-min record: score and flat candidate index (c < 0: empty).
 template <class T>
 struct alignas(16) Partial {
@@ -106,6 +117,16 @@ struct Ctx {
     void* Xt;             // T[m][n] row-major copy of X
     void* Bt;             // T[m][R]
     int32_t chunk_cols;   // columns per chunk of the fused evaluation (n_partials chunks)
+    // ALNS outer loop (dense and sparse single instances)
+    void* alns_state;         // AlnsState
+    int32_t* alns_kidx_cur;   // [n] current (last accepted) solution
+    int32_t* alns_kidx_best;  // [n] best solution
+    void* alns_r_cur;         // T[m] residual of the current solution
+    uint64_t* alns_weight;    // [n] integer sampling weights of the worst-remove operator
+    uint64_t* alns_prefix;    // [n] their inclusive prefix sums
+    uint64_t* alns_first;     // [n] stamp of the first draw of a variable in an iteration
+    int32_t* alns_picked;     // [n] variables drawn, in the order of the draws
+    uint8_t* alns_touched;    // [m] sparse repair: rows of the column being reassigned
     // batched residual on the matrix cores (options.residual_mfma)
     void* Xp;             // bf16[3][m][mfma_ldk] planes whose sum is X
     void* Qt;             // bf16[R][mfma_ldk] current codes D[k_j] per instance
@@ -137,6 +158,13 @@ constexpr int CSC_MAX_PARTITIONS = 1024;
 // ----------------------------------------------------------------------------------------
 // per-path entry points (all enqueue on c->stream)
 // ----------------------------------------------------------------------------------------
+dmmv_status alns_start(Ctx* c);
+dmmv_status alns_destroy_repair(Ctx* c, const dmmv_alns_params& prm, int32_t it, int32_t count);
+dmmv_status alns_finish_iteration(Ctx* c, const dmmv_alns_params& prm, int32_t* trace, void* trace_t);
+dmmv_status alns_export(Ctx* c, void* t_best_out);
+dmmv_status csc_alns_impact(Ctx* c, double alpha);
+dmmv_status csc_alns_repair(Ctx* c, int32_t count, uint64_t seed);
+dmmv_status csc_alns_after_copy(Ctx* c);
 int64_t mfma_ldk(int64_t n);
 dmmv_status batched_mfma_build(Ctx* c);
 dmmv_status batched_mfma_residual(Ctx* c);

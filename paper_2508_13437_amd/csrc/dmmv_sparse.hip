@@ -15,6 +15,7 @@
 // incrementally by the kernel that applies a move (drop the rows the move touched, insert the
 // changed rows that are at or before the floor, sort, truncate; rebuild when it runs low).
 #include "dmmv_sparse_common.h"
+#include "dmmv_alns_common.h"
 
 namespace dmmv {
 
@@ -489,6 +490,182 @@ dmmv_status csc_apply(Ctx* c) { return c->p.dtype == DMMV_F64 ? apply_t<double>(
 dmmv_status csc_select_apply(Ctx* c, int32_t iters, dmmv_move* trace, void* trace_t) {
     return c->p.dtype == DMMV_F64 ? select_apply_t<double>(c, iters, trace, trace_t)
                                   : select_apply_t<float>(c, iters, trace, trace_t);
+}
+
+// =========================================================================================
+// ALNS outer loop: the kernels that depend on the sparse layout
+// =========================================================================================
+// worst-remove operator: integer sampling weight of every variable, one wavefront per column
+template <class T>
+__global__ __launch_bounds__(256) void k_alns_impact_cscp(int64_t m, int64_t n, int32_t mp, int32_t P,
+                                                         const int32_t* __restrict__ segptr,
+                                                         const uint16_t* __restrict__ row16,
+                                                         const T* __restrict__ cval, const T* __restrict__ r,
+                                                         const InstState<T>* st, double alpha,
+                                                         uint64_t* __restrict__ weight, const AlnsState* S) {
+    if (S->d_op != 1) return;
+    const int lane = threadIdx.x & 63;
+    const int64_t j = blockIdx.x * 4ll + (threadIdx.x >> 6);
+    if (j >= n) return;
+    const double t = (double)st[0].t;
+    const double scale = alns_impact_scale(t);
+    uint64_t sum = 0;
+    if (scale != 0.0) {
+        for (int32_t p = 0; p < P; ++p) {
+            const int32_t e0 = segptr[(int64_t)p * n + j], e1 = segptr[(int64_t)p * n + j + 1];
+            for (int32_t e = e0 + lane; e < e1; e += 64) {
+                const uint32_t loc = row16[e];
+                if (loc == (uint32_t)mp) continue;
+                const double sk = __builtin_fabs((double)r[(int64_t)p * mp + loc]);
+                sum += alns_impact_term(__builtin_fabs((double)cval[e]), sk, t, alpha, scale);
+            }
+        }
+    }
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) sum += (uint64_t)__shfl_xor((long long)sum, off, 64);
+    if (lane == 0) {
+        int shift = alns_bits(m) + 24 + alns_bits(n) - 62;
+        if (shift < 0) shift = 0;
+        weight[j] = 1 + (sum >> shift);
+    }
+}
+
+// repair: single workgroup, the picked variables one after the other.  A greedy choice needs
+// the worst-case error over ALL rows for both neighbouring levels: the rows of the column are
+// marked, the others contribute their |r| as it stands.
+template <class T>
+__global__ __launch_bounds__(1024) void k_alns_repair_cscp(int64_t m, int64_t n, int32_t nd, int32_t mp, int32_t P,
+                                                          const int32_t* __restrict__ segptr,
+                                                          const uint16_t* __restrict__ row16,
+                                                          const T* __restrict__ cval, const T* __restrict__ D,
+                                                          T* r, int32_t* kidx, int32_t count,
+                                                          const int32_t* __restrict__ picked, uint8_t* touched,
+                                                          InstState<T>* st, const AlnsState* S, uint64_t seed,
+                                                          uint64_t inst) {
+    __shared__ T sh[16];
+    const int32_t it = S->it;
+    const bool greedy = S->r_op == 1;
+    for (int32_t pos = 0; pos < count; ++pos) {
+        const int64_t j = picked[pos];
+        const int32_t kc = kidx[j];
+        const bool has_lo = kc > 0, has_hi = kc < nd - 1;
+        int32_t knew;
+        if (has_lo && has_hi) {
+            if (greedy) {
+                for (int32_t p = 0; p < P; ++p) {
+                    const int32_t e0 = segptr[(int64_t)p * n + j], e1 = segptr[(int64_t)p * n + j + 1];
+                    for (int32_t e = e0 + threadIdx.x; e < e1; e += blockDim.x) {
+                        const uint32_t loc = row16[e];
+                        if (loc != (uint32_t)mp) touched[(int64_t)p * mp + loc] = 1;
+                    }
+                }
+                __syncthreads();
+                const T dlo = step_of(D[kc - 1], D[kc], (T)1), dhi = step_of(D[kc + 1], D[kc], (T)1);
+                T rest = (T)0;
+                for (int64_t i = threadIdx.x; i < m; i += blockDim.x)
+                    if (!touched[i]) rest = dmmv_max(rest, dmmv_abs(r[i]));
+                T elo = rest, ehi = rest;
+                for (int32_t p = 0; p < P; ++p) {
+                    const int32_t e0 = segptr[(int64_t)p * n + j], e1 = segptr[(int64_t)p * n + j + 1];
+                    for (int32_t e = e0 + threadIdx.x; e < e1; e += blockDim.x) {
+                        const uint32_t loc = row16[e];
+                        if (loc == (uint32_t)mp) continue;
+                        const T a = cval[e], ri = r[(int64_t)p * mp + loc];
+                        elo = dmmv_max(elo, dmmv_abs(dmmv_fma(dlo, a, ri)));
+                        ehi = dmmv_max(ehi, dmmv_abs(dmmv_fma(dhi, a, ri)));
+                    }
+                }
+                elo = block_max(elo, sh);
+                ehi = block_max(ehi, sh);
+                knew = ehi < elo ? kc + 1 : kc - 1;
+                for (int32_t p = 0; p < P; ++p) {
+                    const int32_t e0 = segptr[(int64_t)p * n + j], e1 = segptr[(int64_t)p * n + j + 1];
+                    for (int32_t e = e0 + threadIdx.x; e < e1; e += blockDim.x) {
+                        const uint32_t loc = row16[e];
+                        if (loc != (uint32_t)mp) touched[(int64_t)p * mp + loc] = 0;
+                    }
+                }
+            } else {
+                knew = (alns_rnd(seed, inst, (uint64_t)it, 2, (uint64_t)pos) & 1) ? kc + 1 : kc - 1;
+            }
+        } else {
+            knew = has_lo ? kc - 1 : kc + 1;
+        }
+        const T delta = step_of(D[knew], D[kc], (T)1);
+        for (int32_t p = 0; p < P; ++p) {
+            const int32_t e0 = segptr[(int64_t)p * n + j], e1 = segptr[(int64_t)p * n + j + 1];
+            for (int32_t e = e0 + threadIdx.x; e < e1; e += blockDim.x) {
+                const uint32_t loc = row16[e];
+                if (loc == (uint32_t)mp) continue;
+                const int64_t i = (int64_t)p * mp + loc;
+                r[i] = dmmv_fma(delta, cval[e], r[i]);
+            }
+        }
+        __syncthreads();                      // r and the marks are settled; kidx[j] was read by all
+        if (threadIdx.x == 0) kidx[j] = knew;
+    }
+    T tmax = (T)0;
+    for (int64_t i = threadIdx.x; i < m; i += blockDim.x) tmax = dmmv_max(tmax, dmmv_abs(r[i]));
+    tmax = block_max(tmax, sh);
+    if (threadIdx.x == 0) { st[0].t = tmax; st[0].done = 0; st[0].moves = 0; }
+}
+
+// after a rejected iteration r was restored: the reservoir has to follow
+template <class T>
+__global__ __launch_bounds__(1024) void k_reservoir_build_if_rejected(int64_t m, const T* r, T* res_val,
+                                                                      int32_t* res_row, int32_t* meta,
+                                                                      T* floor_val, const AlnsState* S) {
+    __shared__ ResLds<T> L;
+    if (S->accepted) return;
+    reservoir_rebuild(L, m, r, res_val, res_row, meta, floor_val);
+}
+
+__global__ void k_alns_clear_touched(int64_t m, uint8_t* touched) {
+    const int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    if (i < m) touched[i] = 0;
+}
+
+template <class T>
+static dmmv_status alns_impact_t(Ctx* c, double alpha) {
+    hipLaunchKernelGGL(k_alns_impact_cscp<T>, dim3((unsigned)ceil_div(c->p.n, 4)), dim3(256), 0, c->stream,
+                       c->p.m, c->p.n, c->csc_mp, c->csc_P, (const int32_t*)c->segptr, (const uint16_t*)c->row16,
+                       (const T*)c->cval, (const T*)c->r, (const InstState<T>*)c->state, alpha, c->alns_weight,
+                       (const AlnsState*)c->alns_state);
+    DMMV_LAUNCH_CHECK();
+    return DMMV_OK;
+}
+
+template <class T>
+static dmmv_status alns_repair_t(Ctx* c, int32_t count, uint64_t seed) {
+    if (c->p.m > 0)
+        hipLaunchKernelGGL(k_alns_clear_touched, dim3((unsigned)ceil_div(c->p.m, 256)), dim3(256), 0, c->stream,
+                           c->p.m, c->alns_touched);
+    hipLaunchKernelGGL(k_alns_repair_cscp<T>, dim3(1), dim3(1024), 0, c->stream, c->p.m, c->p.n, c->p.nd,
+                       c->csc_mp, c->csc_P, (const int32_t*)c->segptr, (const uint16_t*)c->row16,
+                       (const T*)c->cval, (const T*)c->D_dev, (T*)c->r, c->kidx, count,
+                       (const int32_t*)c->alns_picked, c->alns_touched, (InstState<T>*)c->state,
+                       (const AlnsState*)c->alns_state, seed, (uint64_t)0);
+    DMMV_LAUNCH_CHECK();
+    return reservoir_t<T>(c);
+}
+
+template <class T>
+static dmmv_status alns_after_copy_t(Ctx* c) {
+    hipLaunchKernelGGL(k_reservoir_build_if_rejected<T>, dim3(1), dim3(1024), 0, c->stream, c->p.m,
+                       (const T*)c->r, (T*)c->res_val, c->res_row, c->res_meta, (T*)c->res_floor,
+                       (const AlnsState*)c->alns_state);
+    DMMV_LAUNCH_CHECK();
+    return DMMV_OK;
+}
+
+dmmv_status csc_alns_impact(Ctx* c, double alpha) {
+    return c->p.dtype == DMMV_F64 ? alns_impact_t<double>(c, alpha) : alns_impact_t<float>(c, alpha);
+}
+dmmv_status csc_alns_repair(Ctx* c, int32_t count, uint64_t seed) {
+    return c->p.dtype == DMMV_F64 ? alns_repair_t<double>(c, count, seed) : alns_repair_t<float>(c, count, seed);
+}
+dmmv_status csc_alns_after_copy(Ctx* c) {
+    return c->p.dtype == DMMV_F64 ? alns_after_copy_t<double>(c) : alns_after_copy_t<float>(c);
 }
 
 }  // namespace dmmv

@@ -26,7 +26,8 @@ STATUS_NAMES = {0: "DMMV_OK", -1: "DMMV_ERR_NULL", -2: "DMMV_ERR_SHAPE", -3: "DM
 
 EXPORTS = ("dmmv_workspace_bytes", "dmmv_create", "dmmv_destroy", "dmmv_set_x",
            "dmmv_set_residual", "dmmv_residual", "dmmv_eval_moves", "dmmv_argmin_move",
-           "dmmv_apply_move", "dmmv_get_state", "dmmv_solve", "dmmv_time_eval", "dmmv_last_error",
+           "dmmv_apply_move", "dmmv_get_state", "dmmv_solve", "dmmv_alns", "dmmv_time_eval",
+           "dmmv_last_error",
            "dmmv_version")
 
 
@@ -47,6 +48,13 @@ class Options(C.Structure):
     _fields_ = [("radius", C.c_int32), ("keep_going", C.c_int32), ("poll_every", C.c_int32),
                 ("sparse_partition_rows", C.c_int32), ("var_mask", C.c_void_p),
                 ("residual_mfma", C.c_int32)]
+
+
+class AlnsParams(C.Structure):
+    _fields_ = [("iters", C.c_int32), ("ls_moves", C.c_int32), ("ls_radius", C.c_int32),
+                ("destroy_count", C.c_int32), ("alpha", C.c_double), ("lambda_", C.c_double),
+                ("sigma1", C.c_double), ("sigma2", C.c_double), ("sigma3", C.c_double),
+                ("seed", C.c_uint64)]
 
 
 _lib = None
@@ -77,6 +85,9 @@ def load() -> C.CDLL:
     lib.dmmv_solve.restype = C.c_int
     lib.dmmv_solve.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
                                C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.dmmv_alns.restype = C.c_int
+    lib.dmmv_alns.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(AlnsParams), C.c_void_p, C.c_void_p,
+                              C.c_void_p, C.c_void_p]
     lib.dmmv_time_eval.restype = C.c_int
     lib.dmmv_time_eval.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_float)]
     lib.dmmv_last_error.restype = C.c_char_p
@@ -304,6 +315,31 @@ def dmmv_solve(h: Handle, x0: Optional[torch.Tensor], iters: int, trace: bool = 
     if trace and iters == 0:
         tr, tt = tr[:, :0], tt[:, :0]
     return SolveResult(x, t, done, tr, tt)
+
+
+@dataclass
+class AlnsResult:
+    x_best: torch.Tensor       # [n]
+    t_best: torch.Tensor       # [1]
+    trace: torch.Tensor        # [iters][4] int32: destroy op, repair op, local-search moves, accepted
+    trace_t: torch.Tensor      # [iters][2]: error after the local search, best error so far
+
+
+def dmmv_alns(h: Handle, x0: Optional[torch.Tensor], iters: int, ls_moves: int = 8, ls_radius: int = 1,
+              destroy_count: int = 0, alpha: float = 0.3, lambda_: float = 0.2, sigma1: float = 3.0,
+              sigma2: float = 2.0, sigma3: float = 1.0, seed: int = 1) -> AlnsResult:
+    """The ALNS outer loop around the descent (single dense or sparse instance)."""
+    prm = AlnsParams(int(iters), int(ls_moves), int(ls_radius), int(destroy_count), float(alpha),
+                     float(lambda_), float(sigma1), float(sigma2), float(sigma3), int(seed))
+    if x0 is not None:
+        x0 = x0.to(h.device, h.dtype).contiguous()
+    x_best = h._new((h.n,))
+    t_best = h._new((1,))
+    trace = torch.full((max(iters, 1), 4), -1, dtype=torch.int32, device=h.device)
+    trace_t = h._new((max(iters, 1), 2))
+    _check(load().dmmv_alns(h._h, _ptr(x0), C.byref(prm), _ptr(x_best), _ptr(t_best), _ptr(trace),
+                            _ptr(trace_t)))
+    return AlnsResult(x_best, t_best, trace[:iters], trace_t[:iters])
 
 
 def dmmv_time_eval(h: Handle, reps: int) -> float:

@@ -1,0 +1,124 @@
+"""Parity of the ALNS outer loop (dmmv_alns, through the C ABI) against the CPU oracle.
+
+Every random decision is a function of (seed, iteration, stream, counter) and every decision a
+floating-point value takes is taken on integers or by a fixed sequence of IEEE operations, so
+operator choices, local-search move counts, acceptance flags, errors, the best solution and its
+error must all be bitwise equal."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as orc
+from workloads import make_config, random_batched, random_dense, random_sparse
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def dmmv():
+    from paper_2508_13437_amd import dmmv as mod
+    return mod
+
+
+def T(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def N(t):
+    return t.detach().cpu().numpy()
+
+
+def alns_check(inst, iters, **kw):
+    m = dmmv()
+    hopt = {}
+    if "sparse_partition_rows" in kw:
+        hopt["sparse_partition_rows"] = kw.pop("sparse_partition_rows")
+    print("alns case", inst.name, iters, kw, hopt, flush=True)
+    prm = orc.alns_params(iters, **kw)
+    if inst.kind == "csr":
+        o = orc.alns_csr(inst.m, inst.n, inst.csr_rowptr, inst.csr_col, inst.csr_val, inst.b, inst.D,
+                         inst.x0, prm)
+    else:
+        o = orc.alns_dense(inst.A, inst.b, inst.D, inst.x0, prm)
+    with m.from_instance(inst, DEV, **hopt) as h:
+        res = m.dmmv_alns(h, T(inst.x0), iters, **kw)
+        tr, tt = N(res.trace), N(res.trace_t)
+        assert np.array_equal(tr[:, 0], o.destroy), (tr[:, 0], o.destroy)
+        assert np.array_equal(tr[:, 1], o.repair)
+        assert np.array_equal(tt[:, 0], o.t), (tt[:, 0], o.t)
+        assert np.array_equal(tr[:, 2], o.moves)
+        assert np.array_equal(tr[:, 3], o.accepted)
+        assert np.array_equal(tt[:, 1], o.best)
+        assert np.array_equal(N(res.x_best), o.x)
+        assert N(res.t_best)[0] == o.t_best
+        # the handle holds the current solution: its r is the residual of its x, t = max |r|
+        x, r, t = m.dmmv_get_state(h)
+        x, r, t = N(x), N(r), N(t)
+        if inst.m:
+            assert np.abs(r).max() == t[0]
+        acc = np.nonzero(o.accepted)[0]
+        want_cur = o.t[acc[-1]] if acc.size else None
+        if want_cur is not None:
+            assert t[0] == want_cur
+    return o
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("shape", [(5, 3, 2), (40, 16, 5), (130, 70, 4), (300, 33, 9), (1100, 12, 16)])
+def test_alns_dense(shape, dtype):
+    mm, nn, nd = shape
+    alns_check(random_dense(7000 + mm, mm, nn, nd, dtype=dtype), 25, ls_moves=4, destroy_count=max(1, nn // 8), seed=mm)
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_alns_dense_integer_ties(seed):
+    o = alns_check(random_dense(7100 + seed, 30, 20, 4, dtype=np.float32, integer=True), 40, ls_moves=5,
+                   destroy_count=3, seed=seed, ls_radius=0)
+    assert set(o.destroy.tolist()) == {0, 1} and set(o.repair.tolist()) == {0, 1}
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("shape", [(20, 9, 3, 0.4), (200, 150, 3, 0.1), (700, 300, 4, 0.05), (64, 40, 5, 1.0)])
+def test_alns_sparse(shape, dtype):
+    mm, nn, nd, dens = shape
+    alns_check(random_sparse(7200 + mm, mm, nn, nd, dens, dtype=dtype), 20, ls_moves=4,
+               destroy_count=max(1, nn // 10), seed=mm + 1)
+
+
+@pytest.mark.parametrize("rows", [7, 64, 1000])
+def test_alns_sparse_row_partitions(rows):
+    alns_check(random_sparse(7300, 300, 120, 3, 0.15, dtype=np.float32, integer=True), 20, ls_moves=3,
+               destroy_count=9, seed=4, sparse_partition_rows=rows)
+
+
+def test_alns_edge_parameters():
+    inst = random_dense(7400, 25, 10, 4)
+    alns_check(inst, 0)
+    alns_check(inst, 8, ls_moves=0, destroy_count=2, seed=2)
+    alns_check(inst, 8, ls_moves=3, destroy_count=10, seed=3)       # every variable unassigned
+    alns_check(inst, 8, ls_moves=3, destroy_count=500, seed=3)      # clipped to n
+    alns_check(inst, 8, ls_moves=3, destroy_count=0, seed=5)        # default rate: one variable
+    two = random_dense(7401, 12, 6, 2)                              # |D| = 2: one neighbour level only
+    alns_check(two, 12, ls_moves=3, destroy_count=2, seed=9)
+
+
+@pytest.mark.parametrize("idx", [1, 2, 3])
+def test_alns_small_configs(idx):
+    inst = make_config(idx, "small") if idx != 1 else make_config(1)
+    alns_check(inst, 12, ls_moves=6, seed=idx)
+
+
+def test_alns_same_seed_same_run_and_batched_is_refused():
+    m = dmmv()
+    inst = random_dense(7500, 60, 24, 5, dtype=np.float32)
+    with m.from_instance(inst, DEV) as h:
+        a = m.dmmv_alns(h, T(inst.x0), 15, seed=11)
+        b = m.dmmv_alns(h, T(inst.x0), 15, seed=11)
+        c = m.dmmv_alns(h, T(inst.x0), 15, seed=12)
+        assert torch.equal(a.trace, b.trace) and torch.equal(a.trace_t, b.trace_t) and torch.equal(a.x_best, b.x_best)
+        assert not torch.equal(a.trace_t, c.trace_t)
+    bi = random_batched(7501, 20, 6, 4, 3)
+    with m.from_instance(bi, DEV) as h:
+        with pytest.raises(m.DmmvError) as e:
+            m.dmmv_alns(h, T(bi.x0), 3)
+        assert e.value.status == -8
