@@ -122,3 +122,11 @@ def test_alns_same_seed_same_run_and_batched_is_refused():
         with pytest.raises(m.DmmvError) as e:
             m.dmmv_alns(h, T(bi.x0), 3)
         assert e.value.status == -8
+
+
+@pytest.mark.parametrize("idx,iters,ls", [(2, 40, 4), (3, 4, 3)])
+def test_alns_full_size_configs(idx, iters, ls):
+    """Full-size FIR and tomography workloads, a few outer iterations (what the oracle manages
+    in seconds), default destroy rate (0.5 % of n: 1 and 328 variables)."""
+    inst = make_config(idx)
+    alns_check(inst, iters, ls_moves=ls, seed=100 + idx)
