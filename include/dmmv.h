@@ -110,6 +110,9 @@ typedef struct {
                                 agrees with the sequential-order kernel only to fp32 rounding of the
                                 sum; 0 (default) = sequential order, bitwise reproducible.
                                 dmmv_create fails with DMMV_ERR_UNSUPPORTED if 1 is not applicable */
+    int32_t alns;            /* batched problems: 1 = reserve the workspace dmmv_alns needs (current
+                                and best solution, sampling weights and draws per instance, about
+                                R*(36 n + m w) bytes).  Single-instance handles always have it    */
 } dmmv_options;
 
 /* Bytes of device workspace dmmv_create needs for this problem (0 on invalid input, with
@@ -217,7 +220,9 @@ typedef struct {
  * operator (0 random, 1 worst-remove), repair operator (0 random, 1 greedy), moves the local
  * search made, accepted; trace_t [iters][2] = error after the local search, best error so
  * far.  Afterwards the handle holds the current (last accepted) solution.  Waits for the
- * stream.  DMMV_ERR_UNSUPPORTED for batched handles. */
+ * stream.  Batched handles (created with options.alns = 1): every instance runs its own loop
+ * with its own random stream (the instance number is part of the counter); x0 and x_best_out
+ * are [R][n], t_best_out [R], trace [R][iters][4], trace_t [R][iters][2]. */
 dmmv_status dmmv_alns(dmmv_handle h, const void* x0, const dmmv_alns_params* params, void* x_best_out,
                       void* t_best_out, int32_t* trace, void* trace_t);
 

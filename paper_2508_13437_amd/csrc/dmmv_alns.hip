@@ -18,33 +18,40 @@
 namespace dmmv {
 
 // ----------------------------------------------------------------------------------------
-// loop control
+// loop control.  R instances (R = 1 unless batched): instance q owns S[q], st[q], the slices
+// q*n.. of weight / prefix / first, q*count.. of picked; x and r are instance-contiguous
+// (kidx[j*R + q], r[i*R + q]) as everywhere in the batched path.
 // ----------------------------------------------------------------------------------------
 template <class T>
-__global__ void k_alns_init(AlnsState* S, const InstState<T>* st) {
-    if (threadIdx.x != 0) return;
-    for (int q = 0; q < 4; ++q) S->w[q] = 1.0;
-    S->t_cur = (double)st[0].t;
-    S->t_best = (double)st[0].t;
-    S->it = 0; S->d_op = 0; S->r_op = 0; S->accepted = 0; S->new_best = 0;
+__global__ void k_alns_init(AlnsState* S, const InstState<T>* st, int64_t R) {
+    const int64_t q = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    if (q >= R) return;
+    for (int u = 0; u < 4; ++u) S[q].w[u] = 1.0;
+    S[q].t_cur = (double)st[q].t;
+    S[q].t_best = (double)st[q].t;
+    S[q].it = 0; S[q].d_op = 0; S[q].r_op = 0; S[q].accepted = 0; S[q].new_best = 0;
 }
 
 // operators of this outer iteration by roulette wheel
-__global__ void k_alns_begin(AlnsState* S, uint64_t seed, uint64_t inst, int32_t it) {
-    if (threadIdx.x != 0) return;
-    const double ud = alns_unit(alns_rnd(seed, inst, (uint64_t)it, 0, 0));
-    const double ur = alns_unit(alns_rnd(seed, inst, (uint64_t)it, 0, 1));
-    S->it = it;
-    S->d_op = (ud * (S->w[0] + S->w[1]) < S->w[0]) ? 0 : 1;
-    S->r_op = (ur * (S->w[2] + S->w[3]) < S->w[2]) ? 0 : 1;
+__global__ void k_alns_begin(AlnsState* S, int64_t R, uint64_t seed, int32_t it) {
+    const int64_t q = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    if (q >= R) return;
+    const double ud = alns_unit(alns_rnd(seed, (uint64_t)q, (uint64_t)it, 0, 0));
+    const double ur = alns_unit(alns_rnd(seed, (uint64_t)q, (uint64_t)it, 0, 1));
+    S[q].it = it;
+    S[q].d_op = (ud * (S[q].w[0] + S[q].w[1]) < S[q].w[0]) ? 0 : 1;
+    S[q].r_op = (ur * (S[q].w[2] + S[q].w[3]) < S[q].w[2]) ? 0 : 1;
 }
 
-// inclusive prefix sums of the weights (single workgroup); only for the worst-remove operator
-__global__ __launch_bounds__(1024) void k_alns_scan(int64_t n, const uint64_t* __restrict__ weight,
-                                                    uint64_t* __restrict__ prefix, const AlnsState* S) {
+// inclusive prefix sums of the weights (one workgroup per instance); only for worst-remove
+__global__ __launch_bounds__(1024) void k_alns_scan(int64_t n, const uint64_t* __restrict__ weight_all,
+                                                    uint64_t* __restrict__ prefix_all, const AlnsState* S) {
     __shared__ uint64_t sh[1024];
     __shared__ uint64_t carry;
-    if (S->d_op != 1) return;
+    const int64_t q = blockIdx.x;
+    if (S[q].d_op != 1) return;
+    const uint64_t* __restrict__ weight = weight_all + q * n;
+    uint64_t* __restrict__ prefix = prefix_all + q * n;
     if (threadIdx.x == 0) carry = 0;
     __syncthreads();
     for (int64_t base = 0; base < n; base += 1024) {
@@ -65,28 +72,33 @@ __global__ __launch_bounds__(1024) void k_alns_scan(int64_t n, const uint64_t* _
     }
 }
 
-// Draw `count` distinct variables (single workgroup).  Draw c takes rnd(.., 1, c) mod total and
-// the first variable whose prefix sum exceeds it (all weights 1 for the random operator); a
-// variable drawn before is skipped.  1024 draws are made at a time: a draw is the first of its
-// variable exactly if it holds the largest stamp (iteration, -c) that variable has seen.
+// Draw `count` distinct variables (one workgroup per instance).  Draw c takes rnd(.., 1, c) mod
+// total and the first variable whose prefix sum exceeds it (all weights 1 for the random
+// operator); a variable drawn before is skipped.  blockDim.x draws are made at a time: a draw is
+// the first of its variable exactly if it holds the largest stamp (iteration, -c) that
+// variable has seen.
 __global__ __launch_bounds__(1024) void k_alns_sample(int64_t n, int32_t count,
-                                                      const uint64_t* __restrict__ prefix,
-                                                      unsigned long long* first,
-                                                      int32_t* __restrict__ picked, const AlnsState* S,
-                                                      uint64_t seed, uint64_t inst) {
+                                                      const uint64_t* __restrict__ prefix_all,
+                                                      unsigned long long* first_all,
+                                                      int32_t* __restrict__ picked_all, const AlnsState* S,
+                                                      uint64_t seed) {
     __shared__ int32_t sh_cnt[16];
     __shared__ int32_t sh_have;
-    const int32_t it = S->it;
-    const bool weighted = S->d_op == 1;
+    const int64_t q = blockIdx.x;
+    const uint64_t* __restrict__ prefix = prefix_all + q * n;
+    unsigned long long* first = first_all + q * n;
+    int32_t* __restrict__ picked = picked_all + q * (int64_t)count;
+    const int32_t it = S[q].it;
+    const bool weighted = S[q].d_op == 1;
     const uint64_t total = weighted ? prefix[n - 1] : (uint64_t)n;
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = blockDim.x >> 6;
     if (threadIdx.x == 0) sh_have = 0;
     __syncthreads();
-    for (uint64_t base = 0;; base += 1024) {
+    for (uint64_t base = 0;; base += blockDim.x) {
         const int32_t have = sh_have;
         if (have >= count) break;
         const uint64_t c = base + threadIdx.x;
-        const uint64_t v = alns_rnd(seed, inst, (uint64_t)it, 1, c) % total;
+        const uint64_t v = alns_rnd(seed, (uint64_t)q, (uint64_t)it, 1, c) % total;
         int64_t j;
         if (weighted) {
             int64_t lo = 0, hi = n - 1;
@@ -106,7 +118,7 @@ __global__ __launch_bounds__(1024) void k_alns_sample(int64_t n, int32_t count,
         if (lane == 0) sh_cnt[w] = __popcll(bal);
         __syncthreads();
         int32_t before = 0, all = 0;
-        for (int q = 0; q < 16; ++q) { if (q < w) before += sh_cnt[q]; all += sh_cnt[q]; }
+        for (int u = 0; u < nw; ++u) { if (u < w) before += sh_cnt[u]; all += sh_cnt[u]; }
         const int32_t pos = have + before + __popcll(bal & ((1ull << lane) - 1ull));
         if (is_first && pos < count) picked[pos] = (int32_t)j;
         __syncthreads();
@@ -115,68 +127,76 @@ __global__ __launch_bounds__(1024) void k_alns_sample(int64_t n, int32_t count,
     }
 }
 
-// acceptance, best solution, weights, trace (one thread)
+// acceptance, best solution, weights, trace (one thread per instance)
 template <class T>
-__global__ void k_alns_end(AlnsState* S, InstState<T>* st, double lambda, double sigma1, double sigma2,
-                           double sigma3, int32_t* trace, T* trace_t) {
-    if (threadIdx.x != 0) return;
-    const double t = (double)st[0].t;
-    const int32_t it = S->it;
-    const int accepted = t <= S->t_cur;
+__global__ void k_alns_end(AlnsState* S, InstState<T>* st, int64_t R, int32_t iters, double lambda,
+                           double sigma1, double sigma2, double sigma3, int32_t* trace, T* trace_t) {
+    const int64_t q = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    if (q >= R) return;
+    const double t = (double)st[q].t;
+    const int32_t it = S[q].it;
+    const int accepted = t <= S[q].t_cur;
     int new_best = 0;
     if (accepted) {
         double psi = sigma3;
-        if (t < S->t_cur) psi = sigma2;
-        if (t < S->t_best) { psi = sigma1; S->t_best = t; new_best = 1; }
-        S->t_cur = t;
+        if (t < S[q].t_cur) psi = sigma2;
+        if (t < S[q].t_best) { psi = sigma1; S[q].t_best = t; new_best = 1; }
+        S[q].t_cur = t;
         const double keep = 1.0 - lambda;
-        S->w[S->d_op] = keep * S->w[S->d_op] + lambda * psi;
-        S->w[2 + S->r_op] = keep * S->w[2 + S->r_op] + lambda * psi;
+        S[q].w[S[q].d_op] = keep * S[q].w[S[q].d_op] + lambda * psi;
+        S[q].w[2 + S[q].r_op] = keep * S[q].w[2 + S[q].r_op] + lambda * psi;
     }
-    S->accepted = accepted;
-    S->new_best = new_best;
+    S[q].accepted = accepted;
+    S[q].new_best = new_best;
+    const int64_t slot = q * (int64_t)iters + it;
     if (trace) {
-        trace[it * 4 + 0] = S->d_op; trace[it * 4 + 1] = S->r_op;
-        trace[it * 4 + 2] = st[0].moves; trace[it * 4 + 3] = accepted;
+        trace[slot * 4 + 0] = S[q].d_op; trace[slot * 4 + 1] = S[q].r_op;
+        trace[slot * 4 + 2] = st[q].moves; trace[slot * 4 + 3] = accepted;
     }
-    if (trace_t) { trace_t[it * 2 + 0] = st[0].t; trace_t[it * 2 + 1] = (T)S->t_best; }
-    if (!accepted) st[0].t = (T)S->t_cur;           // the copy kernel restores x and r
+    if (trace_t) { trace_t[slot * 2 + 0] = st[q].t; trace_t[slot * 2 + 1] = (T)S[q].t_best; }
+    if (!accepted) st[q].t = (T)S[q].t_cur;          // the copy kernel restores x and r
 }
 
 // accepted: current <- working (and best <- working for a new best); rejected: working <- current
 template <class T>
-__global__ void k_alns_copy(int64_t m, int64_t n, const AlnsState* S, int32_t* kidx, int32_t* kidx_cur,
-                            int32_t* kidx_best, T* r, T* r_cur) {
+__global__ void k_alns_copy(int64_t m, int64_t n, int64_t R, const AlnsState* S, int32_t* kidx,
+                            int32_t* kidx_cur, int32_t* kidx_best, T* r, T* r_cur) {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     const int64_t t0 = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
-    if (S->accepted) {
-        const bool nb = S->new_best != 0;
-        for (int64_t j = t0; j < n; j += stride) { const int32_t k = kidx[j]; kidx_cur[j] = k; if (nb) kidx_best[j] = k; }
-        for (int64_t i = t0; i < m; i += stride) r_cur[i] = r[i];
-    } else {
-        for (int64_t j = t0; j < n; j += stride) kidx[j] = kidx_cur[j];
-        for (int64_t i = t0; i < m; i += stride) r[i] = r_cur[i];
+    for (int64_t e = t0; e < n * R; e += stride) {
+        const AlnsState& s = S[e % R];
+        if (s.accepted) {
+            const int32_t k = kidx[e];
+            kidx_cur[e] = k;
+            if (s.new_best) kidx_best[e] = k;
+        } else {
+            kidx[e] = kidx_cur[e];
+        }
+    }
+    for (int64_t e = t0; e < m * R; e += stride) {
+        if (S[e % R].accepted) r_cur[e] = r[e]; else r[e] = r_cur[e];
     }
 }
 
 template <class T>
-__global__ void k_alns_snapshot(int64_t m, int64_t n, const int32_t* kidx, int32_t* kidx_cur,
+__global__ void k_alns_snapshot(int64_t m, int64_t n, int64_t R, const int32_t* kidx, int32_t* kidx_cur,
                                 int32_t* kidx_best, const T* r, T* r_cur, unsigned long long* first) {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     const int64_t t0 = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
-    for (int64_t j = t0; j < n; j += stride) { kidx_cur[j] = kidx[j]; kidx_best[j] = kidx[j]; first[j] = 0; }
-    for (int64_t i = t0; i < m; i += stride) r_cur[i] = r[i];
+    for (int64_t e = t0; e < n * R; e += stride) { kidx_cur[e] = kidx[e]; kidx_best[e] = kidx[e]; first[e] = 0; }
+    for (int64_t e = t0; e < m * R; e += stride) r_cur[e] = r[e];
 }
 
 template <class T>
-__global__ void k_alns_export(const AlnsState* S, T* t_best_out) {
-    if (threadIdx.x == 0 && t_best_out) t_best_out[0] = (T)S->t_best;
+__global__ void k_alns_export(const AlnsState* S, int64_t R, T* t_best_out) {
+    const int64_t q = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    if (q < R && t_best_out) t_best_out[q] = (T)S[q].t_best;
 }
 
 // ----------------------------------------------------------------------------------------
-// dense: impact weights and repair
+// dense matrix: impact weights and repair
 // ----------------------------------------------------------------------------------------
-// one workgroup per variable: weight_j = 1 + (sum over rows of the fixed-point terms >> shift)
+// single instance: one workgroup per variable, the rows spread over its threads
 template <class T>
 __global__ __launch_bounds__(256) void k_alns_impact_dense(int64_t m, int64_t n, const T* __restrict__ A,
                                                            int64_t lda, const T* __restrict__ r,
@@ -201,30 +221,67 @@ __global__ __launch_bounds__(256) void k_alns_impact_dense(int64_t m, int64_t n,
     }
 }
 
-// single workgroup; thread i owns the rows i, i + 1024, ...; the picked variables are
-// reassigned one after the other, r follows each reassignment
+// batched: lane = instance (r coalesced, X through the scalar unit, no reduction); grid.x =
+// group of 64 instances, each of the 4 wavefronts takes the variables blockIdx.y*4 + w, +4*gridDim.y, ...
 template <class T>
-__global__ __launch_bounds__(1024) void k_alns_repair_dense(int64_t m, int32_t nd, const T* __restrict__ A,
-                                                            int64_t lda, const T* __restrict__ D, T* r,
+__global__ __launch_bounds__(256) void k_alns_impact_batched(int64_t m, int64_t n, int64_t R,
+                                                             const T* __restrict__ Xt,
+                                                             const T* __restrict__ scale_q,
+                                                             const T* __restrict__ r,
+                                                             const InstState<T>* st, double alpha,
+                                                             uint64_t* __restrict__ weight, const AlnsState* S) {
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t q = blockIdx.x * 64ll + lane;
+    const bool live = q < R && S[q < R ? q : 0].d_op == 1;
+    if (__ballot(live) == 0ull) return;
+    const int64_t qc = q < R ? q : R - 1;
+    const double t = (double)st[qc].t;
+    const double scale = alns_impact_scale(t);
+    const double sc = (double)scale_q[qc];
+    int shift = alns_bits(m) + 24 + alns_bits(n) - 62;
+    if (shift < 0) shift = 0;
+    for (int64_t j = blockIdx.y * 4ll + w; j < n; j += 4ll * gridDim.y) {
+        uint64_t sum = 0;
+        if (live && scale != 0.0) {
+            for (int64_t i = 0; i < m; ++i) {
+                const double a = __builtin_fabs(sc * (double)Xt[i * n + j]);
+                sum += alns_impact_term(a, __builtin_fabs((double)r[i * R + qc]), t, alpha, scale);
+            }
+        }
+        if (live) weight[q * n + j] = 1 + (sum >> shift);
+    }
+}
+
+// one workgroup per instance; thread i owns the rows i, i + blockDim.x, ...; the picked
+// variables are reassigned one after the other, r follows each reassignment
+template <class T>
+__global__ __launch_bounds__(1024) void k_alns_repair_dense(int64_t m, int64_t R, int32_t nd,
+                                                            const T* __restrict__ A, int64_t lda,
+                                                            const T* __restrict__ D,
+                                                            const T* __restrict__ scale_q, T* r,
                                                             int32_t* kidx, int32_t count,
-                                                            const int32_t* __restrict__ picked,
+                                                            const int32_t* __restrict__ picked_all,
                                                             InstState<T>* st, const AlnsState* S,
-                                                            uint64_t seed, uint64_t inst) {
+                                                            uint64_t seed) {
     __shared__ T sh[16];
-    const int32_t it = S->it;
-    const bool greedy = S->r_op == 1;
+    const int64_t q = blockIdx.x;
+    const int32_t* __restrict__ picked = picked_all + q * (int64_t)count;
+    const int32_t it = S[q].it;
+    const bool greedy = S[q].r_op == 1;
+    const T sc = scale_q[q];
     for (int32_t pos = 0; pos < count; ++pos) {
         const int64_t j = picked[pos];
-        const int32_t kc = kidx[j];
+        const int32_t kc = kidx[j * R + q];
         const bool has_lo = kc > 0, has_hi = kc < nd - 1;
         const T* __restrict__ col = A + lda * j;
         int32_t knew;
         if (has_lo && has_hi) {
             if (greedy) {
-                const T dlo = step_of(D[kc - 1], D[kc], (T)1), dhi = step_of(D[kc + 1], D[kc], (T)1);
+                const T dlo = step_of(D[kc - 1], D[kc], sc), dhi = step_of(D[kc + 1], D[kc], sc);
                 T elo = (T)0, ehi = (T)0;
                 for (int64_t i = threadIdx.x; i < m; i += blockDim.x) {
-                    const T a = col[i], ri = r[i];
+                    const T a = col[i], ri = r[i * R + q];
                     elo = dmmv_max(elo, dmmv_abs(dmmv_fma(dlo, a, ri)));
                     ehi = dmmv_max(ehi, dmmv_abs(dmmv_fma(dhi, a, ri)));
                 }
@@ -232,30 +289,36 @@ __global__ __launch_bounds__(1024) void k_alns_repair_dense(int64_t m, int32_t n
                 ehi = block_max(ehi, sh);
                 knew = ehi < elo ? kc + 1 : kc - 1;
             } else {
-                knew = (alns_rnd(seed, inst, (uint64_t)it, 2, (uint64_t)pos) & 1) ? kc + 1 : kc - 1;
+                knew = (alns_rnd(seed, (uint64_t)q, (uint64_t)it, 2, (uint64_t)pos) & 1) ? kc + 1 : kc - 1;
             }
         } else {
             knew = has_lo ? kc - 1 : kc + 1;
         }
-        const T delta = step_of(D[knew], D[kc], (T)1);
-        for (int64_t i = threadIdx.x; i < m; i += blockDim.x) r[i] = dmmv_fma(delta, col[i], r[i]);
-        __syncthreads();                      // every thread has read kidx[j] of this step
-        if (threadIdx.x == 0) kidx[j] = knew;
+        const T delta = step_of(D[knew], D[kc], sc);
+        for (int64_t i = threadIdx.x; i < m; i += blockDim.x) r[i * R + q] = dmmv_fma(delta, col[i], r[i * R + q]);
+        __syncthreads();                      // every thread has read kidx of this step
+        if (threadIdx.x == 0) kidx[j * R + q] = knew;
     }
     T tmax = (T)0;
-    for (int64_t i = threadIdx.x; i < m; i += blockDim.x) tmax = dmmv_max(tmax, dmmv_abs(r[i]));
+    for (int64_t i = threadIdx.x; i < m; i += blockDim.x) tmax = dmmv_max(tmax, dmmv_abs(r[i * R + q]));
     tmax = block_max(tmax, sh);
-    if (threadIdx.x == 0) { st[0].t = tmax; st[0].done = 0; st[0].moves = 0; }
+    if (threadIdx.x == 0) { st[q].t = tmax; st[q].done = 0; st[q].moves = 0; }
 }
 
 // ----------------------------------------------------------------------------------------
 // host side: one outer iteration's kernels around the local search
 // ----------------------------------------------------------------------------------------
+static unsigned blocks_for(int64_t items, int per_block) {
+    int64_t b = (items + per_block - 1) / per_block;
+    return (unsigned)(b < 1 ? 1 : b);
+}
+
 template <class T>
 static dmmv_status start_t(Ctx* c) {
-    hipLaunchKernelGGL(k_alns_init<T>, dim3(1), dim3(64), 0, c->stream, (AlnsState*)c->alns_state,
-                       (const InstState<T>*)c->state);
-    hipLaunchKernelGGL(k_alns_snapshot<T>, dim3(256), dim3(256), 0, c->stream, c->p.m, c->p.n,
+    const int64_t R = c->p.R;
+    hipLaunchKernelGGL(k_alns_init<T>, dim3(blocks_for(R, 256)), dim3(256), 0, c->stream,
+                       (AlnsState*)c->alns_state, (const InstState<T>*)c->state, R);
+    hipLaunchKernelGGL(k_alns_snapshot<T>, dim3(1024), dim3(256), 0, c->stream, c->p.m, c->p.n, R,
                        (const int32_t*)c->kidx, c->alns_kidx_cur, c->alns_kidx_best, (const T*)c->r,
                        (T*)c->alns_r_cur, (unsigned long long*)c->alns_first);
     DMMV_LAUNCH_CHECK();
@@ -265,26 +328,34 @@ static dmmv_status start_t(Ctx* c) {
 template <class T>
 static dmmv_status destroy_repair_t(Ctx* c, const dmmv_alns_params& prm, int32_t it, int32_t count) {
     AlnsState* S = (AlnsState*)c->alns_state;
-    hipLaunchKernelGGL(k_alns_begin, dim3(1), dim3(64), 0, c->stream, S, prm.seed, (uint64_t)0, it);
+    const int64_t R = c->p.R;
+    hipLaunchKernelGGL(k_alns_begin, dim3(blocks_for(R, 256)), dim3(256), 0, c->stream, S, R, prm.seed, it);
     if (c->kind == KIND_DENSE) {
         hipLaunchKernelGGL(k_alns_impact_dense<T>, dim3((unsigned)c->p.n), dim3(256), 0, c->stream, c->p.m,
                            c->p.n, (const T*)c->p.A_dense, c->p.lda, (const T*)c->r,
                            (const InstState<T>*)c->state, prm.alpha, c->alns_weight, (const AlnsState*)S);
+    } else if (c->kind == KIND_BATCHED) {
+        int64_t ny = (c->p.n + 3) / 4;
+        if (ny > 2048) ny = 2048;
+        hipLaunchKernelGGL(k_alns_impact_batched<T>, dim3(blocks_for(R, 64), (unsigned)ny), dim3(256), 0,
+                           c->stream, c->p.m, c->p.n, R, (const T*)c->Xt, (const T*)c->scale_dev,
+                           (const T*)c->r, (const InstState<T>*)c->state, prm.alpha, c->alns_weight,
+                           (const AlnsState*)S);
     } else {
         DMMV_TRY(csc_alns_impact(c, prm.alpha));
     }
-    hipLaunchKernelGGL(k_alns_scan, dim3(1), dim3(1024), 0, c->stream, c->p.n, (const uint64_t*)c->alns_weight,
-                       c->alns_prefix, (const AlnsState*)S);
-    hipLaunchKernelGGL(k_alns_sample, dim3(1), dim3(1024), 0, c->stream, c->p.n, count,
+    hipLaunchKernelGGL(k_alns_scan, dim3((unsigned)R), dim3(1024), 0, c->stream, c->p.n,
+                       (const uint64_t*)c->alns_weight, c->alns_prefix, (const AlnsState*)S);
+    hipLaunchKernelGGL(k_alns_sample, dim3((unsigned)R), dim3(R > 1 ? 256 : 1024), 0, c->stream, c->p.n, count,
                        (const uint64_t*)c->alns_prefix, (unsigned long long*)c->alns_first, c->alns_picked,
-                       (const AlnsState*)S, prm.seed, (uint64_t)0);
-    if (c->kind == KIND_DENSE) {
-        hipLaunchKernelGGL(k_alns_repair_dense<T>, dim3(1), dim3(1024), 0, c->stream, c->p.m, c->p.nd,
-                           (const T*)c->p.A_dense, c->p.lda, (const T*)c->D_dev, (T*)c->r, c->kidx, count,
-                           (const int32_t*)c->alns_picked, (InstState<T>*)c->state, (const AlnsState*)S,
-                           prm.seed, (uint64_t)0);
-    } else {
+                       (const AlnsState*)S, prm.seed);
+    if (c->kind == KIND_CSC) {
         DMMV_TRY(csc_alns_repair(c, count, prm.seed));
+    } else {
+        hipLaunchKernelGGL(k_alns_repair_dense<T>, dim3((unsigned)R), dim3(R > 1 ? 256 : 1024), 0, c->stream,
+                           c->p.m, R, c->p.nd, (const T*)c->p.A_dense, c->p.lda, (const T*)c->D_dev,
+                           (const T*)c->scale_dev, (T*)c->r, c->kidx, count, (const int32_t*)c->alns_picked,
+                           (InstState<T>*)c->state, (const AlnsState*)S, prm.seed);
     }
     DMMV_LAUNCH_CHECK();
     return DMMV_OK;
@@ -293,10 +364,13 @@ static dmmv_status destroy_repair_t(Ctx* c, const dmmv_alns_params& prm, int32_t
 template <class T>
 static dmmv_status finish_iteration_t(Ctx* c, const dmmv_alns_params& prm, int32_t* trace, void* trace_t) {
     AlnsState* S = (AlnsState*)c->alns_state;
-    hipLaunchKernelGGL(k_alns_end<T>, dim3(1), dim3(64), 0, c->stream, S, (InstState<T>*)c->state, prm.lambda,
-                       prm.sigma1, prm.sigma2, prm.sigma3, trace, (T*)trace_t);
-    hipLaunchKernelGGL(k_alns_copy<T>, dim3(256), dim3(256), 0, c->stream, c->p.m, c->p.n, (const AlnsState*)S,
-                       c->kidx, c->alns_kidx_cur, c->alns_kidx_best, (T*)c->r, (T*)c->alns_r_cur);
+    const int64_t R = c->p.R;
+    hipLaunchKernelGGL(k_alns_end<T>, dim3(blocks_for(R, 256)), dim3(256), 0, c->stream, S,
+                       (InstState<T>*)c->state, R, prm.iters, prm.lambda, prm.sigma1, prm.sigma2, prm.sigma3,
+                       trace, (T*)trace_t);
+    hipLaunchKernelGGL(k_alns_copy<T>, dim3(1024), dim3(256), 0, c->stream, c->p.m, c->p.n, R,
+                       (const AlnsState*)S, c->kidx, c->alns_kidx_cur, c->alns_kidx_best, (T*)c->r,
+                       (T*)c->alns_r_cur);
     DMMV_LAUNCH_CHECK();
     if (c->kind == KIND_CSC) DMMV_TRY(csc_alns_after_copy(c));
     return DMMV_OK;
@@ -304,8 +378,8 @@ static dmmv_status finish_iteration_t(Ctx* c, const dmmv_alns_params& prm, int32
 
 template <class T>
 static dmmv_status export_t(Ctx* c, void* t_best_out) {
-    hipLaunchKernelGGL(k_alns_export<T>, dim3(1), dim3(64), 0, c->stream, (const AlnsState*)c->alns_state,
-                       (T*)t_best_out);
+    hipLaunchKernelGGL(k_alns_export<T>, dim3(blocks_for(c->p.R, 256)), dim3(256), 0, c->stream,
+                       (const AlnsState*)c->alns_state, c->p.R, (T*)t_best_out);
     DMMV_LAUNCH_CHECK();
     return DMMV_OK;
 }

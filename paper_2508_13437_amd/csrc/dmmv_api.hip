@@ -71,16 +71,17 @@ size_t workspace_layout(const dmmv_problem& p, const dmmv_options& o, Ctx* c, ch
     b.take(&c->r, (size_t)p.m * p.R * esz);
     c->red_elems = 1024;
     b.take(&c->red, (size_t)c->red_elems * esz);
-    if (!batched) {
-        // ALNS outer loop: current and best solution, sampling weights, draws
-        b.take(&c->alns_state, sizeof(AlnsState));
-        b.take(&c->alns_kidx_cur, (size_t)p.n * sizeof(int32_t));
-        b.take(&c->alns_kidx_best, (size_t)p.n * sizeof(int32_t));
-        b.take(&c->alns_r_cur, (size_t)p.m * esz);
-        b.take(&c->alns_weight, (size_t)p.n * sizeof(uint64_t));
-        b.take(&c->alns_prefix, (size_t)p.n * sizeof(uint64_t));
-        b.take(&c->alns_first, (size_t)p.n * sizeof(uint64_t));
-        b.take(&c->alns_picked, (size_t)p.n * sizeof(int32_t));
+    if (!batched || o.alns) {
+        // ALNS outer loop: current and best solution, sampling weights, draws (per instance)
+        const size_t nR = (size_t)p.n * p.R, mR = (size_t)p.m * p.R;
+        b.take(&c->alns_state, (size_t)p.R * sizeof(AlnsState));
+        b.take(&c->alns_kidx_cur, nR * sizeof(int32_t));
+        b.take(&c->alns_kidx_best, nR * sizeof(int32_t));
+        b.take(&c->alns_r_cur, mR * esz);
+        b.take(&c->alns_weight, nR * sizeof(uint64_t));
+        b.take(&c->alns_prefix, nR * sizeof(uint64_t));
+        b.take(&c->alns_first, nR * sizeof(uint64_t));
+        b.take(&c->alns_picked, nR * sizeof(int32_t));
         if (sparse) b.take(&c->alns_touched, (size_t)p.m);
     }
     if (sparse) {
@@ -560,7 +561,9 @@ static dmmv_status alns_run(dmmv_ctx* c, const void* x0, const dmmv_alns_params&
     }();
     c->o = saved;
     DMMV_TRY(st);
-    if (x_best_out) {
+    if (x_best_out && c->kind == KIND_BATCHED) {
+        DMMV_TRY(batched_get_x_from(c, c->alns_kidx_best, x_best_out));
+    } else if (x_best_out) {
         if (c->p.dtype == DMMV_F64)
             hipLaunchKernelGGL(k_index_to_values<double>, grid1(c->p.n, 256), dim3(256), 0, c->stream,
                                (const int32_t*)c->alns_kidx_best, (const double*)c->D_dev, c->p.n, (double*)x_best_out);
@@ -800,7 +803,8 @@ dmmv_status dmmv_alns(dmmv_handle h, const void* x0, const dmmv_alns_params* par
                       void* t_best_out, int32_t* trace, void* trace_t) {
     if (!h) return fail(DMMV_ERR_NULL, "handle is NULL");
     if (!params) return fail(DMMV_ERR_NULL, "params is NULL");
-    if (h->kind == KIND_BATCHED) return fail(DMMV_ERR_UNSUPPORTED, "dmmv_alns: batched handles are not supported");
+    if (h->kind == KIND_BATCHED && !h->o.alns)
+        return fail(DMMV_ERR_STATE, "dmmv_alns: a batched handle needs options.alns = 1 at dmmv_create (workspace for the outer loop)");
     if (params->iters < 0 || params->ls_moves < 0 || params->ls_radius < 0 || params->destroy_count < 0)
         return fail(DMMV_ERR_SHAPE, "dmmv_alns: iters, ls_moves, ls_radius and destroy_count must be >= 0");
     if (!(params->alpha >= 0.0) || !(params->lambda >= 0.0 && params->lambda <= 1.0) ||

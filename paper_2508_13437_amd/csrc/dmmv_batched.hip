@@ -372,6 +372,18 @@ dmmv_status batched_apply(Ctx* c, bool tf, int32_t iters, dmmv_move* trace, void
     return c->p.dtype == DMMV_F64 ? apply_t<double>(c, tf, iters, trace, trace_t) : apply_t<float>(c, tf, iters, trace, trace_t);
 }
 dmmv_status batched_set_x(Ctx* c, const void* x) { return c->p.dtype == DMMV_F64 ? set_x_t<double>(c, x) : set_x_t<float>(c, x); }
+dmmv_status batched_get_x_from(Ctx* c, const int32_t* kidx, void* x) {
+    const int64_t tot = c->p.n * c->p.R;
+    if (tot == 0) return DMMV_OK;
+    if (c->p.dtype == DMMV_F64)
+        hipLaunchKernelGGL(k_index_to_values_batched<double>, dim3((unsigned)ceil_div(tot, 256)), dim3(256), 0, c->stream,
+                           kidx, (const double*)c->D_dev, c->p.n, c->p.R, (double*)x);
+    else
+        hipLaunchKernelGGL(k_index_to_values_batched<float>, dim3((unsigned)ceil_div(tot, 256)), dim3(256), 0, c->stream,
+                           kidx, (const float*)c->D_dev, c->p.n, c->p.R, (float*)x);
+    DMMV_LAUNCH_CHECK();
+    return DMMV_OK;
+}
 dmmv_status batched_get_x(Ctx* c, void* x) { return c->p.dtype == DMMV_F64 ? get_x_t<double>(c, x) : get_x_t<float>(c, x); }
 dmmv_status batched_set_r(Ctx* c, const void* r) {
     // caller layout [R][m] -> internal [m][R]

@@ -117,8 +117,8 @@ struct Ctx {
     void* Xt;             // T[m][n] row-major copy of X
     void* Bt;             // T[m][R]
     int32_t chunk_cols;   // columns per chunk of the fused evaluation (n_partials chunks)
-    // ALNS outer loop (dense and sparse single instances)
-    void* alns_state;         // AlnsState
+    // ALNS outer loop (per instance; batched handles only with options.alns)
+    void* alns_state;         // AlnsState[R]
     int32_t* alns_kidx_cur;   // [n] current (last accepted) solution
     int32_t* alns_kidx_best;  // [n] best solution
     void* alns_r_cur;         // T[m] residual of the current solution
@@ -189,6 +189,7 @@ dmmv_status batched_eval(Ctx* c, void* scores_out, bool want_partials);
 dmmv_status batched_apply(Ctx* c, bool t_from_score, int32_t iters, dmmv_move* trace, void* trace_t);
 dmmv_status batched_set_x(Ctx* c, const void* x_values);
 dmmv_status batched_get_x(Ctx* c, void* x_values);
+dmmv_status batched_get_x_from(Ctx* c, const int32_t* kidx, void* x_values);
 dmmv_status batched_set_r(Ctx* c, const void* r);
 dmmv_status batched_get_r(Ctx* c, void* r);
 dmmv_status batched_maxabs(Ctx* c);     // state[q].t = max_i |r[i][q]|

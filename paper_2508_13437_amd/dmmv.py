@@ -47,7 +47,7 @@ class Problem(C.Structure):
 class Options(C.Structure):
     _fields_ = [("radius", C.c_int32), ("keep_going", C.c_int32), ("poll_every", C.c_int32),
                 ("sparse_partition_rows", C.c_int32), ("var_mask", C.c_void_p),
-                ("residual_mfma", C.c_int32)]
+                ("residual_mfma", C.c_int32), ("alns", C.c_int32)]
 
 
 class AlnsParams(C.Structure):
@@ -127,7 +127,7 @@ class Handle:
 
     def __init__(self, *, D, b, A=None, csr=None, m=None, n=None, scale=None, radius: int = 0,
                  keep_going: bool = False, poll_every: int = 64, var_mask=None,
-                 sparse_partition_rows: int = 0, residual_mfma: bool = False,
+                 sparse_partition_rows: int = 0, residual_mfma: bool = False, alns: bool = False,
                  stream: Optional[torch.cuda.Stream] = None, device=None):
         lib = load()
         self._h = C.c_void_p(None)
@@ -181,6 +181,7 @@ class Handle:
         o.radius, o.keep_going, o.poll_every = int(radius), int(bool(keep_going)), int(poll_every)
         o.sparse_partition_rows = int(sparse_partition_rows)
         o.residual_mfma = int(bool(residual_mfma))
+        o.alns = int(bool(alns))
         if var_mask is not None:
             var_mask = var_mask.to(torch.uint8).contiguous()
             if var_mask.numel() != self.R * self.n:
@@ -319,10 +320,11 @@ def dmmv_solve(h: Handle, x0: Optional[torch.Tensor], iters: int, trace: bool = 
 
 @dataclass
 class AlnsResult:
-    x_best: torch.Tensor       # [n]
-    t_best: torch.Tensor       # [1]
+    x_best: torch.Tensor       # [n] ([R][n] batched)
+    t_best: torch.Tensor       # [1] ([R])
     trace: torch.Tensor        # [iters][4] int32: destroy op, repair op, local-search moves, accepted
     trace_t: torch.Tensor      # [iters][2]: error after the local search, best error so far
+                               # (both with a leading [R] for batched handles)
 
 
 def dmmv_alns(h: Handle, x0: Optional[torch.Tensor], iters: int, ls_moves: int = 8, ls_radius: int = 1,
@@ -333,13 +335,15 @@ def dmmv_alns(h: Handle, x0: Optional[torch.Tensor], iters: int, ls_moves: int =
                      float(lambda_), float(sigma1), float(sigma2), float(sigma3), int(seed))
     if x0 is not None:
         x0 = x0.to(h.device, h.dtype).contiguous()
-    x_best = h._new((h.n,))
-    t_best = h._new((1,))
-    trace = torch.full((max(iters, 1), 4), -1, dtype=torch.int32, device=h.device)
-    trace_t = h._new((max(iters, 1), 2))
+    x_best = h._new(h._xshape())
+    t_best = h._new((h.R,))
+    trace = torch.full((h.R, max(iters, 1), 4), -1, dtype=torch.int32, device=h.device)
+    trace_t = h._new((h.R, max(iters, 1), 2))
     _check(load().dmmv_alns(h._h, _ptr(x0), C.byref(prm), _ptr(x_best), _ptr(t_best), _ptr(trace),
                             _ptr(trace_t)))
-    return AlnsResult(x_best, t_best, trace[:iters], trace_t[:iters])
+    if not h.batched:
+        return AlnsResult(x_best, t_best, trace[0, :iters], trace_t[0, :iters])
+    return AlnsResult(x_best, t_best, trace[:, :iters], trace_t[:, :iters])
 
 
 def dmmv_time_eval(h: Handle, reps: int) -> float:

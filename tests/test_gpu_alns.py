@@ -118,10 +118,50 @@ def test_alns_same_seed_same_run_and_batched_is_refused():
         assert torch.equal(a.trace, b.trace) and torch.equal(a.trace_t, b.trace_t) and torch.equal(a.x_best, b.x_best)
         assert not torch.equal(a.trace_t, c.trace_t)
     bi = random_batched(7501, 20, 6, 4, 3)
-    with m.from_instance(bi, DEV) as h:
+    with m.from_instance(bi, DEV) as h:                     # created without options.alns
         with pytest.raises(m.DmmvError) as e:
             m.dmmv_alns(h, T(bi.x0), 3)
-        assert e.value.status == -8
+        assert e.value.status == -7
+
+
+def batched_alns_check(inst, iters, **kw):
+    m = dmmv()
+    print("alns batched case", inst.name, iters, kw, flush=True)
+    prm = orc.alns_params(iters, **kw)
+    with m.from_instance(inst, DEV, alns=True) as h:
+        res = m.dmmv_alns(h, T(inst.x0), iters, **kw)
+        tr, tt = N(res.trace), N(res.trace_t)
+        xb, tb = N(res.x_best), N(res.t_best)
+        x, r, t = m.dmmv_get_state(h)
+        r, t = N(r), N(t)
+    for q in range(inst.R):
+        o = orc.alns_dense(inst.A, inst.b[q], inst.D, inst.x0[q], prm, inst=q, scale=float(inst.scale[q]))
+        assert np.array_equal(tr[q, :, 0], o.destroy), q
+        assert np.array_equal(tr[q, :, 1], o.repair), q
+        assert np.array_equal(tt[q, :, 0], o.t), (q, tt[q, :, 0], o.t)
+        assert np.array_equal(tr[q, :, 2], o.moves), q
+        assert np.array_equal(tr[q, :, 3], o.accepted), q
+        assert np.array_equal(tt[q, :, 1], o.best), q
+        assert np.array_equal(xb[q], o.x), q
+        assert tb[q] == o.t_best
+        assert np.abs(r[q]).max() == t[q]
+
+
+@pytest.mark.parametrize("shape", [(1, 1, 1, 2), (17, 5, 3, 3), (64, 24, 64, 4), (100, 33, 65, 8), (130, 70, 130, 16)])
+def test_alns_batched_random(shape):
+    mm, nn, R, nd = shape
+    batched_alns_check(random_batched(7600 + mm, mm, nn, R, nd), 10, ls_moves=3, destroy_count=max(1, nn // 8), seed=mm)
+
+
+def test_alns_batched_integer_ties_and_f64():
+    batched_alns_check(random_batched(7700, 40, 16, 20, 5, integer=True), 20, ls_moves=4, destroy_count=3, seed=4,
+                       ls_radius=0)
+    batched_alns_check(random_batched(7701, 30, 12, 9, 4, dtype=np.float64), 12, ls_moves=3, destroy_count=2, seed=6)
+
+
+@pytest.mark.parametrize("idx", [4, 5])
+def test_alns_batched_small_llm_configs(idx):
+    batched_alns_check(make_config(idx, "small"), 6, ls_moves=4, seed=idx)
 
 
 @pytest.mark.parametrize("idx,iters,ls", [(2, 40, 4), (3, 4, 3)])
