@@ -1,13 +1,14 @@
 // Sparse single-instance path, part 1: building the row-partitioned, column-compressed copy
 // of a CSR matrix on the device, the residual, the reservoir of the rows of largest |r|, and
-// the kernels that apply a move.  The evaluation kernels are in dmmv_sparse_eval.hip.
+// the kernels that apply a move, and the layout-dependent kernels of the ALNS outer loop
+// (impact weights, repair).  The evaluation kernels are in dmmv_sparse_eval.hip.
 //
 // Layout.  Rows are cut into P partitions of at most MP rows, MP chosen so that one partition
 // of the residual fits the LDS budget of an evaluation workgroup.  Inside a partition the
 // entries are stored column by column, rows ascending, as a 16-bit row offset and a value
 // (6 bytes per entry in fp32).  Segment s = p*n + j holds the entries of column j that fall in
-// partition p; every segment starts on a multiple of four entries and is padded to one (pad =
-// row offset MP, value 0).
+// partition p; every segment starts on a multiple of four entries, is padded to one and holds
+// at least four (pad = row offset MP, value 0).
 //
 // Reservoir.  The rows of largest |r| in a strict total order (|r| descending, row ascending),
 // kept sorted on the device together with a floor key: the reservoir holds EVERY row at or

@@ -112,3 +112,26 @@ def test_product_does_not_import_the_oracle():
             if f.endswith((".py", ".hip", ".h")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in text.lower(), os.path.join(dirpath, f)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    p = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert p.returncode == 2
+    assert "one GPU" in p.stderr and p.stdout.strip() == ""
+
+
+def test_alns_parameter_blocks_of_binding_and_oracle_have_the_layout_of_the_header(mod):
+    # include/dmmv.h: four int32, five doubles, one uint64 -> 4*4 + 5*8 + 8 bytes, no padding
+    import ctypes as C
+    from oracle import oracle as orc
+    assert C.sizeof(mod.AlnsParams) == 64 == C.sizeof(orc.AlnsParams)
+    assert [f[0].rstrip("_") for f in mod.AlnsParams._fields_] == [f[0].rstrip("_") for f in orc.AlnsParams._fields_]
+    hdr = open(os.path.join(ROOT, "include", "dmmv.h")).read()
+    body = hdr[hdr.index("typedef struct {\n    int32_t iters;"):hdr.index("} dmmv_alns_params;")]
+    import re
+    names = []
+    for decl in re.findall(r"^\s+(?:int32_t|double|uint64_t)\s+([a-z0-9_, ]+);", body, flags=re.M):
+        names += [v.strip() for v in decl.split(",")]
+    assert names == ["iters", "ls_moves", "ls_radius", "destroy_count", "alpha", "lambda", "sigma1", "sigma2", "sigma3", "seed"]
