@@ -110,6 +110,12 @@ typedef struct {
                                 agrees with the sequential-order kernel only to fp32 rounding of the
                                 sum; 0 (default) = sequential order, bitwise reproducible.
                                 dmmv_create fails with DMMV_ERR_UNSUPPORTED if 1 is not applicable */
+    int32_t prune;           /* sparse matrices: 1 = the descent (dmmv_solve without keep_going, the
+                                local search of dmmv_alns) scores only the moves of the variables
+                                with an entry in the row of largest |r_i|: a move that leaves
+                                that row alone cannot lower the maximum, so the moves applied are
+                                the same as with the full evaluation and an iteration costs far
+                                less.  dmmv_eval_moves and dmmv_argmin_move always score all     */
     int32_t alns;            /* batched problems: 1 = reserve the workspace dmmv_alns needs (current
                                 and best solution, sampling weights and draws per instance, about
                                 R*(36 n + m w) bytes).  Single-instance handles always have it    */

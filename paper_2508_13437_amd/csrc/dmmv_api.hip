@@ -112,6 +112,7 @@ size_t workspace_layout(const dmmv_problem& p, const dmmv_options& o, Ctx* c, ch
         b.take(&c->res_row, (size_t)RES_CAP * sizeof(int32_t));
         b.take(&c->res_meta, 4 * sizeof(int32_t));
         b.take(&c->res_floor, esz);
+        if (o.prune) b.take(&c->prune_part, (size_t)(p.n > 0 ? p.n : 1) * part_sz);
     } else if (batched) {
         c->chunk_cols = batched_chunk_cols(p);
         c->n_partials = ceil_div(p.n, c->chunk_cols);
@@ -450,12 +451,25 @@ static dmmv_status apply_any(Ctx* c, bool t_from_score, int32_t iters, dmmv_move
     }
 }
 
+// One step of the descent.  Sparse matrices with options.prune (and not in fixed-work mode)
+// score only the columns that touch the row of largest |r|: same moves, far less work.
+static dmmv_status loop_step(Ctx* c, int32_t iters, dmmv_move* trace, void* trace_t);
+
 // one loop step after the evaluation: pick the best move and apply it if it improves
 static dmmv_status select_apply_any(Ctx* c, int32_t iters, dmmv_move* trace, void* trace_t) {
-    if (c->kind == KIND_CSC) return csc_select_apply(c, iters, trace, trace_t);
+    if (c->kind == KIND_CSC) return csc_select_apply(c, iters, trace, trace_t, false);
     if (c->kind == KIND_DENSE && dense_has_fused_select_apply(c)) return dense_select_apply(c, iters, trace, trace_t);
     DMMV_TRY(launch_select(c, nullptr, nullptr));
     return apply_any(c, true, iters, trace, trace_t);
+}
+
+static dmmv_status loop_step(Ctx* c, int32_t iters, dmmv_move* trace, void* trace_t) {
+    if (c->kind == KIND_CSC && c->o.prune && !c->o.keep_going && c->p.n > 0) {
+        DMMV_TRY(csc_eval_pruned(c, true));
+        return csc_select_apply(c, iters, trace, trace_t, true);
+    }
+    DMMV_TRY(eval_any(c, nullptr, true, true));
+    return select_apply_any(c, iters, trace, trace_t);
 }
 
 static dmmv_status residual_any(Ctx* c) {
@@ -509,8 +523,7 @@ static dmmv_status solve_t(dmmv_ctx* c, const void* x0, int32_t iters, void* x_o
         hipLaunchKernelGGL(k_fill_trace<T>, grid1(R * (int64_t)iters, 256), dim3(256), 0, c->stream, trace, (T*)trace_t, R * (int64_t)iters);
     const int32_t poll = c->o.keep_going ? 0 : c->o.poll_every;
     for (int32_t it = 0; it < iters; ++it) {
-        DMMV_TRY(eval_any(c, nullptr, true, true));
-        DMMV_TRY(select_apply_any(c, iters, trace, trace_t));
+        DMMV_TRY(loop_step(c, iters, trace, trace_t));
         if (poll > 0 && (it + 1) % poll == 0 && it + 1 < iters) {
             int32_t active = 0;
             hipLaunchKernelGGL(k_zero_flags, dim3(1), dim3(64), 0, c->stream, c->flags);
@@ -551,8 +564,7 @@ static dmmv_status alns_run(dmmv_ctx* c, const void* x0, const dmmv_alns_params&
         for (int32_t it = 0; it < prm.iters; ++it) {
             DMMV_TRY(alns_destroy_repair(c, prm, it, (int32_t)count));
             for (int32_t mv = 0; mv < prm.ls_moves; ++mv) {
-                DMMV_TRY(eval_any(c, nullptr, true, true));
-                DMMV_TRY(select_apply_any(c, prm.ls_moves, nullptr, nullptr));
+                DMMV_TRY(loop_step(c, prm.ls_moves, nullptr, nullptr));
             }
             DMMV_TRY(alns_finish_iteration(c, prm, trace, trace_t));
         }
@@ -653,7 +665,13 @@ dmmv_status dmmv_create(dmmv_handle* out, const dmmv_problem* problem, const dmm
         else
             hipLaunchKernelGGL(k_init_state<float>, grid1(problem->R, 256), dim3(256), 0, c->stream, (InstState<float>*)c->state, problem->R);
         DMMV_LAUNCH_CHECK();
-        if (c->kind == KIND_CSC) DMMV_TRY(csc_build(c));
+        c->csc_max_row = 0;
+        if (c->kind == KIND_CSC) {
+            DMMV_TRY(csc_build(c));
+            DMMV_HIP_CHECK(hipMemcpyAsync(&c->csc_max_row, &c->flags[FLAG_MAXROW], sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
+            DMMV_HIP_CHECK(hipStreamSynchronize(c->stream));
+            if (c->csc_max_row > c->p.n) c->csc_max_row = (int32_t)c->p.n;   // duplicates are an error anyway
+        }
         if (c->kind == KIND_BATCHED) DMMV_TRY(batched_build(c));
         c->mfma_planes = 1;
         if (o.residual_mfma) {

@@ -72,7 +72,7 @@ struct alignas(16) Partial {
 };
 
 // device flag slots
-enum { FLAG_ERROR = 0, FLAG_ACTIVE = 1, FLAG_PLANES = 2, FLAG_COUNT = 8 };
+enum { FLAG_ERROR = 0, FLAG_ACTIVE = 1, FLAG_PLANES = 2, FLAG_MAXROW = 3, FLAG_COUNT = 8 };
 // error bits set by kernels
 enum { ERRBIT_X_NOT_IN_D = 1, ERRBIT_CSR_RANGE = 2, ERRBIT_CSR_DUP = 4, ERRBIT_MOVE_RANGE = 8 };
 
@@ -112,6 +112,8 @@ struct Ctx {
     int32_t* res_row;     // [RES_CAP]
     int32_t* res_meta;    // [4] count, floor row
     void* res_floor;      // T[1] floor value
+    int32_t csc_max_row;  // most stored entries in one row (slots of the pruned evaluation)
+    void* prune_part;     // Partial<T>[n] records of the pruned evaluation (options.prune)
 
     // batched
     void* Xt;             // T[m][n] row-major copy of X
@@ -181,7 +183,8 @@ dmmv_status csc_reservoir(Ctx* c);      // rebuild the reservoir of largest |r| 
 dmmv_status csc_eval(Ctx* c, void* scores_out, bool want_partials, bool honor_done);
 dmmv_status csc_eval_stream_only(Ctx* c);   // just the kernel that streams the matrix
 dmmv_status csc_apply(Ctx* c);          // staged move only; caller refreshes t and the reservoir
-dmmv_status csc_select_apply(Ctx* c, int32_t iters, dmmv_move* trace, void* trace_t);
+dmmv_status csc_select_apply(Ctx* c, int32_t iters, dmmv_move* trace, void* trace_t, bool pruned);
+dmmv_status csc_eval_pruned(Ctx* c, bool honor_done);   // records of the columns of the worst row only
 
 dmmv_status batched_build(Ctx* c);
 dmmv_status batched_residual(Ctx* c);

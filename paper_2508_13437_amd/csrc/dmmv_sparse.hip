@@ -40,6 +40,7 @@ __global__ void k_cscp_count(int64_t m, int64_t n, int64_t nnz, int32_t mp,
         return;
     }
     const int64_t p = i / mp;
+    atomicMax(&flags[FLAG_MAXROW], (int32_t)(e1 - e0 < INT32_MAX ? e1 - e0 : INT32_MAX));
     for (int64_t e = e0; e < e1; ++e) {
         const int32_t j = col[e];
         if (j < 0 || j >= n) { atomicOr(&flags[FLAG_ERROR], ERRBIT_CSR_RANGE); continue; }
@@ -473,11 +474,12 @@ static dmmv_status apply_t(Ctx* c) {
 }
 
 template <class T>
-static dmmv_status select_apply_t(Ctx* c, int32_t iters, dmmv_move* trace, void* trace_t) {
+static dmmv_status select_apply_t(Ctx* c, int32_t iters, dmmv_move* trace, void* trace_t, bool pruned) {
     hipLaunchKernelGGL(k_select_apply_cscp<T>, dim3(1), dim3(SA_BLOCK), 0, c->stream, c->p.m, c->p.n,
                        c->p.nd, c->csc_mp, c->csc_P, (const int32_t*)c->segptr, (const uint16_t*)c->row16,
                        (const T*)c->cval, (const T*)c->D_dev, (T*)c->r, c->kidx,
-                       (const Partial<T>*)c->partials, c->p.n > 0 ? c->n_partials : 0,
+                       pruned ? (const Partial<T>*)c->prune_part : (const Partial<T>*)c->partials,
+                       pruned ? (int64_t)c->csc_max_row : (c->p.n > 0 ? c->n_partials : 0),
                        (InstState<T>*)c->state, c->o.keep_going, (T*)c->res_val, c->res_row, c->res_meta,
                        (T*)c->res_floor, iters, trace, (T*)trace_t);
     DMMV_LAUNCH_CHECK();
@@ -488,9 +490,9 @@ dmmv_status csc_build(Ctx* c) { return c->p.dtype == DMMV_F64 ? build_t<double>(
 dmmv_status csc_residual(Ctx* c) { return c->p.dtype == DMMV_F64 ? residual_t<double>(c) : residual_t<float>(c); }
 dmmv_status csc_reservoir(Ctx* c) { return c->p.dtype == DMMV_F64 ? reservoir_t<double>(c) : reservoir_t<float>(c); }
 dmmv_status csc_apply(Ctx* c) { return c->p.dtype == DMMV_F64 ? apply_t<double>(c) : apply_t<float>(c); }
-dmmv_status csc_select_apply(Ctx* c, int32_t iters, dmmv_move* trace, void* trace_t) {
-    return c->p.dtype == DMMV_F64 ? select_apply_t<double>(c, iters, trace, trace_t)
-                                  : select_apply_t<float>(c, iters, trace, trace_t);
+dmmv_status csc_select_apply(Ctx* c, int32_t iters, dmmv_move* trace, void* trace_t, bool pruned) {
+    return c->p.dtype == DMMV_F64 ? select_apply_t<double>(c, iters, trace, trace_t, pruned)
+                                  : select_apply_t<float>(c, iters, trace, trace_t, pruned);
 }
 
 // =========================================================================================

@@ -297,6 +297,94 @@ __global__ __launch_bounds__(FIN_BLOCK) void k_finalize_csc(
 }
 
 // =========================================================================================
+// pruned evaluation (for the descent, where only a strictly improving move matters)
+// =========================================================================================
+// A move improves only if it lowers EVERY row whose |r| equals the current maximum t; a row
+// that has no entry in column j is not changed by moving x_j.  So only the columns with an
+// entry in the row i* of largest |r| (the head of the reservoir) can hold an improving move.
+// One wavefront per entry of row i* scores that column exactly as the full evaluation does
+// (all its entries, plus the maximum over the rows outside the column) and writes one arg-min
+// record.  If an improving move exists, the arg-min over these records is the arg-min over the
+// whole table; if none exists, the best record is not an improvement either, and the loop
+// stops just the same.
+template <class T>
+__global__ __launch_bounds__(64) void k_eval_pruned_csc(
+    int64_t m, int64_t n, int32_t nd, int32_t mp, int32_t P, const int64_t* __restrict__ csr_rowptr,
+    const int32_t* __restrict__ csr_col, const int32_t* __restrict__ segptr,
+    const uint16_t* __restrict__ row16, const T* __restrict__ cval, const T* __restrict__ D,
+    const int32_t* __restrict__ kidx, const T* __restrict__ r, const T* __restrict__ res_val,
+    const int32_t* __restrict__ res_row, const int32_t* __restrict__ res_meta, int32_t radius,
+    const uint8_t* __restrict__ var_mask, const InstState<T>* __restrict__ st, int32_t honor_done,
+    Partial<T>* __restrict__ part) {
+    constexpr int KT = 8;
+    if (honor_done && st[0].done) return;
+    const int lane = threadIdx.x;
+    Partial<T> rec; rec.s = (T)0; rec.c = -1;
+    const int32_t cnt = res_meta[RES_CNT];
+    int64_t j = -1;
+    if (cnt > 0) {
+        const int64_t istar = res_row[0];
+        const int64_t e = csr_rowptr[istar] + blockIdx.x;
+        if (e < csr_rowptr[istar + 1]) j = csr_col[e];
+    }
+    if (j < 0) {                                   // no such entry: an empty record
+        if (lane == 0) part[blockIdx.x] = rec;
+        return;
+    }
+    // maximum over the rows outside column j: first reservoir row the column does not hold
+    T outside = (T)0;
+    {
+        int32_t first = INT32_MAX;
+        for (int32_t base = 0; base < cnt && first == INT32_MAX; base += 64) {
+            const int32_t q = base + lane;
+            const bool absent = q < cnt && !column_has_row<T>(segptr, row16, n, mp, j, res_row[q]);
+            const unsigned long long b = __ballot(absent);
+            if (b) first = base + __builtin_ctzll(b);
+        }
+        if (first != INT32_MAX) {
+            outside = res_val[first];
+        } else if ((int64_t)cnt < m) {             // the column holds the whole reservoir: exact scan
+            T o = (T)0;
+            for (int64_t i = lane; i < m; i += 64)
+                if (!column_has_row<T>(segptr, row16, n, mp, j, (int32_t)i)) o = dmmv_max(o, dmmv_abs(r[i]));
+            outside = wave_max(o);
+        }
+    }
+    const int32_t kcur = kidx[j];
+    const T dcur = D[kcur];
+    const bool var_ok = var_mask ? var_mask[j] != 0 : true;
+    for (int32_t k0 = 0; k0 < nd; k0 += KT) {
+        T delta[KT], acc[KT];
+#pragma unroll
+        for (int q = 0; q < KT; ++q) {
+            delta[q] = step_of(D[k0 + q < nd ? k0 + q : nd - 1], dcur, (T)1);
+            acc[q] = (T)0;
+        }
+        for (int32_t p = 0; p < P; ++p) {
+            const int32_t e0 = segptr[(int64_t)p * n + j], e1 = segptr[(int64_t)p * n + j + 1];
+            for (int32_t e = e0 + lane; e < e1; e += 64) {
+                const uint32_t loc = row16[e];
+                if (loc == (uint32_t)mp) continue;
+                const T a = cval[e], ri = r[(int64_t)p * mp + loc];
+#pragma unroll
+                for (int q = 0; q < KT; ++q) acc[q] = dmmv_max(acc[q], dmmv_abs(dmmv_fma(delta[q], a, ri)));
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < KT; ++q) {
+            const int32_t k = k0 + q;
+            T v = dmmv_max(wave_max(acc[q]), outside);
+            if (k < nd) {
+                if (!cand_allowed(kcur, k, radius, var_ok)) v = Limits<T>::inf();
+                const int64_t cidx = j * (int64_t)nd + k;
+                if (rec_less(v, cidx, rec.s, rec.c)) { rec.s = v; rec.c = cidx; }
+            }
+        }
+    }
+    if (lane == 0) part[blockIdx.x] = rec;
+}
+
+// =========================================================================================
 // host dispatch
 // =========================================================================================
 template <class T, int KT>
@@ -349,6 +437,21 @@ static dmmv_status eval_t(Ctx* c, void* scores, bool want_partials, bool honor_d
 dmmv_status csc_eval(Ctx* c, void* scores_out, bool want_partials, bool honor_done) {
     return c->p.dtype == DMMV_F64 ? eval_t<double>(c, scores_out, want_partials, honor_done)
                                   : eval_t<float>(c, scores_out, want_partials, honor_done);
+}
+template <class T>
+static dmmv_status eval_pruned_t(Ctx* c, bool honor_done) {
+    if (c->csc_max_row <= 0) return DMMV_OK;       // no stored entry anywhere: nothing can move r
+    hipLaunchKernelGGL(k_eval_pruned_csc<T>, dim3((unsigned)c->csc_max_row), dim3(64), 0, c->stream, c->p.m,
+                       c->p.n, c->p.nd, c->csc_mp, c->csc_P, c->p.csr_rowptr, c->p.csr_col,
+                       (const int32_t*)c->segptr, (const uint16_t*)c->row16, (const T*)c->cval,
+                       (const T*)c->D_dev, (const int32_t*)c->kidx, (const T*)c->r, (const T*)c->res_val,
+                       (const int32_t*)c->res_row, (const int32_t*)c->res_meta, c->o.radius, c->o.var_mask,
+                       (const InstState<T>*)c->state, (int32_t)honor_done, (Partial<T>*)c->prune_part);
+    DMMV_LAUNCH_CHECK();
+    return DMMV_OK;
+}
+dmmv_status csc_eval_pruned(Ctx* c, bool honor_done) {
+    return c->p.dtype == DMMV_F64 ? eval_pruned_t<double>(c, honor_done) : eval_pruned_t<float>(c, honor_done);
 }
 dmmv_status csc_eval_stream_only(Ctx* c) {
     return c->p.dtype == DMMV_F64 ? stream_t<double>(c, false) : stream_t<float>(c, false);

@@ -31,8 +31,9 @@ def N(t):
 def alns_check(inst, iters, **kw):
     m = dmmv()
     hopt = {}
-    if "sparse_partition_rows" in kw:
-        hopt["sparse_partition_rows"] = kw.pop("sparse_partition_rows")
+    for key in ("sparse_partition_rows", "prune"):
+        if key in kw:
+            hopt[key] = kw.pop(key)
     print("alns case", inst.name, iters, kw, hopt, flush=True)
     prm = orc.alns_params(iters, **kw)
     if inst.kind == "csr":
@@ -83,6 +84,12 @@ def test_alns_sparse(shape, dtype):
     mm, nn, nd, dens = shape
     alns_check(random_sparse(7200 + mm, mm, nn, nd, dens, dtype=dtype), 20, ls_moves=4,
                destroy_count=max(1, nn // 10), seed=mm + 1)
+
+
+def test_alns_sparse_with_pruned_local_search():
+    alns_check(random_sparse(7250, 700, 300, 4, 0.05, dtype=np.float32), 20, ls_moves=4, destroy_count=12, seed=8,
+               prune=True)
+    alns_check(make_config(3, "small"), 12, ls_moves=6, seed=3, prune=True)
 
 
 @pytest.mark.parametrize("rows", [7, 64, 1000])

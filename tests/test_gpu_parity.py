@@ -636,3 +636,48 @@ def test_batched_mfma_not_applicable_is_an_error():
     with pytest.raises(m.DmmvError) as e:
         m.Handle(D=b64.D, b=T(b64.b), A=T(b64.A.T).t(), scale=b64.scale, residual_mfma=True)
     assert e.value.status == -8
+
+
+# ------------------------------------------------------------- pruned descent on sparse matrices
+@pytest.mark.parametrize("case", ["ties", "full_columns", "long", "tomography", "tiny", "one_column"])
+def test_sparse_pruned_descent_applies_the_same_moves(case):
+    """options.prune scores only the columns that touch the row of largest |r|; whenever an
+    improving move exists it is among them, so the whole trace must equal the oracle's."""
+    m = dmmv()
+    x0 = None
+    if case == "ties":
+        inst, iters, kw = random_sparse(301, 45, 14, 3, density=0.85, dtype=np.float32, integer=True,
+                                        explicit_zeros=True), 40, {}
+    elif case == "full_columns":
+        inst, iters, kw = random_sparse(970, 333, 70, 3, density=0.97, dtype=np.float32), 25, dict(sparse_partition_rows=100)
+    elif case == "long":
+        inst, iters, kw = random_sparse(977, 6000, 400, 5, density=0.02, dtype=np.float32), 400, dict(sparse_partition_rows=2500)
+        x0 = np.random.default_rng(5).choice(inst.D, size=inst.n).astype(np.float32)
+    elif case == "tomography":
+        inst = make_config(3, "small")
+        iters, kw = inst.iters, {}
+    elif case == "tiny":
+        inst, iters, kw = random_sparse(12, 1, 1, 2, density=1.0, dtype=np.float64), 5, {}
+    else:
+        inst, iters, kw = random_sparse(13, 80, 3, 4, density=0.5, dtype=np.float64), 30, dict(radius=1)
+    print("pruned case", case, inst.name, flush=True)
+    hopt = dict(kw)
+    radius = hopt.get("radius", 0)
+    o = oracle_solve(inst, iters, x0=x0, radius=radius)
+    with m.from_instance(inst, DEV, prune=True, **hopt) as h:
+        res = m.dmmv_solve(h, T(inst.x0 if x0 is None else x0), iters, trace=True)
+        check_single_trace(res, o, iters)
+        x, r, t = m.dmmv_get_state(h)
+        assert np.array_equal(N(r), o.r)
+        # the full table is still available on a pruning handle
+        assert np.array_equal(N(m.dmmv_eval_moves(h)), oracle_table(inst, o.x, o.r, radius=radius))
+
+
+def test_sparse_pruned_descent_full_size_tomography_prefix():
+    m = dmmv()
+    inst = make_config(3)
+    iters = 60
+    o = oracle_solve(inst, iters)
+    with m.from_instance(inst, DEV, prune=True) as h:
+        res = m.dmmv_solve(h, T(inst.x0), iters, trace=True)
+    check_single_trace(res, o, iters)
