@@ -681,3 +681,48 @@ def test_sparse_pruned_descent_full_size_tomography_prefix():
     with m.from_instance(inst, DEV, prune=True) as h:
         res = m.dmmv_solve(h, T(inst.x0), iters, trace=True)
     check_single_trace(res, o, iters)
+
+
+# ------------------------------------------------------------- layout options of the boundary
+def test_padded_leading_dimension_dense_and_batched():
+    """A column-major matrix whose columns are lda > m apart (a view into a taller allocation)."""
+    m = dmmv()
+    inst = random_dense(61, 37, 9, 5, dtype=np.float32)
+    lda = 48
+    big = torch.full((inst.n, lda), 1.0e30, dtype=torch.float32, device=DEV)     # poison past row m
+    big[:, :inst.m] = T(np.ascontiguousarray(inst.A.T))
+    A = big.t()[:inst.m]
+    assert A.stride() == (1, lda)
+    with m.Handle(A=A, b=T(inst.b), D=inst.D) as h:
+        assert h._problem.lda == lda
+        res = m.dmmv_solve(h, T(inst.x0), 30, trace=True)
+    check_single_trace(res, oracle_solve(inst, 30), 30)
+    bi = random_batched(62, 37, 9, 70, 4)
+    big = torch.full((bi.n, lda), 1.0e30, dtype=torch.float32, device=DEV)
+    big[:, :bi.m] = T(np.ascontiguousarray(bi.A.T))
+    with m.Handle(A=big.t()[:bi.m], b=T(bi.b), D=bi.D, scale=bi.scale, alns=True) as h:
+        assert h._problem.lda == lda
+        res = m.dmmv_solve(h, T(bi.x0), 12, trace=True)
+        o = oracle_solve(bi, 12)
+        assert np.array_equal(N(res.trace)[:, :, 0], o.trace_j) and np.array_equal(N(res.trace_t), o.trace_t)
+        assert np.array_equal(N(res.x), o.x)
+        a = m.dmmv_alns(h, T(bi.x0), 4, ls_moves=2, destroy_count=2, seed=5)
+        oa = orc.alns_dense(bi.A, bi.b[3], bi.D, bi.x0[3], orc.alns_params(4, ls_moves=2, destroy_count=2, seed=5),
+                            inst=3, scale=float(bi.scale[3]))
+        assert np.array_equal(N(a.trace_t)[3, :, 0], oa.t) and np.array_equal(N(a.x_best)[3], oa.x)
+
+
+def test_batched_var_mask():
+    m = dmmv()
+    inst = random_batched(63, 40, 12, 66, 5)
+    rng = np.random.default_rng(8)
+    vm = (rng.uniform(size=(inst.R, inst.n)) < 0.6).astype(np.uint8)
+    with m.from_instance(inst, DEV, var_mask=T(vm), radius=2) as h:
+        res = m.dmmv_solve(h, T(inst.x0), 10, trace=True)
+    for q in (0, 1, 33, 65):
+        o = orc.solve_dense(inst.A, inst.b[q], inst.D, inst.x0[q], 10, radius=2, var_mask=vm[q],
+                            scale=float(inst.scale[q]))
+        d = o.iters_done
+        assert int(res.iters_done[q]) == d
+        assert np.array_equal(N(res.trace)[q, :d, 0], o.trace_j) and np.array_equal(N(res.trace_t)[q, :d], o.trace_t)
+        assert np.array_equal(N(res.x)[q], o.x)
