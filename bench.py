@@ -10,9 +10,12 @@ reduces them; iterations after the stall have no move left to apply.  Inputs are
 HBM before the timed region starts.
 
 Prints ONE JSON line.  `value` = candidate moves evaluated per second over the whole timed
-region.  `roofline` describes the dominant kernel (the fused evaluation kernel that streams
-all of A), timed with HIP events on the library's stream.  `cpu_baseline` is the CPU oracle
-timed on a bounded sample of the same workload on this host.
+region.  `roofline` describes the dominant kernel (the evaluation kernel that streams all of
+A), timed with HIP events on the library's stream.  `cpu_baseline` is the CPU oracle timed on
+a bounded sample of the same workload on this host.  Further objects of the same line:
+`other_workloads` (the same measurements for the other four workloads), `descent` (sparse: the
+real descent with and without pruning), `alns` (wall time of the ALNS outer loop), `residual`
+(batched: the sequential-order and the matrix-core residual).
 """
 from __future__ import annotations
 
@@ -39,7 +42,8 @@ MEASURED_TRAFFIC_BYTES = {
 
 
 def algorithmic_bytes_per_eval(inst) -> float:
-    """Bytes one evaluation launch must move ("Algorithmic bytes")."""
+    """Bytes one evaluation launch must move: the matrix once (value + 4-byte index per stored
+    entry and the column pointers for a sparse one), r, and the current index of every variable."""
     w = inst.dtype.itemsize
     if inst.kind == "csr":
         return inst.nnz * (w + 4) + (inst.n + 1) * 8 + inst.m * w + inst.n * 4
