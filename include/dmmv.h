@@ -97,7 +97,9 @@ typedef struct {
                                 (fixed-work mode for throughput measurement)                */
     int32_t poll_every;      /* dmmv_solve: every poll_every iterations the host waits for the
                                 stream and stops enqueueing once every instance has stopped;
-                                0 = never wait inside the loop                              */
+                                0 = never wait inside the loop.  A batch (without var_mask)
+                                polls at least every 8 iterations and continues on the
+                                instances that still run, packed densely                    */
     int32_t sparse_partition_rows; /* sparse matrices: rows per LDS-resident partition of r;
                                 0 = automatic (as many as fit 64 KiB, at most 65535).  A tuning
                                 and testing knob: results do not depend on it              */
@@ -211,8 +213,8 @@ typedef struct {
                                 counter): two runs with the same seed are identical              */
 } dmmv_alns_params;
 
-/* Algorithm 1 of the paper around the single-move descent, single dense or sparse instances
- * (R = 1, no scale).  Per outer iteration: (1) one of two destroy operators and one of two
+/* Algorithm 1 of the paper around the single-move descent, for every storage kind.
+ * Per outer iteration: (1) one of two destroy operators and one of two
  * repair operators are chosen by roulette wheel on their weights (Appendix F.2); (2) destroy:
  * destroy_count distinct variables are drawn, uniformly (B.1) or with probability proportional
  * to the impact score d_j (B.2; R_j^k = (t - |s_k|) / |a_kj|, accumulated in fixed point);

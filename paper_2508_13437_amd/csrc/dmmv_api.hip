@@ -119,6 +119,11 @@ size_t workspace_layout(const dmmv_problem& p, const dmmv_options& o, Ctx* c, ch
         b.take(&c->partials, (size_t)(c->n_partials > 0 ? c->n_partials : 1) * p.R * part_sz);
         b.take(&c->Xt, (size_t)p.m * p.n * esz);
         b.take(&c->Bt, (size_t)p.m * p.R * esz);
+        b.take(&c->cmp_r, (size_t)p.m * p.R * esz);
+        b.take(&c->cmp_kidx, (size_t)p.n * p.R * sizeof(int32_t));
+        b.take(&c->cmp_state, (size_t)p.R * state_sz);
+        b.take(&c->cmp_scale, (size_t)p.R * esz);
+        b.take(&c->cmp_orig, (size_t)p.R * sizeof(int32_t));
         if (o.residual_mfma) {
             c->mfma_ldk = mfma_ldk(p.n);
             b.take(&c->Xp, (size_t)3 * p.m * c->mfma_ldk * sizeof(uint16_t));
@@ -521,18 +526,34 @@ static dmmv_status solve_t(dmmv_ctx* c, const void* x0, int32_t iters, void* x_o
     DMMV_TRY(residual_any(c));
     if (iters > 0 && (trace || trace_t))
         hipLaunchKernelGGL(k_fill_trace<T>, grid1(R * (int64_t)iters, 256), dim3(256), 0, c->stream, trace, (T*)trace_t, R * (int64_t)iters);
-    const int32_t poll = c->o.keep_going ? 0 : c->o.poll_every;
-    for (int32_t it = 0; it < iters; ++it) {
-        DMMV_TRY(loop_step(c, iters, trace, trace_t));
-        if (poll > 0 && (it + 1) % poll == 0 && it + 1 < iters) {
-            int32_t active = 0;
-            hipLaunchKernelGGL(k_zero_flags, dim3(1), dim3(64), 0, c->stream, c->flags);
-            hipLaunchKernelGGL(k_count_active<T>, grid1(R, 256), dim3(256), 0, c->stream, (const InstState<T>*)c->state, R, c->flags);
-            DMMV_HIP_CHECK(hipMemcpyAsync(&active, &c->flags[FLAG_ACTIVE], sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
-            DMMV_HIP_CHECK(hipStreamSynchronize(c->stream));
-            if (active == 0) break;
+    int32_t poll = c->o.keep_going ? 0 : c->o.poll_every;
+    // a batch drops its stopped instances at the polling points (their wavefronts would
+    // otherwise keep running for the sake of a few neighbours), so it polls more often
+    const bool compacting = c->kind == KIND_BATCHED && poll > 0 && !c->o.var_mask;
+    if (compacting && poll > 8) poll = 8;
+    dmmv_status loop_st = [&]() -> dmmv_status {
+        for (int32_t it = 0; it < iters; ++it) {
+            DMMV_TRY(loop_step(c, iters, trace, trace_t));
+            if (poll > 0 && (it + 1) % poll == 0 && it + 1 < iters) {
+                int32_t active = 0;
+                if (compacting) {
+                    DMMV_TRY(batched_compact(c, &active));
+                } else {
+                    hipLaunchKernelGGL(k_zero_flags, dim3(1), dim3(64), 0, c->stream, c->flags);
+                    hipLaunchKernelGGL(k_count_active<T>, grid1(R, 256), dim3(256), 0, c->stream, (const InstState<T>*)c->state, R, c->flags);
+                    DMMV_HIP_CHECK(hipMemcpyAsync(&active, &c->flags[FLAG_ACTIVE], sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
+                    DMMV_HIP_CHECK(hipStreamSynchronize(c->stream));
+                }
+                if (active == 0) break;
+            }
         }
+        return DMMV_OK;
+    }();
+    if (compacting) {
+        const dmmv_status back = batched_compact_end(c);
+        if (loop_st == DMMV_OK) loop_st = back;
     }
+    DMMV_TRY(loop_st);
     hipLaunchKernelGGL(k_export_state<T>, grid1(R, 256), dim3(256), 0, c->stream, (const InstState<T>*)c->state, R, (T*)t_out, iters_done);
     DMMV_LAUNCH_CHECK();
     if (x_out) DMMV_TRY(dmmv_get_state(c, x_out, nullptr, nullptr));
@@ -643,6 +664,7 @@ dmmv_status dmmv_create(dmmv_handle* out, const dmmv_problem* problem, const dmm
     const bool sparse = problem->csr_rowptr != nullptr;
     c->kind = sparse ? KIND_CSC : ((problem->R > 1 || problem->scale) ? KIND_BATCHED : KIND_DENSE);
     c->x_set = c->r_valid = false;
+    c->cmp_on = false;
     workspace_layout(*problem, o, c, (char*)workspace);
     c->p.D = nullptr;       // host arrays are copied below and not referenced afterwards
     c->p.scale = nullptr;

@@ -252,7 +252,8 @@ template <class T>
 __global__ void k_apply_batched(int64_t m, int64_t n, int64_t R, const T* __restrict__ X,
                                 int64_t ldx, T* __restrict__ r, int32_t* __restrict__ kidx,
                                 InstState<T>* st, int32_t t_from_score, int32_t iters,
-                                dmmv_move* trace, T* trace_t, int32_t rows_per_block) {
+                                dmmv_move* trace, T* trace_t, int32_t rows_per_block,
+                                const int32_t* __restrict__ orig) {
     const int64_t q = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
     if (q >= R) return;
     const int32_t j = st[q].apply_j;
@@ -270,8 +271,9 @@ __global__ void k_apply_batched(int64_t m, int64_t n, int64_t R, const T* __rest
             const T best_s = st[q].best_s;
             st[q].t = best_s;
             if (moves < iters) {
-                if (trace) { trace[q * (int64_t)iters + moves].j = j; trace[q * (int64_t)iters + moves].k = k; }
-                if (trace_t) trace_t[q * (int64_t)iters + moves] = best_s;
+                const int64_t slot = (orig ? (int64_t)orig[q] : q) * (int64_t)iters + moves;   // caller's instance number
+                if (trace) { trace[slot].j = j; trace[slot].k = k; }
+                if (trace_t) trace_t[slot] = best_s;
             }
         }
         st[q].moves = moves + 1;
@@ -341,7 +343,8 @@ static dmmv_status apply_t(Ctx* c, bool t_from_score, int32_t iters, dmmv_move* 
     dim3 grid((unsigned)ceil_div(R, 64), (unsigned)(m > 0 ? ceil_div(m, rows_per_block) : 1));
     hipLaunchKernelGGL(k_apply_batched<T>, grid, dim3(64), 0, c->stream, m, c->p.n, R,
                        (const T*)c->p.A_dense, c->p.lda, (T*)c->r, c->kidx, (InstState<T>*)c->state,
-                       (int32_t)t_from_score, iters, trace, (T*)trace_t, rows_per_block);
+                       (int32_t)t_from_score, iters, trace, (T*)trace_t, rows_per_block,
+                       c->cmp_on ? (const int32_t*)c->cmp_orig : nullptr);
     DMMV_LAUNCH_CHECK();
     return DMMV_OK;
 }
@@ -362,6 +365,121 @@ static dmmv_status get_x_t(Ctx* c, void* x) {
                        (const int32_t*)c->kidx, (const T*)c->D_dev, c->p.n, c->p.R, (T*)x);
     DMMV_LAUNCH_CHECK();
     return DMMV_OK;
+}
+
+// =========================================================================================
+// dropping stopped instances from the descent
+// =========================================================================================
+// Instances stop at different iterations, and a wavefront works as long as one of its 64
+// instances does.  At the host's polling points the instances still running are therefore
+// gathered into a dense "virtual" batch of their own (same layouts, stride = their number),
+// which the loop's kernels then work on; orig[p] is the caller's number of virtual instance p.
+// Before a new gather, and at the end, the virtual batch is scattered back into the full arrays.
+template <class T>
+__global__ void k_cmp_scatter(int64_t m, int64_t n, int64_t Rv, int64_t Rf, const int32_t* __restrict__ orig,
+                              const T* __restrict__ r_v, T* __restrict__ r_f,
+                              const int32_t* __restrict__ k_v, int32_t* __restrict__ k_f,
+                              const InstState<T>* __restrict__ st_v, InstState<T>* __restrict__ st_f) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const int64_t t0 = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    for (int64_t e = t0; e < m * Rv; e += stride) r_f[(e / Rv) * Rf + orig[e % Rv]] = r_v[e];
+    for (int64_t e = t0; e < n * Rv; e += stride) k_f[(e / Rv) * Rf + orig[e % Rv]] = k_v[e];
+    for (int64_t p = t0; p < Rv; p += stride) st_f[orig[p]] = st_v[p];
+}
+
+// the running instances in ascending order (single workgroup); their number goes to
+// flags[FLAG_ACTIVE]
+template <class T>
+__global__ __launch_bounds__(1024) void k_cmp_list(int64_t Rf, const InstState<T>* __restrict__ st_f,
+                                                   int32_t* __restrict__ orig, int32_t* flags) {
+    __shared__ int32_t sh_cnt[16];
+    __shared__ int32_t sh_base;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    if (threadIdx.x == 0) sh_base = 0;
+    __syncthreads();
+    for (int64_t b0 = 0; b0 < Rf; b0 += 1024) {
+        const int64_t q = b0 + threadIdx.x;
+        const bool on = q < Rf && !st_f[q].done;
+        const unsigned long long bal = __ballot(on);
+        if (lane == 0) sh_cnt[w] = __popcll(bal);
+        __syncthreads();
+        int32_t before = 0, all = 0;
+        for (int u = 0; u < 16; ++u) { if (u < w) before += sh_cnt[u]; all += sh_cnt[u]; }
+        const int32_t base = sh_base;
+        if (on) orig[base + before + __popcll(bal & ((1ull << lane) - 1ull))] = (int32_t)q;
+        __syncthreads();
+        if (threadIdx.x == 0) sh_base = base + all;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) flags[FLAG_ACTIVE] = sh_base;
+}
+
+template <class T>
+__global__ void k_cmp_gather(int64_t m, int64_t n, int64_t Rv, int64_t Rf, const int32_t* __restrict__ orig,
+                             const T* __restrict__ r_f, T* __restrict__ r_v,
+                             const int32_t* __restrict__ k_f, int32_t* __restrict__ k_v,
+                             const InstState<T>* __restrict__ st_f, InstState<T>* __restrict__ st_v,
+                             const T* __restrict__ sc_f, T* __restrict__ sc_v) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const int64_t t0 = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    for (int64_t e = t0; e < m * Rv; e += stride) r_v[e] = r_f[(e / Rv) * Rf + orig[e % Rv]];
+    for (int64_t e = t0; e < n * Rv; e += stride) k_v[e] = k_f[(e / Rv) * Rf + orig[e % Rv]];
+    for (int64_t p = t0; p < Rv; p += stride) { st_v[p] = st_f[orig[p]]; sc_v[p] = sc_f[orig[p]]; }
+}
+
+template <class T>
+static dmmv_status compact_scatter_t(Ctx* c) {
+    hipLaunchKernelGGL(k_cmp_scatter<T>, dim3(2048), dim3(256), 0, c->stream, c->p.m, c->p.n, c->p.R, c->cmp_full_R,
+                       (const int32_t*)c->cmp_orig, (const T*)c->r, (T*)c->cmp_full_r, (const int32_t*)c->kidx,
+                       c->cmp_full_kidx, (const InstState<T>*)c->state, (InstState<T>*)c->cmp_full_state);
+    DMMV_LAUNCH_CHECK();
+    return DMMV_OK;
+}
+
+static void compact_to_full(Ctx* c) {
+    c->r = c->cmp_full_r; c->kidx = c->cmp_full_kidx; c->state = c->cmp_full_state;
+    c->scale_dev = c->cmp_full_scale; c->p.R = c->cmp_full_R;
+    c->cmp_on = false;
+}
+
+// At a polling point of the descent: how many instances still run (HOST, *active_out), and the
+// loop's arrays re-pointed at a virtual batch of just those when that is worth it.
+template <class T>
+static dmmv_status compact_t(Ctx* c, int32_t* active_out) {
+    if (c->cmp_on) {
+        DMMV_TRY(compact_scatter_t<T>(c));
+        compact_to_full(c);
+    }
+    const int64_t Rf = c->p.R, m = c->p.m, n = c->p.n;
+    hipLaunchKernelGGL(k_cmp_list<T>, dim3(1), dim3(1024), 0, c->stream, Rf, (const InstState<T>*)c->state,
+                       c->cmp_orig, c->flags);
+    int32_t active = 0;
+    DMMV_HIP_CHECK(hipMemcpyAsync(&active, &c->flags[FLAG_ACTIVE], sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
+    DMMV_HIP_CHECK(hipStreamSynchronize(c->stream));
+    *active_out = active;
+    if (active == 0 || (int64_t)active * 4 > Rf * 3) return DMMV_OK;      // nothing left, or not worth it
+    c->cmp_full_r = c->r; c->cmp_full_kidx = c->kidx; c->cmp_full_state = c->state;
+    c->cmp_full_scale = c->scale_dev; c->cmp_full_R = Rf;
+    hipLaunchKernelGGL(k_cmp_gather<T>, dim3(2048), dim3(256), 0, c->stream, m, n, (int64_t)active, Rf,
+                       (const int32_t*)c->cmp_orig, (const T*)c->cmp_full_r, (T*)c->cmp_r,
+                       (const int32_t*)c->cmp_full_kidx, c->cmp_kidx, (const InstState<T>*)c->cmp_full_state,
+                       (InstState<T>*)c->cmp_state, (const T*)c->cmp_full_scale, (T*)c->cmp_scale);
+    DMMV_LAUNCH_CHECK();
+    c->r = c->cmp_r; c->kidx = c->cmp_kidx; c->state = c->cmp_state; c->scale_dev = c->cmp_scale;
+    c->p.R = active;
+    c->cmp_on = true;
+    return DMMV_OK;
+}
+
+dmmv_status batched_compact(Ctx* c, int32_t* active_out) {
+    return c->p.dtype == DMMV_F64 ? compact_t<double>(c, active_out) : compact_t<float>(c, active_out);
+}
+// back to the caller's batch (no-op when the loop never left it)
+dmmv_status batched_compact_end(Ctx* c) {
+    if (!c->cmp_on) return DMMV_OK;
+    dmmv_status st = c->p.dtype == DMMV_F64 ? compact_scatter_t<double>(c) : compact_scatter_t<float>(c);
+    compact_to_full(c);
+    return st;
 }
 
 dmmv_status batched_build(Ctx* c) { return c->p.dtype == DMMV_F64 ? build_t<double>(c) : build_t<float>(c); }

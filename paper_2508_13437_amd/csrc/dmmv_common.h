@@ -129,6 +129,18 @@ struct Ctx {
     uint64_t* alns_first;     // [n] stamp of the first draw of a variable in an iteration
     int32_t* alns_picked;     // [n] variables drawn, in the order of the draws
     uint8_t* alns_touched;    // [m] sparse repair: rows of the column being reassigned
+    // batched descent: virtual batch of the instances still running
+    bool cmp_on;              // the loop's arrays currently point at the virtual batch
+    void* cmp_r;              // T[m][R'] / int32[n][R'] / InstState[R'] / T[R'] / int32[R'] (orig)
+    int32_t* cmp_kidx;
+    void* cmp_state;
+    void* cmp_scale;
+    int32_t* cmp_orig;
+    void* cmp_full_r;         // the caller's batch while cmp_on
+    int32_t* cmp_full_kidx;
+    void* cmp_full_state;
+    void* cmp_full_scale;
+    int64_t cmp_full_R;
     // batched residual on the matrix cores (options.residual_mfma)
     void* Xp;             // bf16[3][m][mfma_ldk] planes whose sum is X
     void* Qt;             // bf16[R][mfma_ldk] current codes D[k_j] per instance
@@ -196,6 +208,8 @@ dmmv_status batched_get_x_from(Ctx* c, const int32_t* kidx, void* x_values);
 dmmv_status batched_set_r(Ctx* c, const void* r);
 dmmv_status batched_get_r(Ctx* c, void* r);
 dmmv_status batched_maxabs(Ctx* c);     // state[q].t = max_i |r[i][q]|
+dmmv_status batched_compact(Ctx* c, int32_t* active_out);   // polling point of the descent
+dmmv_status batched_compact_end(Ctx* c);
 
 // ----------------------------------------------------------------------------------------
 // device helpers

@@ -726,3 +726,19 @@ def test_batched_var_mask():
         assert int(res.iters_done[q]) == d
         assert np.array_equal(N(res.trace)[q, :d, 0], o.trace_j) and np.array_equal(N(res.trace_t)[q, :d], o.trace_t)
         assert np.array_equal(N(res.x)[q], o.x)
+
+
+# ------------------------------------------------------------- batched descent drops stopped instances
+@pytest.mark.parametrize("poll", [1, 2, 3, 8])
+def test_batched_descent_continues_on_the_running_instances_only(poll):
+    """At its polling points a batch gathers the instances that still run into a dense batch of
+    their own; traces, move counts and results must not notice."""
+    inst = random_batched(8100 + poll, 90, 24, 200, 6, iters=40)
+    batched_check(inst, 40, poll_every=poll)
+    # integer data: many instances stop at once, some never move
+    batched_check(random_batched(8200 + poll, 30, 10, 130, 4, integer=True), 25, poll_every=poll)
+
+
+def test_batched_descent_small_llm_config_with_polling():
+    o = batched_check(make_config(4, "small"), 60, poll_every=4)
+    assert o.iters_done.min() < o.iters_done.max()
