@@ -128,7 +128,11 @@ def run_config(idx: int, steps: int, warmup: int, iters_override, device: str, d
     out = {}
     # how far does the real descent get (normal mode, stops at the local optimum)?
     with dmmv.from_instance(inst, device) as h:
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
         res = dmmv.dmmv_solve(h, x0, iters)
+        torch.cuda.synchronize()
+        normal_s = time.perf_counter() - t0
         improving = res.iters_done.cpu().numpy().astype(np.int64)
         t_final = res.max_violation.cpu().numpy().astype(np.float64)
     # timed: fixed-work mode
@@ -151,6 +155,7 @@ def run_config(idx: int, steps: int, warmup: int, iters_override, device: str, d
         "instance_iters_per_sec": steps * iters * inst.R / dt,
         "ms_per_step": dt / steps * 1e3, "us_per_iter": dt / (steps * iters) * 1e6,
         "improving_moves_applied": int(improving.sum()),
+        "descent_until_local_optimum_ms": normal_s * 1e3,
         "final_max_violation": float(t_final.max()),
         "dtype": "f64" if inst.dtype == np.float64 else "f32",
         "roofline": roofline_for(inst, eval_ms), "input_gen_s": round(t_gen, 2),
