@@ -63,7 +63,12 @@ __device__ __forceinline__ int alns_bits(int64_t x) { int b = 0; while (x > 0) {
 __device__ __forceinline__ uint64_t alns_impact_term(double a_abs, double sk, double t, double alpha,
                                                      double scale) {
     if (a_abs == 0.0) return 0;
-    const double R = (t - sk) / a_abs;
+    const double slack = t - sk;
+    // Shortcut with the same result: slack > a * 18 / alpha makes alpha * R exceed 17.9 whatever
+    // the roundings, so exp(-alpha R) < 1.7e-8 and the term, below 2^24 * 1.7e-8 < 1, truncates
+    // to 0.  Most rows are far from the maximum, so most terms end here.
+    if (slack > a_abs * (18.0 / alpha)) return 0;
+    const double R = slack / a_abs;
     const double E = alns_expneg(alpha * R);
     const double g = (sk * E) * scale;
     return (uint64_t)g;
