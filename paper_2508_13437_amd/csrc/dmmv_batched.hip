@@ -130,7 +130,10 @@ __global__ __launch_bounds__(1024) void k_maxabs_batched(int64_t m, int64_t R, c
 // wavefronts; each takes tiles of TJ variables of the chunk in turn.  For nd > KT the values
 // of D are covered KT at a time.  Xt is the row-major copy of X, so the TJ entries of a row
 // are one scalar load.
-template <class T, int KT, int TJ, int RB = DMMV_BATCHED_RB>
+// ROT (nd = KT + 1): the null move is not computed at all.  Every lane takes the KT values
+// AFTER its own current one, cyclically (the steps are per-lane registers anyway), and the null
+// move enters the table and the arg-min with its known score t.
+template <class T, int KT, int TJ, bool ROT = false, int RB = DMMV_BATCHED_RB>
 __global__ __launch_bounds__(256) void k_eval_batched(
     int64_t m, int64_t n, int64_t R, int32_t nd, int32_t chunk_cols, const T* __restrict__ Xt,
     const T* __restrict__ D, const int32_t* __restrict__ kidx, const T* __restrict__ scale,
@@ -148,6 +151,7 @@ __global__ __launch_bounds__(256) void k_eval_batched(
     const bool live = q < R;
     const int64_t qc = live ? q : R - 1;
     const T sc = scale[qc];
+    const T t_now = st[qc].t;
     const bool skip = part && !scores && st[qc].done;   // stopped instances score nothing
     const int64_t jbeg = blockIdx.y * (int64_t)chunk_cols;
     const int64_t jend = jbeg + chunk_cols < n ? jbeg + chunk_cols : n;
@@ -166,16 +170,24 @@ __global__ __launch_bounds__(256) void k_eval_batched(
                 kcur[u] = kidx[j * R + qc];
                 dcur[u] = shD[kcur[u]];
             }
-            for (int32_t k0 = 0; k0 < nd; k0 += KT) {
+            for (int32_t k0 = 0; k0 < (ROT ? 1 : nd); k0 += KT) {
                 T delta[TJ][KT], acc[TJ][KT];
 #pragma unroll
                 for (int u = 0; u < TJ; ++u)
 #pragma unroll
                     for (int v = 0; v < KT; ++v) {
-                        const int32_t k = k0 + v < nd ? k0 + v : nd - 1;
+                        int32_t k;
+                        if (ROT) { k = kcur[u] + 1 + v; k = k >= nd ? k - nd : k; }
+                        else k = k0 + v < nd ? k0 + v : nd - 1;
                         delta[u][v] = step_of(shD[k], dcur[u], sc);
                         acc[u][v] = (T)0;
                     }
+                if (ROT) {
+                    // the value indices are recomputed after the row loop rather than kept in
+                    // registers across it
+#pragma unroll
+                    for (int u = 0; u < TJ; ++u) asm volatile("" : "+v"(kcur[u]));
+                }
                 if (j0 + TJ <= n) {
                     // RB rows per pass: all their loads (r in vector registers, the X tile in
                     // scalar registers) are issued before the first row is scored, so one pass
@@ -216,13 +228,19 @@ __global__ __launch_bounds__(256) void k_eval_batched(
                         const bool var_ok = var_mask ? var_mask[q * n + j] != 0 : true;
 #pragma unroll
                         for (int v = 0; v < KT; ++v) {
-                            const int32_t k = k0 + v;
-                            if (k >= nd) continue;
+                            int32_t k;
+                            if (ROT) { k = kcur[u] + 1 + v; k = k >= nd ? k - nd : k; }
+                            else { k = k0 + v; if (k >= nd) continue; }
                             T val = acc[u][v];
                             if (!cand_allowed(kcur[u], k, radius, var_ok)) val = Limits<T>::inf();
                             const int64_t cidx = j * (int64_t)nd + k;
                             if (scores) scores[q * (n * (int64_t)nd) + cidx] = val;
                             if (rec_less(val, cidx, bs, bc)) { bs = val; bc = cidx; }
+                        }
+                        if (ROT) {                               // the null move: fma(0, a, r) = r, score t
+                            const int64_t cidx = j * (int64_t)nd + kcur[u];
+                            if (scores) scores[q * (n * (int64_t)nd) + cidx] = t_now;
+                            if (rec_less(t_now, cidx, bs, bc)) { bs = t_now; bc = cidx; }
                         }
                     }
                 }
@@ -315,10 +333,10 @@ static dmmv_status maxabs_t(Ctx* c) {
     return DMMV_OK;
 }
 
-template <class T, int KT, int TJ>
+template <class T, int KT, int TJ, bool ROT = false>
 static dmmv_status eval_launch(Ctx* c, void* scores, bool want_partials) {
     dim3 grid((unsigned)ceil_div(c->p.R, 64), (unsigned)c->n_partials);
-    hipLaunchKernelGGL((k_eval_batched<T, KT, TJ>), grid, dim3(256), (size_t)c->p.nd * sizeof(T), c->stream,
+    hipLaunchKernelGGL((k_eval_batched<T, KT, TJ, ROT>), grid, dim3(256), (size_t)c->p.nd * sizeof(T), c->stream,
                        c->p.m, c->p.n, c->p.R, c->p.nd, c->chunk_cols, (const T*)c->Xt,
                        (const T*)c->D_dev, (const int32_t*)c->kidx, (const T*)c->scale_dev,
                        (const T*)c->r, c->o.radius, c->o.var_mask, (const InstState<T>*)c->state,
@@ -331,6 +349,13 @@ template <class T>
 static dmmv_status eval_t(Ctx* c, void* scores, bool want_partials) {
     if ((size_t)c->p.nd * sizeof(T) > 48 * 1024)
         return fail(DMMV_ERR_UNSUPPORTED, "batched path: nd = %d does not fit the LDS value table", c->p.nd);
+    // the usual code widths (4, 3 and 2 bits) in fp32: without computing the null move
+    // (in fp64 the variant needs more than the 256 registers that two wavefronts per SIMD leave)
+    if (sizeof(T) == 4) {
+        if (c->p.nd == 16) return eval_launch<float, 15, 4, true>(c, scores, want_partials);
+        if (c->p.nd == 8) return eval_launch<float, 7, 8, true>(c, scores, want_partials);
+        if (c->p.nd == 4) return eval_launch<float, 3, 8, true>(c, scores, want_partials);
+    }
     if (c->p.nd > 8) return eval_launch<T, 16, 4>(c, scores, want_partials);
     if (c->p.nd > 4) return eval_launch<T, 8, 8>(c, scores, want_partials);
     return eval_launch<T, 4, 8>(c, scores, want_partials);
