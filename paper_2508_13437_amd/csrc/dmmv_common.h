@@ -286,16 +286,61 @@ __device__ __forceinline__ bool rec_less(T s1, int64_t c1, T s2, int64_t c2) {
     return (s1 < s2) || (s1 == s2 && c1 < c2);
 }
 
+// Row reductions run on DPP permutations (no LDS crossbar); the four row results are then read
+// through the scalar unit.  All 64 lanes must be active.
+__device__ __forceinline__ float dmmv_min(float a, float b) { return __builtin_fminf(a, b); }
+__device__ __forceinline__ double dmmv_min(double a, double b) { return __builtin_fmin(a, b); }
+
+__device__ __forceinline__ float read_lane(float v, int l) {
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l));
+}
+__device__ __forceinline__ double read_lane(double v, int l) {
+    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), l),
+                            __builtin_amdgcn_readlane(__double2loint(v), l));
+}
+__device__ __forceinline__ int64_t read_lane(int64_t v, int l) {
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, l);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)((uint64_t)v >> 32), l);
+    return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+template <int CTRL>
+__device__ __forceinline__ int64_t dpp_mov(int64_t v) {
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)v, CTRL, 0xF, 0xF, true);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)((uint64_t)v >> 32), CTRL, 0xF, 0xF, true);
+    return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+
+// minimum over the wavefront, the same value in every lane
+template <class T>
+__device__ __forceinline__ T wave_min(T v) {
+    v = dmmv_min(v, dpp_mov<DPP_QUAD_XOR1>(v));
+    v = dmmv_min(v, dpp_mov<DPP_QUAD_XOR2>(v));
+    v = dmmv_min(v, dpp_mov<DPP_ROW_HALF_MIRROR>(v));
+    v = dmmv_min(v, dpp_mov<DPP_ROW_MIRROR>(v));
+    return dmmv_min(dmmv_min(read_lane(v, 0), read_lane(v, 16)), dmmv_min(read_lane(v, 32), read_lane(v, 48)));
+}
+__device__ __forceinline__ int64_t wave_min(int64_t v) {
+    int64_t o;
+    o = dpp_mov<DPP_QUAD_XOR1>(v); v = o < v ? o : v;
+    o = dpp_mov<DPP_QUAD_XOR2>(v); v = o < v ? o : v;
+    o = dpp_mov<DPP_ROW_HALF_MIRROR>(v); v = o < v ? o : v;
+    o = dpp_mov<DPP_ROW_MIRROR>(v); v = o < v ? o : v;
+    const int64_t a = read_lane(v, 0), b = read_lane(v, 16), c = read_lane(v, 32), d = read_lane(v, 48);
+    const int64_t ab = a < b ? a : b, cd = c < d ? c : d;
+    return ab < cd ? ab : cd;
+}
+
+// (score, index) minimum in two passes: the smallest score, then the smallest index among the
+// lanes that hold it.  Empty records take part as (+inf, INT64_MAX).
 template <class T>
 __device__ __forceinline__ void wave_argmin(T& s, int64_t& c) {
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        T os = __shfl_xor(s, off, 64);
-        int64_t oc = __shfl_xor(c, off, 64);
-        bool take = rec_less(os, oc, s, c);
-        s = take ? os : s;
-        c = take ? oc : c;
-    }
+    const bool empty = c < 0;
+    const T se = empty ? Limits<T>::inf() : s;
+    const T smin = wave_min(se);
+    const int64_t ce = (!empty && se == smin) ? c : INT64_MAX;
+    const int64_t cmin = wave_min(ce);
+    s = cmin == INT64_MAX ? (T)0 : smin;
+    c = cmin == INT64_MAX ? (int64_t)-1 : cmin;
 }
 
 // Block-wide version; result valid in thread 0.  sh_s/sh_c hold blockDim.x/64 entries.

@@ -314,16 +314,18 @@ __global__ __launch_bounds__(SA_BLOCK) void k_select_apply_cscp(
     __shared__ T sh_sval[SA_MAXCOL];            // their new |r|
     __shared__ int32_t sh_ns, sh_j, sh_k;
     __shared__ T sh_delta, sh_best;
-    if (st[0].done) return;
+    // the loop state and the records are fetched together (one memory latency, not two)
+    const InstState<T> z0 = st[0];
     T s = (T)0;
     int64_t c = -1;
     for (int64_t q = threadIdx.x; q < n_part; q += SA_BLOCK) {
         const Partial<T> pr = part[q];
         if (rec_less(pr.s, pr.c, s, c)) { s = pr.s; c = pr.c; }
     }
+    if (z0.done) return;
     block_argmin(s, c, sh_s, sh_c);
     if (threadIdx.x == 0) {
-        InstState<T> z = st[0];
+        InstState<T> z = z0;
         int32_t j = -1, k = -1;
         if (c >= 0) { j = (int32_t)(c / nd); k = (int32_t)(c % nd); }
         const bool improving = c >= 0 && s < z.t;

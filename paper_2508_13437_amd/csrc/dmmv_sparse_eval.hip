@@ -220,28 +220,47 @@ __global__ __launch_bounds__(FIN_BLOCK) void k_finalize_csc(
     const uint32_t* __restrict__ part_mask, int32_t radius, const uint8_t* __restrict__ var_mask,
     const InstState<T>* __restrict__ st, int32_t honor_done, T* __restrict__ scores,
     Partial<T>* __restrict__ part) {
+    constexpr int KPF = 8;                                 // values of D whose partition maxima are fetched up front
     __shared__ T sh_rv[RES_CAP];
     __shared__ int32_t sh_rr[RES_CAP];
     __shared__ T sh_s[FIN_BLOCK / 64];
     __shared__ int64_t sh_c[FIN_BLOCK / 64];
-    if (honor_done && st[0].done) return;
+    const int lane = threadIdx.x & 63;
+    const int64_t j = blockIdx.x * (int64_t)FIN_BLOCK + threadIdx.x;
+    const bool live = j < n;
+    const int64_t jc = live ? j : n - 1;
+    // Every global load that does not depend on another is issued here, before the first
+    // wait: the stop flag, the reservoir, the column's masks, its current value and the
+    // partition maxima of its first KPF values.  The kernel is a chain of memory latencies
+    // otherwise.
+    const int32_t done = st[0].done;
     const int32_t cnt = res_meta[RES_CNT];
+    T rv = (T)-1;
+    int32_t rr = -1;
+    if (threadIdx.x < RES_CAP) { rv = res_val[threadIdx.x]; rr = res_row[threadIdx.x]; }
+    uint32_t cm = 0;
+    for (int32_t p = 0; p < P; ++p) cm |= part_mask[(int64_t)p * n + jc];
+    const int32_t kcur = kidx[jc];
+    T pmax[KPF];
+#pragma unroll
+    for (int k = 0; k < KPF; ++k) {
+        pmax[k] = (T)0;
+        if (k < nd)
+            for (int32_t p = 0; p < P; ++p)
+                pmax[k] = dmmv_max(pmax[k], part_scores[(int64_t)p * (n * (int64_t)nd) + jc * (int64_t)nd + k]);
+    }
+    if (honor_done && done) return;
     if (threadIdx.x < RES_CAP) {
-        sh_rv[threadIdx.x] = threadIdx.x < cnt ? res_val[threadIdx.x] : (T)-1;
-        sh_rr[threadIdx.x] = threadIdx.x < cnt ? res_row[threadIdx.x] : -1;
+        sh_rv[threadIdx.x] = (int32_t)threadIdx.x < cnt ? rv : (T)-1;
+        sh_rr[threadIdx.x] = (int32_t)threadIdx.x < cnt ? rr : -1;
     }
     __syncthreads();
     const int32_t nfast = cnt < RES_FAST ? cnt : RES_FAST;
     const uint32_t full = (1u << nfast) - 1u;              // RES_FAST < 32
-    const int lane = threadIdx.x & 63;
-    const int64_t j = blockIdx.x * (int64_t)FIN_BLOCK + threadIdx.x;
-    const bool live = j < n;
 
     T outside = (T)0;
     bool need_walk = false;
     if (live) {
-        uint32_t cm = 0;
-        for (int32_t p = 0; p < P; ++p) cm |= part_mask[(int64_t)p * n + j];
         const uint32_t missing = full & ~cm;
         if (missing) outside = sh_rv[__builtin_ctz(missing)];
         else if ((int64_t)nfast >= m) outside = (T)0;          // the column holds every row
@@ -279,12 +298,18 @@ __global__ __launch_bounds__(FIN_BLOCK) void k_finalize_csc(
     T bs = (T)0;
     int64_t bc = -1;
     if (live) {
-        const int32_t kcur = kidx[j];
         const bool var_ok = var_mask ? var_mask[j] != 0 : true;
         for (int32_t k = 0; k < nd; ++k) {
             const int64_t cidx = j * (int64_t)nd + k;
             T v = outside;
-            for (int32_t p = 0; p < P; ++p) v = dmmv_max(v, part_scores[(int64_t)p * (n * (int64_t)nd) + cidx]);
+            if (k < KPF) {
+                T pm = pmax[0];
+#pragma unroll
+                for (int q = 1; q < KPF; ++q) pm = k == q ? pmax[q] : pm;
+                v = dmmv_max(v, pm);
+            } else {
+                for (int32_t p = 0; p < P; ++p) v = dmmv_max(v, part_scores[(int64_t)p * (n * (int64_t)nd) + cidx]);
+            }
             if (!cand_allowed(kcur, k, radius, var_ok)) v = Limits<T>::inf();
             if (scores) scores[cidx] = v;
             if (rec_less(v, cidx, bs, bc)) { bs = v; bc = cidx; }
