@@ -16,6 +16,9 @@
  * library exponential, the three bound equations of the worst-remove operator evaluated
  * literally, draw frequencies, greedy repair against fresh recomputation, and the loop's
  * invariants.
+ * The swap move (swap_oracle_impl.inc) is pinned by fresh recomputation of ||A x' - b||_inf for
+ * the exchanged x', by Proposition 1 and Corollary 1 evaluated in rational arithmetic, and by
+ * the A = I closed form.
  */
 #include <math.h>
 #include <stdint.h>
@@ -29,6 +32,7 @@
 #define FMA fma
 #define FABS fabs
 #include "dmmv_oracle_impl.inc"
+#include "swap_oracle_impl.inc"
 #include "alns_oracle_impl.inc"
 #undef REAL
 #undef SFX
@@ -40,6 +44,7 @@
 #define FMA fmaf
 #define FABS fabsf
 #include "dmmv_oracle_impl.inc"
+#include "swap_oracle_impl.inc"
 #include "alns_oracle_impl.inc"
 #undef REAL
 #undef SFX

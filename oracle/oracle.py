@@ -307,13 +307,14 @@ class AlnsParams(C.Structure):
     _fields_ = [("iters", C.c_int32), ("ls_moves", C.c_int32), ("ls_radius", C.c_int32),
                 ("destroy_count", C.c_int32), ("alpha", C.c_double), ("lambda_", C.c_double),
                 ("sigma1", C.c_double), ("sigma2", C.c_double), ("sigma3", C.c_double),
-                ("seed", C.c_uint64)]
+                ("seed", C.c_uint64), ("ls_swaps", C.c_int32), ("reserved", C.c_int32)]
 
 
 def alns_params(iters, ls_moves=8, ls_radius=1, destroy_count=0, alpha=0.3, lambda_=0.2,
-                sigma1=3.0, sigma2=2.0, sigma3=1.0, seed=1) -> AlnsParams:
+                sigma1=3.0, sigma2=2.0, sigma3=1.0, seed=1, ls_swaps=0) -> AlnsParams:
     return AlnsParams(int(iters), int(ls_moves), int(ls_radius), int(destroy_count), float(alpha),
-                      float(lambda_), float(sigma1), float(sigma2), float(sigma3), int(seed))
+                      float(lambda_), float(sigma1), float(sigma2), float(sigma3), int(seed),
+                      int(ls_swaps), 0)
 
 
 @dataclass
@@ -356,6 +357,9 @@ def full_csr(A):
 
 
 def _csc_of(m, n, rowptr, col, val, dt):
+    rowptr = np.ascontiguousarray(rowptr, dtype=np.int64)
+    col = np.ascontiguousarray(col, dtype=np.int32)
+    val = np.ascontiguousarray(val, dtype=dt)
     nnz = int(rowptr[m])
     colptr = np.empty(n + 1, dtype=np.int64)
     rowidx = np.empty(max(nnz, 1), dtype=np.int32)
@@ -431,3 +435,69 @@ def alns_dense(A, b, D, x0, params: AlnsParams, inst=0, scale=1.0) -> AlnsResult
     A = np.asarray(A, dtype=dt)
     rowptr, col, val = full_csr(A)
     return alns_csr(A.shape[0], A.shape[1], rowptr, col, val, b, D, x0, params, inst, scale)
+
+
+# ------------------------------------------------------------------------------ swap move
+def swap_table_csr(m, n, rowptr, col, val, D, x, r, scale=1.0, var_mask=None) -> np.ndarray:
+    """t' of every ordered pair (i, j) with x_i > x_j, +inf elsewhere; shape [n, n]
+    (Appendix B "Swap Move")."""
+    dt = np.asarray(D).dtype
+    D = np.ascontiguousarray(D)
+    colptr, rowidx, cval = _csc_of(m, n, rowptr, col, val, dt)
+    k = values_to_index(x, D)
+    r = np.ascontiguousarray(r, dtype=dt)
+    vm = _mask(var_mask, n)
+    table = np.empty(n * n, dtype=dt)
+    _fn("oracle_swap_table", dt)(C.c_int64(m), C.c_int64(n), _p(colptr), _p(rowidx), _p(cval), _p(D),
+                                 _real(dt)(scale), _p(k), _p(r), _p(vm), _p(table))
+    return table.reshape(n, n)
+
+
+def best_swap_csr(m, n, rowptr, col, val, D, x, r, scale=1.0, var_mask=None):
+    """Algorithm 2: (i, j, t') of the best strictly improving swap, or (-1, -1, t)."""
+    dt = np.asarray(D).dtype
+    D = np.ascontiguousarray(D)
+    colptr, rowidx, cval = _csc_of(m, n, rowptr, col, val, dt)
+    k = values_to_index(x, D)
+    r = np.ascontiguousarray(r, dtype=dt)
+    vm = _mask(var_mask, n)
+    t_new = _real(dt)(0)
+    f = _fn("oracle_best_swap", dt)
+    f.restype = C.c_int64
+    c = int(f(C.c_int64(m), C.c_int64(n), _p(colptr), _p(rowidx), _p(cval), _p(D), _real(dt)(scale),
+              _p(k), _p(r), _p(vm), C.byref(t_new)))
+    if c < 0:
+        return -1, -1, dt.type(t_new.value)
+    return c // n, c % n, dt.type(t_new.value)
+
+
+def apply_swap_csr(m, n, rowptr, col, val, D, x, r, i, j, scale=1.0):
+    """Exchange x_i and x_j; returns (x', r', t')."""
+    dt = np.asarray(D).dtype
+    D = np.ascontiguousarray(D)
+    colptr, rowidx, cval = _csc_of(m, n, rowptr, col, val, dt)
+    k = values_to_index(x, D)
+    r = np.array(r, dtype=dt, copy=True)
+    f = _fn("oracle_apply_swap", dt)
+    f.restype = _real(dt)
+    t = f(C.c_int64(m), _p(colptr), _p(rowidx), _p(cval), _p(D), _real(dt)(scale), _p(k), _p(r),
+          C.c_int64(i), C.c_int64(j))
+    return D[k], r, dt.type(t)
+
+
+def swap_table_dense(A, D, x, r, scale=1.0, var_mask=None) -> np.ndarray:
+    A = np.asarray(A, dtype=np.asarray(D).dtype)
+    rowptr, col, val = full_csr(A)
+    return swap_table_csr(A.shape[0], A.shape[1], rowptr, col, val, D, x, r, scale, var_mask)
+
+
+def best_swap_dense(A, D, x, r, scale=1.0, var_mask=None):
+    A = np.asarray(A, dtype=np.asarray(D).dtype)
+    rowptr, col, val = full_csr(A)
+    return best_swap_csr(A.shape[0], A.shape[1], rowptr, col, val, D, x, r, scale, var_mask)
+
+
+def apply_swap_dense(A, D, x, r, i, j, scale=1.0):
+    A = np.asarray(A, dtype=np.asarray(D).dtype)
+    rowptr, col, val = full_csr(A)
+    return apply_swap_csr(A.shape[0], A.shape[1], rowptr, col, val, D, x, r, i, j, scale)
