@@ -211,6 +211,12 @@ typedef struct {
                                 without improvement                                              */
     uint64_t seed;           /* every random decision is a function of (seed, iteration, stream,
                                 counter): two runs with the same seed are identical              */
+    int32_t ls_swaps;        /* local search: after the descent, at most this many swap moves
+                                (Algorithm 2; section "Search Operators": 1-OPT, then a swap),
+                                each counted as one more move; it stops at the first search that
+                                finds no improving swap.  Dense and batched handles only        */
+    int32_t k_eps;           /* rows of the swap filter (Corollary 1; Appendix F uses 100);
+                                0 = 100                                                          */
 } dmmv_alns_params;
 
 /* Algorithm 1 of the paper around the single-move descent, for every storage kind.
@@ -226,13 +232,30 @@ typedef struct {
  * x0 (DEVICE, [n], NULL = keep the current x) is the starting point.  Outputs (DEVICE, any
  * may be NULL): x_best_out [n] values, t_best_out [1], trace [iters][4] int32 = destroy
  * operator (0 random, 1 worst-remove), repair operator (0 random, 1 greedy), moves the local
- * search made, accepted; trace_t [iters][2] = error after the local search, best error so
+ * search made (swaps included), accepted; trace_t [iters][2] = error after the local search, best error so
  * far.  Afterwards the handle holds the current (last accepted) solution.  Waits for the
  * stream.  Batched handles (created with options.alns = 1): every instance runs its own loop
  * with its own random stream (the instance number is part of the counter); x0 and x_best_out
  * are [R][n], t_best_out [R], trace [R][iters][4], trace_t [R][iters][2]. */
 dmmv_status dmmv_alns(dmmv_handle h, const void* x0, const dmmv_alns_params* params, void* x_best_out,
                       void* t_best_out, int32_t* trace, void* trace_t);
+
+/* A swap: variables i and j exchange their values (x_i > x_j before).  i = -1: none. */
+typedef struct { int64_t i, j; } dmmv_swap;
+
+/* Swap move of the local search (dense and batched handles; DMMV_ERR_UNSUPPORTED for sparse
+ * matrices).  Over all pairs (i, j) with x_i > x_j (both allowed by var_mask), with
+ *     Delta = s * (D[k_i] - D[k_j]),   r'_k = fma(Delta, A_kj - A_ki, r_k),   t' = max_k |r'_k|,
+ * the pair with the smallest t' is found, the lowest pair number i*n + j on a tie, and reported
+ * if t' < t (strict improvement, Proposition 1); otherwise best.i = best.j = -1 and best_t = t.
+ * apply != 0 carries the swap out: the two variables exchange their values, r <- r', t <- t'.
+ * k_eps (0 = 100, at most 128) is the number of rows of largest |r_k| on which a pair is
+ * tested first (the filter of Corollary 1, a necessary condition for an improvement): it
+ * changes the time taken, never the result, which is that of the full enumeration.
+ * best [R] and best_t [R] (DEVICE) may be NULL.  Needs a residual.
+ * Paper: section "Search Operators", Proposition 1, Corollary 1; Appendix A (new residual);
+ * Appendix B "Swap Move", Algorithm 2. */
+dmmv_status dmmv_swap_move(dmmv_handle h, int32_t k_eps, int32_t apply, dmmv_swap* best, void* best_t);
 
 /* Message of the last failure on this thread (static storage, HOST). */
 const char* dmmv_last_error(void);

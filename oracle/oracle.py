@@ -307,14 +307,14 @@ class AlnsParams(C.Structure):
     _fields_ = [("iters", C.c_int32), ("ls_moves", C.c_int32), ("ls_radius", C.c_int32),
                 ("destroy_count", C.c_int32), ("alpha", C.c_double), ("lambda_", C.c_double),
                 ("sigma1", C.c_double), ("sigma2", C.c_double), ("sigma3", C.c_double),
-                ("seed", C.c_uint64), ("ls_swaps", C.c_int32), ("reserved", C.c_int32)]
+                ("seed", C.c_uint64), ("ls_swaps", C.c_int32), ("k_eps", C.c_int32)]
 
 
 def alns_params(iters, ls_moves=8, ls_radius=1, destroy_count=0, alpha=0.3, lambda_=0.2,
-                sigma1=3.0, sigma2=2.0, sigma3=1.0, seed=1, ls_swaps=0) -> AlnsParams:
+                sigma1=3.0, sigma2=2.0, sigma3=1.0, seed=1, ls_swaps=0, k_eps=0) -> AlnsParams:
     return AlnsParams(int(iters), int(ls_moves), int(ls_radius), int(destroy_count), float(alpha),
                       float(lambda_), float(sigma1), float(sigma2), float(sigma3), int(seed),
-                      int(ls_swaps), 0)
+                      int(ls_swaps), int(k_eps))
 
 
 @dataclass

@@ -84,6 +84,12 @@ size_t workspace_layout(const dmmv_problem& p, const dmmv_options& o, Ctx* c, ch
         b.take(&c->alns_picked, nR * sizeof(int32_t));
         if (sparse) b.take(&c->alns_touched, (size_t)p.m);
     }
+    if (!sparse) {
+        c->swap_nb = swap_blocks_per_instance(p);
+        b.take(&c->swap_rows, (size_t)p.R * SWAP_KMAX * sizeof(int32_t));
+        b.take(&c->swap_part, (size_t)p.R * c->swap_nb * part_sz);
+        b.take(&c->swap_skip, (size_t)p.R * sizeof(int32_t));
+    }
     if (sparse) {
         // rows per partition: what fits the LDS budget, addressable by a 16-bit offset
         int64_t mp = o.sparse_partition_rows > 0 ? o.sparse_partition_rows : (int64_t)(CSC_LDS_BYTES / esz);
@@ -587,6 +593,11 @@ static dmmv_status alns_run(dmmv_ctx* c, const void* x0, const dmmv_alns_params&
             for (int32_t mv = 0; mv < prm.ls_moves; ++mv) {
                 DMMV_TRY(loop_step(c, prm.ls_moves, nullptr, nullptr));
             }
+            if (prm.ls_swaps > 0) {
+                DMMV_TRY(swap_clear_skip(c));
+                for (int32_t sw = 0; sw < prm.ls_swaps; ++sw)
+                    DMMV_TRY(swap_move(c, prm.k_eps, 1, true, nullptr, nullptr));
+            }
             DMMV_TRY(alns_finish_iteration(c, prm, trace, trace_t));
         }
         DMMV_TRY(alns_export(c, t_best_out));
@@ -847,10 +858,23 @@ dmmv_status dmmv_alns(dmmv_handle h, const void* x0, const dmmv_alns_params* par
         return fail(DMMV_ERR_STATE, "dmmv_alns: a batched handle needs options.alns = 1 at dmmv_create (workspace for the outer loop)");
     if (params->iters < 0 || params->ls_moves < 0 || params->ls_radius < 0 || params->destroy_count < 0)
         return fail(DMMV_ERR_SHAPE, "dmmv_alns: iters, ls_moves, ls_radius and destroy_count must be >= 0");
+    if (params->ls_swaps < 0 || params->k_eps < 0)
+        return fail(DMMV_ERR_SHAPE, "dmmv_alns: ls_swaps and k_eps must be >= 0");
+    if (params->ls_swaps > 0 && h->kind == KIND_CSC)
+        return fail(DMMV_ERR_UNSUPPORTED, "dmmv_alns: the swap move (ls_swaps > 0) is not implemented for sparse matrices");
     if (!(params->alpha >= 0.0) || !(params->lambda >= 0.0 && params->lambda <= 1.0) ||
         !(params->sigma1 >= 0.0) || !(params->sigma2 >= 0.0) || !(params->sigma3 >= 0.0))
         return fail(DMMV_ERR_DOMAIN, "dmmv_alns: need alpha >= 0, 0 <= lambda <= 1, sigma >= 0");
     return alns_run(h, x0, *params, x_best_out, t_best_out, trace, trace_t);
+}
+
+dmmv_status dmmv_swap_move(dmmv_handle h, int32_t k_eps, int32_t apply, dmmv_swap* best, void* best_t) {
+    if (!h) return fail(DMMV_ERR_NULL, "dmmv_swap_move: handle is NULL");
+    if (k_eps < 0) return fail(DMMV_ERR_SHAPE, "dmmv_swap_move: k_eps < 0");
+    if (h->kind == KIND_CSC)
+        return fail(DMMV_ERR_UNSUPPORTED, "dmmv_swap_move: not implemented for sparse matrices");
+    if (!h->r_valid) return fail(DMMV_ERR_STATE, "dmmv_swap_move: no residual (call dmmv_residual or dmmv_solve first)");
+    return swap_move(h, k_eps, apply, false, best, best_t);
 }
 
 dmmv_status dmmv_time_eval(dmmv_handle h, int32_t reps, float* ms_out) {

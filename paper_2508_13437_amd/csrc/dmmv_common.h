@@ -41,6 +41,9 @@ constexpr int RES_CAP = 128;      // capacity
 constexpr int RES_MIN = 16;       // rebuild when fewer entries remain
 constexpr int RES_FAST = 8;       // entries checked inline while streaming (one mask bit each)
 
+// swap move: most rows of largest |r| the filter tries first
+constexpr int SWAP_KMAX = 128;
+
 // Per-instance loop state kept on the device.
 template <class T>
 struct alignas(16) InstState {
@@ -141,6 +144,11 @@ struct Ctx {
     void* cmp_full_state;
     void* cmp_full_scale;
     int64_t cmp_full_R;
+    // swap move (dense and batched)
+    int32_t swap_nb;          // workgroups per instance of the evaluation
+    int32_t* swap_rows;       // [R][SWAP_KMAX] rows of largest |r|, decreasing
+    void* swap_part;          // Partial<T>[R][swap_nb]
+    int32_t* swap_skip;       // [R] 1: the last search of this ALNS iteration found no swap
     // batched residual on the matrix cores (options.residual_mfma)
     void* Xp;             // bf16[3][m][mfma_ldk] planes whose sum is X
     void* Qt;             // bf16[R][mfma_ldk] current codes D[k_j] per instance
@@ -188,6 +196,12 @@ dmmv_status dense_eval(Ctx* c, void* scores_out, bool want_partials, bool honor_
 bool dense_has_fused_select_apply(const Ctx* c);
 dmmv_status dense_select_apply(Ctx* c, int32_t iters, dmmv_move* trace, void* trace_t);
 dmmv_status dense_apply(Ctx* c, bool t_from_score, int32_t iters, dmmv_move* trace, void* trace_t);
+
+int32_t swap_blocks_per_instance(const dmmv_problem& p);
+dmmv_status swap_clear_skip(Ctx* c);
+// best strictly improving swap of every instance (i = -1: none), carried out if apply != 0;
+// use_skip: pass over instances marked by an earlier search and mark those without a swap
+dmmv_status swap_move(Ctx* c, int32_t k_eps, int32_t apply, bool use_skip, dmmv_swap* best, void* best_t);
 
 dmmv_status csc_build(Ctx* c);
 dmmv_status csc_residual(Ctx* c);

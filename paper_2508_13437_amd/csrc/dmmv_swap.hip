@@ -1,0 +1,357 @@
+// Swap move of the local search (paper: section "Search Operators", Proposition 1 and
+// Corollary 1; Appendix B "Swap Move", Algorithm 2) for dense matrices and batches.
+//
+// A swap exchanges the values of two variables x_i > x_j.  With Delta = s * (D[k_i] - D[k_j])
+// the new residual is r'_k = fma(Delta, A_kj - A_ki, r_k) and the swap kept is the one with
+// the smallest t' = max_k |r'_k| (lowest pair number c = i*n + j on a tie), if t' < t.
+//
+// The filter of Corollary 1 tests a necessary condition on the k_eps rows of largest |r_k|.
+// Here the condition is the evaluation itself restricted to those rows: a pair whose new
+// residual reaches t on one of them cannot improve.  The rows are tried in order of
+// decreasing |r_k| and a pair is dropped at the first row that reaches t, or that exceeds the
+// best t' found so far; what survives is evaluated on every row.  Dropping only such pairs
+// leaves the result that of the full enumeration, whatever the order in which wavefronts
+// find their candidates.
+//
+// Work split: one workgroup handles one instance and a subset of the first variables i; a
+// lane takes one second variable j.  The first rows of the filter are staged in LDS (as
+// many as fit beside the instance's values D[k_j] and its residual); pairs that pass them
+// are finished by the whole wavefront, one lane per row, so that A is read along its
+// columns.
+#include "dmmv_common.h"
+
+namespace dmmv {
+
+namespace {
+
+constexpr int SW_BLOCK = 256;
+constexpr int SW_WAVES = SW_BLOCK / 64;
+constexpr size_t SW_LDS_BUDGET = 60 * 1024;    // dynamic LDS of the evaluation kernel
+
+__device__ __forceinline__ unsigned long long order_bits(float v) { return (unsigned long long)__float_as_uint(v); }
+__device__ __forceinline__ unsigned long long order_bits(double v) { return (unsigned long long)__double_as_longlong(v); }
+__device__ __forceinline__ void from_order_bits(unsigned long long b, float& v) { v = __uint_as_float((uint32_t)b); }
+__device__ __forceinline__ void from_order_bits(unsigned long long b, double& v) { v = __longlong_as_double((long long)b); }
+
+// ---- the K rows of largest |r| of every instance, in decreasing order (row ascending on a
+// tie).  One workgroup per instance; K selection steps, each a maximum over the rows that
+// come after the previous pick in that order.
+template <class T, bool RL>
+__global__ __launch_bounds__(SW_BLOCK) void k_swap_top(int64_t m, int64_t R, int32_t K,
+                                                        const T* __restrict__ r,
+                                                        const int32_t* __restrict__ skip,
+                                                        int32_t* __restrict__ rows_all) {
+    extern __shared__ __align__(16) unsigned char sw_smem[];
+    T* sh_abs = reinterpret_cast<T*>(sw_smem);                     // [m] when RL
+    __shared__ T sh_a[SW_WAVES];
+    __shared__ int64_t sh_r[SW_WAVES];
+    const int64_t q = blockIdx.x;
+    if (skip && skip[q]) return;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    if (RL) {
+        for (int64_t i = threadIdx.x; i < m; i += SW_BLOCK) sh_abs[i] = dmmv_abs(r[i * R + q]);
+        __syncthreads();
+    }
+    T pa = Limits<T>::inf();
+    int64_t prow = -1;
+    for (int32_t step = 0; step < K; ++step) {
+        T a = (T)-1;
+        int64_t row = INT64_MAX;
+        for (int64_t i = threadIdx.x; i < m; i += SW_BLOCK) {
+            const T v = RL ? sh_abs[i] : dmmv_abs(r[i * R + q]);
+            const bool after = v < pa || (v == pa && i > prow);
+            if (after && v > a) { a = v; row = i; }
+        }
+        const T wa = wave_max(a);
+        if (lane == 0) sh_a[w] = wa;
+        __syncthreads();
+        T amax = sh_a[0];
+#pragma unroll
+        for (int u = 1; u < SW_WAVES; ++u) amax = dmmv_max(amax, sh_a[u]);
+        const int64_t wr = wave_min(a == amax ? row : (int64_t)INT64_MAX);
+        if (lane == 0) sh_r[w] = wr;
+        __syncthreads();
+        int64_t rmin = sh_r[0];
+#pragma unroll
+        for (int u = 1; u < SW_WAVES; ++u) rmin = sh_r[u] < rmin ? sh_r[u] : rmin;
+        if (threadIdx.x == 0) rows_all[q * K + step] = (int32_t)rmin;
+        pa = amax;
+        prow = rmin;
+        __syncthreads();                                   // sh_a / sh_r are rewritten next step
+    }
+}
+
+// ---- evaluation: grid (R, nb).  Writes one record (t', c) per workgroup; c = -1 if the
+// workgroup found no pair with t' < t.
+template <class T, bool DVL, bool RL>
+__global__ __launch_bounds__(SW_BLOCK) void k_swap_eval(
+    int64_t m, int64_t n, int64_t R, int32_t nb, int32_t K, int32_t L, const T* __restrict__ A,
+    int64_t lda, const T* __restrict__ D, const T* __restrict__ scale,
+    const int32_t* __restrict__ kidx, const T* __restrict__ r, const InstState<T>* __restrict__ st,
+    const uint8_t* __restrict__ var_mask, const int32_t* __restrict__ rows_all,
+    const int32_t* __restrict__ skip, Partial<T>* __restrict__ part) {
+    extern __shared__ __align__(16) unsigned char sw_smem[];
+    // carve: rtop[K] | dv[n] (DVL) | rcol[m] (RL) | atop[L][n] | rows[K]
+    T* rtop = reinterpret_cast<T*>(sw_smem);
+    T* sh_dv = rtop + K;
+    T* sh_rc = sh_dv + (DVL ? n : 0);
+    T* atop = sh_rc + (RL ? m : 0);
+    int32_t* sh_rows = reinterpret_cast<int32_t*>(atop + (int64_t)L * n);
+    __shared__ unsigned long long sh_best;                 // order bits of the best t' of the workgroup
+    __shared__ T sh_s[SW_WAVES];
+    __shared__ int64_t sh_c[SW_WAVES];
+
+    const int64_t q = blockIdx.x;
+    const int blk = blockIdx.y;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    Partial<T>* out = part + q * nb + blk;
+    if (skip && skip[q]) {
+        if (threadIdx.x == 0) { Partial<T> e; e.s = (T)0; e.c = -1; *out = e; }
+        return;
+    }
+    const int32_t* __restrict__ rows_g = rows_all + q * K;
+    const uint8_t* __restrict__ vm = var_mask ? var_mask + q * n : nullptr;
+    for (int l = threadIdx.x; l < K; l += SW_BLOCK) {
+        const int32_t row = rows_g[l];
+        sh_rows[l] = row;
+        rtop[l] = r[(int64_t)row * R + q];
+    }
+    if (DVL)
+        for (int64_t j = threadIdx.x; j < n; j += SW_BLOCK) sh_dv[j] = D[kidx[j * R + q]];
+    if (RL)
+        for (int64_t i = threadIdx.x; i < m; i += SW_BLOCK) sh_rc[i] = r[i * R + q];
+    for (int64_t e = threadIdx.x; e < (int64_t)L * n; e += SW_BLOCK) {
+        const int64_t l = e / n, j = e % n;
+        atop[e] = A[(int64_t)rows_g[l] + j * lda];
+    }
+    if (threadIdx.x == 0) sh_best = order_bits(Limits<T>::inf());
+    __syncthreads();
+    volatile unsigned long long* vbest = &sh_best;
+
+    auto dv = [&](int64_t j) -> T { return DVL ? sh_dv[j] : D[kidx[j * R + q]]; };
+    auto rr = [&](int64_t i) -> T { return RL ? sh_rc[i] : r[i * R + q]; };
+
+    const T t = st[q].t;
+    const T sc = scale[q];
+    T best_t = Limits<T>::inf();
+    int64_t best_c = -1;                                   // the wavefront's record (uniform)
+
+    for (int64_t i = blk; i < n; i += nb) {
+        if (vm && !vm[i]) continue;
+        const T dvi = dv(i);
+        const T* __restrict__ Ai = A + i * lda;
+        for (int64_t j0 = (int64_t)w * 64; j0 < n; j0 += SW_BLOCK) {
+            const int64_t j = j0 + lane;
+            bool alive = false;
+            T Delta = (T)0;
+            if (j < n) {
+                const T dvj = dv(j);
+                if (dvi > dvj && (!vm || vm[j])) {
+                    alive = true;
+                    const T diff = dvi - dvj;
+                    Delta = sc * diff;
+                }
+            }
+            if (!__any(alive)) continue;
+            T shared_t;
+            from_order_bits(*vbest, shared_t);
+            T bnd = dmmv_min(best_t, shared_t);
+            // filter rows held in LDS: one lane per pair
+            for (int l = 0; l < L; ++l) {
+                if (alive) {
+                    const T d = atop[(int64_t)l * n + j] - atop[(int64_t)l * n + i];
+                    const T v = dmmv_abs(dmmv_fma(Delta, d, rtop[l]));
+                    alive = v < t && !(v > bnd);
+                }
+                if (!__any(alive)) break;
+            }
+            // the pairs left: the whole wavefront finishes one at a time, one lane per row
+            unsigned long long todo = __ballot(alive);
+            while (todo) {
+                const int src = __builtin_ctzll(todo);
+                todo &= todo - 1;
+                const int64_t sj = j0 + src;
+                const T diff = dvi - dv(sj);
+                const T Dl = sc * diff;
+                const T* __restrict__ Aj = A + sj * lda;
+                from_order_bits(*vbest, shared_t);
+                bnd = dmmv_min(best_t, shared_t);
+                T v = (T)0;
+                for (int l = L + lane; l < K; l += 64) {
+                    const int64_t row = sh_rows[l];
+                    v = dmmv_max(v, dmmv_abs(dmmv_fma(Dl, Aj[row] - Ai[row], rtop[l])));
+                }
+                T wm = wave_max(v);
+                bool ok = wm < t && !(wm > bnd);
+                for (int64_t base = 0; base < m && ok; base += 256) {
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int64_t row = base + u * 64 + lane;
+                        if (row < m) v = dmmv_max(v, dmmv_abs(dmmv_fma(Dl, Aj[row] - Ai[row], rr(row))));
+                    }
+                    wm = wave_max(v);
+                    ok = wm < t && !(wm > bnd);
+                }
+                if (ok) {
+                    const int64_t c = i * n + sj;
+                    if (rec_less(wm, c, best_t, best_c)) {
+                        best_t = wm;
+                        best_c = c;
+                        if (lane == 0) atomicMin(&sh_best, order_bits(wm));
+                    }
+                }
+            }
+        }
+    }
+    if (lane == 0) { sh_s[w] = best_t; sh_c[w] = best_c; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        T bs = sh_s[0];
+        int64_t bc = sh_c[0];
+        for (int u = 1; u < SW_WAVES; ++u)
+            if (rec_less(sh_s[u], sh_c[u], bs, bc)) { bs = sh_s[u]; bc = sh_c[u]; }
+        Partial<T> p;
+        p.s = bc < 0 ? (T)0 : bs;
+        p.c = bc;
+        *out = p;
+    }
+}
+
+// ---- reduce the records of an instance, report, and carry the swap out.  One workgroup per
+// instance.
+template <class T>
+__global__ __launch_bounds__(SW_BLOCK) void k_swap_apply(
+    int64_t m, int64_t n, int64_t R, int32_t nb, int32_t apply, const T* __restrict__ A, int64_t lda,
+    const T* __restrict__ D, const T* __restrict__ scale, int32_t* __restrict__ kidx,
+    T* __restrict__ r, InstState<T>* __restrict__ st, const Partial<T>* __restrict__ part,
+    int32_t* __restrict__ skip, int32_t mark_skip, dmmv_swap* __restrict__ best_out,
+    T* __restrict__ best_t_out) {
+    __shared__ T sh_s[SW_WAVES];
+    __shared__ int64_t sh_c[SW_WAVES];
+    __shared__ T sh_bs;
+    __shared__ int64_t sh_bc;
+    const int64_t q = blockIdx.x;
+    if (skip && skip[q]) {
+        if (threadIdx.x == 0) {
+            if (best_out) { best_out[q].i = -1; best_out[q].j = -1; }
+            if (best_t_out) best_t_out[q] = st[q].t;
+        }
+        return;
+    }
+    T s = (T)0;
+    int64_t c = -1;
+    for (int e = threadIdx.x; e < nb; e += SW_BLOCK) {
+        const Partial<T> p = part[q * nb + e];
+        if (rec_less(p.s, p.c, s, c)) { s = p.s; c = p.c; }
+    }
+    block_argmin(s, c, sh_s, sh_c);
+    if (threadIdx.x == 0) { sh_bs = s; sh_bc = c; }
+    __syncthreads();
+    s = sh_bs;
+    c = sh_bc;
+    if (threadIdx.x == 0) {
+        if (best_out) { best_out[q].i = c < 0 ? -1 : c / n; best_out[q].j = c < 0 ? -1 : c % n; }
+        if (best_t_out) best_t_out[q] = c < 0 ? st[q].t : s;
+        if (c < 0 && skip && mark_skip) skip[q] = 1;
+    }
+    if (c < 0 || !apply) return;
+    const int64_t i = c / n, j = c % n;
+    const int32_t ki = kidx[i * R + q], kj = kidx[j * R + q];
+    const T diff = D[ki] - D[kj];
+    const T Delta = scale[q] * diff;
+    const T* __restrict__ Ai = A + i * lda;
+    const T* __restrict__ Aj = A + j * lda;
+    for (int64_t k = threadIdx.x; k < m; k += SW_BLOCK)
+        r[k * R + q] = dmmv_fma(Delta, Aj[k] - Ai[k], r[k * R + q]);
+    __syncthreads();                                       // every thread has read ki and kj
+    if (threadIdx.x == 0) {
+        kidx[i * R + q] = kj;
+        kidx[j * R + q] = ki;
+        st[q].t = s;
+        st[q].moves += 1;
+    }
+}
+
+__global__ void k_swap_clear(int32_t* skip, int64_t R) {
+    const int64_t q = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    if (q < R) skip[q] = 0;
+}
+
+template <class T>
+dmmv_status swap_t(Ctx* c, int32_t k_eps, int32_t apply, bool use_skip, dmmv_swap* best, void* best_t) {
+    const int64_t m = c->p.m, n = c->p.n, R = c->p.R;
+    if (n == 0 || R == 0) return DMMV_OK;
+    int32_t K = k_eps > 0 ? k_eps : 100;
+    if (K > SWAP_KMAX) K = SWAP_KMAX;
+    if ((int64_t)K > m) K = (int32_t)m;
+    const int32_t nb = c->swap_nb;
+    int32_t* skip = use_skip ? c->swap_skip : nullptr;
+    // LDS: the K residuals and rows always; then D[k_j], the residual, and filter rows of A
+    size_t used = (size_t)K * (sizeof(T) + sizeof(int32_t)) + 64;
+    const bool dvl = used + (size_t)n * sizeof(T) <= SW_LDS_BUDGET;
+    if (dvl) used += (size_t)n * sizeof(T);
+    const bool rl = used + (size_t)m * sizeof(T) <= SW_LDS_BUDGET;
+    if (rl) used += (size_t)m * sizeof(T);
+    int64_t L = n > 0 ? (int64_t)((SW_LDS_BUDGET - used) / ((size_t)n * sizeof(T))) : 0;
+    if (L > K) L = K;
+    used += (size_t)L * n * sizeof(T);
+
+    if (K > 0) {
+        const bool top_rl = (size_t)m * sizeof(T) <= SW_LDS_BUDGET;
+        const size_t top_lds = top_rl ? (size_t)m * sizeof(T) : 0;
+        if (top_rl)
+            hipLaunchKernelGGL((k_swap_top<T, true>), dim3((unsigned)R), dim3(SW_BLOCK), top_lds, c->stream, m, R, K,
+                               (const T*)c->r, (const int32_t*)skip, c->swap_rows);
+        else
+            hipLaunchKernelGGL((k_swap_top<T, false>), dim3((unsigned)R), dim3(SW_BLOCK), 0, c->stream, m, R, K,
+                               (const T*)c->r, (const int32_t*)skip, c->swap_rows);
+    }
+    const dim3 grid((unsigned)R, (unsigned)nb);
+#define DMMV_SWAP_LAUNCH(DV, RLL)                                                                          \
+    hipLaunchKernelGGL((k_swap_eval<T, DV, RLL>), grid, dim3(SW_BLOCK), used, c->stream, m, n, R, nb, K,  \
+                       (int32_t)L, (const T*)c->p.A_dense, c->p.lda, (const T*)c->D_dev,                   \
+                       (const T*)c->scale_dev, (const int32_t*)c->kidx, (const T*)c->r,                    \
+                       (const InstState<T>*)c->state, c->o.var_mask, (const int32_t*)c->swap_rows,         \
+                       (const int32_t*)skip, (Partial<T>*)c->swap_part)
+    if (dvl && rl) DMMV_SWAP_LAUNCH(true, true);
+    else if (dvl) DMMV_SWAP_LAUNCH(true, false);
+    else if (rl) DMMV_SWAP_LAUNCH(false, true);
+    else DMMV_SWAP_LAUNCH(false, false);
+#undef DMMV_SWAP_LAUNCH
+    hipLaunchKernelGGL(k_swap_apply<T>, dim3((unsigned)R), dim3(SW_BLOCK), 0, c->stream, m, n, R, nb, apply,
+                       (const T*)c->p.A_dense, c->p.lda, (const T*)c->D_dev, (const T*)c->scale_dev, c->kidx,
+                       (T*)c->r, (InstState<T>*)c->state, (const Partial<T>*)c->swap_part, skip,
+                       use_skip ? 1 : 0, best, (T*)best_t);
+    DMMV_LAUNCH_CHECK();
+    return DMMV_OK;
+}
+
+}  // namespace
+
+int32_t swap_blocks_per_instance(const dmmv_problem& p) {
+    // about 2048 workgroups in all, at most one per first variable
+    int64_t nb = ceil_div(2048, p.R > 0 ? p.R : 1);
+    if (nb > p.n) nb = p.n;
+    if (nb < 1) nb = 1;
+    return (int32_t)nb;
+}
+
+dmmv_status swap_clear_skip(Ctx* c) {
+    if (c->kind == KIND_CSC || !c->swap_skip)
+        return fail(DMMV_ERR_UNSUPPORTED, "swap move: not implemented for sparse matrices");
+    if (c->p.R == 0) return DMMV_OK;
+    hipLaunchKernelGGL(k_swap_clear, dim3((unsigned)ceil_div(c->p.R, 256)), dim3(256), 0, c->stream, c->swap_skip,
+                       c->p.R);
+    DMMV_LAUNCH_CHECK();
+    return DMMV_OK;
+}
+
+dmmv_status swap_move(Ctx* c, int32_t k_eps, int32_t apply, bool use_skip, dmmv_swap* best, void* best_t) {
+    // the buffers below exist for dense matrices and batches only
+    if (c->kind == KIND_CSC || !c->swap_skip || !c->swap_rows || !c->swap_part)
+        return fail(DMMV_ERR_UNSUPPORTED, "swap move: not implemented for sparse matrices");
+    return c->p.dtype == DMMV_F64 ? swap_t<double>(c, k_eps, apply, use_skip, best, best_t)
+                                  : swap_t<float>(c, k_eps, apply, use_skip, best, best_t);
+}
+
+}  // namespace dmmv

@@ -26,7 +26,7 @@ STATUS_NAMES = {0: "DMMV_OK", -1: "DMMV_ERR_NULL", -2: "DMMV_ERR_SHAPE", -3: "DM
 
 EXPORTS = ("dmmv_workspace_bytes", "dmmv_create", "dmmv_destroy", "dmmv_set_x",
            "dmmv_set_residual", "dmmv_residual", "dmmv_eval_moves", "dmmv_argmin_move",
-           "dmmv_apply_move", "dmmv_get_state", "dmmv_solve", "dmmv_alns", "dmmv_time_eval",
+           "dmmv_apply_move", "dmmv_get_state", "dmmv_solve", "dmmv_alns", "dmmv_swap_move", "dmmv_time_eval",
            "dmmv_last_error",
            "dmmv_version")
 
@@ -54,7 +54,7 @@ class AlnsParams(C.Structure):
     _fields_ = [("iters", C.c_int32), ("ls_moves", C.c_int32), ("ls_radius", C.c_int32),
                 ("destroy_count", C.c_int32), ("alpha", C.c_double), ("lambda_", C.c_double),
                 ("sigma1", C.c_double), ("sigma2", C.c_double), ("sigma3", C.c_double),
-                ("seed", C.c_uint64)]
+                ("seed", C.c_uint64), ("ls_swaps", C.c_int32), ("k_eps", C.c_int32)]
 
 
 _lib = None
@@ -88,6 +88,8 @@ def load() -> C.CDLL:
     lib.dmmv_alns.restype = C.c_int
     lib.dmmv_alns.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(AlnsParams), C.c_void_p, C.c_void_p,
                               C.c_void_p, C.c_void_p]
+    lib.dmmv_swap_move.restype = C.c_int
+    lib.dmmv_swap_move.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
     lib.dmmv_time_eval.restype = C.c_int
     lib.dmmv_time_eval.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_float)]
     lib.dmmv_last_error.restype = C.c_char_p
@@ -331,10 +333,12 @@ class AlnsResult:
 
 def dmmv_alns(h: Handle, x0: Optional[torch.Tensor], iters: int, ls_moves: int = 8, ls_radius: int = 1,
               destroy_count: int = 0, alpha: float = 0.3, lambda_: float = 0.2, sigma1: float = 3.0,
-              sigma2: float = 2.0, sigma3: float = 1.0, seed: int = 1) -> AlnsResult:
-    """The ALNS outer loop around the descent (single dense or sparse instance)."""
+              sigma2: float = 2.0, sigma3: float = 1.0, seed: int = 1, ls_swaps: int = 0,
+              k_eps: int = 0) -> AlnsResult:
+    """The ALNS outer loop around the descent (and, with ls_swaps, the swap move)."""
     prm = AlnsParams(int(iters), int(ls_moves), int(ls_radius), int(destroy_count), float(alpha),
-                     float(lambda_), float(sigma1), float(sigma2), float(sigma3), int(seed))
+                     float(lambda_), float(sigma1), float(sigma2), float(sigma3), int(seed),
+                     int(ls_swaps), int(k_eps))
     if x0 is not None:
         x0 = x0.to(h.device, h.dtype).contiguous()
     x_best = h._new(h._xshape())
@@ -346,6 +350,22 @@ def dmmv_alns(h: Handle, x0: Optional[torch.Tensor], iters: int, ls_moves: int =
     if not h.batched:
         return AlnsResult(x_best, t_best, trace[0, :iters], trace_t[0, :iters])
     return AlnsResult(x_best, t_best, trace[:, :iters], trace_t[:, :iters])
+
+
+@dataclass
+class SwapResult:
+    i: torch.Tensor          # [R] int64, -1 = no improving swap
+    j: torch.Tensor          # [R] int64
+    t: torch.Tensor          # [R] error after the swap (the current error when there is none)
+
+
+def dmmv_swap_move(h: Handle, k_eps: int = 0, apply: bool = True) -> SwapResult:
+    """Best strictly improving exchange of two variables' values (Algorithm 2)."""
+    best = torch.empty((h.R, 2), dtype=torch.int64, device=h.device)
+    best_t = h._new((h.R,))
+    _check(load().dmmv_swap_move(h._h, C.c_int32(int(k_eps)), C.c_int32(1 if apply else 0), _ptr(best),
+                                 _ptr(best_t)))
+    return SwapResult(best[:, 0], best[:, 1], best_t)
 
 
 def dmmv_time_eval(h: Handle, reps: int) -> float:

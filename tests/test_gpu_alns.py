@@ -177,3 +177,19 @@ def test_alns_full_size_configs(idx, iters, ls):
     in seconds), default destroy rate (0.5 % of n: 1 and 328 variables)."""
     inst = make_config(idx)
     alns_check(inst, iters, ls_moves=ls, seed=100 + idx)
+
+
+# ---- the swap move inside the local search (dense and batched) -----------------------------
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_alns_dense_with_swaps(dtype):
+    alns_check(random_dense(7900, 60, 30, 5, dtype=dtype), 12, ls_moves=3, ls_swaps=2, destroy_count=4, seed=5)
+    alns_check(random_dense(7901, 33, 50, 3, dtype=dtype, integer=True), 10, ls_moves=2, ls_swaps=3, seed=6)
+
+
+def test_alns_dense_toy_with_swaps():
+    alns_check(make_config(1), 6, ls_moves=20, ls_swaps=2, seed=11, k_eps=16)
+
+
+def test_alns_batched_with_swaps():
+    batched_alns_check(random_batched(7910, 40, 24, 20, 4), 8, ls_moves=3, ls_swaps=2, destroy_count=3, seed=2)
+    batched_alns_check(random_batched(7911, 30, 16, 70, 5, integer=True), 8, ls_moves=2, ls_swaps=2, seed=3)
