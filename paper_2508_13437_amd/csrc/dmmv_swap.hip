@@ -13,11 +13,11 @@
 // leaves the result that of the full enumeration, whatever the order in which wavefronts
 // find their candidates.
 //
-// Work split: one workgroup handles one instance and a subset of the first variables i; a
-// lane takes one second variable j.  The first rows of the filter are staged in LDS (as
-// many as fit beside the instance's values D[k_j] and its residual); pairs that pass them
-// are finished by the whole wavefront, one lane per row, so that A is read along its
-// columns.
+// Work split: one workgroup handles one instance; each of its wavefronts takes variables u and
+// a lane one partner v > u, so every unordered pair is met once.  The first rows of the filter
+// are staged in LDS (as many as fit beside the instance's values D[k_j]), the others are read
+// from memory; pairs that pass all of them are finished by the whole wavefront, one lane per
+// row, so that A is read along its columns.
 #include "dmmv_common.h"
 
 namespace dmmv {
@@ -26,7 +26,10 @@ namespace {
 
 constexpr int SW_BLOCK = 256;
 constexpr int SW_WAVES = SW_BLOCK / 64;
-constexpr size_t SW_LDS_BUDGET = 60 * 1024;    // dynamic LDS of the evaluation kernel
+constexpr int SWE_BLOCK = 1024;                // evaluation: many wavefronts share one instance's LDS tile
+constexpr int SWE_WAVES = SWE_BLOCK / 64;
+constexpr int SWE_QCAP = 128;                  // queue of a wavefront: under 64 waiting plus at most 64 new
+constexpr size_t SW_LDS_BUDGET = 52 * 1024;    // dynamic LDS of the evaluation kernel (8 KiB more are static)
 
 __device__ __forceinline__ unsigned long long order_bits(float v) { return (unsigned long long)__float_as_uint(v); }
 __device__ __forceinline__ unsigned long long order_bits(double v) { return (unsigned long long)__double_as_longlong(v); }
@@ -83,23 +86,30 @@ __global__ __launch_bounds__(SW_BLOCK) void k_swap_top(int64_t m, int64_t R, int
 
 // ---- evaluation: grid (R, nb).  Writes one record (t', c) per workgroup; c = -1 if the
 // workgroup found no pair with t' < t.
-template <class T, bool DVL, bool RL>
-__global__ __launch_bounds__(SW_BLOCK) void k_swap_eval(
+//
+// A wavefront owns a variable u and walks its partners v > u, 64 at a time, through the filter
+// rows held in LDS.  Every such row drops about half of the pairs still alive when many rows
+// are close to t (the state a descent leaves), so the survivors are packed into a queue of the
+// wavefront and taken through the remaining filter rows (read from memory) 64 at a time, all
+// lanes busy.  What passes every filter row is evaluated on all m rows by the whole wavefront,
+// one lane per row.
+template <class T, bool DVL>
+__global__ __launch_bounds__(SWE_BLOCK) void k_swap_eval(
     int64_t m, int64_t n, int64_t R, int32_t nb, int32_t K, int32_t L, const T* __restrict__ A,
-    int64_t lda, const T* __restrict__ D, const T* __restrict__ scale,
+    int64_t lda, const T* __restrict__ At, const T* __restrict__ D, const T* __restrict__ scale,
     const int32_t* __restrict__ kidx, const T* __restrict__ r, const InstState<T>* __restrict__ st,
     const uint8_t* __restrict__ var_mask, const int32_t* __restrict__ rows_all,
     const int32_t* __restrict__ skip, Partial<T>* __restrict__ part) {
     extern __shared__ __align__(16) unsigned char sw_smem[];
-    // carve: rtop[K] | dv[n] (DVL) | rcol[m] (RL) | atop[L][n] | rows[K]
+    // carve: rtop[K] | dv[n] (DVL) | atop[L][n] | rows[K]
     T* rtop = reinterpret_cast<T*>(sw_smem);
     T* sh_dv = rtop + K;
-    T* sh_rc = sh_dv + (DVL ? n : 0);
-    T* atop = sh_rc + (RL ? m : 0);
+    T* atop = sh_dv + (DVL ? n : 0);
     int32_t* sh_rows = reinterpret_cast<int32_t*>(atop + (int64_t)L * n);
+    __shared__ int32_t sh_queue[SWE_WAVES][SWE_QCAP];      // partners v waiting for the later rows
     __shared__ unsigned long long sh_best;                 // order bits of the best t' of the workgroup
-    __shared__ T sh_s[SW_WAVES];
-    __shared__ int64_t sh_c[SW_WAVES];
+    __shared__ T sh_s[SWE_WAVES];
+    __shared__ int64_t sh_c[SWE_WAVES];
 
     const int64_t q = blockIdx.x;
     const int blk = blockIdx.y;
@@ -111,105 +121,138 @@ __global__ __launch_bounds__(SW_BLOCK) void k_swap_eval(
     }
     const int32_t* __restrict__ rows_g = rows_all + q * K;
     const uint8_t* __restrict__ vm = var_mask ? var_mask + q * n : nullptr;
-    for (int l = threadIdx.x; l < K; l += SW_BLOCK) {
+    for (int l = threadIdx.x; l < K; l += SWE_BLOCK) {
         const int32_t row = rows_g[l];
         sh_rows[l] = row;
         rtop[l] = r[(int64_t)row * R + q];
     }
     if (DVL)
-        for (int64_t j = threadIdx.x; j < n; j += SW_BLOCK) sh_dv[j] = D[kidx[j * R + q]];
-    if (RL)
-        for (int64_t i = threadIdx.x; i < m; i += SW_BLOCK) sh_rc[i] = r[i * R + q];
-    for (int64_t e = threadIdx.x; e < (int64_t)L * n; e += SW_BLOCK) {
+        for (int64_t j = threadIdx.x; j < n; j += SWE_BLOCK) sh_dv[j] = D[kidx[j * R + q]];
+    for (int64_t e = threadIdx.x; e < (int64_t)L * n; e += SWE_BLOCK) {
         const int64_t l = e / n, j = e % n;
         atop[e] = A[(int64_t)rows_g[l] + j * lda];
     }
     if (threadIdx.x == 0) sh_best = order_bits(Limits<T>::inf());
     __syncthreads();
     volatile unsigned long long* vbest = &sh_best;
+    volatile int32_t* queue = sh_queue[w];
 
     auto dv = [&](int64_t j) -> T { return DVL ? sh_dv[j] : D[kidx[j * R + q]]; };
-    auto rr = [&](int64_t i) -> T { return RL ? sh_rc[i] : r[i * R + q]; };
+    // Unordered pairs {u, v}, u < v, each taken in the orientation its values give: with
+    // Ds = +Delta when x_u > x_v (pair (u, v)) and -Delta when x_v > x_u (pair (v, u)) the new
+    // residual of either is fma(Ds, A_kv - A_ku, r_k), bit for bit (a - b = -(b - a) and
+    // fma(-x, y, z) = fma(x, -y, z) exactly).
+    const T sc = scale[q];
+    auto step_of = [&](T dvu, T dvv) -> T {
+        if (dvu > dvv) { const T diff = dvu - dvv; return sc * diff; }
+        const T diff = dvv - dvu;
+        return -(sc * diff);
+    };
 
     const T t = st[q].t;
-    const T sc = scale[q];
     T best_t = Limits<T>::inf();
     int64_t best_c = -1;                                   // the wavefront's record (uniform)
+    auto bound = [&]() -> T {
+        T shared_t;
+        from_order_bits(*vbest, shared_t);
+        return dmmv_min(best_t, shared_t);
+    };
 
-    for (int64_t i = blk; i < n; i += nb) {
-        if (vm && !vm[i]) continue;
-        const T dvi = dv(i);
-        const T* __restrict__ Ai = A + i * lda;
-        for (int64_t j0 = (int64_t)w * 64; j0 < n; j0 += SW_BLOCK) {
-            const int64_t j = j0 + lane;
-            bool alive = false;
-            T Delta = (T)0;
-            if (j < n) {
-                const T dvj = dv(j);
-                if (dvi > dvj && (!vm || vm[j])) {
-                    alive = true;
-                    const T diff = dvi - dvj;
-                    Delta = sc * diff;
-                }
+    // the first `cnt` queued partners of u: remaining filter rows, then the full evaluation
+    auto drain = [&](int64_t u, T dvu, const T* __restrict__ Au, int cnt) {
+        bool alive = lane < cnt;
+        const int64_t v = alive ? (int64_t)queue[lane] : u;
+        const T Ds = alive ? step_of(dvu, dv(v)) : (T)0;
+        T bnd = bound();
+        for (int l = L; l < K && __any(alive); ++l) {
+            if (alive) {
+                const int64_t row = sh_rows[l];
+                const T au = At ? At[row * n + u] : Au[row];
+                const T av = At ? At[row * n + v] : A[row + v * lda];
+                const T val = dmmv_abs(dmmv_fma(Ds, av - au, rtop[l]));
+                alive = val < t && !(val > bnd);
             }
-            if (!__any(alive)) continue;
-            T shared_t;
-            from_order_bits(*vbest, shared_t);
-            T bnd = dmmv_min(best_t, shared_t);
-            // filter rows held in LDS: one lane per pair
-            for (int l = 0; l < L; ++l) {
-                if (alive) {
-                    const T d = atop[(int64_t)l * n + j] - atop[(int64_t)l * n + i];
-                    const T v = dmmv_abs(dmmv_fma(Delta, d, rtop[l]));
-                    alive = v < t && !(v > bnd);
-                }
-                if (!__any(alive)) break;
-            }
-            // the pairs left: the whole wavefront finishes one at a time, one lane per row
-            unsigned long long todo = __ballot(alive);
-            while (todo) {
-                const int src = __builtin_ctzll(todo);
-                todo &= todo - 1;
-                const int64_t sj = j0 + src;
-                const T diff = dvi - dv(sj);
-                const T Dl = sc * diff;
-                const T* __restrict__ Aj = A + sj * lda;
-                from_order_bits(*vbest, shared_t);
-                bnd = dmmv_min(best_t, shared_t);
-                T v = (T)0;
-                for (int l = L + lane; l < K; l += 64) {
-                    const int64_t row = sh_rows[l];
-                    v = dmmv_max(v, dmmv_abs(dmmv_fma(Dl, Aj[row] - Ai[row], rtop[l])));
-                }
-                T wm = wave_max(v);
-                bool ok = wm < t && !(wm > bnd);
-                for (int64_t base = 0; base < m && ok; base += 256) {
+        }
+        unsigned long long todo = __ballot(alive);
+        while (todo) {
+            const int src = __builtin_ctzll(todo);
+            todo &= todo - 1;
+            const int64_t sv = (int64_t)queue[src];
+            const T dvv = dv(sv);
+            const T Dl = step_of(dvu, dvv);
+            const T* __restrict__ Av = A + sv * lda;
+            bnd = bound();
+            T val = (T)0, wm = (T)0;
+            bool ok = true;
+            for (int64_t base = 0; base < m && ok; base += 256) {
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const int64_t row = base + u * 64 + lane;
-                        if (row < m) v = dmmv_max(v, dmmv_abs(dmmv_fma(Dl, Aj[row] - Ai[row], rr(row))));
-                    }
-                    wm = wave_max(v);
-                    ok = wm < t && !(wm > bnd);
+                for (int x = 0; x < 4; ++x) {
+                    const int64_t row = base + x * 64 + lane;
+                    if (row < m) val = dmmv_max(val, dmmv_abs(dmmv_fma(Dl, Av[row] - Au[row], r[row * R + q])));
                 }
-                if (ok) {
-                    const int64_t c = i * n + sj;
-                    if (rec_less(wm, c, best_t, best_c)) {
-                        best_t = wm;
-                        best_c = c;
-                        if (lane == 0) atomicMin(&sh_best, order_bits(wm));
-                    }
+                wm = wave_max(val);
+                ok = wm < t && !(wm > bnd);
+            }
+            if (ok && wm < t) {
+                const int64_t c = dvu > dvv ? u * n + sv : sv * n + u;
+                if (rec_less(wm, c, best_t, best_c)) {
+                    best_t = wm;
+                    best_c = c;
+                    if (lane == 0) atomicMin(&sh_best, order_bits(wm));
                 }
             }
         }
+    };
+
+    // n < 2^31 (the variables are numbered with int32 throughout the library), and L * n
+    // elements fit in LDS, so 32-bit indices do below.
+    const int32_t n32 = (int32_t)n;
+    const unsigned long long below = (1ull << lane) - 1ull;
+    for (int32_t u = blk * SWE_WAVES + w; u < n32; u += nb * SWE_WAVES) {
+        if (vm && !vm[u]) continue;
+        const T dvu = dv(u);
+        const T* __restrict__ Au = A + (int64_t)u * lda;
+        int qn = 0;                                        // queued partners (uniform)
+        for (int32_t v0 = (u + 1) & ~63; v0 < n32; v0 += 64) {
+            const int32_t v = v0 + lane;
+            bool alive = false;
+            T Ds = (T)0;
+            if (v > u && v < n32) {
+                const T dvv = dv(v);
+                alive = dvu != dvv;
+                if (vm) alive = alive && vm[v];
+                Ds = step_of(dvu, dvv);
+            }
+            const T bnd = bound();
+            const T* __restrict__ row_l = atop;
+            for (int l = 0; l < L; ++l, row_l += n32) {
+                const T val = dmmv_abs(dmmv_fma(Ds, row_l[alive ? v : u] - row_l[u], rtop[l]));
+                alive = alive && val < t && !(val > bnd);
+                if (!__any(alive)) break;
+            }
+            const unsigned long long bal = __ballot(alive);
+            if (!bal) continue;
+            if (alive) queue[qn + __popcll(bal & below)] = v;
+            qn += __popcll(bal);
+            __builtin_amdgcn_wave_barrier();
+            if (qn >= 64) {
+                drain(u, dvu, Au, 64);
+                const int32_t carry = 64 + lane < qn ? queue[64 + lane] : 0;
+                __builtin_amdgcn_wave_barrier();
+                if (64 + lane < qn) queue[lane] = carry;
+                __builtin_amdgcn_wave_barrier();
+                qn -= 64;
+            }
+        }
+        if (qn > 0) drain(u, dvu, Au, qn);
     }
     if (lane == 0) { sh_s[w] = best_t; sh_c[w] = best_c; }
     __syncthreads();
     if (threadIdx.x == 0) {
         T bs = sh_s[0];
         int64_t bc = sh_c[0];
-        for (int u = 1; u < SW_WAVES; ++u)
-            if (rec_less(sh_s[u], sh_c[u], bs, bc)) { bs = sh_s[u]; bc = sh_c[u]; }
+        for (int x = 1; x < SWE_WAVES; ++x)
+            if (rec_less(sh_s[x], sh_c[x], bs, bc)) { bs = sh_s[x]; bc = sh_c[x]; }
         Partial<T> p;
         p.s = bc < 0 ? (T)0 : bs;
         p.c = bc;
@@ -286,12 +329,10 @@ dmmv_status swap_t(Ctx* c, int32_t k_eps, int32_t apply, bool use_skip, dmmv_swa
     if ((int64_t)K > m) K = (int32_t)m;
     const int32_t nb = c->swap_nb;
     int32_t* skip = use_skip ? c->swap_skip : nullptr;
-    // LDS: the K residuals and rows always; then D[k_j], the residual, and filter rows of A
+    // LDS: the K residuals and rows always; then D[k_j] and filter rows of A
     size_t used = (size_t)K * (sizeof(T) + sizeof(int32_t)) + 64;
     const bool dvl = used + (size_t)n * sizeof(T) <= SW_LDS_BUDGET;
     if (dvl) used += (size_t)n * sizeof(T);
-    const bool rl = used + (size_t)m * sizeof(T) <= SW_LDS_BUDGET;
-    if (rl) used += (size_t)m * sizeof(T);
     int64_t L = n > 0 ? (int64_t)((SW_LDS_BUDGET - used) / ((size_t)n * sizeof(T))) : 0;
     if (L > K) L = K;
     used += (size_t)L * n * sizeof(T);
@@ -307,16 +348,15 @@ dmmv_status swap_t(Ctx* c, int32_t k_eps, int32_t apply, bool use_skip, dmmv_swa
                                (const T*)c->r, (const int32_t*)skip, c->swap_rows);
     }
     const dim3 grid((unsigned)R, (unsigned)nb);
-#define DMMV_SWAP_LAUNCH(DV, RLL)                                                                          \
-    hipLaunchKernelGGL((k_swap_eval<T, DV, RLL>), grid, dim3(SW_BLOCK), used, c->stream, m, n, R, nb, K,  \
-                       (int32_t)L, (const T*)c->p.A_dense, c->p.lda, (const T*)c->D_dev,                   \
+#define DMMV_SWAP_LAUNCH(DV)                                                                               \
+    hipLaunchKernelGGL((k_swap_eval<T, DV>), grid, dim3(SWE_BLOCK), used, c->stream, m, n, R, nb, K,       \
+                       (int32_t)L, (const T*)c->p.A_dense, c->p.lda,                                       \
+                       (const T*)(c->kind == KIND_BATCHED ? c->Xt : nullptr), (const T*)c->D_dev,          \
                        (const T*)c->scale_dev, (const int32_t*)c->kidx, (const T*)c->r,                    \
                        (const InstState<T>*)c->state, c->o.var_mask, (const int32_t*)c->swap_rows,         \
                        (const int32_t*)skip, (Partial<T>*)c->swap_part)
-    if (dvl && rl) DMMV_SWAP_LAUNCH(true, true);
-    else if (dvl) DMMV_SWAP_LAUNCH(true, false);
-    else if (rl) DMMV_SWAP_LAUNCH(false, true);
-    else DMMV_SWAP_LAUNCH(false, false);
+    if (dvl) DMMV_SWAP_LAUNCH(true);
+    else DMMV_SWAP_LAUNCH(false);
 #undef DMMV_SWAP_LAUNCH
     hipLaunchKernelGGL(k_swap_apply<T>, dim3((unsigned)R), dim3(SW_BLOCK), 0, c->stream, m, n, R, nb, apply,
                        (const T*)c->p.A_dense, c->p.lda, (const T*)c->D_dev, (const T*)c->scale_dev, c->kidx,

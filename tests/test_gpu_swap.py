@@ -172,3 +172,38 @@ def test_swap_errors():
         with pytest.raises(m.DmmvError) as e:
             m.dmmv_swap_move(h, k_eps=-1)
         assert e.value.status == -2
+
+
+@pytest.mark.parametrize("descend", [0, 100000])
+def test_swap_full_size_llm_layer_sampled(descend):
+    """Full-size batch (4096 instances, 4096 variables, 2048 rows each): the oracle cannot
+    enumerate 8 million pairs per instance, so for sampled instances it (a) carries out the
+    reported swap and must get the reported error and the same residual, and (b) searches the
+    pairs inside a random subset of the variables that contains the reported pair, where the
+    reported pair must again be the best, with the same error."""
+    m = dmmv()
+    inst = make_config(4)
+    print("swap full size", inst.name, descend, flush=True)
+    rng = np.random.default_rng(77 + descend)
+    with m.from_instance(inst, DEV) as h:
+        m.dmmv_solve(h, T(inst.x0), descend)
+        x0, r0, t0 = (N(a) for a in m.dmmv_get_state(h))
+        res = m.dmmv_swap_move(h, apply=True)
+        gi, gj, gt = N(res.i), N(res.j), N(res.t)
+        x1, r1, t1 = (N(a) for a in m.dmmv_get_state(h))
+    assert np.array_equal(t1, gt)
+    assert np.all(gt <= t0) and np.all((gi >= 0) == (gt < t0))
+    # untouched instances and untouched variables keep their state
+    none = gi < 0
+    assert np.array_equal(x1[none], x0[none]) and np.array_equal(r1[none], r0[none])
+    assert (gi >= 0).sum() > inst.R // 2
+    for q in rng.choice(np.nonzero(gi >= 0)[0], size=6, replace=False):
+        sc = float(inst.scale[q])
+        S = np.unique(np.concatenate([rng.choice(inst.n, size=70, replace=False), [gi[q], gj[q]]]))
+        oi, oj, ot = orc.best_swap_dense(inst.A[:, S], inst.D, x0[q][S], r0[q], scale=sc)
+        assert ot == gt[q], (q, ot, gt[q])
+        assert (S[oi], S[oj]) == (gi[q], gj[q]), (q, S[oi], S[oj], gi[q], gj[q])
+        xs, rs, ts = orc.apply_swap_dense(inst.A[:, S], inst.D, x0[q][S], r0[q], oi, oj, scale=sc)
+        assert ts == gt[q] and np.array_equal(rs, r1[q])
+        xe = x0[q].copy(); xe[gi[q]], xe[gj[q]] = x0[q][gj[q]], x0[q][gi[q]]
+        assert np.array_equal(x1[q], xe)
