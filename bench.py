@@ -165,6 +165,8 @@ def run_config(idx: int, steps: int, warmup: int, iters_override, device: str, d
     if inst.kind == "csr":
         out["descent"] = descent_timing(inst, device, x0, iters)
     out["alns"] = alns_timing(inst, device, x0)
+    if inst.kind != "csr":
+        out["swap"] = swap_timing(inst, device, x0, iters)
     if do_cpu:
         out["cpu_baseline"] = cpu_baseline(inst, cpu_budget)
     return out
@@ -190,6 +192,27 @@ def descent_timing(inst, device: str, x0, iters: int) -> dict:
         res[key] = {"ms": dt * 1e3, "moves_applied": moves, "final_max_violation": float(out.max_violation.cpu()[0])}
     res["note"] = ("wall time of dmmv_solve until the local optimum; the host polls every 64 iterations, "
                    "so up to 63 iterations past the last move are enqueued")
+    return res
+
+
+def swap_timing(inst, device: str, x0, iters: int) -> dict:
+    """The swap move (Algorithm 2) at the starting point and at the local optimum of the descent:
+    wall time of one search over all pairs (x_i > x_j) of every instance, nothing carried out."""
+    import torch
+    from paper_2508_13437_amd import dmmv
+
+    res = {"pairs_per_instance": inst.n * (inst.n - 1) // 2}
+    with dmmv.from_instance(inst, device) as h:
+        for key, descend in (("at_x0", 0), ("at_local_optimum", iters)):
+            dmmv.dmmv_solve(h, x0, descend)
+            dmmv.dmmv_swap_move(h, apply=False)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            out = dmmv.dmmv_swap_move(h, apply=False)
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t0
+            res[key] = {"ms": dt * 1e3, "instances_with_improving_swap": int((out.i >= 0).sum().cpu()),
+                        "unordered_pairs_per_sec": res["pairs_per_instance"] * inst.R / dt}
     return res
 
 
@@ -342,6 +365,8 @@ def main():
         line["descent"] = head["descent"]
     if "alns" in head:
         line["alns"] = head["alns"]
+    if "swap" in head:
+        line["swap"] = head["swap"]
     if "cpu_baseline" in head:
         line["cpu_baseline"] = head["cpu_baseline"]
     others = [int(v) for v in args.others.split(",") if v.strip() and int(v) != args.config]

@@ -119,6 +119,9 @@ size_t workspace_layout(const dmmv_problem& p, const dmmv_options& o, Ctx* c, ch
         b.take(&c->res_meta, 4 * sizeof(int32_t));
         b.take(&c->res_floor, esz);
         if (o.prune) b.take(&c->prune_part, (size_t)(p.n > 0 ? p.n : 1) * part_sz);
+        b.take(&c->swap_part, (size_t)swap_csc_records(p) * part_sz);
+        b.take(&c->swap_skip, sizeof(int32_t));
+        b.take(&c->swap_gbest, sizeof(unsigned long long));
     } else if (batched) {
         c->chunk_cols = batched_chunk_cols(p);
         c->n_partials = ceil_div(p.n, c->chunk_cols);
@@ -860,8 +863,6 @@ dmmv_status dmmv_alns(dmmv_handle h, const void* x0, const dmmv_alns_params* par
         return fail(DMMV_ERR_SHAPE, "dmmv_alns: iters, ls_moves, ls_radius and destroy_count must be >= 0");
     if (params->ls_swaps < 0 || params->k_eps < 0)
         return fail(DMMV_ERR_SHAPE, "dmmv_alns: ls_swaps and k_eps must be >= 0");
-    if (params->ls_swaps > 0 && h->kind == KIND_CSC)
-        return fail(DMMV_ERR_UNSUPPORTED, "dmmv_alns: the swap move (ls_swaps > 0) is not implemented for sparse matrices");
     if (!(params->alpha >= 0.0) || !(params->lambda >= 0.0 && params->lambda <= 1.0) ||
         !(params->sigma1 >= 0.0) || !(params->sigma2 >= 0.0) || !(params->sigma3 >= 0.0))
         return fail(DMMV_ERR_DOMAIN, "dmmv_alns: need alpha >= 0, 0 <= lambda <= 1, sigma >= 0");
@@ -871,8 +872,6 @@ dmmv_status dmmv_alns(dmmv_handle h, const void* x0, const dmmv_alns_params* par
 dmmv_status dmmv_swap_move(dmmv_handle h, int32_t k_eps, int32_t apply, dmmv_swap* best, void* best_t) {
     if (!h) return fail(DMMV_ERR_NULL, "dmmv_swap_move: handle is NULL");
     if (k_eps < 0) return fail(DMMV_ERR_SHAPE, "dmmv_swap_move: k_eps < 0");
-    if (h->kind == KIND_CSC)
-        return fail(DMMV_ERR_UNSUPPORTED, "dmmv_swap_move: not implemented for sparse matrices");
     if (!h->r_valid) return fail(DMMV_ERR_STATE, "dmmv_swap_move: no residual (call dmmv_residual or dmmv_solve first)");
     return swap_move(h, k_eps, apply, false, best, best_t);
 }

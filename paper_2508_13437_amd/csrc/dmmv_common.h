@@ -144,11 +144,12 @@ struct Ctx {
     void* cmp_full_state;
     void* cmp_full_scale;
     int64_t cmp_full_R;
-    // swap move (dense and batched)
-    int32_t swap_nb;          // workgroups per instance of the evaluation
-    int32_t* swap_rows;       // [R][SWAP_KMAX] rows of largest |r|, decreasing
-    void* swap_part;          // Partial<T>[R][swap_nb]
+    // swap move
+    int32_t swap_nb;          // dense, batched: workgroups per instance of the evaluation
+    int32_t* swap_rows;       // dense, batched: [R][SWAP_KMAX] rows of largest |r|, decreasing
+    void* swap_part;          // Partial<T>[R][swap_nb]; sparse: one per evaluation workgroup
     int32_t* swap_skip;       // [R] 1: the last search of this ALNS iteration found no swap
+    unsigned long long* swap_gbest;   // sparse: order bits of the best t' found so far by any workgroup
     // batched residual on the matrix cores (options.residual_mfma)
     void* Xp;             // bf16[3][m][mfma_ldk] planes whose sum is X
     void* Qt;             // bf16[R][mfma_ldk] current codes D[k_j] per instance
@@ -202,6 +203,8 @@ dmmv_status swap_clear_skip(Ctx* c);
 // best strictly improving swap of every instance (i = -1: none), carried out if apply != 0;
 // use_skip: pass over instances marked by an earlier search and mark those without a swap
 dmmv_status swap_move(Ctx* c, int32_t k_eps, int32_t apply, bool use_skip, dmmv_swap* best, void* best_t);
+int64_t swap_csc_records(const dmmv_problem& p);
+dmmv_status swap_move_csc(Ctx* c, int32_t apply, bool use_skip, dmmv_swap* best, void* best_t);
 
 dmmv_status csc_build(Ctx* c);
 dmmv_status csc_residual(Ctx* c);

@@ -323,7 +323,7 @@ __global__ void k_swap_clear(int32_t* skip, int64_t R) {
 template <class T>
 dmmv_status swap_t(Ctx* c, int32_t k_eps, int32_t apply, bool use_skip, dmmv_swap* best, void* best_t) {
     const int64_t m = c->p.m, n = c->p.n, R = c->p.R;
-    if (n == 0 || R == 0) return DMMV_OK;
+    if (R == 0) return DMMV_OK;
     int32_t K = k_eps > 0 ? k_eps : 100;
     if (K > SWAP_KMAX) K = SWAP_KMAX;
     if ((int64_t)K > m) K = (int32_t)m;
@@ -377,8 +377,7 @@ int32_t swap_blocks_per_instance(const dmmv_problem& p) {
 }
 
 dmmv_status swap_clear_skip(Ctx* c) {
-    if (c->kind == KIND_CSC || !c->swap_skip)
-        return fail(DMMV_ERR_UNSUPPORTED, "swap move: not implemented for sparse matrices");
+    if (!c->swap_skip) return fail(DMMV_ERR_STATE, "swap move: workspace is missing");
     if (c->p.R == 0) return DMMV_OK;
     hipLaunchKernelGGL(k_swap_clear, dim3((unsigned)ceil_div(c->p.R, 256)), dim3(256), 0, c->stream, c->swap_skip,
                        c->p.R);
@@ -387,9 +386,9 @@ dmmv_status swap_clear_skip(Ctx* c) {
 }
 
 dmmv_status swap_move(Ctx* c, int32_t k_eps, int32_t apply, bool use_skip, dmmv_swap* best, void* best_t) {
-    // the buffers below exist for dense matrices and batches only
-    if (c->kind == KIND_CSC || !c->swap_skip || !c->swap_rows || !c->swap_part)
-        return fail(DMMV_ERR_UNSUPPORTED, "swap move: not implemented for sparse matrices");
+    if (c->kind == KIND_CSC) return swap_move_csc(c, apply, use_skip, best, best_t);
+    if (!c->swap_skip || !c->swap_rows || !c->swap_part)
+        return fail(DMMV_ERR_STATE, "swap move: workspace is missing");
     return c->p.dtype == DMMV_F64 ? swap_t<double>(c, k_eps, apply, use_skip, best, best_t)
                                   : swap_t<float>(c, k_eps, apply, use_skip, best, best_t);
 }

@@ -193,3 +193,8 @@ def test_alns_dense_toy_with_swaps():
 def test_alns_batched_with_swaps():
     batched_alns_check(random_batched(7910, 40, 24, 20, 4), 8, ls_moves=3, ls_swaps=2, destroy_count=3, seed=2)
     batched_alns_check(random_batched(7911, 30, 16, 70, 5, integer=True), 8, ls_moves=2, ls_swaps=2, seed=3)
+
+
+def test_alns_sparse_with_swaps():
+    alns_check(random_sparse(7920, 80, 60, 3, density=0.12), 10, ls_moves=3, ls_swaps=2, destroy_count=4, seed=8)
+    alns_check(random_sparse(7921, 50, 70, 4, density=0.1, integer=True), 8, ls_moves=2, ls_swaps=2, seed=9, prune=1)

@@ -25,7 +25,7 @@ def N(t):
     return t.detach().cpu().numpy()
 
 
-def chain_check(inst, max_swaps, k_eps=0, var_mask=None, descend=0):
+def chain_check(inst, max_swaps, k_eps=0, var_mask=None, descend=0, **hopt):
     """Swap after swap from x0 (after `descend` moves of the descent) until none improves."""
     m = dmmv()
     print("swap case", inst.name, max_swaps, k_eps, descend, flush=True)
@@ -33,7 +33,7 @@ def chain_check(inst, max_swaps, k_eps=0, var_mask=None, descend=0):
     b = inst.b.reshape(R, inst.m)
     x0 = inst.x0.reshape(R, inst.n)
     scale = inst.scale if inst.scale is not None else np.ones(R, dtype=inst.dtype)
-    opts = {}
+    opts = dict(hopt)
     if var_mask is not None:
         opts["var_mask"] = T(var_mask)
     with m.from_instance(inst, DEV, **opts) as h:
@@ -51,12 +51,20 @@ def chain_check(inst, max_swaps, k_eps=0, var_mask=None, descend=0):
             x, r, t = (N(a).reshape(R, -1) for a in m.dmmv_get_state(h))
             for q in range(R):
                 vm = None if var_mask is None else np.asarray(var_mask).reshape(R, inst.n)[q]
-                oi, oj, ot = orc.best_swap_dense(inst.A, inst.D, xs[q], rs[q], scale=float(scale[q]), var_mask=vm)
+                if inst.kind == "csr":
+                    oi, oj, ot = orc.best_swap_csr(inst.m, inst.n, inst.csr_rowptr, inst.csr_col, inst.csr_val,
+                                                   inst.D, xs[q], rs[q], var_mask=vm)
+                else:
+                    oi, oj, ot = orc.best_swap_dense(inst.A, inst.D, xs[q], rs[q], scale=float(scale[q]), var_mask=vm)
                 assert (gi[q], gj[q]) == (oi, oj), (step, q, gi[q], gj[q], oi, oj, gt[q], ot)
                 assert gt[q] == ot
                 if oi >= 0:
                     n_found += 1
-                    xs[q], rs[q], tq = orc.apply_swap_dense(inst.A, inst.D, xs[q], rs[q], oi, oj, scale=float(scale[q]))
+                    if inst.kind == "csr":
+                        xs[q], rs[q], tq = orc.apply_swap_csr(inst.m, inst.n, inst.csr_rowptr, inst.csr_col,
+                                                              inst.csr_val, inst.D, xs[q], rs[q], oi, oj)
+                    else:
+                        xs[q], rs[q], tq = orc.apply_swap_dense(inst.A, inst.D, xs[q], rs[q], oi, oj, scale=float(scale[q]))
                     assert tq == ot
                 else:
                     live[q] = False
@@ -150,19 +158,13 @@ def test_swap_all_values_equal_and_empty():
         res = m.dmmv_swap_move(h)
         assert N(res.i)[0] == -1 and N(res.t)[0] == N(m.dmmv_get_state(h)[2])[0]
     chain_check(random_dense(9001, 0, 6, 3), 1)
+    chain_check(random_dense(9002, 5, 0, 3), 1)
+    chain_check(random_sparse(9003, 6, 0, 3), 1)
+    chain_check(random_sparse(9004, 0, 5, 3), 1)
 
 
 def test_swap_errors():
     m = dmmv()
-    inst = random_sparse(9100, 30, 20, 3)
-    with m.from_instance(inst, DEV) as h:
-        m.dmmv_solve(h, T(inst.x0), 0)
-        with pytest.raises(m.DmmvError) as e:
-            m.dmmv_swap_move(h)
-        assert e.value.status == -8
-        with pytest.raises(m.DmmvError) as e:
-            m.dmmv_alns(h, T(inst.x0), 2, ls_swaps=1)
-        assert e.value.status == -8
     inst = random_dense(9101, 10, 5, 3)
     with m.from_instance(inst, DEV) as h:
         with pytest.raises(m.DmmvError) as e:
@@ -174,36 +176,43 @@ def test_swap_errors():
         assert e.value.status == -2
 
 
-@pytest.mark.parametrize("descend", [0, 100000])
-def test_swap_full_size_llm_layer_sampled(descend):
-    """Full-size batch (4096 instances, 4096 variables, 2048 rows each): the oracle cannot
-    enumerate 8 million pairs per instance, so for sampled instances it (a) carries out the
-    reported swap and must get the reported error and the same residual, and (b) searches the
-    pairs inside a random subset of the variables that contains the reported pair, where the
-    reported pair must again be the best, with the same error."""
-    m = dmmv()
-    inst = make_config(4)
-    print("swap full size", inst.name, descend, flush=True)
-    rng = np.random.default_rng(77 + descend)
-    with m.from_instance(inst, DEV) as h:
-        m.dmmv_solve(h, T(inst.x0), descend)
-        x0, r0, t0 = (N(a) for a in m.dmmv_get_state(h))
-        res = m.dmmv_swap_move(h, apply=True)
-        gi, gj, gt = N(res.i), N(res.j), N(res.t)
-        x1, r1, t1 = (N(a) for a in m.dmmv_get_state(h))
-    assert np.array_equal(t1, gt)
-    assert np.all(gt <= t0) and np.all((gi >= 0) == (gt < t0))
-    # untouched instances and untouched variables keep their state
-    none = gi < 0
-    assert np.array_equal(x1[none], x0[none]) and np.array_equal(r1[none], r0[none])
-    assert (gi >= 0).sum() > inst.R // 2
-    for q in rng.choice(np.nonzero(gi >= 0)[0], size=6, replace=False):
-        sc = float(inst.scale[q])
-        S = np.unique(np.concatenate([rng.choice(inst.n, size=70, replace=False), [gi[q], gj[q]]]))
-        oi, oj, ot = orc.best_swap_dense(inst.A[:, S], inst.D, x0[q][S], r0[q], scale=sc)
-        assert ot == gt[q], (q, ot, gt[q])
-        assert (S[oi], S[oj]) == (gi[q], gj[q]), (q, S[oi], S[oj], gi[q], gj[q])
-        xs, rs, ts = orc.apply_swap_dense(inst.A[:, S], inst.D, x0[q][S], r0[q], oi, oj, scale=sc)
-        assert ts == gt[q] and np.array_equal(rs, r1[q])
-        xe = x0[q].copy(); xe[gi[q]], xe[gj[q]] = x0[q][gj[q]], x0[q][gi[q]]
-        assert np.array_equal(x1[q], xe)
+# ---- sparse matrices --------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("shape", [(1, 1, 2, 1.0), (5, 3, 2, 0.6), (40, 30, 3, 0.2), (150, 100, 4, 0.08),
+                                   (300, 260, 3, 0.03), (90, 500, 5, 0.05)])
+def test_swap_sparse_random(shape, dtype):
+    mm, nn, nd, dens = shape
+    chain_check(random_sparse(9200 + mm, mm, nn, nd, density=dens, dtype=dtype), 3)
+
+
+def test_swap_sparse_integer_ties_and_explicit_zeros():
+    found = chain_check(random_sparse(9300, 40, 60, 3, density=0.15, integer=True), 5)
+    assert found > 0
+    chain_check(random_sparse(9301, 30, 50, 4, density=0.2, integer=True, explicit_zeros=True, dtype=np.float64), 5)
+
+
+def test_swap_sparse_several_partitions_and_empty_columns():
+    # rows cut into partitions of 16: columns span several segments, some are empty
+    chain_check(random_sparse(9400, 100, 80, 3, density=0.05), 3, sparse_partition_rows=16)
+    chain_check(random_sparse(9401, 70, 40, 4, density=0.02), 2, sparse_partition_rows=8)
+
+
+def test_swap_sparse_columns_cover_the_reservoir():
+    # few rows: every row sits in the reservoir, and dense columns store most of them, so the
+    # residual that stays is taken from deep in the reservoir, or is zero
+    chain_check(random_sparse(9500, 12, 20, 3, density=0.9), 3)
+    chain_check(random_sparse(9501, 6, 9, 4, density=1.0, dtype=np.float64), 3)
+    # more rows than the reservoir holds, columns that store almost all of them: full scan
+    chain_check(random_sparse(9502, 200, 12, 3, density=0.97), 2)
+
+
+def test_swap_sparse_after_descent_and_mask():
+    chain_check(random_sparse(9600, 120, 90, 3, density=0.1), 3, descend=300)
+    inst = random_sparse(9601, 60, 50, 4, density=0.15)
+    vm = (np.random.default_rng(3).random(50) < 0.7).astype(np.uint8)
+    chain_check(inst, 3, var_mask=vm)
+
+
+def test_swap_sparse_tomography_small():
+    chain_check(make_config(3, "small"), 1, descend=0)
+    chain_check(make_config(3, "small"), 1, descend=2000)
