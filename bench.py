@@ -165,8 +165,7 @@ def run_config(idx: int, steps: int, warmup: int, iters_override, device: str, d
     if inst.kind == "csr":
         out["descent"] = descent_timing(inst, device, x0, iters)
     out["alns"] = alns_timing(inst, device, x0)
-    if inst.kind != "csr":
-        out["swap"] = swap_timing(inst, device, x0, iters)
+    out["swap"] = swap_timing(inst, device, x0, iters)
     if do_cpu:
         out["cpu_baseline"] = cpu_baseline(inst, cpu_budget)
     return out

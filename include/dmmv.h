@@ -214,7 +214,7 @@ typedef struct {
     int32_t ls_swaps;        /* local search: after the descent, at most this many swap moves
                                 (Algorithm 2; section "Search Operators": 1-OPT, then a swap),
                                 each counted as one more move; it stops at the first search that
-                                finds no improving swap.  Dense and batched handles only        */
+                                finds no improving swap                                           */
     int32_t k_eps;           /* rows of the swap filter (Corollary 1; Appendix F uses 100);
                                 0 = 100                                                          */
 } dmmv_alns_params;
@@ -243,15 +243,18 @@ dmmv_status dmmv_alns(dmmv_handle h, const void* x0, const dmmv_alns_params* par
 /* A swap: variables i and j exchange their values (x_i > x_j before).  i = -1: none. */
 typedef struct { int64_t i, j; } dmmv_swap;
 
-/* Swap move of the local search (dense and batched handles; DMMV_ERR_UNSUPPORTED for sparse
- * matrices).  Over all pairs (i, j) with x_i > x_j (both allowed by var_mask), with
+/* Swap move of the local search, for every storage kind.  Over all pairs (i, j) with
+ * x_i > x_j (both allowed by var_mask), with
  *     Delta = s * (D[k_i] - D[k_j]),   r'_k = fma(Delta, A_kj - A_ki, r_k),   t' = max_k |r'_k|,
  * the pair with the smallest t' is found, the lowest pair number i*n + j on a tie, and reported
  * if t' < t (strict improvement, Proposition 1); otherwise best.i = best.j = -1 and best_t = t.
  * apply != 0 carries the swap out: the two variables exchange their values, r <- r', t <- t'.
  * k_eps (0 = 100, at most 128) is the number of rows of largest |r_k| on which a pair is
  * tested first (the filter of Corollary 1, a necessary condition for an improvement): it
- * changes the time taken, never the result, which is that of the full enumeration.
+ * changes the time taken, never the result, which is that of the full enumeration.  Sparse
+ * matrices ignore it: there the filter is the row of largest |r_k| itself (one of the two
+ * variables must have an entry in it) and, for the rows stored in neither column, the
+ * library's list of the rows of largest |r_k|.
  * best [R] and best_t [R] (DEVICE) may be NULL.  Needs a residual.
  * Paper: section "Search Operators", Proposition 1, Corollary 1; Appendix A (new residual);
  * Appendix B "Swap Move", Algorithm 2. */

@@ -216,3 +216,43 @@ def test_swap_sparse_after_descent_and_mask():
 def test_swap_sparse_tomography_small():
     chain_check(make_config(3, "small"), 1, descend=0)
     chain_check(make_config(3, "small"), 1, descend=2000)
+
+
+@pytest.mark.parametrize("descend", [0, 100000])
+def test_swap_full_size_tomography_sampled(descend):
+    """Full-size sparse instance (65536 variables): the oracle carries out the reported swap and
+    must get the reported error and residual, and searches the pairs inside random subsets of the
+    variables that contain the reported pair, where that pair must again be the best."""
+    import scipy.sparse as sp
+    m = dmmv()
+    inst = make_config(3)
+    print("swap full size", inst.name, descend, flush=True)
+    rng = np.random.default_rng(78 + descend)
+    with m.from_instance(inst, DEV) as h:
+        m.dmmv_solve(h, T(inst.x0), descend)
+        x0, r0, t0 = (N(a) for a in m.dmmv_get_state(h))
+        res = m.dmmv_swap_move(h, apply=True)
+        gi, gj, gt = int(N(res.i)[0]), int(N(res.j)[0]), N(res.t)[0]
+        x1, r1, t1 = (N(a) for a in m.dmmv_get_state(h))
+        # the descent goes on from the state the swap left
+        after = m.dmmv_solve(h, None, 50)
+        assert N(after.max_violation)[0] <= gt
+    assert gi >= 0 and gt < t0[0] and t1[0] == gt
+    M = sp.csr_matrix((inst.csr_val, inst.csr_col, inst.csr_rowptr), shape=(inst.m, inst.n))
+    kstar = int(np.argmax(np.abs(r0)))
+    in_row = M.indices[M.indptr[kstar]:M.indptr[kstar + 1]]
+    assert gi in in_row or gj in in_row
+    for rep in range(3):
+        S = np.unique(np.concatenate([rng.choice(inst.n, size=300, replace=False),
+                                      rng.choice(in_row, size=min(10, in_row.size), replace=False), [gi, gj]]))
+        sub = M[:, S].tocsr()
+        sub.sort_indices()
+        oi, oj, ot = orc.best_swap_csr(inst.m, S.size, sub.indptr.astype(np.int64), sub.indices.astype(np.int32),
+                                       sub.data, inst.D, x0[S], r0)
+        assert ot == gt and (S[oi], S[oj]) == (gi, gj), (rep, ot, gt, S[oi], S[oj], gi, gj)
+        if rep == 0:
+            xs, rs, ts = orc.apply_swap_csr(inst.m, S.size, sub.indptr.astype(np.int64), sub.indices.astype(np.int32),
+                                            sub.data, inst.D, x0[S], r0, oi, oj)
+            assert ts == gt and np.array_equal(rs, r1)
+    xe = x0.copy(); xe[gi], xe[gj] = x0[gj], x0[gi]
+    assert np.array_equal(x1, xe)
