@@ -217,6 +217,14 @@ typedef struct {
                                 finds no improving swap                                           */
     int32_t k_eps;           /* rows of the swap filter (Corollary 1; Appendix F uses 100);
                                 0 = 100                                                          */
+    int32_t l2_guard;        /* 1 = an iteration is accepted only if the l2 norm of the residual
+                                does not increase either (the check the paper applies at every
+                                AMVM iteration of the quantisation use case, section "Experiment
+                                setup and results").  The squared norm is summed in double
+                                precision in a fixed order: rows in blocks of 256, inside a block
+                                acc = fma(r_i, r_i, acc) by ascending row, then the block sums by
+                                ascending block                                                  */
+    int32_t reserved;        /* must be 0                                                        */
 } dmmv_alns_params;
 
 /* Algorithm 1 of the paper around the single-move descent, for every storage kind.

@@ -307,14 +307,15 @@ class AlnsParams(C.Structure):
     _fields_ = [("iters", C.c_int32), ("ls_moves", C.c_int32), ("ls_radius", C.c_int32),
                 ("destroy_count", C.c_int32), ("alpha", C.c_double), ("lambda_", C.c_double),
                 ("sigma1", C.c_double), ("sigma2", C.c_double), ("sigma3", C.c_double),
-                ("seed", C.c_uint64), ("ls_swaps", C.c_int32), ("k_eps", C.c_int32)]
+                ("seed", C.c_uint64), ("ls_swaps", C.c_int32), ("k_eps", C.c_int32),
+                ("l2_guard", C.c_int32), ("reserved", C.c_int32)]
 
 
 def alns_params(iters, ls_moves=8, ls_radius=1, destroy_count=0, alpha=0.3, lambda_=0.2,
-                sigma1=3.0, sigma2=2.0, sigma3=1.0, seed=1, ls_swaps=0, k_eps=0) -> AlnsParams:
+                sigma1=3.0, sigma2=2.0, sigma3=1.0, seed=1, ls_swaps=0, k_eps=0, l2_guard=0) -> AlnsParams:
     return AlnsParams(int(iters), int(ls_moves), int(ls_radius), int(destroy_count), float(alpha),
                       float(lambda_), float(sigma1), float(sigma2), float(sigma3), int(seed),
-                      int(ls_swaps), int(k_eps))
+                      int(ls_swaps), int(k_eps), int(l2_guard), 0)
 
 
 @dataclass
@@ -328,6 +329,7 @@ class AlnsResult:
     t: np.ndarray            # [iters] error after the local search
     best: np.ndarray         # [iters] best error so far
     weights: np.ndarray      # [4] final operator weights
+    q2: Optional[np.ndarray] = None   # [iters] squared l2 norm of the residual after the local search
 
 
 def alns_mix(z: int) -> int:
@@ -419,14 +421,23 @@ def alns_csr(m, n, rowptr, col, val, b, D, x0, params: AlnsParams, inst=0, scale
     tr = [np.zeros(it, dtype=np.int32) for _ in range(4)]
     tr_t, tr_best = np.zeros(it, dtype=dt), np.zeros(it, dtype=dt)
     w = np.zeros(4, dtype=np.float64)
+    tr_q2 = np.zeros(it, dtype=np.float64)
     f = _fn("oracle_alns", dt)
     f.restype = _real(dt)
     t_best = f(C.c_int64(m), C.c_int64(n), C.c_int32(D.size), _p(rowptr), _p(col), _p(val), _p(b), _p(D),
                _real(dt)(scale), _p(k), C.byref(params), C.c_uint64(inst), _p(tr[0]), _p(tr[1]), _p(tr[2]),
-               _p(tr[3]), _p(tr_t), _p(tr_best), _p(w))
+               _p(tr[3]), _p(tr_t), _p(tr_best), _p(w), _p(tr_q2))
     q = int(params.iters)
     return AlnsResult(D[k], float(t_best), tr[0][:q], tr[1][:q], tr[2][:q], tr[3][:q], tr_t[:q],
-                      tr_best[:q], w)
+                      tr_best[:q], w, tr_q2[:q])
+
+
+def sumsq(r) -> float:
+    """Squared l2 norm in double precision, in the fixed order of the ALNS guard."""
+    r = np.ascontiguousarray(r)
+    f = _fn("oracle_sumsq", r.dtype)
+    f.restype = C.c_double
+    return float(f(C.c_int64(r.size), _p(r)))
 
 
 def alns_dense(A, b, D, x0, params: AlnsParams, inst=0, scale=1.0) -> AlnsResult:

@@ -22,10 +22,54 @@ namespace dmmv {
 // q*n.. of weight / prefix / first, q*count.. of picked; x and r are instance-contiguous
 // (kidx[j*R + q], r[i*R + q]) as everywhere in the batched path.
 // ----------------------------------------------------------------------------------------
+// Squared l2 norm of the residual of every instance, in double precision and in a fixed order:
+// rows in blocks of 256, inside a block acc = fma(r_i, r_i, acc) by ascending row, then the
+// block sums by ascending block.  Batch: one lane per instance walks all rows (coalesced over
+// the instances).
 template <class T>
-__global__ void k_alns_init(AlnsState* S, const InstState<T>* st, int64_t R) {
+__global__ void k_alns_sumsq_batched(int64_t m, int64_t R, const T* __restrict__ r, double* __restrict__ q2) {
     const int64_t q = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
     if (q >= R) return;
+    double total = 0.0;
+    for (int64_t i0 = 0; i0 < m; i0 += 256) {
+        double acc = 0.0;
+        const int64_t i1 = i0 + 256 < m ? i0 + 256 : m;
+        for (int64_t i = i0; i < i1; ++i) {
+            const double v = (double)r[i * R + q];
+            acc = __builtin_fma(v, v, acc);
+        }
+        total += acc;
+    }
+    q2[q] = total;
+}
+
+// Single instance: one thread per block of 256 rows, then one thread adds the block sums.
+template <class T>
+__global__ __launch_bounds__(1024) void k_alns_sumsq_single(int64_t m, const T* __restrict__ r,
+                                                            double* __restrict__ blocks, double* __restrict__ q2) {
+    const int64_t nblk = (m + 255) / 256;
+    for (int64_t bk = threadIdx.x; bk < nblk; bk += blockDim.x) {
+        double acc = 0.0;
+        const int64_t i0 = bk * 256, i1 = i0 + 256 < m ? i0 + 256 : m;
+        for (int64_t i = i0; i < i1; ++i) {
+            const double v = (double)r[i];
+            acc = __builtin_fma(v, v, acc);
+        }
+        blocks[bk] = acc;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double total = 0.0;
+        for (int64_t bk = 0; bk < nblk; ++bk) total += blocks[bk];
+        q2[0] = total;
+    }
+}
+
+template <class T>
+__global__ void k_alns_init(AlnsState* S, const InstState<T>* st, int64_t R, const double* q2) {
+    const int64_t q = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    if (q >= R) return;
+    S[q].q2_cur = q2 ? q2[q] : 0.0;
     for (int u = 0; u < 4; ++u) S[q].w[u] = 1.0;
     S[q].t_cur = (double)st[q].t;
     S[q].t_best = (double)st[q].t;
@@ -130,14 +174,17 @@ __global__ __launch_bounds__(1024) void k_alns_sample(int64_t n, int32_t count,
 // acceptance, best solution, weights, trace (one thread per instance)
 template <class T>
 __global__ void k_alns_end(AlnsState* S, InstState<T>* st, int64_t R, int32_t iters, double lambda,
-                           double sigma1, double sigma2, double sigma3, int32_t* trace, T* trace_t) {
+                           double sigma1, double sigma2, double sigma3, const double* q2, int32_t* trace,
+                           T* trace_t) {
     const int64_t q = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
     if (q >= R) return;
     const double t = (double)st[q].t;
     const int32_t it = S[q].it;
-    const int accepted = t <= S[q].t_cur;
+    // q2 != NULL: the l2 norm of the residual must not increase either
+    const int accepted = t <= S[q].t_cur && (!q2 || q2[q] <= S[q].q2_cur);
     int new_best = 0;
     if (accepted) {
+        if (q2) S[q].q2_cur = q2[q];
         double psi = sigma3;
         if (t < S[q].t_cur) psi = sigma2;
         if (t < S[q].t_best) { psi = sigma1; S[q].t_best = t; new_best = 1; }
@@ -314,10 +361,25 @@ static unsigned blocks_for(int64_t items, int per_block) {
 }
 
 template <class T>
-static dmmv_status start_t(Ctx* c) {
+static dmmv_status sumsq_t(Ctx* c) {
     const int64_t R = c->p.R;
+    if (c->kind == KIND_BATCHED)
+        hipLaunchKernelGGL(k_alns_sumsq_batched<T>, dim3(blocks_for(R, 64)), dim3(64), 0, c->stream, c->p.m, R,
+                           (const T*)c->r, c->alns_q2);
+    else
+        hipLaunchKernelGGL(k_alns_sumsq_single<T>, dim3(1), dim3(1024), 0, c->stream, c->p.m, (const T*)c->r,
+                           c->alns_q2_blocks, c->alns_q2);
+    DMMV_LAUNCH_CHECK();
+    return DMMV_OK;
+}
+
+template <class T>
+static dmmv_status start_t(Ctx* c, bool l2_guard) {
+    const int64_t R = c->p.R;
+    if (l2_guard) DMMV_TRY(sumsq_t<T>(c));
     hipLaunchKernelGGL(k_alns_init<T>, dim3(blocks_for(R, 256)), dim3(256), 0, c->stream,
-                       (AlnsState*)c->alns_state, (const InstState<T>*)c->state, R);
+                       (AlnsState*)c->alns_state, (const InstState<T>*)c->state, R,
+                       l2_guard ? (const double*)c->alns_q2 : nullptr);
     hipLaunchKernelGGL(k_alns_snapshot<T>, dim3(1024), dim3(256), 0, c->stream, c->p.m, c->p.n, R,
                        (const int32_t*)c->kidx, c->alns_kidx_cur, c->alns_kidx_best, (const T*)c->r,
                        (T*)c->alns_r_cur, (unsigned long long*)c->alns_first);
@@ -365,9 +427,10 @@ template <class T>
 static dmmv_status finish_iteration_t(Ctx* c, const dmmv_alns_params& prm, int32_t* trace, void* trace_t) {
     AlnsState* S = (AlnsState*)c->alns_state;
     const int64_t R = c->p.R;
+    if (prm.l2_guard) DMMV_TRY(sumsq_t<T>(c));
     hipLaunchKernelGGL(k_alns_end<T>, dim3(blocks_for(R, 256)), dim3(256), 0, c->stream, S,
                        (InstState<T>*)c->state, R, prm.iters, prm.lambda, prm.sigma1, prm.sigma2, prm.sigma3,
-                       trace, (T*)trace_t);
+                       prm.l2_guard ? (const double*)c->alns_q2 : nullptr, trace, (T*)trace_t);
     hipLaunchKernelGGL(k_alns_copy<T>, dim3(1024), dim3(256), 0, c->stream, c->p.m, c->p.n, R,
                        (const AlnsState*)S, c->kidx, c->alns_kidx_cur, c->alns_kidx_best, (T*)c->r,
                        (T*)c->alns_r_cur);
@@ -384,7 +447,10 @@ static dmmv_status export_t(Ctx* c, void* t_best_out) {
     return DMMV_OK;
 }
 
-dmmv_status alns_start(Ctx* c) { return c->p.dtype == DMMV_F64 ? start_t<double>(c) : start_t<float>(c); }
+dmmv_status alns_start(Ctx* c, bool l2_guard) {
+    return c->p.dtype == DMMV_F64 ? start_t<double>(c, l2_guard) : start_t<float>(c, l2_guard);
+}
+dmmv_status alns_sumsq(Ctx* c) { return c->p.dtype == DMMV_F64 ? sumsq_t<double>(c) : sumsq_t<float>(c); }
 dmmv_status alns_destroy_repair(Ctx* c, const dmmv_alns_params& prm, int32_t it, int32_t count) {
     return c->p.dtype == DMMV_F64 ? destroy_repair_t<double>(c, prm, it, count)
                                   : destroy_repair_t<float>(c, prm, it, count);

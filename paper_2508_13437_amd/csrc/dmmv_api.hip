@@ -83,6 +83,8 @@ size_t workspace_layout(const dmmv_problem& p, const dmmv_options& o, Ctx* c, ch
         b.take(&c->alns_first, nR * sizeof(uint64_t));
         b.take(&c->alns_picked, nR * sizeof(int32_t));
         if (sparse) b.take(&c->alns_touched, (size_t)p.m);
+        b.take(&c->alns_q2, (size_t)p.R * sizeof(double));
+        b.take(&c->alns_q2_blocks, (size_t)(ceil_div(p.m, 256) + 1) * sizeof(double));
     }
     if (!sparse) {
         c->swap_nb = swap_blocks_per_instance(p);
@@ -577,7 +579,7 @@ static dmmv_status alns_run(dmmv_ctx* c, const void* x0, const dmmv_alns_params&
     if (!c->x_set) return fail(DMMV_ERR_STATE, "dmmv_alns: no starting point (x0 is NULL and dmmv_set_x was never called)");
     DMMV_TRY(residual_any(c));
     if (c->p.n == 0) {
-        DMMV_TRY(alns_start(c));
+        DMMV_TRY(alns_start(c, false));
         DMMV_TRY(alns_export(c, t_best_out));
         DMMV_HIP_CHECK(hipStreamSynchronize(c->stream));
         return DMMV_OK;
@@ -590,7 +592,7 @@ static dmmv_status alns_run(dmmv_ctx* c, const void* x0, const dmmv_alns_params&
     c->o.radius = prm.ls_radius;
     c->o.keep_going = 0;
     dmmv_status st = [&]() -> dmmv_status {
-        DMMV_TRY(alns_start(c));
+        DMMV_TRY(alns_start(c, prm.l2_guard != 0));
         for (int32_t it = 0; it < prm.iters; ++it) {
             DMMV_TRY(alns_destroy_repair(c, prm, it, (int32_t)count));
             for (int32_t mv = 0; mv < prm.ls_moves; ++mv) {
@@ -863,6 +865,8 @@ dmmv_status dmmv_alns(dmmv_handle h, const void* x0, const dmmv_alns_params* par
         return fail(DMMV_ERR_SHAPE, "dmmv_alns: iters, ls_moves, ls_radius and destroy_count must be >= 0");
     if (params->ls_swaps < 0 || params->k_eps < 0)
         return fail(DMMV_ERR_SHAPE, "dmmv_alns: ls_swaps and k_eps must be >= 0");
+    if ((params->l2_guard != 0 && params->l2_guard != 1) || params->reserved != 0)
+        return fail(DMMV_ERR_DOMAIN, "dmmv_alns: l2_guard must be 0 or 1 and reserved 0");
     if (!(params->alpha >= 0.0) || !(params->lambda >= 0.0 && params->lambda <= 1.0) ||
         !(params->sigma1 >= 0.0) || !(params->sigma2 >= 0.0) || !(params->sigma3 >= 0.0))
         return fail(DMMV_ERR_DOMAIN, "dmmv_alns: need alpha >= 0, 0 <= lambda <= 1, sigma >= 0");

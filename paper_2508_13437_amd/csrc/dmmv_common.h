@@ -61,6 +61,7 @@ struct alignas(16) AlnsState {
     double w[4];        // operator weights: random destroy, worst-remove, random repair, greedy repair
     double t_cur;       // error of the current (last accepted) solution
     double t_best;      // error of the best solution so far
+    double q2_cur;      // squared l2 norm of the residual of the current solution (l2 guard)
     int32_t it;         // outer iteration in progress
     int32_t d_op, r_op; // operators chosen for it
     int32_t accepted;   // verdict of the iteration just finished
@@ -132,6 +133,8 @@ struct Ctx {
     uint64_t* alns_first;     // [n] stamp of the first draw of a variable in an iteration
     int32_t* alns_picked;     // [n] variables drawn, in the order of the draws
     uint8_t* alns_touched;    // [m] sparse repair: rows of the column being reassigned
+    double* alns_q2;          // [R] squared l2 norm of the working residual (l2 guard)
+    double* alns_q2_blocks;   // [ceil(m / 256)] single instance: block sums of the above
     // batched descent: virtual batch of the instances still running
     bool cmp_on;              // the loop's arrays currently point at the virtual batch
     void* cmp_r;              // T[m][R'] / int32[n][R'] / InstState[R'] / T[R'] / int32[R'] (orig)
@@ -181,7 +184,8 @@ constexpr int CSC_MAX_PARTITIONS = 1024;
 // ----------------------------------------------------------------------------------------
 // per-path entry points (all enqueue on c->stream)
 // ----------------------------------------------------------------------------------------
-dmmv_status alns_start(Ctx* c);
+dmmv_status alns_start(Ctx* c, bool l2_guard);
+dmmv_status alns_sumsq(Ctx* c);          // alns_q2 <- squared l2 norm of r, per instance
 dmmv_status alns_destroy_repair(Ctx* c, const dmmv_alns_params& prm, int32_t it, int32_t count);
 dmmv_status alns_finish_iteration(Ctx* c, const dmmv_alns_params& prm, int32_t* trace, void* trace_t);
 dmmv_status alns_export(Ctx* c, void* t_best_out);

@@ -54,7 +54,8 @@ class AlnsParams(C.Structure):
     _fields_ = [("iters", C.c_int32), ("ls_moves", C.c_int32), ("ls_radius", C.c_int32),
                 ("destroy_count", C.c_int32), ("alpha", C.c_double), ("lambda_", C.c_double),
                 ("sigma1", C.c_double), ("sigma2", C.c_double), ("sigma3", C.c_double),
-                ("seed", C.c_uint64), ("ls_swaps", C.c_int32), ("k_eps", C.c_int32)]
+                ("seed", C.c_uint64), ("ls_swaps", C.c_int32), ("k_eps", C.c_int32),
+                ("l2_guard", C.c_int32), ("reserved", C.c_int32)]
 
 
 _lib = None
@@ -334,11 +335,11 @@ class AlnsResult:
 def dmmv_alns(h: Handle, x0: Optional[torch.Tensor], iters: int, ls_moves: int = 8, ls_radius: int = 1,
               destroy_count: int = 0, alpha: float = 0.3, lambda_: float = 0.2, sigma1: float = 3.0,
               sigma2: float = 2.0, sigma3: float = 1.0, seed: int = 1, ls_swaps: int = 0,
-              k_eps: int = 0) -> AlnsResult:
+              k_eps: int = 0, l2_guard: bool = False) -> AlnsResult:
     """The ALNS outer loop around the descent (and, with ls_swaps, the swap move)."""
     prm = AlnsParams(int(iters), int(ls_moves), int(ls_radius), int(destroy_count), float(alpha),
                      float(lambda_), float(sigma1), float(sigma2), float(sigma3), int(seed),
-                     int(ls_swaps), int(k_eps))
+                     int(ls_swaps), int(k_eps), 1 if l2_guard else 0, 0)
     if x0 is not None:
         x0 = x0.to(h.device, h.dtype).contiguous()
     x_best = h._new(h._xshape())

@@ -123,10 +123,10 @@ def test_bench_refuses_more_than_one_gpu():
 
 
 def test_alns_parameter_blocks_of_binding_and_oracle_have_the_layout_of_the_header(mod):
-    # include/dmmv.h: four int32, five doubles, one uint64, two int32 -> 4*4 + 5*8 + 8 + 2*4 bytes, no padding
+    # include/dmmv.h: four int32, five doubles, one uint64, four int32 -> 4*4 + 5*8 + 8 + 4*4 bytes, no padding
     import ctypes as C
     from oracle import oracle as orc
-    assert C.sizeof(mod.AlnsParams) == 72 == C.sizeof(orc.AlnsParams)
+    assert C.sizeof(mod.AlnsParams) == 80 == C.sizeof(orc.AlnsParams)
     assert [f[0].rstrip("_") for f in mod.AlnsParams._fields_] == [f[0].rstrip("_") for f in orc.AlnsParams._fields_]
     hdr = open(os.path.join(ROOT, "include", "dmmv.h")).read()
     body = hdr[hdr.index("typedef struct {\n    int32_t iters;"):hdr.index("} dmmv_alns_params;")]
@@ -134,4 +134,4 @@ def test_alns_parameter_blocks_of_binding_and_oracle_have_the_layout_of_the_head
     names = []
     for decl in re.findall(r"^\s+(?:int32_t|double|uint64_t)\s+([a-z0-9_, ]+);", body, flags=re.M):
         names += [v.strip() for v in decl.split(",")]
-    assert names == ["iters", "ls_moves", "ls_radius", "destroy_count", "alpha", "lambda", "sigma1", "sigma2", "sigma3", "seed", "ls_swaps", "k_eps"]
+    assert names == ["iters", "ls_moves", "ls_radius", "destroy_count", "alpha", "lambda", "sigma1", "sigma2", "sigma3", "seed", "ls_swaps", "k_eps", "l2_guard", "reserved"]

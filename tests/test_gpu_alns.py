@@ -198,3 +198,24 @@ def test_alns_batched_with_swaps():
 def test_alns_sparse_with_swaps():
     alns_check(random_sparse(7920, 80, 60, 3, density=0.12), 10, ls_moves=3, ls_swaps=2, destroy_count=4, seed=8)
     alns_check(random_sparse(7921, 50, 70, 4, density=0.1, integer=True), 8, ls_moves=2, ls_swaps=2, seed=9, prune=1)
+
+
+# ---- l2 guard of the acceptance step ----------------------------------------------------------
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_alns_l2_guard_dense(dtype):
+    alns_check(random_dense(7930, 300, 30, 5, dtype=dtype), 30, ls_moves=2, destroy_count=4, seed=5, l2_guard=1)
+    alns_check(random_dense(7931, 700, 20, 4, dtype=dtype), 20, ls_moves=1, ls_swaps=1, seed=6, l2_guard=1)
+
+
+def test_alns_l2_guard_changes_the_run():
+    # the guard must actually reject something here, else the cases above show nothing
+    inst = random_dense(7930, 300, 30, 5)
+    a = orc.alns_dense(inst.A, inst.b, inst.D, inst.x0, orc.alns_params(30, ls_moves=2, destroy_count=4, seed=5))
+    b = orc.alns_dense(inst.A, inst.b, inst.D, inst.x0, orc.alns_params(30, ls_moves=2, destroy_count=4, seed=5, l2_guard=1))
+    assert not np.array_equal(a.accepted, b.accepted)
+
+
+def test_alns_l2_guard_sparse_and_batched():
+    alns_check(random_sparse(7932, 600, 80, 3, density=0.1), 15, ls_moves=2, destroy_count=5, seed=7, l2_guard=1)
+    batched_alns_check(random_batched(7933, 300, 24, 70, 4), 10, ls_moves=2, destroy_count=3, seed=2, l2_guard=1)
+    batched_alns_check(random_batched(7934, 40, 16, 9, 5, dtype=np.float64), 10, ls_moves=2, seed=3, l2_guard=1)

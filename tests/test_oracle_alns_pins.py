@@ -224,3 +224,39 @@ def test_alns_dense_entry_equals_full_storage_sparse_entry():
     # the first local search of a run that destroys nothing would be the plain descent:
     # with the repaired variable moved, the descent still reaches a local optimum of the same kind
     assert a.t_best <= np.abs(inst.A.astype(np.float64) @ inst.x0 - inst.b).max() * (1 + 1e-6)
+
+
+# ---- l2 guard of the acceptance step -----------------------------------------------------------
+def test_sumsq_against_numpy_and_exact_on_integers():
+    rng = np.random.default_rng(21)
+    for m in (0, 1, 255, 256, 257, 1000, 5000):
+        r = rng.normal(size=m)
+        assert np.isclose(orc.sumsq(r), float(np.dot(r, r)), rtol=1e-13, atol=0)
+        ri = rng.integers(-1000, 1000, size=m).astype(np.float32)
+        assert orc.sumsq(ri) == float(np.sum(ri.astype(np.int64) ** 2))      # every partial sum is exact
+    # fp32 residuals are squared in double precision: no fp32 rounding of the squares
+    r32 = np.array([1.0 + 2.0 ** -20, 3.0], dtype=np.float32)
+    assert orc.sumsq(r32) == (1.0 + 2.0 ** -20) ** 2 + 9.0
+
+
+def test_l2_guard_keeps_both_norms_from_increasing():
+    rng = np.random.default_rng(22)
+    A = rng.normal(size=(40, 18)); D = np.arange(-3.0, 4.0)
+    b = A @ rng.choice(D, 18) + rng.uniform(-0.4, 0.4, 40)
+    x0 = rng.choice(D, 18)
+    free = orc.alns_dense(A, b, D, x0, orc.alns_params(40, ls_moves=2, seed=5))
+    guard = orc.alns_dense(A, b, D, x0, orc.alns_params(40, ls_moves=2, seed=5, l2_guard=1))
+    r0 = A @ x0 - b
+    for res, guarded in ((free, False), (guard, True)):
+        q_cur, t_cur = float(r0 @ r0), np.abs(r0).max()
+        for it in range(40):
+            ok = res.t[it] <= t_cur and (not guarded or res.q2[it] <= q_cur)
+            assert bool(res.accepted[it]) == ok, (guarded, it)
+            if ok:
+                if guarded:
+                    assert res.q2[it] <= q_cur
+                q_cur, t_cur = res.q2[it], res.t[it]
+    # the guard rejected something the plain rule accepts (else the test shows nothing)
+    assert guard.accepted.sum() < free.accepted.sum() or not np.array_equal(guard.t, free.t)
+    # the best solution's residual has the recorded error
+    assert np.isclose(np.abs(A @ guard.x - b).max(), guard.t_best)
