@@ -36,52 +36,37 @@ __device__ __forceinline__ unsigned long long order_bits(double v) { return (uns
 __device__ __forceinline__ void from_order_bits(unsigned long long b, float& v) { v = __uint_as_float((uint32_t)b); }
 __device__ __forceinline__ void from_order_bits(unsigned long long b, double& v) { v = __longlong_as_double((long long)b); }
 
-// ---- the K rows of largest |r| of every instance, in decreasing order (row ascending on a
-// tie).  One workgroup per instance; K selection steps, each a maximum over the rows that
-// come after the previous pick in that order.
-template <class T, bool RL>
+// ---- K rows of large |r| per instance for the filter, in decreasing order.  Which rows the
+// filter tries first changes the time a search takes, never its result, so an exact top-K
+// selection is not needed: every thread takes the largest |r| among its rows i = thread,
+// thread + 256, ... and the 256 maxima are ranked (larger first, lower row first among equal
+// values).  The row of largest |r| always comes first; of the next largest most are there.
+// One workgroup per instance.
+template <class T>
 __global__ __launch_bounds__(SW_BLOCK) void k_swap_top(int64_t m, int64_t R, int32_t K,
                                                         const T* __restrict__ r,
                                                         const int32_t* __restrict__ skip,
                                                         int32_t* __restrict__ rows_all) {
-    extern __shared__ __align__(16) unsigned char sw_smem[];
-    T* sh_abs = reinterpret_cast<T*>(sw_smem);                     // [m] when RL
-    __shared__ T sh_a[SW_WAVES];
-    __shared__ int64_t sh_r[SW_WAVES];
+    __shared__ T sh_a[SW_BLOCK];
+    __shared__ int32_t sh_row[SW_BLOCK];
     const int64_t q = blockIdx.x;
     if (skip && skip[q]) return;
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    if (RL) {
-        for (int64_t i = threadIdx.x; i < m; i += SW_BLOCK) sh_abs[i] = dmmv_abs(r[i * R + q]);
-        __syncthreads();
+    T a = (T)-1;                                           // no row: ranks after every real one
+    int32_t row = INT32_MAX;
+    for (int64_t i = threadIdx.x; i < m; i += SW_BLOCK) {
+        const T v = dmmv_abs(r[i * R + q]);
+        if (v > a) { a = v; row = (int32_t)i; }
     }
-    T pa = Limits<T>::inf();
-    int64_t prow = -1;
-    for (int32_t step = 0; step < K; ++step) {
-        T a = (T)-1;
-        int64_t row = INT64_MAX;
-        for (int64_t i = threadIdx.x; i < m; i += SW_BLOCK) {
-            const T v = RL ? sh_abs[i] : dmmv_abs(r[i * R + q]);
-            const bool after = v < pa || (v == pa && i > prow);
-            if (after && v > a) { a = v; row = i; }
-        }
-        const T wa = wave_max(a);
-        if (lane == 0) sh_a[w] = wa;
-        __syncthreads();
-        T amax = sh_a[0];
-#pragma unroll
-        for (int u = 1; u < SW_WAVES; ++u) amax = dmmv_max(amax, sh_a[u]);
-        const int64_t wr = wave_min(a == amax ? row : (int64_t)INT64_MAX);
-        if (lane == 0) sh_r[w] = wr;
-        __syncthreads();
-        int64_t rmin = sh_r[0];
-#pragma unroll
-        for (int u = 1; u < SW_WAVES; ++u) rmin = sh_r[u] < rmin ? sh_r[u] : rmin;
-        if (threadIdx.x == 0) rows_all[q * K + step] = (int32_t)rmin;
-        pa = amax;
-        prow = rmin;
-        __syncthreads();                                   // sh_a / sh_r are rewritten next step
+    sh_a[threadIdx.x] = a;
+    sh_row[threadIdx.x] = row;
+    __syncthreads();
+    int32_t rank = 0;
+    for (int x = 0; x < SW_BLOCK; ++x) {
+        const T oa = sh_a[x];
+        const int32_t orow = sh_row[x];
+        rank += (oa > a || (oa == a && orow < row)) ? 1 : 0;
     }
+    if (row != INT32_MAX && rank < K) rows_all[q * K + rank] = row;
 }
 
 // ---- evaluation: grid (R, nb).  Writes one record (t', c) per workgroup; c = -1 if the
@@ -337,16 +322,9 @@ dmmv_status swap_t(Ctx* c, int32_t k_eps, int32_t apply, bool use_skip, dmmv_swa
     if (L > K) L = K;
     used += (size_t)L * n * sizeof(T);
 
-    if (K > 0) {
-        const bool top_rl = (size_t)m * sizeof(T) <= SW_LDS_BUDGET;
-        const size_t top_lds = top_rl ? (size_t)m * sizeof(T) : 0;
-        if (top_rl)
-            hipLaunchKernelGGL((k_swap_top<T, true>), dim3((unsigned)R), dim3(SW_BLOCK), top_lds, c->stream, m, R, K,
-                               (const T*)c->r, (const int32_t*)skip, c->swap_rows);
-        else
-            hipLaunchKernelGGL((k_swap_top<T, false>), dim3((unsigned)R), dim3(SW_BLOCK), 0, c->stream, m, R, K,
-                               (const T*)c->r, (const int32_t*)skip, c->swap_rows);
-    }
+    if (K > 0)
+        hipLaunchKernelGGL(k_swap_top<T>, dim3((unsigned)R), dim3(SW_BLOCK), 0, c->stream, m, R, K, (const T*)c->r,
+                           (const int32_t*)skip, c->swap_rows);
     const dim3 grid((unsigned)R, (unsigned)nb);
 #define DMMV_SWAP_LAUNCH(DV)                                                                               \
     hipLaunchKernelGGL((k_swap_eval<T, DV>), grid, dim3(SWE_BLOCK), used, c->stream, m, n, R, nb, K,       \
