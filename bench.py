@@ -162,6 +162,13 @@ def run_config(idx: int, steps: int, warmup: int, iters_override, device: str, d
     })
     if inst.kind == "batched":
         out["residual"] = residual_timing(inst, device, x0)
+        if inst.dtype == np.float32 and inst.nd <= 32:
+            # the same evaluation with the multiply-adds on the matrix cores (options.batched_eval = 2)
+            with dmmv.from_instance(inst, device, batched_eval=2) as h:
+                dmmv.dmmv_set_x(h, x0)
+                dmmv.dmmv_residual(h)
+                out["eval_matrix_core_ms"] = dmmv.dmmv_time_eval(h, 3) / 3
+                out["eval_vector_unit_ms"] = eval_ms
     if inst.kind == "csr":
         out["descent"] = descent_timing(inst, device, x0, iters)
     out["alns"] = alns_timing(inst, device, x0)
@@ -360,6 +367,9 @@ def main():
     }
     if "residual" in head:
         line["residual"] = head["residual"]
+    for key in ("eval_matrix_core_ms", "eval_vector_unit_ms"):
+        if key in head:
+            line[key] = head[key]
     if "descent" in head:
         line["descent"] = head["descent"]
     if "alns" in head:

@@ -121,6 +121,14 @@ typedef struct {
     int32_t alns;            /* batched problems: 1 = reserve the workspace dmmv_alns needs (current
                                 and best solution, sampling weights and draws per instance, about
                                 R*(36 n + m w) bytes).  Single-instance handles always have it    */
+    int32_t batched_eval;    /* batched problems: which kernel scores the moves.  0 or 1 = the
+                                vector-unit kernel (default); 2 = the matrix-core kernel, for fp32
+                                with nd <= 32 (dmmv_create fails with DMMV_ERR_UNSUPPORTED
+                                otherwise; it needs R * m more floats of workspace).  It forms every
+                                fused multiply-add as one element of an outer product with K = 1,
+                                rounded once like the vector instruction, so both kernels give the
+                                same bits; on MI355X it is the slower of the two (the maximum over
+                                the rows stays on the vector unit and does not overlap)           */
 } dmmv_options;
 
 /* Bytes of device workspace dmmv_create needs for this problem (0 on invalid input, with

@@ -135,6 +135,8 @@ size_t workspace_layout(const dmmv_problem& p, const dmmv_options& o, Ctx* c, ch
         b.take(&c->cmp_state, (size_t)p.R * state_sz);
         b.take(&c->cmp_scale, (size_t)p.R * esz);
         b.take(&c->cmp_orig, (size_t)p.R * sizeof(int32_t));
+        c->eval_mfma = o.batched_eval == 2 && batched_eval_mfma_applicable(p);
+        if (c->eval_mfma) b.take(&c->rT, (size_t)batched_eval_mfma_rt_elems(p) * sizeof(float));
         if (o.residual_mfma) {
             c->mfma_ldk = mfma_ldk(p.n);
             b.take(&c->Xp, (size_t)3 * p.m * c->mfma_ldk * sizeof(uint16_t));
@@ -654,6 +656,13 @@ dmmv_status dmmv_create(dmmv_handle* out, const dmmv_problem* problem, const dmm
     if (options) o = *options;
     if (o.radius < 0 || o.poll_every < 0 || o.sparse_partition_rows < 0)
         return fail(DMMV_ERR_SHAPE, "options: radius, poll_every and sparse_partition_rows must be >= 0");
+    if (o.batched_eval < 0 || o.batched_eval > 2)
+        return fail(DMMV_ERR_SHAPE, "options.batched_eval must be 0, 1 or 2");
+    if (o.batched_eval == 2) {
+        const bool is_batched = !problem->csr_rowptr && (problem->R > 1 || problem->scale);
+        if (!is_batched || !batched_eval_mfma_applicable(*problem))
+            return fail(DMMV_ERR_UNSUPPORTED, "options.batched_eval = 2 needs an fp32 batched problem with nd <= 32");
+    }
     if (o.residual_mfma) {
         // the matrix-core residual needs fp32, the batched layout and codes that bf16 holds exactly
         const bool is_batched = !problem->csr_rowptr && (problem->R > 1 || problem->scale);

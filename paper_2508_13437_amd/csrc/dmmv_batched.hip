@@ -507,10 +507,16 @@ dmmv_status batched_compact_end(Ctx* c) {
     return st;
 }
 
-dmmv_status batched_build(Ctx* c) { return c->p.dtype == DMMV_F64 ? build_t<double>(c) : build_t<float>(c); }
+dmmv_status batched_build(Ctx* c) {
+    if (c->eval_mfma) DMMV_TRY(batched_eval_mfma_build(c));
+    return c->p.dtype == DMMV_F64 ? build_t<double>(c) : build_t<float>(c);
+}
 dmmv_status batched_residual(Ctx* c) { return c->p.dtype == DMMV_F64 ? residual_t<double>(c) : residual_t<float>(c); }
 dmmv_status batched_maxabs(Ctx* c) { return c->p.dtype == DMMV_F64 ? maxabs_t<double>(c) : maxabs_t<float>(c); }
-dmmv_status batched_eval(Ctx* c, void* s, bool p) { return c->p.dtype == DMMV_F64 ? eval_t<double>(c, s, p) : eval_t<float>(c, s, p); }
+dmmv_status batched_eval(Ctx* c, void* s, bool p) {
+    if (c->eval_mfma) return batched_eval_mfma(c, s, p);
+    return c->p.dtype == DMMV_F64 ? eval_t<double>(c, s, p) : eval_t<float>(c, s, p);
+}
 dmmv_status batched_apply(Ctx* c, bool tf, int32_t iters, dmmv_move* trace, void* trace_t) {
     return c->p.dtype == DMMV_F64 ? apply_t<double>(c, tf, iters, trace, trace_t) : apply_t<float>(c, tf, iters, trace, trace_t);
 }

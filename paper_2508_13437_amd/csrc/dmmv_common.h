@@ -153,6 +153,9 @@ struct Ctx {
     void* swap_part;          // Partial<T>[R][swap_nb]; sparse: one per evaluation workgroup
     int32_t* swap_skip;       // [R] 1: the last search of this ALNS iteration found no swap
     unsigned long long* swap_gbest;   // sparse: order bits of the best t' found so far by any workgroup
+    // batched evaluation on the matrix cores
+    bool eval_mfma;       // the matrix-core kernel scores the moves
+    void* rT;             // float[R][m64] instance-major copy of r, rows padded with zeros to a multiple of 64
     // batched residual on the matrix cores (options.residual_mfma)
     void* Xp;             // bf16[3][m][mfma_ldk] planes whose sum is X
     void* Qt;             // bf16[R][mfma_ldk] current codes D[k_j] per instance
@@ -219,6 +222,10 @@ dmmv_status csc_apply(Ctx* c);          // staged move only; caller refreshes t 
 dmmv_status csc_select_apply(Ctx* c, int32_t iters, dmmv_move* trace, void* trace_t, bool pruned);
 dmmv_status csc_eval_pruned(Ctx* c, bool honor_done);   // records of the columns of the worst row only
 
+bool batched_eval_mfma_applicable(const dmmv_problem& p);
+int64_t batched_eval_mfma_rt_elems(const dmmv_problem& p);
+dmmv_status batched_eval_mfma_build(Ctx* c);
+dmmv_status batched_eval_mfma(Ctx* c, void* scores_out, bool want_partials);
 dmmv_status batched_build(Ctx* c);
 dmmv_status batched_residual(Ctx* c);
 dmmv_status batched_eval(Ctx* c, void* scores_out, bool want_partials);

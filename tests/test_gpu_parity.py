@@ -742,3 +742,44 @@ def test_batched_descent_continues_on_the_running_instances_only(poll):
 def test_batched_descent_small_llm_config_with_polling():
     o = batched_check(make_config(4, "small"), 60, poll_every=4)
     assert o.iters_done.min() < o.iters_done.max()
+
+
+# ---- batched evaluation with the multiply-adds on the matrix cores (options.batched_eval = 2) --
+@pytest.mark.parametrize("shape", [(1, 1, 1, 2), (17, 5, 3, 3), (64, 8, 64, 4), (100, 33, 65, 8),
+                                   (130, 70, 130, 16), (50, 19, 7, 21), (70, 40, 9, 32)])
+def test_batched_matrix_core_evaluation_random(shape):
+    mm, nn, R, nd = shape
+    batched_check(random_batched(40 + mm, mm, nn, R, nd, dtype=np.float32), 12, batched_eval=2)
+
+
+def test_batched_matrix_core_evaluation_ties_radius_and_tables():
+    m = dmmv()
+    batched_check(random_batched(9, 30, 10, 70, 4, dtype=np.float32, integer=True), 15, batched_eval=2)
+    batched_check(random_batched(12, 60, 14, 20, 8, dtype=np.float32), 10, radius=1, batched_eval=2)
+    # the full score table, bit for bit that of the vector-unit kernel and of the oracle
+    inst = random_batched(66, 75, 21, 67, 16, dtype=np.float32)
+    tabs = []
+    for mode in (1, 2):
+        with m.from_instance(inst, DEV, batched_eval=mode) as h:
+            m.dmmv_set_x(h, T(inst.x0))
+            r = N(m.dmmv_residual(h))
+            tabs.append(N(m.dmmv_eval_moves(h)))
+    assert np.array_equal(tabs[0], tabs[1])
+    for q in (0, 33, 66):
+        want = orc.eval_moves_dense(inst.A, inst.D, inst.x0[q], r[q], scale=inst.scale[q])
+        assert np.array_equal(tabs[1][q], want)
+
+
+@pytest.mark.parametrize("idx", [4, 5])
+def test_batched_matrix_core_evaluation_small_llm_configs(idx):
+    inst = make_config(idx, "small")
+    batched_check(inst, inst.iters, batched_eval=2)
+
+
+def test_batched_matrix_core_evaluation_not_applicable_is_an_error():
+    m = dmmv()
+    for inst in (random_batched(8, 40, 12, 9, 5, dtype=np.float64), random_batched(9, 20, 6, 5, 40, dtype=np.float32),
+                 random_dense(10, 20, 6, 4, dtype=np.float32)):
+        with pytest.raises(m.DmmvError) as e:
+            m.from_instance(inst, DEV, batched_eval=2)
+        assert e.value.status == -8
