@@ -172,6 +172,9 @@ def run_config(idx: int, steps: int, warmup: int, iters_override, device: str, d
     if inst.kind == "csr":
         out["descent"] = descent_timing(inst, device, x0, iters)
     out["alns"] = alns_timing(inst, device, x0)
+    if inst.kind == "dense":
+        # same loop, the local search finding each variable's best value by bisection over D
+        out["alns_value_search"] = alns_timing(inst, device, x0, value_search=True)
     out["swap"] = swap_timing(inst, device, x0, iters)
     if do_cpu:
         out["cpu_baseline"] = cpu_baseline(inst, cpu_budget)
@@ -222,7 +225,7 @@ def swap_timing(inst, device: str, x0, iters: int) -> dict:
     return res
 
 
-def alns_timing(inst, device: str, x0) -> dict:
+def alns_timing(inst, device: str, x0, **hopt) -> dict:
     """The ALNS outer loop (destroy, repair, local search, accept) around the descent: wall time of
     one dmmv_alns call with the paper's destroy rate (0.5 % of n) and coefficient (alpha = 0.3)."""
     import torch
@@ -230,7 +233,7 @@ def alns_timing(inst, device: str, x0) -> dict:
 
     outer = {"csr": 20, "dense": 200, "batched": 4}[inst.kind]
     ls_moves = 8 if inst.kind != "batched" else 4
-    with dmmv.from_instance(inst, device, alns=True, prune=inst.kind == "csr") as h:
+    with dmmv.from_instance(inst, device, alns=True, prune=inst.kind == "csr", **hopt) as h:
         dmmv.dmmv_alns(h, x0, 2, ls_moves=ls_moves, seed=1)             # warm-up
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -374,6 +377,8 @@ def main():
         line["descent"] = head["descent"]
     if "alns" in head:
         line["alns"] = head["alns"]
+    if "alns_value_search" in head:
+        line["alns_value_search"] = head["alns_value_search"]
     if "swap" in head:
         line["swap"] = head["swap"]
     if "cpu_baseline" in head:

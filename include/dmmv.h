@@ -121,6 +121,14 @@ typedef struct {
     int32_t alns;            /* batched problems: 1 = reserve the workspace dmmv_alns needs (current
                                 and best solution, sampling weights and draws per instance, about
                                 R*(36 n + m w) bytes).  Single-instance handles always have it    */
+    int32_t value_search;    /* dense matrices: 1 = the descent (dmmv_solve without keep_going, the
+                                local search of dmmv_alns) finds the best value of each variable
+                                by bisection over D instead of scoring all nd values: the score of
+                                a variable's values is quasi-convex in the value's index, also as
+                                computed (D ascends and rounding is monotone), so about log2(nd)
+                                values are scored per variable and the moves applied are the same
+                                as with the full evaluation.  dmmv_eval_moves and
+                                dmmv_argmin_move always score all                                */
     int32_t batched_eval;    /* batched problems: which kernel scores the moves.  0 or 1 = the
                                 vector-unit kernel (default); 2 = the matrix-core kernel, for fp32
                                 with nd <= 32 (dmmv_create fails with DMMV_ERR_UNSUPPORTED

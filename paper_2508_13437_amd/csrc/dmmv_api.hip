@@ -145,6 +145,7 @@ size_t workspace_layout(const dmmv_problem& p, const dmmv_options& o, Ctx* c, ch
     } else {
         c->n_partials = dense_num_partials(p);
         b.take(&c->partials, (size_t)(c->n_partials > 0 ? c->n_partials : 1) * part_sz);
+        if (o.value_search) b.take(&c->search_part, (size_t)(p.n > 0 ? p.n : 1) * part_sz);
     }
     return (b.off + 255) / 256 * 256;
 }
@@ -485,6 +486,18 @@ static dmmv_status loop_step(Ctx* c, int32_t iters, dmmv_move* trace, void* trac
     if (c->kind == KIND_CSC && c->o.prune && !c->o.keep_going && c->p.n > 0) {
         DMMV_TRY(csc_eval_pruned(c, true));
         return csc_select_apply(c, iters, trace, trace_t, true);
+    }
+    if (c->kind == KIND_DENSE && c->o.value_search && !c->o.keep_going && c->p.n > 0) {
+        // one record per variable instead of one per evaluation workgroup
+        DMMV_TRY(dense_eval_search(c, true));
+        void* const part = c->partials;
+        const int64_t n_part = c->n_partials;
+        c->partials = c->search_part;
+        c->n_partials = c->p.n;
+        const dmmv_status st = select_apply_any(c, iters, trace, trace_t);
+        c->partials = part;
+        c->n_partials = n_part;
+        return st;
     }
     DMMV_TRY(eval_any(c, nullptr, true, true));
     return select_apply_any(c, iters, trace, trace_t);

@@ -147,6 +147,7 @@ struct Ctx {
     void* cmp_full_state;
     void* cmp_full_scale;
     int64_t cmp_full_R;
+    void* search_part;        // dense, options.value_search: Partial<T>[n], one record per variable
     // swap move
     int32_t swap_nb;          // dense, batched: workgroups per instance of the evaluation
     int32_t* swap_rows;       // dense, batched: [R][SWAP_KMAX] rows of largest |r|, decreasing
@@ -203,6 +204,7 @@ int64_t dense_num_partials(const dmmv_problem& p);    // arg-min records one eva
 dmmv_status dense_eval(Ctx* c, void* scores_out, bool want_partials, bool honor_done);
 bool dense_has_fused_select_apply(const Ctx* c);
 dmmv_status dense_select_apply(Ctx* c, int32_t iters, dmmv_move* trace, void* trace_t);
+dmmv_status dense_eval_search(Ctx* c, bool honor_done);   // one record per variable into search_part
 dmmv_status dense_apply(Ctx* c, bool t_from_score, int32_t iters, dmmv_move* trace, void* trace_t);
 
 int32_t swap_blocks_per_instance(const dmmv_problem& p);

@@ -783,3 +783,66 @@ def test_batched_matrix_core_evaluation_not_applicable_is_an_error():
         with pytest.raises(m.DmmvError) as e:
             m.from_instance(inst, DEV, batched_eval=2)
         assert e.value.status == -8
+
+
+# ---- dense descent with the best value of a variable found by bisection (options.value_search)
+def search_check(inst, iters, **hopt):
+    print("value search case", inst.name, iters, hopt, flush=True)
+    oopt = {k: v for k, v in hopt.items() if k in ("radius",)}
+    vm = hopt.pop("var_mask_np", None)
+    if vm is not None:
+        oopt["var_mask"] = vm
+        hopt["var_mask"] = T(vm)
+    o = oracle_solve(inst, iters, **oopt)
+    with dmmv().from_instance(inst, DEV, value_search=True, **hopt) as h:
+        res = dmmv().dmmv_solve(h, T(inst.x0), iters, trace=True)
+        check_single_trace(res, o, iters)
+        x, r, t = dmmv().dmmv_get_state(h)
+        assert np.array_equal(N(r), o.r) and N(t)[0] == (np.abs(o.r).max() if inst.m else 0)
+    return o
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("shape", [(1, 1, 2), (7, 3, 3), (40, 17, 4), (130, 33, 16), (300, 20, 65), (520, 12, 257),
+                                   (90, 9, 1024)])
+def test_value_search_dense_random(shape, dtype):
+    mm, nn, nd = shape
+    o = search_check(random_dense(9700 + mm, mm, nn, nd, dtype=dtype), 40)
+    assert mm < 40 or o.iters_done > 0
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("seed", range(4))
+def test_value_search_integer_ties_and_plateaus(seed, dtype):
+    # small integers: equal scores on neighbouring values are frequent; the lowest value must win
+    search_check(random_dense(9800 + seed, 37, 11, 13, dtype=dtype, integer=True), 40)
+    # columns of zeros and ones: long runs of values with the same score
+    inst = random_dense(9810 + seed, 25, 9, 13, dtype=dtype, integer=True)
+    inst.A[:, ::2] = np.sign(inst.A[:, ::2])
+    inst.A[:, 3] = 0
+    search_check(inst, 40)
+
+
+def test_value_search_radius_mask_and_tall_matrix():
+    inst = random_dense(9820, 90, 17, 40, dtype=np.float64)
+    vm = (np.random.default_rng(3).uniform(size=inst.n) < 0.5).astype(np.uint8)
+    for radius in (1, 3, 0):
+        search_check(inst, 30, radius=radius, var_mask_np=vm)
+    # more rows than a thread keeps in registers: rows are read from memory at every step
+    search_check(random_dense(9821, 5000, 4, 50, dtype=np.float32), 12)
+    search_check(random_dense(9822, 40001, 3, 9, dtype=np.float64), 6)
+
+
+def test_value_search_fir_configs_and_alns():
+    search_check(make_config(2, "small"), 80)
+    search_check(make_config(2), 500)
+    search_check(make_config(1), 200)
+    # inside the ALNS loop the local search takes the same moves
+    m = dmmv()
+    inst = make_config(2, "small")
+    prm = orc.alns_params(15, ls_moves=4, seed=4)
+    o = orc.alns_dense(inst.A, inst.b, inst.D, inst.x0, prm)
+    with m.from_instance(inst, DEV, value_search=True) as h:
+        res = m.dmmv_alns(h, T(inst.x0), 15, ls_moves=4, seed=4)
+    assert np.array_equal(N(res.trace_t)[:, 0], o.t) and np.array_equal(N(res.trace)[:, 2], o.moves)
+    assert np.array_equal(N(res.x_best), o.x)
