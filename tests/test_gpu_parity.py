@@ -846,3 +846,13 @@ def test_value_search_fir_configs_and_alns():
         res = m.dmmv_alns(h, T(inst.x0), 15, ls_moves=4, seed=4)
     assert np.array_equal(N(res.trace_t)[:, 0], o.t) and np.array_equal(N(res.trace)[:, 2], o.moves)
     assert np.array_equal(N(res.x_best), o.x)
+
+
+def test_value_search_many_small_shapes():
+    rng = np.random.default_rng(4343)
+    for case in range(40):
+        mm, nn, nd = int(rng.integers(0, 120)), int(rng.integers(1, 30)), int(rng.integers(2, 80))
+        dtype = [np.float32, np.float64][case % 2]
+        inst = random_dense(21000 + case, mm, nn, min(nd, 13) if case % 3 == 0 else nd, dtype=dtype,
+                            integer=bool(case % 3 == 0))
+        search_check(inst, 25, radius=int(rng.integers(0, 4)))

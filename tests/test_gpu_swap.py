@@ -256,3 +256,21 @@ def test_swap_full_size_tomography_sampled(descend):
             assert ts == gt and np.array_equal(rs, r1)
     xe = x0.copy(); xe[gi], xe[gj] = x0[gj], x0[gi]
     assert np.array_equal(x1, xe)
+
+
+def test_swap_many_small_shapes():
+    """A sweep of odd small shapes (seeded), every storage kind and both precisions."""
+    rng = np.random.default_rng(4242)
+    for case in range(60):
+        mm, nn, nd = int(rng.integers(0, 90)), int(rng.integers(1, 75)), int(rng.integers(2, 10))
+        dtype = [np.float32, np.float64][case % 2]
+        kind = case % 3
+        if kind == 0:
+            inst = random_dense(20000 + case, mm, nn, nd, dtype=dtype, integer=bool(case % 4 == 0))
+        elif kind == 1:
+            inst = random_batched(20000 + case, max(mm, 1), nn, int(rng.integers(1, 12)), nd, dtype=dtype,
+                                  integer=bool(case % 4 == 1))
+        else:
+            inst = random_sparse(20000 + case, max(mm, 1), nn, nd, density=float(rng.uniform(0.05, 0.6)), dtype=dtype,
+                                 integer=bool(case % 4 == 2))
+        chain_check(inst, 2, k_eps=int(rng.integers(0, 9)))
