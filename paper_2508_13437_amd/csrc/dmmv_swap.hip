@@ -29,7 +29,8 @@ constexpr int SW_WAVES = SW_BLOCK / 64;
 constexpr int SWE_BLOCK = 1024;                // evaluation: many wavefronts share one instance's LDS tile
 constexpr int SWE_WAVES = SWE_BLOCK / 64;
 constexpr int SWE_QCAP = 128;                  // queue of a wavefront: under 64 waiting plus at most 64 new
-constexpr size_t SW_LDS_BUDGET = 52 * 1024;    // dynamic LDS of the evaluation kernel (8 KiB more are static)
+constexpr size_t SW_LDS_BUDGET = 68 * 1024;    // dynamic LDS of the evaluation kernel (8 KiB more are static):
+                                               // two workgroups share a compute unit's 160 KiB
 
 __device__ __forceinline__ unsigned long long order_bits(float v) { return (unsigned long long)__float_as_uint(v); }
 __device__ __forceinline__ unsigned long long order_bits(double v) { return (unsigned long long)__double_as_longlong(v); }
@@ -326,6 +327,14 @@ dmmv_status swap_t(Ctx* c, int32_t k_eps, int32_t apply, bool use_skip, dmmv_swa
         hipLaunchKernelGGL(k_swap_top<T>, dim3((unsigned)R), dim3(SW_BLOCK), 0, c->stream, m, R, K, (const T*)c->r,
                            (const int32_t*)skip, c->swap_rows);
     const dim3 grid((unsigned)R, (unsigned)nb);
+    static bool attr_set = false;                          // per instantiation of this function
+    if (!attr_set) {
+        DMMV_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_swap_eval<T, true>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)SW_LDS_BUDGET));
+        DMMV_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_swap_eval<T, false>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)SW_LDS_BUDGET));
+        attr_set = true;
+    }
 #define DMMV_SWAP_LAUNCH(DV)                                                                               \
     hipLaunchKernelGGL((k_swap_eval<T, DV>), grid, dim3(SWE_BLOCK), used, c->stream, m, n, R, nb, K,       \
                        (int32_t)L, (const T*)c->p.A_dense, c->p.lda,                                       \
