@@ -135,3 +135,33 @@ def test_alns_parameter_blocks_of_binding_and_oracle_have_the_layout_of_the_head
     for decl in re.findall(r"^\s+(?:int32_t|double|uint64_t)\s+([a-z0-9_, ]+);", body, flags=re.M):
         names += [v.strip() for v in decl.split(",")]
     assert names == ["iters", "ls_moves", "ls_radius", "destroy_count", "alpha", "lambda", "sigma1", "sigma2", "sigma3", "seed", "ls_swaps", "k_eps", "l2_guard", "reserved"]
+
+
+def test_options_block_of_the_binding_has_the_layout_of_the_header(mod):
+    import re
+    hdr = open(os.path.join(ROOT, "include", "dmmv.h")).read()
+    body = hdr[hdr.index("typedef struct {\n    int32_t radius;"):hdr.index("} dmmv_options;")]
+    names = []
+    for decl in re.findall(r"^\s+(?:const\s+)?(?:int32_t|uint8_t\*)\s+\*?([a-z0-9_]+);", body, flags=re.M):
+        names.append(decl)
+    assert names == [f[0] for f in mod.Options._fields_], (names, [f[0] for f in mod.Options._fields_])
+    # four int32, one pointer (8-byte aligned already), six int32 -> padded to the pointer's alignment
+    assert C.sizeof(mod.Options) == 48
+
+
+def test_workspace_grows_with_the_options_that_need_buffers(mod):
+    lib = mod.load()
+    pd, keep = _problem(mod, m=300, n=40)
+    o = mod.Options()
+    base = lib.dmmv_workspace_bytes(C.byref(pd), C.byref(o))
+    o.value_search = 1
+    assert lib.dmmv_workspace_bytes(C.byref(pd), C.byref(o)) >= base + 40 * 16
+    pb, keepb = _problem(mod, dtype=np.float32, m=100, n=50, R=3, scale=(1.0, 2.0, 0.5))
+    o = mod.Options()
+    base = lib.dmmv_workspace_bytes(C.byref(pb), C.byref(o))
+    o.batched_eval = 2
+    with_rt = lib.dmmv_workspace_bytes(C.byref(pb), C.byref(o))
+    assert with_rt >= base + 3 * 128 * 4                     # rows padded to a multiple of 64
+    o = mod.Options()
+    o.alns = 1
+    assert lib.dmmv_workspace_bytes(C.byref(pb), C.byref(o)) > base
