@@ -134,8 +134,9 @@ def test_alns_same_seed_same_run_and_batched_is_refused():
 def batched_alns_check(inst, iters, **kw):
     m = dmmv()
     print("alns batched case", inst.name, iters, kw, flush=True)
+    hopt = {key: kw.pop(key) for key in ("batched_eval",) if key in kw}
     prm = orc.alns_params(iters, **kw)
-    with m.from_instance(inst, DEV, alns=True) as h:
+    with m.from_instance(inst, DEV, alns=True, **hopt) as h:
         res = m.dmmv_alns(h, T(inst.x0), iters, **kw)
         tr, tt = N(res.trace), N(res.trace_t)
         xb, tb = N(res.x_best), N(res.t_best)
@@ -219,3 +220,8 @@ def test_alns_l2_guard_sparse_and_batched():
     alns_check(random_sparse(7932, 600, 80, 3, density=0.1), 15, ls_moves=2, destroy_count=5, seed=7, l2_guard=1)
     batched_alns_check(random_batched(7933, 300, 24, 70, 4), 10, ls_moves=2, destroy_count=3, seed=2, l2_guard=1)
     batched_alns_check(random_batched(7934, 40, 16, 9, 5, dtype=np.float64), 10, ls_moves=2, seed=3, l2_guard=1)
+
+
+def test_alns_batched_with_the_matrix_core_evaluation():
+    batched_alns_check(random_batched(7940, 70, 24, 20, 4), 8, ls_moves=3, ls_swaps=1, destroy_count=3, seed=2,
+                       batched_eval=2)
