@@ -36,6 +36,11 @@ __device__ __forceinline__ unsigned long long order_bits(float v) { return (unsi
 __device__ __forceinline__ unsigned long long order_bits(double v) { return (unsigned long long)__double_as_longlong(v); }
 __device__ __forceinline__ void from_order_bits(unsigned long long b, float& v) { v = __uint_as_float((uint32_t)b); }
 __device__ __forceinline__ void from_order_bits(unsigned long long b, double& v) { v = __longlong_as_double((long long)b); }
+// the largest value below t >= 0 (finite); -1 for t = 0, which no magnitude is at or below
+__device__ __forceinline__ float value_below(float t) { return t > 0.0f ? __uint_as_float(__float_as_uint(t) - 1u) : -1.0f; }
+__device__ __forceinline__ double value_below(double t) {
+    return t > 0.0 ? __longlong_as_double(__double_as_longlong(t) - 1ll) : -1.0;
+}
 
 // ---- K rows of large |r| per instance for the filter, in decreasing order.  Which rows the
 // filter tries first changes the time a search takes, never its result, so an exact top-K
@@ -150,13 +155,14 @@ __global__ __launch_bounds__(SWE_BLOCK) void k_swap_eval(
         const int64_t v = alive ? (int64_t)queue[lane] : u;
         const T Ds = alive ? step_of(dvu, dv(v)) : (T)0;
         T bnd = bound();
+        const T thr = dmmv_min(bnd, value_below(t));       // val < t and val <= bound in one test
         for (int l = L; l < K && __any(alive); ++l) {
             if (alive) {
                 const int64_t row = sh_rows[l];
                 const T au = At ? At[row * n + u] : Au[row];
                 const T av = At ? At[row * n + v] : A[row + v * lda];
                 const T val = dmmv_abs(dmmv_fma(Ds, av - au, rtop[l]));
-                alive = val < t && !(val > bnd);
+                alive = val <= thr;
             }
         }
         unsigned long long todo = __ballot(alive);
@@ -194,6 +200,7 @@ __global__ __launch_bounds__(SWE_BLOCK) void k_swap_eval(
     // elements fit in LDS, so 32-bit indices do below.
     const int32_t n32 = (int32_t)n;
     const unsigned long long below = (1ull << lane) - 1ull;
+    const T t_below = value_below(t);
     for (int32_t u = blk * SWE_WAVES + w; u < n32; u += nb * SWE_WAVES) {
         if (vm && !vm[u]) continue;
         const T dvu = dv(u);
@@ -209,12 +216,22 @@ __global__ __launch_bounds__(SWE_BLOCK) void k_swap_eval(
                 if (vm) alive = alive && vm[v];
                 Ds = step_of(dvu, dvv);
             }
-            const T bnd = bound();
+            // One threshold for both tests: val < t and val <= bound  <=>  val <= min(bound, t-),
+            // t- the largest value below t.  After the first row (which, far from a local
+            // optimum, often leaves no pair of the 64) the rows are taken without a branch: a
+            // wavefront instruction costs the same however many lanes still need it.
+            const T thr = dmmv_min(bound(), t_below);
+            const int32_t vv = alive ? v : u;              // a lane without a pair reads in bounds
             const T* __restrict__ row_l = atop;
-            for (int l = 0; l < L; ++l, row_l += n32) {
-                const T val = dmmv_abs(dmmv_fma(Ds, row_l[alive ? v : u] - row_l[u], rtop[l]));
-                alive = alive && val < t && !(val > bnd);
-                if (!__any(alive)) break;
+            if (L > 0) {
+                const T val = dmmv_abs(dmmv_fma(Ds, row_l[vv] - row_l[u], rtop[0]));
+                alive = alive & (val <= thr);
+                if (!__any(alive)) continue;
+                row_l += n32;
+            }
+            for (int l = 1; l < L; ++l, row_l += n32) {
+                const T val = dmmv_abs(dmmv_fma(Ds, row_l[vv] - row_l[u], rtop[l]));
+                alive = alive & (val <= thr);
             }
             const unsigned long long bal = __ballot(alive);
             if (!bal) continue;
