@@ -125,8 +125,7 @@ __global__ __launch_bounds__(SWE_BLOCK) void k_swap_eval(
     }
     if (threadIdx.x == 0) sh_best = order_bits(Limits<T>::inf());
     __syncthreads();
-    volatile unsigned long long* vbest = &sh_best;
-    volatile int32_t* queue = sh_queue[w];
+    int32_t* queue = sh_queue[w];                          // written and read by this wavefront only
 
     auto dv = [&](int64_t j) -> T { return DVL ? sh_dv[j] : D[kidx[j * R + q]]; };
     // Unordered pairs {u, v}, u < v, each taken in the orientation its values give: with
@@ -145,7 +144,7 @@ __global__ __launch_bounds__(SWE_BLOCK) void k_swap_eval(
     int64_t best_c = -1;                                   // the wavefront's record (uniform)
     auto bound = [&]() -> T {
         T shared_t;
-        from_order_bits(*vbest, shared_t);
+        from_order_bits(__hip_atomic_load(&sh_best, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP), shared_t);
         return dmmv_min(best_t, shared_t);
     };
 

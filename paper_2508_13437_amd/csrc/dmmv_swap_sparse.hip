@@ -117,7 +117,6 @@ __global__ __launch_bounds__(SS_BLOCK) void k_swap_eval_csc(
     }
     if (threadIdx.x == 0) sh_best = ss_bits(Limits<T>::inf());
     __syncthreads();
-    volatile unsigned long long* vbest = &sh_best;
 
     const T t = st[0].t;
     const T dvu = D[kidx[u]];
@@ -137,7 +136,7 @@ __global__ __launch_bounds__(SS_BLOCK) void k_swap_eval_csc(
         if (!__any(alive)) continue;
         T gb, sb;
         ss_from_bits(__atomic_load_n(gbest, __ATOMIC_RELAXED), gb);
-        ss_from_bits(*vbest, sb);
+        ss_from_bits(__hip_atomic_load(&sh_best, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP), sb);
         const T bnd = dmmv_min(best_t, dmmv_min(gb, sb));
         // residual that stays: the first row, by decreasing |r|, stored in neither column
         T outside = (T)0;
