@@ -82,7 +82,11 @@ size_t workspace_layout(const dmmv_problem& p, const dmmv_options& o, Ctx* c, ch
         b.take(&c->alns_prefix, nR * sizeof(uint64_t));
         b.take(&c->alns_first, nR * sizeof(uint64_t));
         b.take(&c->alns_picked, nR * sizeof(int32_t));
-        if (sparse) b.take(&c->alns_touched, (size_t)p.m);
+        if (sparse) {
+            b.take(&c->alns_touched, (size_t)p.m);
+            b.take(&c->alns_g_row, ((size_t)1 << 20) * sizeof(int32_t));
+            b.take(&c->alns_g_val, ((size_t)1 << 20) * esz);
+        }
         b.take(&c->alns_q2, (size_t)p.R * sizeof(double));
         b.take(&c->alns_q2_blocks, (size_t)(ceil_div(p.m, 256) + 1) * sizeof(double));
     }
@@ -726,9 +730,11 @@ dmmv_status dmmv_create(dmmv_handle* out, const dmmv_problem* problem, const dmm
             hipLaunchKernelGGL(k_init_state<float>, grid1(problem->R, 256), dim3(256), 0, c->stream, (InstState<float>*)c->state, problem->R);
         DMMV_LAUNCH_CHECK();
         c->csc_max_row = 0;
+        c->csc_max_col = 0;
         if (c->kind == KIND_CSC) {
             DMMV_TRY(csc_build(c));
             DMMV_HIP_CHECK(hipMemcpyAsync(&c->csc_max_row, &c->flags[FLAG_MAXROW], sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
+            DMMV_HIP_CHECK(hipMemcpyAsync(&c->csc_max_col, &c->flags[FLAG_MAXCOL], sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
             DMMV_HIP_CHECK(hipStreamSynchronize(c->stream));
             if (c->csc_max_row > c->p.n) c->csc_max_row = (int32_t)c->p.n;   // duplicates are an error anyway
         }

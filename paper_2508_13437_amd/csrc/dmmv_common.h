@@ -76,7 +76,7 @@ struct alignas(16) Partial {
 };
 
 // device flag slots
-enum { FLAG_ERROR = 0, FLAG_ACTIVE = 1, FLAG_PLANES = 2, FLAG_MAXROW = 3, FLAG_COUNT = 8 };
+enum { FLAG_ERROR = 0, FLAG_ACTIVE = 1, FLAG_PLANES = 2, FLAG_MAXROW = 3, FLAG_MAXCOL = 4, FLAG_COUNT = 8 };
 // error bits set by kernels
 enum { ERRBIT_X_NOT_IN_D = 1, ERRBIT_CSR_RANGE = 2, ERRBIT_CSR_DUP = 4, ERRBIT_MOVE_RANGE = 8 };
 
@@ -117,6 +117,7 @@ struct Ctx {
     int32_t* res_meta;    // [4] count, floor row
     void* res_floor;      // T[1] floor value
     int32_t csc_max_row;  // most stored entries in one row (slots of the pruned evaluation)
+    int32_t csc_max_col;  // most entries of one column, the segments' padding included
     void* prune_part;     // Partial<T>[n] records of the pruned evaluation (options.prune)
 
     // batched
@@ -133,6 +134,8 @@ struct Ctx {
     uint64_t* alns_first;     // [n] stamp of the first draw of a variable in an iteration
     int32_t* alns_picked;     // [n] variables drawn, in the order of the draws
     uint8_t* alns_touched;    // [m] sparse repair: rows of the column being reassigned
+    int32_t* alns_g_row;      // sparse repair: entries of the picked columns, global row (-1: padding)
+    void* alns_g_val;         //   and value, a fixed stride per picked column (2^20 entries in all)
     double* alns_q2;          // [R] squared l2 norm of the working residual (l2 guard)
     double* alns_q2_blocks;   // [ceil(m / 256)] single instance: block sums of the above
     // batched descent: virtual batch of the instances still running

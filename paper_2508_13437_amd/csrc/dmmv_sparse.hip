@@ -125,6 +125,15 @@ __global__ void k_cscp_sort(int64_t nseg, int32_t mp, const int32_t* __restrict_
     for (int32_t e = e1 + lane; e < epad; e += 64) { row16[e] = (uint16_t)mp; cval[e] = (T)0; }
 }
 
+// most entries of one column over all its segments, padding included
+__global__ void k_cscp_maxcol(int64_t n, int32_t P, const int32_t* __restrict__ segptr, int32_t* flags) {
+    const int64_t j = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    if (j >= n) return;
+    int64_t len = 0;
+    for (int32_t p = 0; p < P; ++p) len += segptr[(int64_t)p * n + j + 1] - segptr[(int64_t)p * n + j];
+    atomicMax(&flags[FLAG_MAXCOL], (int32_t)(len < INT32_MAX ? len : INT32_MAX));
+}
+
 // column range of every evaluation workgroup: per partition, equal shares of its entries.
 // blk_lo[p*(gbp+1) + b] = first column of workgroup b of partition p.
 __global__ void k_cscp_ranges(int64_t n, int32_t P, int32_t gbp, const int32_t* __restrict__ segptr,
@@ -444,6 +453,8 @@ static dmmv_status build_t(Ctx* c) {
     if (nseg > 0)
         hipLaunchKernelGGL(k_cscp_sort<T>, dim3((unsigned)ceil_div(nseg, 4)), dim3(256), 0, c->stream, nseg, c->csc_mp, (const int32_t*)c->segptr, (const int32_t*)c->fillpos, (const uint16_t*)c->row16_tmp, (const T*)c->cval_tmp, c->row16, (T*)c->cval, c->flags);
     hipLaunchKernelGGL(k_cscp_ranges, dim3((unsigned)ceil_div((int64_t)c->csc_P * (c->csc_gb + 1), 256)), dim3(256), 0, c->stream, n, c->csc_P, c->csc_gb, (const int32_t*)c->segptr, c->blk_lo);
+    if (n > 0)
+        hipLaunchKernelGGL(k_cscp_maxcol, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, c->stream, n, c->csc_P, (const int32_t*)c->segptr, c->flags);
     DMMV_LAUNCH_CHECK();
     return DMMV_OK;
 }
@@ -539,7 +550,7 @@ __global__ __launch_bounds__(256) void k_alns_impact_cscp(int64_t m, int64_t n, 
 // the worst-case error over ALL rows for both neighbouring levels: the rows of the column are
 // marked, the others contribute their |r| as it stands.
 template <class T>
-__global__ __launch_bounds__(1024) void k_alns_repair_cscp(int64_t m, int64_t n, int32_t nd, int32_t mp, int32_t P,
+__global__ __launch_bounds__(1024) void k_alns_repair_cscp_general(int64_t m, int64_t n, int32_t nd, int32_t mp, int32_t P,
                                                           const int32_t* __restrict__ segptr,
                                                           const uint16_t* __restrict__ row16,
                                                           const T* __restrict__ cval, const T* __restrict__ D,
@@ -615,6 +626,191 @@ __global__ __launch_bounds__(1024) void k_alns_repair_cscp(int64_t m, int64_t n,
     if (threadIdx.x == 0) { st[0].t = tmax; st[0].done = 0; st[0].moves = 0; }
 }
 
+// Repair without the chain of dependent loads.  From one workgroup every dependent access to
+// memory costs about a microsecond, and the general kernel needs three to five per picked
+// variable (segment bounds, entries, residuals, ...).  Here the entries of all picked columns are
+// first gathered, by many workgroups, into a scratch array with a fixed stride per column
+// (k_alns_gather: global row and value, row -1 for padding), so the repair kernel knows the
+// address of a pick's entries without loading anything, fetches the next pick's entries while
+// it works on the current one, and is left with the residuals themselves: one dependent access
+// per pick for the random operator, two for the greedy one.
+// Greedy: a thread keeps one entry (row, value, residual) in registers for the whole step; the
+// column's rows are marked in an LDS bitmap; the maxima of |r| over chunks of 64 rows live in LDS,
+// so "the largest |r| outside the column" is the kept maximum of the chunks the column does not
+// touch and a row-by-row look (one wavefront per chunk, loads issued together) at those it
+// does; the touched chunks get their new maxima from that look and from the new residuals.
+// Maxima are exact in any order, so the choices are those of the general kernel.
+constexpr int RP_CHUNK = 64;
+constexpr int RP_MAXCHUNKS = 2048;        // rows up to 131072
+constexpr int RP_BLOCK = 1024;            // longest column (padding included) the kernel takes
+constexpr int64_t RP_GATHER_CAP = 1 << 20;   // entries of the scratch array
+
+template <class T>
+__global__ void k_alns_gather(int64_t n, int32_t mp, int32_t P, int32_t stride, const int32_t* __restrict__ segptr,
+                              const uint16_t* __restrict__ row16, const T* __restrict__ cval,
+                              const int32_t* __restrict__ picked, int32_t* __restrict__ g_row,
+                              T* __restrict__ g_val) {
+    const int64_t q = blockIdx.x;
+    const int64_t j = picked[q];
+    int32_t base = 0;
+    for (int32_t p = 0; p < P; ++p) {
+        const int32_t e0 = segptr[(int64_t)p * n + j], e1 = segptr[(int64_t)p * n + j + 1];
+        for (int32_t e = e0 + threadIdx.x; e < e1; e += blockDim.x) {
+            const uint32_t loc = row16[e];
+            const bool pad = loc == (uint32_t)mp;
+            g_row[q * stride + base + (e - e0)] = pad ? -1 : (int32_t)((int64_t)p * mp + loc);
+            g_val[q * stride + base + (e - e0)] = pad ? (T)0 : cval[e];
+        }
+        base += e1 - e0;
+    }
+    for (int32_t t = base + threadIdx.x; t < stride; t += blockDim.x) { g_row[q * stride + t] = -1; g_val[q * stride + t] = (T)0; }
+}
+
+template <class T>
+__global__ __launch_bounds__(RP_BLOCK) void k_alns_repair_gathered(
+    int64_t m, int32_t nd, int32_t stride, const int32_t* __restrict__ g_row, const T* __restrict__ g_val,
+    const T* __restrict__ D, T* r, int32_t* kidx, int32_t count, const int32_t* __restrict__ picked,
+    InstState<T>* st, const AlnsState* S, uint64_t seed, uint64_t inst) {
+    __shared__ T sh[16];
+    __shared__ T sh_pair[16][2];
+    __shared__ T sh_cmax[RP_MAXCHUNKS];                       // max |r| of every chunk
+    __shared__ unsigned int sh_rowbit[RP_MAXCHUNKS * RP_CHUNK / 32];   // rows of the current column
+    __shared__ int32_t sh_dirty[RP_BLOCK];                    // chunks the column touches, each once
+    __shared__ unsigned int sh_isdirty[RP_MAXCHUNKS];
+    __shared__ int32_t sh_ndirty;
+    const int32_t it = S->it;
+    const bool greedy = S->r_op == 1;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    constexpr int NW = RP_BLOCK / 64;
+    const int64_t nch = (m + RP_CHUNK - 1) / RP_CHUNK;
+    if (greedy) {
+        for (int64_t c0 = w; c0 < nch; c0 += 8 * NW) {
+            T v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int64_t i = (c0 + (int64_t)u * NW) * RP_CHUNK + lane;
+                v[u] = i < m ? dmmv_abs(r[i]) : (T)0;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int64_t c = c0 + (int64_t)u * NW;
+                if (c < nch) {
+                    const T cm = wave_max(v[u]);
+                    if (lane == 0) { sh_cmax[c] = cm; sh_isdirty[c] = 0u; }
+                }
+            }
+        }
+        for (int64_t q = threadIdx.x; q < (nch * RP_CHUNK + 31) / 32; q += RP_BLOCK) sh_rowbit[q] = 0u;
+        if (threadIdx.x == 0) sh_ndirty = 0;
+        __syncthreads();
+    }
+    const bool mine = (int32_t)threadIdx.x < stride;
+    // entry of the first pick
+    int32_t row_n = -1;
+    T a_n = (T)0;
+    if (mine && count > 0) { row_n = g_row[threadIdx.x]; a_n = g_val[threadIdx.x]; }
+    int32_t kc_n = count > 0 ? kidx[picked[0]] : 0;
+    for (int32_t pos = 0; pos < count; ++pos) {
+        const int64_t j = picked[pos];
+        const int32_t kc = kc_n;
+        const int32_t row = row_n;
+        const T a = a_n;
+        const bool real = row >= 0;
+        const bool has_lo = kc > 0, has_hi = kc < nd - 1;
+        const bool evaluate = greedy && has_lo && has_hi;
+        const T ri = real ? r[row] : (T)0;
+        if (greedy && real) {
+            atomicOr(&sh_rowbit[row >> 5], 1u << (row & 31));
+            const int32_t c = row / RP_CHUNK;
+            if (atomicExch(&sh_isdirty[c], 1u) == 0u) sh_dirty[atomicAdd(&sh_ndirty, 1)] = c;
+        }
+        if (greedy) __syncthreads();
+        // largest |r| outside the column: row-by-row look at the chunks it touches
+        T rest = (T)0;
+        if (greedy) {
+            const int32_t ndirty = sh_ndirty;
+            for (int32_t d0 = w; d0 < ndirty; d0 += 8 * NW) {
+                T v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int32_t d = d0 + u * NW;
+                    T val = (T)0;
+                    if (d < ndirty) {
+                        const int64_t i = (int64_t)sh_dirty[d] * RP_CHUNK + lane;
+                        const bool in_col = (sh_rowbit[i >> 5] >> (i & 31)) & 1u;
+                        if (i < m && !in_col) val = dmmv_abs(r[i]);
+                    }
+                    v[u] = val;
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int32_t d = d0 + u * NW;
+                    if (d < ndirty) {                       // uniform per wavefront
+                        const T um = wave_max(v[u]);
+                        rest = dmmv_max(rest, um);
+                        if (lane == 0) sh_cmax[sh_dirty[d]] = um;   // the column's rows join below
+                    }
+                }
+            }
+        }
+        // the next pick's entries: requested after the loads this step waits for
+        if (pos + 1 < count) {
+            if (mine) { row_n = g_row[(int64_t)(pos + 1) * stride + threadIdx.x]; a_n = g_val[(int64_t)(pos + 1) * stride + threadIdx.x]; }
+            kc_n = kidx[picked[pos + 1]];
+        }
+        int32_t knew;
+        if (evaluate) {
+            for (int64_t c = threadIdx.x; c < nch; c += RP_BLOCK)
+                if (sh_isdirty[c] == 0u) rest = dmmv_max(rest, sh_cmax[c]);
+            const T dlo = step_of(D[kc - 1], D[kc], (T)1), dhi = step_of(D[kc + 1], D[kc], (T)1);
+            T elo = rest, ehi = rest;
+            if (real) {
+                elo = dmmv_max(elo, dmmv_abs(dmmv_fma(dlo, a, ri)));
+                ehi = dmmv_max(ehi, dmmv_abs(dmmv_fma(dhi, a, ri)));
+            }
+            elo = wave_max(elo);
+            ehi = wave_max(ehi);
+            if (lane == 0) { sh_pair[w][0] = elo; sh_pair[w][1] = ehi; }
+            __syncthreads();
+            elo = sh_pair[0][0];
+            ehi = sh_pair[0][1];
+#pragma unroll
+            for (int u = 1; u < NW; ++u) { elo = dmmv_max(elo, sh_pair[u][0]); ehi = dmmv_max(ehi, sh_pair[u][1]); }
+            knew = ehi < elo ? kc + 1 : kc - 1;
+        } else {
+            if (has_lo && has_hi) knew = (alns_rnd(seed, inst, (uint64_t)it, 2, (uint64_t)pos) & 1) ? kc + 1 : kc - 1;
+            else knew = has_lo ? kc - 1 : kc + 1;
+            if (greedy) __syncthreads();                    // the chunk maxima written above are in place
+        }
+        // reassign: r follows; greedy: the touched chunks take in the new residuals, the marks go
+        const T delta = step_of(D[knew], D[kc], (T)1);
+        if (real) {
+            const T nv = dmmv_fma(delta, a, ri);
+            r[row] = nv;
+            if (greedy) {
+                const int32_t c = row / RP_CHUNK;
+                // |.| >= 0: the bit patterns order like the values
+                if constexpr (sizeof(T) == 4)
+                    atomicMax(reinterpret_cast<unsigned int*>(&sh_cmax[c]), __float_as_uint(dmmv_abs(nv)));
+                else
+                    atomicMax(reinterpret_cast<unsigned long long*>(&sh_cmax[c]), (unsigned long long)__double_as_longlong(dmmv_abs(nv)));
+                atomicAnd(&sh_rowbit[row >> 5], ~(1u << (row & 31)));
+                sh_isdirty[c] = 0u;
+            }
+        }
+        if (threadIdx.x == 0) { kidx[j] = knew; sh_ndirty = 0; }
+        __syncthreads();                                     // r, kidx and the tables are settled
+    }
+    T tmax = (T)0;
+    if (greedy) {
+        for (int64_t c = threadIdx.x; c < nch; c += RP_BLOCK) tmax = dmmv_max(tmax, sh_cmax[c]);
+    } else {
+        for (int64_t i = threadIdx.x; i < m; i += RP_BLOCK) tmax = dmmv_max(tmax, dmmv_abs(r[i]));
+    }
+    tmax = block_max(tmax, sh);
+    if (threadIdx.x == 0) { st[0].t = tmax; st[0].done = 0; st[0].moves = 0; }
+}
+
 // after a rejected iteration r was restored: the reservoir has to follow
 template <class T>
 __global__ __launch_bounds__(1024) void k_reservoir_build_if_rejected(int64_t m, const T* r, T* res_val,
@@ -642,14 +838,30 @@ static dmmv_status alns_impact_t(Ctx* c, double alpha) {
 
 template <class T>
 static dmmv_status alns_repair_t(Ctx* c, int32_t count, uint64_t seed) {
-    if (c->p.m > 0)
-        hipLaunchKernelGGL(k_alns_clear_touched, dim3((unsigned)ceil_div(c->p.m, 256)), dim3(256), 0, c->stream,
-                           c->p.m, c->alns_touched);
-    hipLaunchKernelGGL(k_alns_repair_cscp<T>, dim3(1), dim3(1024), 0, c->stream, c->p.m, c->p.n, c->p.nd,
-                       c->csc_mp, c->csc_P, (const int32_t*)c->segptr, (const uint16_t*)c->row16,
-                       (const T*)c->cval, (const T*)c->D_dev, (T*)c->r, c->kidx, count,
-                       (const int32_t*)c->alns_picked, c->alns_touched, (InstState<T>*)c->state,
-                       (const AlnsState*)c->alns_state, seed, (uint64_t)0);
+    // where the tables and the scratch array fit: gather the picked columns, then the kernel
+    // without dependent loads; else the general kernel
+    const int32_t stride = (int32_t)(ceil_div(c->csc_max_col > 0 ? c->csc_max_col : 1, 64) * 64);
+    const bool fast = ceil_div(c->p.m, RP_CHUNK) <= RP_MAXCHUNKS && stride <= RP_BLOCK &&
+                      (int64_t)count * stride <= RP_GATHER_CAP && c->alns_g_row && c->alns_g_val;
+    if (fast) {
+        if (count > 0)
+            hipLaunchKernelGGL(k_alns_gather<T>, dim3((unsigned)count), dim3(128), 0, c->stream, c->p.n, c->csc_mp,
+                               c->csc_P, stride, (const int32_t*)c->segptr, (const uint16_t*)c->row16,
+                               (const T*)c->cval, (const int32_t*)c->alns_picked, c->alns_g_row, (T*)c->alns_g_val);
+        hipLaunchKernelGGL(k_alns_repair_gathered<T>, dim3(1), dim3(RP_BLOCK), 0, c->stream, c->p.m, c->p.nd, stride,
+                           (const int32_t*)c->alns_g_row, (const T*)c->alns_g_val, (const T*)c->D_dev, (T*)c->r,
+                           c->kidx, count, (const int32_t*)c->alns_picked, (InstState<T>*)c->state,
+                           (const AlnsState*)c->alns_state, seed, (uint64_t)0);
+    } else {
+        if (c->p.m > 0)
+            hipLaunchKernelGGL(k_alns_clear_touched, dim3((unsigned)ceil_div(c->p.m, 256)), dim3(256), 0, c->stream,
+                               c->p.m, c->alns_touched);
+        hipLaunchKernelGGL(k_alns_repair_cscp_general<T>, dim3(1), dim3(1024), 0, c->stream, c->p.m, c->p.n, c->p.nd,
+                           c->csc_mp, c->csc_P, (const int32_t*)c->segptr, (const uint16_t*)c->row16,
+                           (const T*)c->cval, (const T*)c->D_dev, (T*)c->r, c->kidx, count,
+                           (const int32_t*)c->alns_picked, c->alns_touched, (InstState<T>*)c->state,
+                           (const AlnsState*)c->alns_state, seed, (uint64_t)0);
+    }
     DMMV_LAUNCH_CHECK();
     return reservoir_t<T>(c);
 }
