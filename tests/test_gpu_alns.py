@@ -225,3 +225,10 @@ def test_alns_l2_guard_sparse_and_batched():
 def test_alns_batched_with_the_matrix_core_evaluation():
     batched_alns_check(random_batched(7940, 70, 24, 20, 4), 8, ls_moves=3, ls_swaps=1, destroy_count=3, seed=2,
                        batched_eval=2)
+
+
+def test_alns_sparse_general_repair_kernel():
+    # a column longer than the gathered kernel takes (1024 entries), and more rows than its tables
+    # hold (131072): both fall back to the general repair kernel
+    alns_check(random_sparse(7950, 1400, 20, 3, density=0.9), 8, ls_moves=2, destroy_count=5, seed=4)
+    alns_check(random_sparse(7951, 140000, 24, 4, density=0.002), 6, ls_moves=2, destroy_count=6, seed=5)
