@@ -409,6 +409,124 @@ __global__ __launch_bounds__(64) void k_eval_pruned_csc(
     if (lane == 0) part[blockIdx.x] = rec;
 }
 
+// The same records with fewer trips to memory, for columns of at most 64 * PR_SLOTS entries
+// (padding included).  The kernel above is a chain of some fourteen dependent accesses (row of
+// largest |r| -> its entries -> segment bounds -> binary searches for the reservoir rows ->
+// current value -> entries -> residuals); a wavefront that has nothing else to do pays each of
+// them in full.  Here a lane keeps up to PR_SLOTS entries of the column (row, value, residual)
+// and two reservoir rows in registers, so whether a reservoir row is in the column is a
+// comparison across lanes, and what remains is six dependent accesses.
+constexpr int PR_SLOTS = 8;
+
+template <class T>
+__global__ __launch_bounds__(64) void k_eval_pruned_csc_reg(
+    int64_t m, int64_t n, int32_t nd, int32_t mp, int32_t P, const int64_t* __restrict__ csr_rowptr,
+    const int32_t* __restrict__ csr_col, const int32_t* __restrict__ segptr,
+    const uint16_t* __restrict__ row16, const T* __restrict__ cval, const T* __restrict__ D,
+    const int32_t* __restrict__ kidx, const T* __restrict__ r, const T* __restrict__ res_val,
+    const int32_t* __restrict__ res_row, const int32_t* __restrict__ res_meta, int32_t radius,
+    const uint8_t* __restrict__ var_mask, const InstState<T>* __restrict__ st, int32_t honor_done,
+    Partial<T>* __restrict__ part) {
+    constexpr int KT = 8;
+    static_assert(RES_CAP <= 128, "two reservoir entries per lane");
+    const int lane = threadIdx.x;
+    // 1: everything that depends on nothing
+    const int32_t done = st[0].done;
+    const int32_t cnt = res_meta[RES_CNT];
+    const int32_t rr0 = res_row[lane], rr1 = res_row[lane + 64];      // RES_CAP = 128 entries exist
+    const T rv0 = res_val[lane], rv1 = res_val[lane + 64];
+    if (honor_done && done) return;
+    Partial<T> rec; rec.s = (T)0; rec.c = -1;
+    int64_t j = -1;
+    if (cnt > 0) {
+        const int64_t istar = __builtin_amdgcn_readfirstlane(rr0);
+        const int64_t e = csr_rowptr[istar] + blockIdx.x;                   // 2
+        if (e < csr_rowptr[istar + 1]) j = csr_col[e];                      // 3
+    }
+    if (j < 0) {                                   // no such entry: an empty record
+        if (lane == 0) part[blockIdx.x] = rec;
+        return;
+    }
+    // 4: the segment bounds and the current value; a lane's slots are entries lane, lane + 64, ...
+    const int32_t kcur = kidx[j];
+    int32_t ent[PR_SLOTS], part_of[PR_SLOTS];
+#pragma unroll
+    for (int u = 0; u < PR_SLOTS; ++u) { ent[u] = -1; part_of[u] = 0; }
+    {
+        int32_t base = 0;
+        for (int32_t p = 0; p < P; ++p) {
+            const int32_t e0 = segptr[(int64_t)p * n + j], len = segptr[(int64_t)p * n + j + 1] - e0;
+#pragma unroll
+            for (int u = 0; u < PR_SLOTS; ++u) {
+                const int32_t t = lane + 64 * u - base;
+                if (t >= 0 && t < len) { ent[u] = e0 + t; part_of[u] = p; }
+            }
+            base += len;
+        }
+    }
+    // 5: entries, current value of D;  6: residuals
+    int32_t row[PR_SLOTS];
+    T a[PR_SLOTS], ri[PR_SLOTS];
+#pragma unroll
+    for (int u = 0; u < PR_SLOTS; ++u) {
+        row[u] = -1;
+        a[u] = (T)0;
+        if (ent[u] >= 0) {
+            const uint32_t loc = row16[ent[u]];
+            if (loc != (uint32_t)mp) { row[u] = part_of[u] * mp + (int32_t)loc; a[u] = cval[ent[u]]; }
+        }
+    }
+    const T dcur = D[kcur];
+#pragma unroll
+    for (int u = 0; u < PR_SLOTS; ++u) ri[u] = row[u] >= 0 ? r[row[u]] : (T)0;
+    // maximum over the rows outside column j: first reservoir row the column does not hold
+    T outside = (T)0;
+    {
+        int32_t first = -1;
+        for (int32_t q = 0; q < cnt; ++q) {
+            const int32_t want = q < 64 ? __builtin_amdgcn_readlane(rr0, q) : __builtin_amdgcn_readlane(rr1, q - 64);
+            bool hit = false;
+#pragma unroll
+            for (int u = 0; u < PR_SLOTS; ++u) hit = hit || row[u] == want;
+            if (!__any(hit)) { first = q; break; }
+        }
+        if (first >= 0) {
+            outside = first < 64 ? read_lane(rv0, first) : read_lane(rv1, first - 64);
+        } else if ((int64_t)cnt < m) {             // the column holds the whole reservoir: exact scan
+            T o = (T)0;
+            for (int64_t i = lane; i < m; i += 64)
+                if (!column_has_row<T>(segptr, row16, n, mp, j, (int32_t)i)) o = dmmv_max(o, dmmv_abs(r[i]));
+            outside = wave_max(o);
+        }
+    }
+    const bool var_ok = var_mask ? var_mask[j] != 0 : true;
+    for (int32_t k0 = 0; k0 < nd; k0 += KT) {
+        T delta[KT], acc[KT];
+#pragma unroll
+        for (int q = 0; q < KT; ++q) {
+            delta[q] = step_of(D[k0 + q < nd ? k0 + q : nd - 1], dcur, (T)1);
+            acc[q] = (T)0;
+        }
+#pragma unroll
+        for (int u = 0; u < PR_SLOTS; ++u)
+            if (row[u] >= 0) {
+#pragma unroll
+                for (int q = 0; q < KT; ++q) acc[q] = dmmv_max(acc[q], dmmv_abs(dmmv_fma(delta[q], a[u], ri[u])));
+            }
+#pragma unroll
+        for (int q = 0; q < KT; ++q) {
+            const int32_t k = k0 + q;
+            T v = dmmv_max(wave_max(acc[q]), outside);
+            if (k < nd) {
+                if (!cand_allowed(kcur, k, radius, var_ok)) v = Limits<T>::inf();
+                const int64_t cidx = j * (int64_t)nd + k;
+                if (rec_less(v, cidx, rec.s, rec.c)) { rec.s = v; rec.c = cidx; }
+            }
+        }
+    }
+    if (lane == 0) part[blockIdx.x] = rec;
+}
+
 // =========================================================================================
 // host dispatch
 // =========================================================================================
@@ -466,7 +584,9 @@ dmmv_status csc_eval(Ctx* c, void* scores_out, bool want_partials, bool honor_do
 template <class T>
 static dmmv_status eval_pruned_t(Ctx* c, bool honor_done) {
     if (c->csc_max_row <= 0) return DMMV_OK;       // no stored entry anywhere: nothing can move r
-    hipLaunchKernelGGL(k_eval_pruned_csc<T>, dim3((unsigned)c->csc_max_row), dim3(64), 0, c->stream, c->p.m,
+    // short columns: the variant that keeps the column in registers
+    auto kernel = c->csc_max_col <= 64 * PR_SLOTS ? k_eval_pruned_csc_reg<T> : k_eval_pruned_csc<T>;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)c->csc_max_row), dim3(64), 0, c->stream, c->p.m,
                        c->p.n, c->p.nd, c->csc_mp, c->csc_P, c->p.csr_rowptr, c->p.csr_col,
                        (const int32_t*)c->segptr, (const uint16_t*)c->row16, (const T*)c->cval,
                        (const T*)c->D_dev, (const int32_t*)c->kidx, (const T*)c->r, (const T*)c->res_val,

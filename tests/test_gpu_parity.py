@@ -639,7 +639,7 @@ def test_batched_mfma_not_applicable_is_an_error():
 
 
 # ------------------------------------------------------------- pruned descent on sparse matrices
-@pytest.mark.parametrize("case", ["ties", "full_columns", "long", "tomography", "tiny", "one_column"])
+@pytest.mark.parametrize("case", ["ties", "full_columns", "long", "tomography", "tiny", "one_column", "long_columns"])
 def test_sparse_pruned_descent_applies_the_same_moves(case):
     """options.prune scores only the columns that touch the row of largest |r|; whenever an
     improving move exists it is among them, so the whole trace must equal the oracle's."""
@@ -656,6 +656,9 @@ def test_sparse_pruned_descent_applies_the_same_moves(case):
     elif case == "tomography":
         inst = make_config(3, "small")
         iters, kw = inst.iters, {}
+    elif case == "long_columns":
+        # columns of more entries than a wavefront keeps in registers: the other kernel variant
+        inst, iters, kw = random_sparse(978, 900, 30, 4, density=0.8, dtype=np.float32), 30, dict(sparse_partition_rows=300)
     elif case == "tiny":
         inst, iters, kw = random_sparse(12, 1, 1, 2, density=1.0, dtype=np.float64), 5, {}
     else:
