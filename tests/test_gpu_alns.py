@@ -232,3 +232,18 @@ def test_alns_sparse_general_repair_kernel():
     # hold (131072): both fall back to the general repair kernel
     alns_check(random_sparse(7950, 1400, 20, 3, density=0.9), 8, ls_moves=2, destroy_count=5, seed=4)
     alns_check(random_sparse(7951, 140000, 24, 4, density=0.002), 6, ls_moves=2, destroy_count=6, seed=5)
+
+
+def test_alns_dense_all_options_together():
+    # value search in the local search, swaps after it, the l2 guard in the acceptance step
+    m = dmmv()
+    inst = random_dense(7960, 200, 24, 40, dtype=np.float64)
+    kw = dict(ls_moves=3, ls_swaps=2, destroy_count=4, seed=12, l2_guard=1, k_eps=8)
+    o = orc.alns_dense(inst.A, inst.b, inst.D, inst.x0, orc.alns_params(25, **kw))
+    with m.from_instance(inst, DEV, value_search=True) as h:
+        res = m.dmmv_alns(h, T(inst.x0), 25, **kw)
+    tr, tt = N(res.trace), N(res.trace_t)
+    assert np.array_equal(tr[:, 0], o.destroy) and np.array_equal(tr[:, 1], o.repair)
+    assert np.array_equal(tr[:, 2], o.moves) and np.array_equal(tr[:, 3], o.accepted)
+    assert np.array_equal(tt[:, 0], o.t) and np.array_equal(tt[:, 1], o.best)
+    assert np.array_equal(N(res.x_best), o.x) and N(res.t_best)[0] == o.t_best
