@@ -288,10 +288,21 @@ __global__ __launch_bounds__(256) void k_alns_impact_batched(int64_t m, int64_t 
     const double sc = (double)scale_q[qc];
     int shift = alns_bits(m) + 24 + alns_bits(n) - 62;
     if (shift < 0) shift = 0;
+    const float pre = (float)(18.0 / alpha * 1.01);
+    const float tf = (float)t, scf = (float)sc;             // exact for fp32 problems
     for (int64_t j = blockIdx.y * 4ll + w; j < n; j += 4ll * gridDim.y) {
         uint64_t sum = 0;
         if (live && scale != 0.0) {
             for (int64_t i = 0; i < m; ++i) {
+                if constexpr (sizeof(T) == 4) {
+                    // Most terms truncate to 0 (alns_impact_term: slack > a * 18 / alpha).  In fp32 that
+                    // is decided first, with a margin of 1 % that covers the roundings of the three
+                    // fp32 operations, so the double-precision arithmetic runs only for the terms
+                    // that may count.
+                    const float af = __builtin_fabsf(scf * (float)Xt[i * n + j]);
+                    const float slack = tf - __builtin_fabsf((float)r[i * R + qc]);
+                    if (slack > af * pre) continue;
+                }
                 const double a = __builtin_fabs(sc * (double)Xt[i * n + j]);
                 sum += alns_impact_term(a, __builtin_fabs((double)r[i * R + qc]), t, alpha, scale);
             }
