@@ -9,6 +9,7 @@ index vector the C code uses; a value that is not in D raises ValueError.
 from __future__ import annotations
 
 import ctypes as C
+import os
 from dataclasses import dataclass
 from typing import Optional
 
@@ -22,7 +23,9 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        _lib = C.CDLL(_build.build())
+        # DMMV_ORACLE_LIB: another build of this library (the mutation tests load deliberately
+        # broken ones to see that the pins catch them)
+        _lib = C.CDLL(os.environ.get("DMMV_ORACLE_LIB") or _build.build())
         _lib.oracle_num_threads.restype = C.c_int
         for s in ("f32", "f64"):
             real = C.c_float if s == "f32" else C.c_double

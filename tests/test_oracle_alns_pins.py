@@ -100,19 +100,39 @@ def test_impact_weight_ignores_rows_with_zero_coefficient_and_handles_zero_resid
     assert np.array_equal(w_full, w_sparse)
 
 
+def test_sample_takes_the_variable_whose_interval_of_the_prefix_sums_holds_the_draw():
+    """Draw c of an iteration is v = rnd(seed, inst, it, 1, c) mod total; it names the first
+    variable whose inclusive prefix sum exceeds v, and a variable already taken is drawn again."""
+    w = np.array([5, 1, 10, 4], dtype=np.uint64)
+    prefix = np.cumsum(w.astype(np.int64))
+    on_a_boundary = 0
+    for it in range(60):
+        v = orc.alns_rnd(11, 2, it, 1, 0) % 20
+        on_a_boundary += int(v in (5, 6, 16))
+        want = int(np.searchsorted(prefix, v, side="right"))
+        assert orc.alns_sample(4, w, 1, 11, 2, it)[0] == want
+    assert on_a_boundary > 0                               # v equal to a prefix sum was among them
+    # equal weights: variable = v mod n, repeats skipped, in draw order
+    n = 9
+    for it in range(10):
+        want, c = [], 0
+        while len(want) < 4:
+            j = int(orc.alns_rnd(8, 1, it, 1, c) % n)
+            c += 1
+            if j not in want:
+                want.append(j)
+        assert orc.alns_sample(n, None, 4, 8, 1, it).tolist() == want
+        assert orc.alns_sample(n, np.ones(n, dtype=np.uint64), 4, 8, 1, it).tolist() == want
+
+
 def test_sample_distinct_ordered_and_proportional():
     n = 50
     p = orc.alns_sample(n, None, n, 3, 0, 0)
     assert sorted(p.tolist()) == list(range(n))            # all of them: a permutation
     p = orc.alns_sample(n, None, 7, 3, 0, 1)
     assert len(set(p.tolist())) == 7 and p.min() >= 0 and p.max() < n
-    # the first draw is the first variable whose prefix sum exceeds rnd mod total
-    w = np.array([5, 1, 10, 4], dtype=np.uint64)
-    for it in range(20):
-        v = orc.alns_rnd(11, 2, it, 1, 0) % 20
-        want = int(np.searchsorted(np.cumsum(w.astype(np.int64)), v, side="right"))
-        assert orc.alns_sample(4, w, 1, 11, 2, it)[0] == want
     # frequencies of single draws follow the weights
+    w = np.array([5, 1, 10, 4], dtype=np.uint64)
     counts = np.zeros(4)
     N = 6000
     for it in range(N):
@@ -120,6 +140,20 @@ def test_sample_distinct_ordered_and_proportional():
     expect = N * w.astype(np.float64) / 20
     chi2 = ((counts - expect) ** 2 / expect).sum()
     assert chi2 < 16.3                                     # 99.9 % point of chi-square with 3 dof
+
+
+def test_greedy_repair_moves_down_when_both_neighbours_score_the_same():
+    """A column of zeros: either neighbour leaves the residual as it is, so the errors tie and
+    the lower level is taken; at the lowest level only the upper neighbour exists."""
+    A = np.array([[1.0, 0.0, 0.0], [2.0, 0.0, 0.0]])
+    rowptr, col, val = orc.full_csr(A)
+    D = np.array([-1.0, 0.0, 1.0, 2.0])
+    x = np.array([1.0, 1.0, -1.0])
+    b = np.array([0.5, 0.25])
+    r = orc.residual_dense(A, b, D, x)
+    x_new, r_new = orc.alns_repair(2, 3, rowptr, col, val, D, x, r, np.array([1, 2], dtype=np.int32), True, 1, 0, 0)
+    assert x_new.tolist() == [1.0, 0.0, 0.0]
+    assert np.array_equal(r_new, r)
 
 
 def test_greedy_repair_is_the_better_of_the_two_neighbour_levels():
@@ -199,6 +233,103 @@ def test_alns_loop_invariants(kind, dtype):
     other = orc.alns_csr(inst.m, inst.n, rowptr, col, val, inst.b, inst.D, inst.x0,
                          orc.alns_params(40, ls_moves=6, ls_radius=1, destroy_count=3, seed=6))
     assert not np.array_equal(other.t, res.t)
+
+
+def test_operator_choice_and_weights_replayed_from_the_trace():
+    """Roulette wheel and weight update of the appendix on parameter setting, replayed outside the
+    oracle from its trace: operator 0 of a pair is taken when u (w0 + w1) < w0 with u =
+    (rnd >> 11) 2^-53 of stream 0, and an accepted iteration moves the two chosen weights to
+    (1 - lambda) w + lambda psi, psi = sigma1 for a new best and sigma3 otherwise (with this
+    acceptance rule the current solution is always a best one, so sigma2 never applies)."""
+    inst = random_dense(507, 30, 12, 5, integer=True)
+    rowptr, col, val = orc.full_csr(inst.A)
+    lam, s1, s2, s3 = 0.35, 5.0, 2.5, 0.25
+    iters = 60
+    prm = orc.alns_params(iters, ls_moves=4, ls_radius=1, destroy_count=2, lambda_=lam, sigma1=s1, sigma2=s2,
+                          sigma3=s3, seed=9)
+    res = orc.alns_csr(inst.m, inst.n, rowptr, col, val, inst.b, inst.D, inst.x0, prm, inst=4)
+    w = [1.0, 1.0, 1.0, 1.0]
+    best = np.abs(inst.A.astype(np.float64) @ inst.x0 - inst.b).max()
+    seen = set()
+    for it in range(iters):
+        ud = (orc.alns_rnd(9, 4, it, 0, 0) >> 11) * 2.0 ** -53
+        ur = (orc.alns_rnd(9, 4, it, 0, 1) >> 11) * 2.0 ** -53
+        d_op = 0 if ud * (w[0] + w[1]) < w[0] else 1
+        r_op = 0 if ur * (w[2] + w[3]) < w[2] else 1
+        assert (res.destroy[it], res.repair[it]) == (d_op, r_op)
+        if res.accepted[it]:
+            psi = s1 if res.t[it] < best else s3
+            seen.add(psi)
+            best = min(best, res.t[it])
+            w[d_op] = (1 - lam) * w[d_op] + lam * psi
+            w[2 + r_op] = (1 - lam) * w[2 + r_op] + lam * psi
+        assert res.best[it] == best
+    assert seen == {s1, s3}
+    assert np.allclose(res.weights, w, rtol=1e-14, atol=0)
+    # far from 1/2 the choice is that of u alone: u < 1/2 takes operator 0 at the first iteration
+    for seed in range(12):
+        one = orc.alns_csr(inst.m, inst.n, rowptr, col, val, inst.b, inst.D, inst.x0,
+                           orc.alns_params(1, ls_moves=1, destroy_count=1, seed=seed))
+        u = (orc.alns_rnd(seed, 0, 0, 0, 0) >> 11) * 2.0 ** -53
+        assert one.destroy[0] == (0 if u < 0.5 else 1)
+
+
+def test_the_returned_solution_is_the_first_one_that_reached_the_best_error():
+    """Algorithm 1 replaces the best solution only by a strictly better one: iterations that are
+    accepted with an equal error move the current solution, not the returned one."""
+    inst = random_dense(508, 24, 10, 4, integer=True)
+    rowptr, col, val = orc.full_csr(inst.A)
+    found = 0
+    for seed in range(6):
+        full = orc.alns_csr(inst.m, inst.n, rowptr, col, val, inst.b, inst.D, inst.x0,
+                            orc.alns_params(50, ls_moves=3, destroy_count=2, seed=seed))
+        t0 = np.abs(inst.A.astype(np.float64) @ inst.x0 - inst.b).max()
+        improving = [it for it in range(50) if full.best[it] < (full.best[it - 1] if it else t0)]
+        last = improving[-1] + 1 if improving else 0
+        later_equal = [it for it in range(last, 50) if full.accepted[it]]
+        short = orc.alns_csr(inst.m, inst.n, rowptr, col, val, inst.b, inst.D, inst.x0,
+                             orc.alns_params(last, ls_moves=3, destroy_count=2, seed=seed))
+        assert np.array_equal(full.x, short.x)
+        found += len(later_equal) > 0
+    assert found > 0                                       # some run did accept equal errors afterwards
+
+
+def test_greedy_repair_counts_the_rows_outside_the_column():
+    """The error of a candidate level is the maximum over ALL rows.  Here a row the variable does
+    not appear in dominates both candidates, they tie, and the lower level is taken - although
+    the upper level is better on the variable's own row."""
+    rowptr = np.array([0, 1, 2], dtype=np.int64)           # A = identity, stored sparse
+    col = np.array([0, 1], dtype=np.int32)
+    val = np.array([1.0, 1.0])
+    D = np.array([-1.0, 0.0, 1.0])
+    x = np.array([0.0, 1.0])
+    b = np.array([1.0, -9.0])                              # r = (-1, 10)
+    r = x - b
+    x_new, r_new = orc.alns_repair(2, 2, rowptr, col, val, D, x, r, np.array([0], dtype=np.int32), True, 1, 0, 0)
+    assert x_new.tolist() == [-1.0, 1.0] and r_new.tolist() == [-2.0, 10.0]
+    # without the dominating row the upper level wins
+    b2 = np.array([1.0, 1.0])
+    x_new, _ = orc.alns_repair(2, 2, rowptr, col, val, D, x, x - b2, np.array([0], dtype=np.int32), True, 1, 0, 0)
+    assert x_new.tolist() == [1.0, 1.0]
+
+
+def test_impact_weights_of_a_huge_matrix_are_shifted_to_keep_their_total_below_2_to_the_62():
+    """m = 2^20 rows and n = 2^19 columns: 21 + 24 + 20 bits could reach 2^65, so every weight is
+    1 + (sum >> 3).  Entries on rows that attain the largest violation have slack 0 and add
+    trunc(t 2^24 / 2^e) each."""
+    m, n = 1 << 20, 1 << 19
+    r = np.zeros(m)
+    t = 12582913 / 2.0 ** 24                               # 0.75 + 2^-24: frexp exponent 0
+    r[5] = t
+    r[77] = -t
+    rows = np.array([5, 5, 77], dtype=np.int64)
+    cols = np.array([3, 9, 9], dtype=np.int32)
+    rowptr = np.zeros(m + 1, dtype=np.int64)
+    np.add.at(rowptr, rows + 1, 1)
+    rowptr = np.cumsum(rowptr)
+    w = orc.alns_impact_weights(m, n, rowptr, cols, np.array([2.0, -1.0, 0.5]), r, alpha=0.3)
+    assert w[3] == 1 + (12582913 >> 3) and w[9] == 1 + ((2 * 12582913) >> 3)
+    assert w[0] == 1 and int(w.sum()) == n + (12582913 >> 3) + ((2 * 12582913) >> 3)
 
 
 def test_alns_zero_iterations_and_lower_bound_by_enumeration():

@@ -104,6 +104,31 @@ def test_best_swap_is_the_lowest_pair_among_the_smallest_errors():
         assert (i, j) == (-1, -1) and tn == t
 
 
+def test_a_swap_that_leaves_the_error_unchanged_is_not_taken():
+    """Two equal columns at different levels: exchanging them changes nothing, t' = t, and only
+    t' < t counts (Algorithm 2)."""
+    A = np.array([[1.0, 1.0], [-2.0, -2.0], [0.5, 0.5]])
+    D = np.array([-1.0, 0.0, 1.0])
+    x = np.array([1.0, -1.0])
+    b = np.array([0.25, 0.5, -0.75])
+    r = oracle.residual_dense(A, b, D, x)
+    assert oracle.swap_table_dense(A, D, x, r)[0, 1] == np.max(np.abs(r))
+    assert oracle.best_swap_dense(A, D, x, r) == (-1, -1, np.max(np.abs(r)))
+
+
+def test_equal_improvements_go_to_the_lowest_pair():
+    """Columns 1 and 2 are both zero and both at the lowest level: exchanging column 0 with either
+    gives the same t' = 0 < t; the pair with the lower index i * n + j is the one returned."""
+    A = np.array([[1.0, 0.0, 0.0]])
+    D = np.array([-1.0, 0.0, 1.0])
+    x = np.array([1.0, -1.0, -1.0])
+    b = np.array([-1.0])
+    r = oracle.residual_dense(A, b, D, x)
+    tab = oracle.swap_table_dense(A, D, x, r)
+    assert tab[0, 1] == 0.0 and tab[0, 2] == 0.0 and np.max(np.abs(r)) == 2.0
+    assert oracle.best_swap_dense(A, D, x, r) == (0, 1, 0.0)
+
+
 def test_identity_matrix_closed_form():
     """A = I: only rows i and j change, s'_i = x_j - b_i and s'_j = x_i - b_j."""
     rng = np.random.default_rng(5)
