@@ -487,6 +487,7 @@ static dmmv_status select_apply_any(Ctx* c, int32_t iters, dmmv_move* trace, voi
 }
 
 static dmmv_status loop_step(Ctx* c, int32_t iters, dmmv_move* trace, void* trace_t) {
+    if (batched_pruned_applicable(c)) return batched_descent_pruned(c, 1, iters, trace, trace_t);
     if (c->kind == KIND_CSC && c->o.prune && !c->o.keep_going && c->p.n > 0) {
         DMMV_TRY(csc_eval_pruned(c, true));
         return csc_select_apply(c, iters, trace, trace_t, true);
@@ -559,9 +560,12 @@ static dmmv_status solve_t(dmmv_ctx* c, const void* x0, int32_t iters, void* x_o
     int32_t poll = c->o.keep_going ? 0 : c->o.poll_every;
     // a batch drops its stopped instances at the polling points (their wavefronts would
     // otherwise keep running for the sake of a few neighbours), so it polls more often
-    const bool compacting = c->kind == KIND_BATCHED && poll > 0 && !c->o.var_mask;
+    const bool pruned_batch = batched_pruned_applicable(c);
+    const bool compacting = c->kind == KIND_BATCHED && poll > 0 && !c->o.var_mask && !pruned_batch;
     if (compacting && poll > 8) poll = 8;
     dmmv_status loop_st = [&]() -> dmmv_status {
+        // a pruned batch runs all its iterations in one launch; every instance stops by itself
+        if (pruned_batch) return batched_descent_pruned(c, iters, iters, trace, trace_t);
         for (int32_t it = 0; it < iters; ++it) {
             DMMV_TRY(loop_step(c, iters, trace, trace_t));
             if (poll > 0 && (it + 1) % poll == 0 && it + 1 < iters) {
@@ -614,8 +618,10 @@ static dmmv_status alns_run(dmmv_ctx* c, const void* x0, const dmmv_alns_params&
         DMMV_TRY(alns_start(c, prm.l2_guard != 0));
         for (int32_t it = 0; it < prm.iters; ++it) {
             DMMV_TRY(alns_destroy_repair(c, prm, it, (int32_t)count));
-            for (int32_t mv = 0; mv < prm.ls_moves; ++mv) {
-                DMMV_TRY(loop_step(c, prm.ls_moves, nullptr, nullptr));
+            if (batched_pruned_applicable(c)) {
+                DMMV_TRY(batched_descent_pruned(c, prm.ls_moves, prm.ls_moves, nullptr, nullptr));
+            } else {
+                for (int32_t mv = 0; mv < prm.ls_moves; ++mv) DMMV_TRY(loop_step(c, prm.ls_moves, nullptr, nullptr));
             }
             if (prm.ls_swaps > 0) {
                 DMMV_TRY(swap_clear_skip(c));

@@ -243,6 +243,10 @@ dmmv_status batched_get_r(Ctx* c, void* r);
 dmmv_status batched_maxabs(Ctx* c);     // state[q].t = max_i |r[i][q]|
 dmmv_status batched_compact(Ctx* c, int32_t* active_out);   // polling point of the descent
 dmmv_status batched_compact_end(Ctx* c);
+// options.prune on a batch: `steps` iterations of the descent for every instance in one launch,
+// same moves as evaluation + selection + apply (an instance stops at its local optimum)
+bool batched_pruned_applicable(const Ctx* c);
+dmmv_status batched_descent_pruned(Ctx* c, int32_t steps, int32_t iters, dmmv_move* trace, void* trace_t);
 
 // ----------------------------------------------------------------------------------------
 // device helpers

@@ -134,7 +134,7 @@ def test_alns_same_seed_same_run_and_batched_is_refused():
 def batched_alns_check(inst, iters, **kw):
     m = dmmv()
     print("alns batched case", inst.name, iters, kw, flush=True)
-    hopt = {key: kw.pop(key) for key in ("batched_eval",) if key in kw}
+    hopt = {key: kw.pop(key) for key in ("batched_eval", "prune") if key in kw}
     prm = orc.alns_params(iters, **kw)
     with m.from_instance(inst, DEV, alns=True, **hopt) as h:
         res = m.dmmv_alns(h, T(inst.x0), iters, **kw)

@@ -1,0 +1,92 @@
+"""options.prune on a batch of instances: the descent screens every candidate on the 16 rows of
+largest |r| and scores only those that can still win.  It must make exactly the moves of the
+full evaluation, i.e. the oracle's (bitwise: traces, x, t, residual)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as orc
+from workloads import make_config, random_batched
+
+from test_gpu_parity import DEV, N, T, batched_check, dmmv
+from test_gpu_alns import batched_alns_check
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("shape", [(1, 1, 1, 2), (3, 2, 2, 3), (17, 5, 3, 3), (64, 8, 64, 4), (100, 33, 65, 8),
+                                   (130, 70, 130, 16), (300, 300, 7, 16), (50, 19, 7, 21), (1030, 40, 5, 40)])
+def test_pruned_batched_random(shape):
+    mm, nn, R, nd = shape
+    print("pruned batched case", shape, flush=True)
+    batched_check(random_batched(9000 + mm, mm, nn, R, nd, dtype=np.float32), 14, prune=True)
+
+
+def test_pruned_batched_f64_and_integer_ties():
+    batched_check(random_batched(9100, 40, 12, 9, 5, dtype=np.float64), 10, prune=True)
+    batched_check(random_batched(9101, 30, 10, 70, 4, dtype=np.float32, integer=True), 15, prune=True)
+    batched_check(random_batched(9102, 70, 40, 33, 9, dtype=np.float64, integer=True), 25, prune=True)
+    batched_check(random_batched(9103, 5, 300, 12, 6, dtype=np.float32, integer=True), 25, prune=True)
+
+
+@pytest.mark.parametrize("radius", [1, 2, 7])
+def test_pruned_batched_radius(radius):
+    batched_check(random_batched(9200 + radius, 60, 14, 20, 8, dtype=np.float32), 12, radius=radius, prune=True)
+    batched_check(random_batched(9210 + radius, 45, 300, 6, 12, dtype=np.float32, integer=True), 12, radius=radius, prune=True)
+
+
+def test_pruned_batched_var_mask():
+    m = dmmv()
+    inst = random_batched(9300, 40, 12, 66, 5)
+    rng = np.random.default_rng(8)
+    vm = (rng.uniform(size=(inst.R, inst.n)) < 0.6).astype(np.uint8)
+    with m.from_instance(inst, DEV, var_mask=T(vm), radius=2, prune=True) as h:
+        res = m.dmmv_solve(h, T(inst.x0), 10, trace=True)
+    for q in (0, 1, 33, 65):
+        o = orc.solve_dense(inst.A, inst.b[q], inst.D, inst.x0[q], 10, radius=2, var_mask=vm[q],
+                            scale=float(inst.scale[q]))
+        d = o.iters_done
+        assert int(res.iters_done[q]) == d
+        assert np.array_equal(N(res.trace)[q, :d, 0], o.trace_j) and np.array_equal(N(res.trace_t)[q, :d], o.trace_t)
+        assert np.array_equal(N(res.x)[q], o.x)
+
+
+@pytest.mark.parametrize("idx", [4, 5])
+def test_pruned_batched_small_llm_configs(idx):
+    inst = make_config(idx, "small")
+    batched_check(inst, inst.iters, prune=True)
+
+
+def test_pruned_batched_continues_where_the_last_call_stopped():
+    """Two calls of 4 and 30 iterations make the moves of one call of 34 (the second call starts
+    from a freshly computed residual, so its t may differ from the maintained one by rounding)."""
+    m = dmmv()
+    inst = random_batched(9400, 80, 30, 40, 6)
+    o = orc.solve_batched(inst.A, inst.b, inst.D, inst.scale, inst.x0, 34)
+    with m.from_instance(inst, DEV, prune=True) as h:
+        first = m.dmmv_solve(h, T(inst.x0), 4)
+        second = m.dmmv_solve(h, T(N(first.x)), 30)
+    assert np.array_equal(N(second.x), o.x) and np.allclose(N(second.max_violation), o.t, rtol=1e-5, atol=0)
+    assert np.array_equal(N(first.iters_done) + N(second.iters_done), o.iters_done)
+
+
+def test_pruned_and_full_descent_agree_on_a_larger_batch():
+    m = dmmv()
+    inst = random_batched(9500, 700, 520, 300, 16, iters=60)
+    out = []
+    for prune in (False, True):
+        with m.from_instance(inst, DEV, prune=prune) as h:
+            res = m.dmmv_solve(h, T(inst.x0), 60, trace=True)
+            out.append((N(res.x), N(res.max_violation), N(res.iters_done), N(res.trace), N(res.trace_t)))
+    for a, b in zip(out[0], out[1]):
+        assert np.array_equal(a, b)
+    assert out[0][2].max() > 5
+
+
+def test_alns_batched_with_pruned_local_search():
+    batched_alns_check(random_batched(9600, 64, 24, 64, 4), 10, ls_moves=3, destroy_count=3, seed=5, prune=True)
+    batched_alns_check(random_batched(9601, 40, 16, 20, 5, integer=True), 20, ls_moves=4, destroy_count=3, seed=4,
+                       ls_radius=2, prune=True)
+    batched_alns_check(random_batched(9602, 30, 12, 9, 4, dtype=np.float64), 12, ls_moves=3, destroy_count=2, seed=6,
+                       ls_swaps=1, l2_guard=1, prune=True)
+    batched_alns_check(make_config(4, "small"), 6, ls_moves=4, seed=4, prune=True)
