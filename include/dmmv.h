@@ -117,7 +117,15 @@ typedef struct {
                                 with an entry in the row of largest |r_i|: a move that leaves
                                 that row alone cannot lower the maximum, so the moves applied are
                                 the same as with the full evaluation and an iteration costs far
-                                less.  dmmv_eval_moves and dmmv_argmin_move always score all     */
+                                less.  Batches of instances: 1 = the descent bounds every move
+                                from below by its score on 16 rows of large |r_i| (a maximum over
+                                some rows never exceeds the maximum over all) and scores over all
+                                rows only the moves, in ascending order of bound, that can still
+                                beat the best score found; same moves again, all iterations of a
+                                call in one launch (used when the instance's r and x fit in
+                                96 KiB of LDS: (m + n) w + 4 n bytes, m <= 16384; otherwise the
+                                full evaluation runs).  Dense single instances ignore it.
+                                dmmv_eval_moves and dmmv_argmin_move always score all             */
     int32_t alns;            /* batched problems: 1 = reserve the workspace dmmv_alns needs (current
                                 and best solution, sampling weights and draws per instance, about
                                 R*(36 n + m w) bytes).  Single-instance handles always have it    */

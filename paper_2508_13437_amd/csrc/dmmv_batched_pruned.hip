@@ -47,8 +47,10 @@ __device__ __forceinline__ size_t bp_lds_bytes(int64_t m, int64_t n) {
     return (size_t)(m + n) * sizeof(T) + (size_t)n * 2 * sizeof(uint16_t);
 }
 
-// KT: candidate values scored together per variable (register tile).
-template <class T, int KT>
+// KT: candidate values scored together per variable (register tile).  RAD: the neighbourhood is
+// a radius around the current level (candidate levels differ from lane to lane); without it the
+// levels are the same for every variable and their values of D are read once per tile.
+template <class T, int KT, bool RAD>
 __global__ __launch_bounds__(BP_BLOCK) void k_descent_batched_pruned(
     int64_t m, int64_t n, int32_t nd, int64_t R, const T* __restrict__ X, int64_t ldx,
     const T* __restrict__ Xt, const T* __restrict__ D, const T* __restrict__ scale,
@@ -74,8 +76,8 @@ __global__ __launch_bounds__(BP_BLOCK) void k_descent_batched_pruned(
     const int32_t rpt = (int32_t)((m + BP_BLOCK - 1) / BP_BLOCK);
     // candidate levels of a variable at level kc: k = base + o for o in [olo, ohi], base = kc
     // inside a radius and 0 otherwise; k == kc and k outside [0, nd) are left out
-    const int32_t olo = radius > 0 ? -radius : 0;
-    const int32_t ohi = radius > 0 ? radius : nd - 1;
+    const int32_t olo = RAD ? -radius : 0;
+    const int32_t ohi = RAD ? radius : nd - 1;
     bool dirty = false;
     __syncthreads();
 
@@ -133,17 +135,24 @@ __global__ __launch_bounds__(BP_BLOCK) void k_descent_batched_pruned(
 #pragma unroll
             for (int u = 0; u < BP_S; ++u) xs[u] = xrow[u][j];
             const T dcur = D[kc];
-            const int32_t base = radius > 0 ? kc : 0;
+            const int32_t base = RAD ? kc : 0;
             T jbest = Limits<T>::inf();
             int32_t jk = 0;
             for (int32_t o0 = olo; o0 <= ohi; o0 += KT) {
-                T delta[KT], lb[KT];
+                T delta[KT], lb[KT], dk[KT];
                 bool ok[KT];
+                // all the tile's values of D are fetched before the first is used (a level outside
+                // D reads an end of it and is masked below)
+#pragma unroll
+                for (int e = 0; e < KT; ++e) {
+                    const int32_t k = base + o0 + e;
+                    dk[e] = D[k < 0 ? 0 : (k < nd ? k : nd - 1)];
+                }
 #pragma unroll
                 for (int e = 0; e < KT; ++e) {
                     const int32_t k = base + o0 + e;
                     ok[e] = var_ok && o0 + e <= ohi && k >= 0 && k < nd && k != kc;
-                    delta[e] = ok[e] ? step_of(D[k], dcur, sc) : (T)0;
+                    delta[e] = ok[e] ? step_of(dk[e], dcur, sc) : (T)0;
                     lb[e] = (T)0;
                 }
 #pragma unroll
@@ -190,7 +199,7 @@ __global__ __launch_bounds__(BP_BLOCK) void k_descent_batched_pruned(
             // meanwhile wavefront 0 looks for this variable's next candidate: the smallest (lb, k)
             // after (ps, k); lanes take the candidate levels
             if (w == 0) {
-                const int32_t base = radius > 0 ? kc : 0;
+                const int32_t base = RAD ? kc : 0;
                 const bool var_ok = vm ? vm[j] != 0 : true;
                 T xs[BP_S];
 #pragma unroll
@@ -273,8 +282,12 @@ dmmv_status descent_t(Ctx* c, int32_t steps, int32_t iters, dmmv_move* trace, vo
         DMMV_LAUNCH_CHECK();
         return DMMV_OK;
     };
-    if (span <= 4) return launch(k_descent_batched_pruned<T, 4>);
-    return launch(k_descent_batched_pruned<T, 16>);
+    if (c->o.radius > 0) {
+        if (span <= 4) return launch(k_descent_batched_pruned<T, 4, true>);
+        return launch(k_descent_batched_pruned<T, 16, true>);
+    }
+    if (span <= 4) return launch(k_descent_batched_pruned<T, 4, false>);
+    return launch(k_descent_batched_pruned<T, 16, false>);
 }
 
 }  // namespace

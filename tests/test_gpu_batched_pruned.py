@@ -90,3 +90,17 @@ def test_alns_batched_with_pruned_local_search():
     batched_alns_check(random_batched(9602, 30, 12, 9, 4, dtype=np.float64), 12, ls_moves=3, destroy_count=2, seed=6,
                        ls_swaps=1, l2_guard=1, prune=True)
     batched_alns_check(make_config(4, "small"), 6, ls_moves=4, seed=4, prune=True)
+
+
+def test_pruned_and_full_descent_agree_on_the_full_size_layer():
+    """Config 4 at full size, 12 iterations: all 4096 instances make the same moves either way."""
+    m = dmmv()
+    inst = make_config(4)
+    out = []
+    for prune in (False, True):
+        print("full-size layer, prune =", prune, flush=True)
+        with m.from_instance(inst, DEV, prune=prune) as h:
+            res = m.dmmv_solve(h, T(inst.x0), 12, trace=True)
+            out.append((N(res.x), N(res.max_violation), N(res.iters_done), N(res.trace), N(res.trace_t)))
+    for a, b in zip(out[0], out[1]):
+        assert np.array_equal(a, b)

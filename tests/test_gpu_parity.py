@@ -511,13 +511,16 @@ def test_config3_tomography_full_prefix_and_sampled_scores():
         assert tab.min() >= 0
 
 
+@pytest.mark.parametrize("prune", [False, True])
 @pytest.mark.parametrize("idx,iters,sample", [(4, 3, 16), (5, 2, 8)])
-def test_llm_configs_full_sampled_instances(idx, iters, sample):
-    """Full-size batched layer: every instance runs on the GPU; a seeded sample of instances
-    is replayed by the oracle and must match bitwise; all instances pass cheap checks."""
+def test_llm_configs_full_sampled_instances(idx, iters, sample, prune):
+    """Full-size batched layer: every instance runs on the GPU (full evaluation, and the descent
+    with exact pruning); a seeded sample of instances is replayed by the oracle and must match
+    bitwise; all instances pass cheap checks."""
     m = dmmv()
     inst = make_config(idx)
-    with m.from_instance(inst, DEV) as h:
+    print("full-size batched case", idx, iters, sample, prune, flush=True)
+    with m.from_instance(inst, DEV, prune=prune) as h:
         res = m.dmmv_solve(h, T(inst.x0), iters, trace=True)
         x = N(res.x)
         t = N(res.max_violation)
