@@ -123,8 +123,8 @@ typedef struct {
                                 rows only the moves, in ascending order of bound, that can still
                                 beat the best score found; same moves again, all iterations of a
                                 call in one launch (used when the instance's r and x fit in
-                                96 KiB of LDS: (m + n) w + 4 n bytes, m <= 16384; otherwise the
-                                full evaluation runs).  Dense single instances ignore it.
+                                96 KiB of LDS: (m + n) w + 2 n bytes, 4 n if nd > 256, and
+                                m <= 16384; otherwise the full evaluation runs).  Dense single instances ignore it.
                                 dmmv_eval_moves and dmmv_argmin_move always score all             */
     int32_t alns;            /* batched problems: 1 = reserve the workspace dmmv_alns needs (current
                                 and best solution, sampling weights and draws per instance, about

@@ -8,10 +8,11 @@
 //      of the rows (the row of largest |r| overall is always one of them);
 //   2. computes, for every candidate, the bound lb(j, k) = max_{i in S} |fma(delta, X_ij, r_i)|
 //      - 16 rows instead of m - and keeps per variable its best candidate by (lb, k);
-//   3. takes candidates in ascending order of (lb, c), c = j nd + k, scores each one over all m
-//      rows (the same fma on the same operands as the full evaluation, so the same bits), and
-//      stops as soon as the next candidate's (lb, c) is not below the best (score, c) found:
-//      every candidate not scored has score >= lb >= that best score, and loses the tie on c;
+//   3. takes candidates in ascending order of (lb, c), c = j nd + k - each wavefront among the
+//      variables it screened, one per round - scores each one over all m rows (the same fma on
+//      the same operands as the full evaluation, so the same bits), and stops when no wavefront's
+//      next candidate has (lb, c) below the best (score, c) found: every candidate not scored
+//      then has score >= lb >= that best score, and loses the tie on c;
 //   4. applies the move if its score is below t.
 // The result is the arg-min of the full table restricted to strictly improving moves, i.e. the
 // move the full evaluation + selection would apply - found with a few full scores instead of
@@ -30,27 +31,27 @@ constexpr int BP_TOPW = 4;                       // screening rows a wavefront c
 constexpr int BP_S = BP_WAVES * BP_TOPW;         // screening rows
 constexpr int BP_MAX_RPT = 64;                   // rows per thread at most (one bit each in a 64-bit mask)
 constexpr size_t BP_LDS_LIMIT = 96 * 1024;       // dynamic LDS a workgroup may ask for
+constexpr int BP_UNROLL = 8;                     // independent global loads a thread issues before it uses them
 
 template <class T>
 struct BpShared {
     T top_r[BP_S];
     int32_t top_row[BP_S];
-    T red_s[BP_WAVES];
-    int64_t red_c[BP_WAVES];
-    T red_m[BP_WAVES];
-    T pop_s;
-    int64_t pop_c;
+    T round_s[2][BP_WAVES];                      // score and candidate each wavefront scored in a round
+    int64_t round_c[2][BP_WAVES];                //   (-1: it had none left that could win)
 };
 
+// does (s, c) beat the best (bs, bc)?  bc < 0: nothing found yet, only scores below bs = t count
 template <class T>
-__device__ __forceinline__ size_t bp_lds_bytes(int64_t m, int64_t n) {
-    return (size_t)(m + n) * sizeof(T) + (size_t)n * 2 * sizeof(uint16_t);
+__device__ __forceinline__ bool bp_better(T s, int64_t c, T bs, int64_t bc) {
+    return c >= 0 && (s < bs || (s == bs && bc >= 0 && c < bc));
 }
 
 // KT: candidate values scored together per variable (register tile).  RAD: the neighbourhood is
 // a radius around the current level (candidate levels differ from lane to lane); without it the
 // levels are the same for every variable and their values of D are read once per tile.
-template <class T, int KT, bool RAD>
+// KI: type of a level index in LDS (8 bits when nd <= 256).
+template <class T, int KT, bool RAD, class KI>
 __global__ __launch_bounds__(BP_BLOCK) void k_descent_batched_pruned(
     int64_t m, int64_t n, int32_t nd, int64_t R, const T* __restrict__ X, int64_t ldx,
     const T* __restrict__ Xt, const T* __restrict__ D, const T* __restrict__ scale,
@@ -61,16 +62,41 @@ __global__ __launch_bounds__(BP_BLOCK) void k_descent_batched_pruned(
     __shared__ BpShared<T> F;
     T* sh_r = reinterpret_cast<T*>(smem);                  // the instance's residual
     T* sh_jmin = sh_r + m;                                 // per variable: bound of its next candidate
-    uint16_t* sh_k = reinterpret_cast<uint16_t*>(sh_jmin + n);   // current level of every variable
-    uint16_t* sh_jarg = sh_k + n;                          // per variable: level of its next candidate
+    KI* sh_k = reinterpret_cast<KI*>(sh_jmin + n);          // current level of every variable
+    KI* sh_jarg = sh_k + n;                                // per variable: level of its next candidate
 
     const int64_t q = blockIdx.x;
     InstState<T> z = st[q];
     if (z.done || steps <= 0) return;                      // the same for the whole workgroup
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    for (int64_t i = tid; i < m; i += BP_BLOCK) sh_r[i] = r[i * R + q];
-    for (int64_t j = tid; j < n; j += BP_BLOCK) sh_k[j] = (uint16_t)kidx[j * R + q];
+    // the instance's column of r and of x: strided reads, eight in flight per thread
+    for (int64_t i0 = tid; i0 < m; i0 += BP_BLOCK * BP_UNROLL) {
+        T a[BP_UNROLL];
+#pragma unroll
+        for (int u = 0; u < BP_UNROLL; ++u) {
+            const int64_t i = i0 + BP_BLOCK * u;
+            a[u] = r[(i < m ? i : m - 1) * R + q];
+        }
+#pragma unroll
+        for (int u = 0; u < BP_UNROLL; ++u) {
+            const int64_t i = i0 + BP_BLOCK * u;
+            if (i < m) sh_r[i] = a[u];
+        }
+    }
+    for (int64_t j0 = tid; j0 < n; j0 += BP_BLOCK * BP_UNROLL) {
+        int32_t a[BP_UNROLL];
+#pragma unroll
+        for (int u = 0; u < BP_UNROLL; ++u) {
+            const int64_t j = j0 + BP_BLOCK * u;
+            a[u] = kidx[(j < n ? j : n - 1) * R + q];
+        }
+#pragma unroll
+        for (int u = 0; u < BP_UNROLL; ++u) {
+            const int64_t j = j0 + BP_BLOCK * u;
+            if (j < n) sh_k[j] = (KI)a[u];
+        }
+    }
     const T sc = scale[q];
     const uint8_t* __restrict__ vm = var_mask ? var_mask + q * n : nullptr;
     const int32_t rpt = (int32_t)((m + BP_BLOCK - 1) / BP_BLOCK);
@@ -164,41 +190,52 @@ __global__ __launch_bounds__(BP_BLOCK) void k_descent_batched_pruned(
                     if (ok[e] && lb[e] < jbest) { jbest = lb[e]; jk = base + o0 + e; }   // k ascends: ties keep the lowest
             }
             sh_jmin[j] = jbest;
-            sh_jarg[j] = (uint16_t)jk;
+            sh_jarg[j] = (KI)jk;
         }
         __syncthreads();
 
         // ---- 3. candidates in ascending (lb, c) until none can beat the best score ---------
+        // Every wavefront walks the candidates of ITS variables (those its threads screened) in
+        // ascending (lb, c) and scores one per round, as long as that candidate can still beat the
+        // best (score, c) the workgroup knew when the round began; the rounds end when no
+        // wavefront had such a candidate.  Then every candidate not scored has
+        // (lb, c) >= (best score, its c), hence score >= lb >= best score, and loses the tie on c.
         T best_s = z.t;                                    // only scores below t count
         int64_t best_c = -1;
-        for (;;) {
+        for (int parity = 0;; parity ^= 1) {
             T s = Limits<T>::inf();
             int64_t c = -1;
             for (int64_t j = tid; j < n; j += BP_BLOCK) {
                 const T v = sh_jmin[j];
                 if (v < s) { s = v; c = j * (int64_t)nd + sh_jarg[j]; }   // j ascends: ties keep the lowest c
             }
-            block_argmin(s, c, F.red_s, F.red_c);
-            if (tid == 0) { F.pop_s = s; F.pop_c = c; }
-            __syncthreads();
-            const T ps = F.pop_s;
-            const int64_t pc = F.pop_c;
-            const bool go = pc >= 0 && (ps < best_s || (ps == best_s && best_c >= 0 && pc < best_c));
-            if (!go) break;                                // the same for the whole workgroup
-            const int64_t j = pc / nd;
-            const int32_t k = (int32_t)(pc % nd);
-            const int32_t kc = sh_k[j];
-            const T dcur = D[kc];
-            const T delta = step_of(D[k], dcur, sc);
-            // its score over all rows
-            const T* __restrict__ col = X + ldx * j;
-            T acc = (T)0;
-            for (int64_t i = tid; i < m; i += BP_BLOCK) acc = dmmv_max(acc, dmmv_abs(dmmv_fma(delta, col[i], sh_r[i])));
-            acc = wave_max(acc);
-            if (lane == 0) F.red_m[w] = acc;
-            // meanwhile wavefront 0 looks for this variable's next candidate: the smallest (lb, k)
-            // after (ps, k); lanes take the candidate levels
-            if (w == 0) {
+            wave_argmin(s, c);
+            const bool live = bp_better(s, c, best_s, best_c);   // the same for the whole wavefront
+            T sfull = (T)0;
+            if (live) {
+                const int64_t j = c / nd;
+                const int32_t k = (int32_t)(c % nd);
+                const int32_t kc = sh_k[j];
+                const T dcur = D[kc];
+                const T delta = step_of(D[k], dcur, sc);
+                // its score over all rows
+                const T* __restrict__ col = X + ldx * j;
+                // (eight loads in flight; a row past the end repeats row m - 1, which changes no maximum)
+                T acc = (T)0;
+                for (int64_t i0 = lane; i0 < m; i0 += 64 * BP_UNROLL) {
+                    T a[BP_UNROLL];
+#pragma unroll
+                    for (int u = 0; u < BP_UNROLL; ++u) {
+                        const int64_t i = i0 + 64 * u;
+                        a[u] = col[i < m ? i : m - 1];
+                    }
+#pragma unroll
+                    for (int u = 0; u < BP_UNROLL; ++u) {
+                        const int64_t i = i0 + 64 * u;
+                        acc = dmmv_max(acc, dmmv_abs(dmmv_fma(delta, a[u], sh_r[i < m ? i : m - 1])));
+                    }
+                }
+                // this variable's next candidate: the smallest (lb, k) after (s, k); lanes take the levels
                 const int32_t base = RAD ? kc : 0;
                 const bool var_ok = vm ? vm[j] != 0 : true;
                 T xs[BP_S];
@@ -214,21 +251,29 @@ __global__ __launch_bounds__(BP_BLOCK) void k_descent_batched_pruned(
                     T lb = (T)0;
 #pragma unroll
                     for (int u = 0; u < BP_S; ++u) lb = dmmv_max(lb, dmmv_abs(dmmv_fma(dl, xs[u], tr[u])));
-                    const bool after = ok && (lb > ps || (lb == ps && kk > k));
+                    const bool after = ok && (lb > s || (lb == s && kk > k));
                     if (after && lb < bl) { bl = lb; bk = kk; }       // kk ascends per lane: ties keep the lowest
                 }
                 wave_argmin(bl, bk);
                 if (lane == 0) {
                     sh_jmin[j] = bk >= 0 ? bl : Limits<T>::inf();
-                    sh_jarg[j] = (uint16_t)(bk >= 0 ? bk : 0);
+                    sh_jarg[j] = (KI)(bk >= 0 ? bk : 0);
                 }
+                sfull = wave_max(acc);
             }
+            if (lane == 0) { F.round_s[parity][w] = sfull; F.round_c[parity][w] = live ? c : (int64_t)-1; }
             __syncthreads();
-            T sfull = F.red_m[0];
+            bool any = false;
 #pragma unroll
-            for (int u = 1; u < BP_WAVES; ++u) sfull = dmmv_max(sfull, F.red_m[u]);
-            if (sfull < best_s || (sfull == best_s && best_c >= 0 && pc < best_c)) { best_s = sfull; best_c = pc; }
-            __syncthreads();                               // red_m, pop_* are rewritten by the next round
+            for (int u = 0; u < BP_WAVES; ++u) {
+                const T us = F.round_s[parity][u];
+                const int64_t uc = F.round_c[parity][u];
+                any = any || uc >= 0;
+                if (bp_better(us, uc, best_s, best_c)) { best_s = us; best_c = uc; }
+            }
+            if (!any) break;                               // the same for the whole workgroup
+            // the other pair of slots is written next: a wavefront gets there only after every
+            // wavefront has passed this round's barrier, i.e. has read the slots of the round before
         }
 
         // ---- 4. decide and apply ---------------------------------------------------------
@@ -239,10 +284,22 @@ __global__ __launch_bounds__(BP_BLOCK) void k_descent_batched_pruned(
             const int32_t k = (int32_t)(best_c % nd);
             const T delta = step_of(D[k], D[sh_k[j]], sc);
             const T* __restrict__ col = X + ldx * j;
-            for (int64_t i = tid; i < m; i += BP_BLOCK) sh_r[i] = dmmv_fma(delta, col[i], sh_r[i]);
+            for (int64_t i0 = tid; i0 < m; i0 += BP_BLOCK * BP_UNROLL) {
+                T a[BP_UNROLL];
+#pragma unroll
+                for (int u = 0; u < BP_UNROLL; ++u) {
+                    const int64_t i = i0 + BP_BLOCK * u;
+                    a[u] = col[i < m ? i : m - 1];
+                }
+#pragma unroll
+                for (int u = 0; u < BP_UNROLL; ++u) {
+                    const int64_t i = i0 + BP_BLOCK * u;
+                    if (i < m) sh_r[i] = dmmv_fma(delta, a[u], sh_r[i]);
+                }
+            }
             __syncthreads();                               // everyone has read sh_k[j]
             if (tid == 0) {
-                sh_k[j] = (uint16_t)k;
+                sh_k[j] = (KI)k;
                 kidx[j * R + q] = k;
                 if (z.moves < iters) {
                     const int64_t slot = q * (int64_t)iters + z.moves;
@@ -267,10 +324,14 @@ __global__ __launch_bounds__(BP_BLOCK) void k_descent_batched_pruned(
     }
 }
 
+static size_t bp_lds_bytes(int64_t m, int64_t n, int32_t nd, size_t esz) {
+    return (size_t)(m + n) * esz + (size_t)n * 2 * (nd <= 256 ? 1 : 2);
+}
+
 template <class T>
 dmmv_status descent_t(Ctx* c, int32_t steps, int32_t iters, dmmv_move* trace, void* trace_t) {
     const int64_t m = c->p.m, n = c->p.n, R = c->p.R;
-    const size_t lds = (size_t)(m + n) * sizeof(T) + (size_t)n * 2 * sizeof(uint16_t);
+    const size_t lds = bp_lds_bytes(m, n, c->p.nd, sizeof(T));
     const int32_t span = c->o.radius > 0 ? 2 * c->o.radius + 1 : c->p.nd;
     auto launch = [&](auto kernel) -> dmmv_status {
         DMMV_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
@@ -282,12 +343,16 @@ dmmv_status descent_t(Ctx* c, int32_t steps, int32_t iters, dmmv_move* trace, vo
         DMMV_LAUNCH_CHECK();
         return DMMV_OK;
     };
-    if (c->o.radius > 0) {
-        if (span <= 4) return launch(k_descent_batched_pruned<T, 4, true>);
-        return launch(k_descent_batched_pruned<T, 16, true>);
+    if (c->p.nd > 256) {
+        if (c->o.radius > 0) return launch(k_descent_batched_pruned<T, 16, true, uint16_t>);
+        return launch(k_descent_batched_pruned<T, 16, false, uint16_t>);
     }
-    if (span <= 4) return launch(k_descent_batched_pruned<T, 4, false>);
-    return launch(k_descent_batched_pruned<T, 16, false>);
+    if (c->o.radius > 0) {
+        if (span <= 4) return launch(k_descent_batched_pruned<T, 4, true, uint8_t>);
+        return launch(k_descent_batched_pruned<T, 16, true, uint8_t>);
+    }
+    if (span <= 4) return launch(k_descent_batched_pruned<T, 4, false, uint8_t>);
+    return launch(k_descent_batched_pruned<T, 16, false, uint8_t>);
 }
 
 }  // namespace
@@ -297,8 +362,7 @@ bool batched_pruned_applicable(const Ctx* c) {
     const int64_t m = c->p.m, n = c->p.n;
     if (n <= 0 || c->p.R > INT32_MAX) return false;
     if (m > (int64_t)BP_BLOCK * BP_MAX_RPT) return false;
-    const size_t lds = (size_t)(m + n) * c->esz + (size_t)n * 4;
-    return lds <= BP_LDS_LIMIT;
+    return bp_lds_bytes(m, n, c->p.nd, c->esz) <= BP_LDS_LIMIT;
 }
 
 dmmv_status batched_descent_pruned(Ctx* c, int32_t steps, int32_t iters, dmmv_move* trace, void* trace_t) {
