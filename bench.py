@@ -409,6 +409,8 @@ def main():
         line["alns"] = head["alns"]
     if "alns_value_search" in head:
         line["alns_value_search"] = head["alns_value_search"]
+    if "alns_full_evaluation" in head:
+        line["alns_full_evaluation"] = head["alns_full_evaluation"]
     if "swap" in head:
         line["swap"] = head["swap"]
     if "cpu_baseline" in head:
