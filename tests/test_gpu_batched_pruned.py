@@ -22,6 +22,14 @@ def test_pruned_batched_random(shape):
     batched_check(random_batched(9000 + mm, mm, nn, R, nd, dtype=np.float32), 14, prune=True)
 
 
+def test_pruned_batched_many_levels_and_instances_too_large_for_lds():
+    # more than 256 levels: 16-bit level indices in LDS
+    batched_check(random_batched(9050, 40, 6, 5, 300, dtype=np.float32), 10, prune=True)
+    batched_check(random_batched(9051, 33, 5, 3, 700, dtype=np.float64), 8, radius=40, prune=True)
+    # (m + n) w + 2 n bytes exceed the LDS a workgroup may take: the full evaluation runs instead
+    batched_check(random_batched(9052, 8, 21000, 3, 3, dtype=np.float32), 4, prune=True)
+
+
 def test_pruned_batched_f64_and_integer_ties():
     batched_check(random_batched(9100, 40, 12, 9, 5, dtype=np.float64), 10, prune=True)
     batched_check(random_batched(9101, 30, 10, 70, 4, dtype=np.float32, integer=True), 15, prune=True)
