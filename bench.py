@@ -348,6 +348,25 @@ def residual_probe(idx: int, device: str, reps: int) -> None:
                       "useful_flops_per_call": 2.0 * inst.m * inst.n * inst.R}))
 
 
+def descent_probe(idx: int, device: str, reps: int) -> None:
+    """For `rocprofv3 --pmc` runs on the pruned batched descent: `reps` calls of dmmv_solve with
+    options.prune on batched workload idx (one launch of k_descent_batched_pruned each)."""
+    import torch
+    from paper_2508_13437_amd import dmmv
+    from workloads import make_config
+
+    inst = make_config(idx)
+    x0 = torch.from_numpy(np.ascontiguousarray(inst.x0)).to(device)
+    with dmmv.from_instance(inst, device, prune=True) as h:
+        for _ in range(reps):
+            out = dmmv.dmmv_solve(h, x0, inst.iters)
+        torch.cuda.synchronize()
+        moves = out.iters_done.cpu().numpy().astype(np.int64)
+    print(json.dumps({"probe": inst.name, "descents": reps, "moves_applied_per_descent": int(moves.sum()),
+                      "instance_iterations_per_descent": int(moves.sum() + (moves < inst.iters).sum()),
+                      "candidates_per_instance_iteration": int(inst.n * (inst.nd - 1))}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -365,6 +384,8 @@ def main():
                          "(for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs)")
     ap.add_argument("--residual-probe", type=int, default=0, metavar="REPS",
                     help="only run the matrix-core batched residual REPS times (for rocprofv3 --pmc runs)")
+    ap.add_argument("--descent-probe", type=int, default=0, metavar="REPS",
+                    help="only run the pruned batched descent REPS times (for rocprofv3 --pmc runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
@@ -380,6 +401,9 @@ def main():
         return
     if args.residual_probe > 0:
         residual_probe(args.config, device, args.residual_probe)
+        return
+    if args.descent_probe > 0:
+        descent_probe(args.config, device, args.descent_probe)
         return
     default_steps = {1: 20, 2: 10, 3: 5, 4: 1, 5: 1}
     steps = args.steps if args.steps is not None else default_steps[args.config]

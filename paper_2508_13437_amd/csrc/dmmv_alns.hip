@@ -268,8 +268,29 @@ __global__ __launch_bounds__(256) void k_alns_impact_dense(int64_t m, int64_t n,
     }
 }
 
-// batched: lane = instance (r coalesced, X through the scalar unit, no reduction); grid.x =
-// group of 64 instances, each of the 4 wavefronts takes the variables blockIdx.y*4 + w, +4*gridDim.y, ...
+// batched: lane = instance (r coalesced, X through the scalar unit); grid.x = group of 64
+// instances, each of the 4 wavefronts takes the variables blockIdx.y*4 + w, +4*gridDim.y, ...
+//
+// Only a few per cent of the terms are not cut off by the shortcut of alns_impact_term (slack >
+// a * 18 / alpha: the term truncates to 0), but they are scattered: almost every group of 64
+// lanes holds one, so testing inside the loop would send every wavefront through the
+// double-precision division and exponential for the sake of a lane or two.  The loop therefore
+// only TESTS (in fp32 for fp32 problems, with a margin of 1 % that covers the roundings of its
+// three operations; the exact test otherwise) and appends the terms that may count to a queue of
+// the wavefront in LDS; whenever 64 are waiting, every lane computes one of them, for whichever
+// instance it belongs to, and adds the integer to that instance's sum with an LDS atomic.  The
+// sum is one of integers, so the order does not matter and the weights are the same bit for bit.
+constexpr int IMQ_CAP = 128;                   // ring of waiting terms per wavefront (drained at 64)
+constexpr int IMQ_ROWS = 8;                    // rows whose operands are fetched before they are tested
+
+template <class T>
+struct ImpactShared {
+    T qx[4][IMQ_CAP], qr[4][IMQ_CAP];          // waiting terms: matrix entry, residual of the row
+    uint8_t qlane[4][IMQ_CAP];                 //   and the lane (instance) they belong to
+    unsigned long long sum[4][64];
+    double sc[4][64], t[4][64], scale[4][64];  // per instance: scale factor, error, fixed-point scale
+};
+
 template <class T>
 __global__ __launch_bounds__(256) void k_alns_impact_batched(int64_t m, int64_t n, int64_t R,
                                                              const T* __restrict__ Xt,
@@ -277,6 +298,7 @@ __global__ __launch_bounds__(256) void k_alns_impact_batched(int64_t m, int64_t 
                                                              const T* __restrict__ r,
                                                              const InstState<T>* st, double alpha,
                                                              uint64_t* __restrict__ weight, const AlnsState* S) {
+    __shared__ ImpactShared<T> L;
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t q = blockIdx.x * 64ll + lane;
@@ -290,30 +312,81 @@ __global__ __launch_bounds__(256) void k_alns_impact_batched(int64_t m, int64_t 
     if (shift < 0) shift = 0;
     const float pre = (float)(18.0 / alpha * 1.01);
     const float tf = (float)t, scf = (float)sc;             // exact for fp32 problems
+    const bool counts = live && scale != 0.0;               // otherwise every weight of the instance is 1
+    L.sc[w][lane] = sc;
+    L.t[w][lane] = t;
+    L.scale[w][lane] = scale;
+    __builtin_amdgcn_wave_barrier();
+    // may the term of matrix entry x and residual rv of this lane's instance count?
+    auto may_count = [&](T x, T rv) -> bool {
+        if constexpr (sizeof(T) == 4) {
+            const float af = __builtin_fabsf(scf * (float)x);
+            const float slack = tf - __builtin_fabsf((float)rv);
+            return !(slack > af * pre);
+        } else {
+            const double a = __builtin_fabs(sc * (double)x);
+            const double slack = t - __builtin_fabs((double)rv);
+            return a != 0.0 && !(slack > a * (18.0 / alpha));
+        }
+    };
     for (int64_t j = blockIdx.y * 4ll + w; j < n; j += 4ll * gridDim.y) {
-        uint64_t sum = 0;
-        if (live && scale != 0.0) {
-            for (int64_t i = 0; i < m; ++i) {
-                if constexpr (sizeof(T) == 4) {
-                    // Most terms truncate to 0 (alns_impact_term: slack > a * 18 / alpha).  In fp32 that
-                    // is decided first, with a margin of 1 % that covers the roundings of the three
-                    // fp32 operations, so the double-precision arithmetic runs only for the terms
-                    // that may count.
-                    const float af = __builtin_fabsf(scf * (float)Xt[i * n + j]);
-                    const float slack = tf - __builtin_fabsf((float)r[i * R + qc]);
-                    if (slack > af * pre) continue;
+        L.sum[w][lane] = 0;
+        int head = 0, waiting = 0;                          // the same in every lane
+        // every lane computes the waiting term `slot` (if it has one) for the instance it belongs to
+        auto drain = [&](int count) {
+            __builtin_amdgcn_wave_barrier();
+            if (lane < count) {
+                const int e = (head + lane) & (IMQ_CAP - 1);
+                const int owner = L.qlane[w][e];
+                const double a = __builtin_fabs(L.sc[w][owner] * (double)L.qx[w][e]);
+                const uint64_t term = alns_impact_term(a, __builtin_fabs((double)L.qr[w][e]), L.t[w][owner], alpha,
+                                                       L.scale[w][owner]);
+                if (term) atomicAdd(&L.sum[w][owner], (unsigned long long)term);
+            }
+            __builtin_amdgcn_wave_barrier();
+            head = (head + count) & (IMQ_CAP - 1);
+            waiting -= count;
+        };
+        for (int64_t i0 = 0; i0 < m; i0 += IMQ_ROWS) {
+            T xs[IMQ_ROWS], rs[IMQ_ROWS];
+#pragma unroll
+            for (int u = 0; u < IMQ_ROWS; ++u) {
+                const int64_t i = i0 + u < m ? i0 + u : m - 1;
+                xs[u] = Xt[i * n + j];
+                rs[u] = r[i * R + qc];
+            }
+#pragma unroll
+            for (int u = 0; u < IMQ_ROWS; ++u) {
+                const bool take = counts && i0 + u < m && may_count(xs[u], rs[u]);
+                const unsigned long long mask = __ballot(take);
+                if (mask) {                                  // the same for the whole wavefront
+                    if (take) {
+                        const int before = __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                                                     __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));
+                        const int e = (head + waiting + before) & (IMQ_CAP - 1);
+                        L.qx[w][e] = xs[u];
+                        L.qr[w][e] = rs[u];
+                        L.qlane[w][e] = (uint8_t)lane;
+                    }
+                    waiting += __builtin_popcountll(mask);
+                    if (waiting >= 64) drain(64);
                 }
-                const double a = __builtin_fabs(sc * (double)Xt[i * n + j]);
-                sum += alns_impact_term(a, __builtin_fabs((double)r[i * R + qc]), t, alpha, scale);
             }
         }
-        if (live) weight[q * n + j] = 1 + (sum >> shift);
+        if (waiting > 0) drain(waiting);
+        if (live) weight[q * n + j] = 1 + ((uint64_t)L.sum[w][lane] >> shift);
+        __builtin_amdgcn_wave_barrier();                    // the sums are cleared for the next variable
     }
 }
 
 // one workgroup per instance; thread i owns the rows i, i + blockDim.x, ...; the picked
-// variables are reassigned one after the other, r follows each reassignment
-template <class T>
+// variables are reassigned one after the other, r follows each reassignment.  STAGE: the
+// instance's r is copied to LDS first and written back at the end (in a batch its rows lie R
+// elements apart in memory, and every picked variable would walk them again).
+constexpr int RD_UNROLL = 8;                   // independent global loads a thread issues before it uses them
+constexpr size_t RD_STAGE_BYTES = 48 * 1024;   // largest r that is staged
+
+template <class T, bool STAGE>
 __global__ __launch_bounds__(1024) void k_alns_repair_dense(int64_t m, int64_t R, int32_t nd,
                                                             const T* __restrict__ A, int64_t lda,
                                                             const T* __restrict__ D,
@@ -322,12 +395,34 @@ __global__ __launch_bounds__(1024) void k_alns_repair_dense(int64_t m, int64_t R
                                                             const int32_t* __restrict__ picked_all,
                                                             InstState<T>* st, const AlnsState* S,
                                                             uint64_t seed) {
+    extern __shared__ __align__(16) unsigned char repair_smem[];
+    T* lr = reinterpret_cast<T*>(repair_smem);
     __shared__ T sh[16];
     const int64_t q = blockIdx.x;
+    const int64_t nt = blockDim.x;
     const int32_t* __restrict__ picked = picked_all + q * (int64_t)count;
     const int32_t it = S[q].it;
     const bool greedy = S[q].r_op == 1;
     const T sc = scale_q[q];
+    if (STAGE) {
+        for (int64_t i0 = threadIdx.x; i0 < m; i0 += nt * RD_UNROLL) {
+            T v[RD_UNROLL];
+#pragma unroll
+            for (int u = 0; u < RD_UNROLL; ++u) {
+                const int64_t i = i0 + nt * u;
+                v[u] = r[(i < m ? i : m - 1) * R + q];
+            }
+#pragma unroll
+            for (int u = 0; u < RD_UNROLL; ++u) {
+                const int64_t i = i0 + nt * u;
+                if (i < m) lr[i] = v[u];
+            }
+        }
+        __syncthreads();
+    }
+    // thread i touches only its own rows of r between barriers, staged or not
+    auto rd = [&](int64_t i) -> T { return STAGE ? lr[i] : r[i * R + q]; };
+    auto wr = [&](int64_t i, T v) { if (STAGE) lr[i] = v; else r[i * R + q] = v; };
     for (int32_t pos = 0; pos < count; ++pos) {
         const int64_t j = picked[pos];
         const int32_t kc = kidx[j * R + q];
@@ -338,10 +433,22 @@ __global__ __launch_bounds__(1024) void k_alns_repair_dense(int64_t m, int64_t R
             if (greedy) {
                 const T dlo = step_of(D[kc - 1], D[kc], sc), dhi = step_of(D[kc + 1], D[kc], sc);
                 T elo = (T)0, ehi = (T)0;
-                for (int64_t i = threadIdx.x; i < m; i += blockDim.x) {
-                    const T a = col[i], ri = r[i * R + q];
-                    elo = dmmv_max(elo, dmmv_abs(dmmv_fma(dlo, a, ri)));
-                    ehi = dmmv_max(ehi, dmmv_abs(dmmv_fma(dhi, a, ri)));
+                for (int64_t i0 = threadIdx.x; i0 < m; i0 += nt * RD_UNROLL) {
+                    T a[RD_UNROLL];
+#pragma unroll
+                    for (int u = 0; u < RD_UNROLL; ++u) {
+                        const int64_t i = i0 + nt * u;
+                        a[u] = col[i < m ? i : m - 1];
+                    }
+#pragma unroll
+                    for (int u = 0; u < RD_UNROLL; ++u) {
+                        const int64_t i = i0 + nt * u;
+                        if (i < m) {
+                            const T ri = rd(i);
+                            elo = dmmv_max(elo, dmmv_abs(dmmv_fma(dlo, a[u], ri)));
+                            ehi = dmmv_max(ehi, dmmv_abs(dmmv_fma(dhi, a[u], ri)));
+                        }
+                    }
                 }
                 elo = block_max(elo, sh);
                 ehi = block_max(ehi, sh);
@@ -353,12 +460,28 @@ __global__ __launch_bounds__(1024) void k_alns_repair_dense(int64_t m, int64_t R
             knew = has_lo ? kc - 1 : kc + 1;
         }
         const T delta = step_of(D[knew], D[kc], sc);
-        for (int64_t i = threadIdx.x; i < m; i += blockDim.x) r[i * R + q] = dmmv_fma(delta, col[i], r[i * R + q]);
+        for (int64_t i0 = threadIdx.x; i0 < m; i0 += nt * RD_UNROLL) {
+            T a[RD_UNROLL];
+#pragma unroll
+            for (int u = 0; u < RD_UNROLL; ++u) {
+                const int64_t i = i0 + nt * u;
+                a[u] = col[i < m ? i : m - 1];
+            }
+#pragma unroll
+            for (int u = 0; u < RD_UNROLL; ++u) {
+                const int64_t i = i0 + nt * u;
+                if (i < m) wr(i, dmmv_fma(delta, a[u], rd(i)));
+            }
+        }
         __syncthreads();                      // every thread has read kidx of this step
         if (threadIdx.x == 0) kidx[j * R + q] = knew;
     }
     T tmax = (T)0;
-    for (int64_t i = threadIdx.x; i < m; i += blockDim.x) tmax = dmmv_max(tmax, dmmv_abs(r[i * R + q]));
+    for (int64_t i = threadIdx.x; i < m; i += nt) {
+        const T v = rd(i);
+        tmax = dmmv_max(tmax, dmmv_abs(v));
+        if (STAGE) r[i * R + q] = v;
+    }
     tmax = block_max(tmax, sh);
     if (threadIdx.x == 0) { st[q].t = tmax; st[q].done = 0; st[q].moves = 0; }
 }
@@ -425,7 +548,10 @@ static dmmv_status destroy_repair_t(Ctx* c, const dmmv_alns_params& prm, int32_t
     if (c->kind == KIND_CSC) {
         DMMV_TRY(csc_alns_repair(c, count, prm.seed));
     } else {
-        hipLaunchKernelGGL(k_alns_repair_dense<T>, dim3((unsigned)R), dim3(R > 1 ? 256 : 1024), 0, c->stream,
+        const size_t rbytes = (size_t)c->p.m * sizeof(T);
+        const bool stage = rbytes <= RD_STAGE_BYTES;
+        auto repair = stage ? k_alns_repair_dense<T, true> : k_alns_repair_dense<T, false>;
+        hipLaunchKernelGGL(repair, dim3((unsigned)R), dim3(R > 1 ? 256 : 1024), stage ? rbytes : 0, c->stream,
                            c->p.m, R, c->p.nd, (const T*)c->p.A_dense, c->p.lda, (const T*)c->D_dev,
                            (const T*)c->scale_dev, (T*)c->r, c->kidx, count, (const int32_t*)c->alns_picked,
                            (InstState<T>*)c->state, (const AlnsState*)S, prm.seed);
