@@ -280,14 +280,19 @@ __global__ __launch_bounds__(256) void k_alns_impact_dense(int64_t m, int64_t n,
 // the wavefront in LDS; whenever 64 are waiting, every lane computes one of them, for whichever
 // instance it belongs to, and adds the integer to that instance's sum with an LDS atomic.  The
 // sum is one of integers, so the order does not matter and the weights are the same bit for bit.
+// A wavefront goes over the rows once for eight consecutive variables, so that an instance's
+// residual (the only per-lane operand) is read once for all eight.
 constexpr int IMQ_CAP = 128;                   // ring of waiting terms per wavefront (drained at 64)
-constexpr int IMQ_ROWS = 8;                    // rows whose operands are fetched before they are tested
+constexpr int IMQ_ROWS = 4;                    // rows whose operands are fetched before they are tested
+constexpr int IMQ_VARS = 8;                    // consecutive variables a wavefront works on per pass over the rows
+                                               //   (r is read once for all of them)
 
 template <class T>
 struct ImpactShared {
-    T qx[4][IMQ_CAP], qr[4][IMQ_CAP];          // waiting terms: matrix entry, residual of the row
-    uint8_t qlane[4][IMQ_CAP];                 //   and the lane (instance) they belong to
-    unsigned long long sum[4][64];
+    T qx[4][IMQ_CAP], qr[4][IMQ_CAP];          // waiting terms: matrix entry, residual of the row,
+    uint8_t qlane[4][IMQ_CAP];                 //   the lane (instance) they belong to
+    uint8_t qvar[4][IMQ_CAP];                  //   and which of the pass's variables
+    unsigned long long sum[4][IMQ_VARS][64];
     double sc[4][64], t[4][64], scale[4][64];  // per instance: scale factor, error, fixed-point scale
 };
 
@@ -329,10 +334,11 @@ __global__ __launch_bounds__(256) void k_alns_impact_batched(int64_t m, int64_t 
             return a != 0.0 && !(slack > a * (18.0 / alpha));
         }
     };
-    for (int64_t j = blockIdx.y * 4ll + w; j < n; j += 4ll * gridDim.y) {
-        L.sum[w][lane] = 0;
+    for (int64_t j0 = (blockIdx.y * 4ll + w) * IMQ_VARS; j0 < n; j0 += 4ll * IMQ_VARS * gridDim.y) {
+#pragma unroll
+        for (int v = 0; v < IMQ_VARS; ++v) L.sum[w][v][lane] = 0;
         int head = 0, waiting = 0;                          // the same in every lane
-        // every lane computes the waiting term `slot` (if it has one) for the instance it belongs to
+        // every lane computes one of the first `count` waiting terms, for the instance it belongs to
         auto drain = [&](int count) {
             __builtin_amdgcn_wave_barrier();
             if (lane < count) {
@@ -341,41 +347,50 @@ __global__ __launch_bounds__(256) void k_alns_impact_batched(int64_t m, int64_t 
                 const double a = __builtin_fabs(L.sc[w][owner] * (double)L.qx[w][e]);
                 const uint64_t term = alns_impact_term(a, __builtin_fabs((double)L.qr[w][e]), L.t[w][owner], alpha,
                                                        L.scale[w][owner]);
-                if (term) atomicAdd(&L.sum[w][owner], (unsigned long long)term);
+                if (term) atomicAdd(&L.sum[w][L.qvar[w][e]][owner], (unsigned long long)term);
             }
             __builtin_amdgcn_wave_barrier();
             head = (head + count) & (IMQ_CAP - 1);
             waiting -= count;
         };
         for (int64_t i0 = 0; i0 < m; i0 += IMQ_ROWS) {
-            T xs[IMQ_ROWS], rs[IMQ_ROWS];
+            T xs[IMQ_ROWS][IMQ_VARS], rs[IMQ_ROWS];
 #pragma unroll
             for (int u = 0; u < IMQ_ROWS; ++u) {
                 const int64_t i = i0 + u < m ? i0 + u : m - 1;
-                xs[u] = Xt[i * n + j];
                 rs[u] = r[i * R + qc];
+#pragma unroll
+                for (int v = 0; v < IMQ_VARS; ++v) xs[u][v] = Xt[i * n + (j0 + v < n ? j0 + v : n - 1)];
             }
 #pragma unroll
             for (int u = 0; u < IMQ_ROWS; ++u) {
-                const bool take = counts && i0 + u < m && may_count(xs[u], rs[u]);
-                const unsigned long long mask = __ballot(take);
-                if (mask) {                                  // the same for the whole wavefront
-                    if (take) {
-                        const int before = __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
-                                                                     __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));
-                        const int e = (head + waiting + before) & (IMQ_CAP - 1);
-                        L.qx[w][e] = xs[u];
-                        L.qr[w][e] = rs[u];
-                        L.qlane[w][e] = (uint8_t)lane;
+#pragma unroll
+                for (int v = 0; v < IMQ_VARS; ++v) {
+                    const bool take = counts && i0 + u < m && j0 + v < n && may_count(xs[u][v], rs[u]);
+                    const unsigned long long mask = __ballot(take);
+                    if (mask) {                              // the same for the whole wavefront
+                        if (take) {
+                            const int before = __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                                                         __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));
+                            const int e = (head + waiting + before) & (IMQ_CAP - 1);
+                            L.qx[w][e] = xs[u][v];
+                            L.qr[w][e] = rs[u];
+                            L.qlane[w][e] = (uint8_t)lane;
+                            L.qvar[w][e] = (uint8_t)v;
+                        }
+                        waiting += __builtin_popcountll(mask);
+                        if (waiting >= 64) drain(64);
                     }
-                    waiting += __builtin_popcountll(mask);
-                    if (waiting >= 64) drain(64);
                 }
             }
         }
         if (waiting > 0) drain(waiting);
-        if (live) weight[q * n + j] = 1 + ((uint64_t)L.sum[w][lane] >> shift);
-        __builtin_amdgcn_wave_barrier();                    // the sums are cleared for the next variable
+        if (live) {
+#pragma unroll
+            for (int v = 0; v < IMQ_VARS; ++v)
+                if (j0 + v < n) weight[q * n + j0 + v] = 1 + ((uint64_t)L.sum[w][v][lane] >> shift);
+        }
+        __builtin_amdgcn_wave_barrier();                    // the sums are cleared for the next pass
     }
 }
 
@@ -531,7 +546,7 @@ static dmmv_status destroy_repair_t(Ctx* c, const dmmv_alns_params& prm, int32_t
                            c->p.n, (const T*)c->p.A_dense, c->p.lda, (const T*)c->r,
                            (const InstState<T>*)c->state, prm.alpha, c->alns_weight, (const AlnsState*)S);
     } else if (c->kind == KIND_BATCHED) {
-        int64_t ny = (c->p.n + 3) / 4;
+        int64_t ny = (c->p.n + 4 * IMQ_VARS - 1) / (4 * IMQ_VARS);     // a wavefront takes IMQ_VARS variables per pass
         if (ny > 2048) ny = 2048;
         hipLaunchKernelGGL(k_alns_impact_batched<T>, dim3(blocks_for(R, 64), (unsigned)ny), dim3(256), 0,
                            c->stream, c->p.m, c->p.n, R, (const T*)c->Xt, (const T*)c->scale_dev,
