@@ -275,8 +275,8 @@ __global__ __launch_bounds__(256) void k_alns_impact_dense(int64_t m, int64_t n,
 // a * 18 / alpha: the term truncates to 0), but they are scattered: almost every group of 64
 // lanes holds one, so testing inside the loop would send every wavefront through the
 // double-precision division and exponential for the sake of a lane or two.  The loop therefore
-// only TESTS (in fp32 for fp32 problems, with a margin of 1 % that covers the roundings of its
-// three operations; the exact test otherwise) and appends the terms that may count to a queue of
+// only TESTS (one comparison in the working precision, with a margin of 1 %) and appends the
+// terms that may count to a queue of
 // the wavefront in LDS; whenever 64 are waiting, every lane computes one of them, for whichever
 // instance it belongs to, and adds the integer to that instance's sum with an LDS atomic.  The
 // sum is one of integers, so the order does not matter and the weights are the same bit for bit.
@@ -290,8 +290,8 @@ constexpr int IMQ_VARS = 8;                    // consecutive variables a wavefr
 template <class T>
 struct ImpactShared {
     T qx[4][IMQ_CAP], qr[4][IMQ_CAP];          // waiting terms: matrix entry, residual of the row,
-    uint8_t qlane[4][IMQ_CAP];                 //   the lane (instance) they belong to
-    uint8_t qvar[4][IMQ_CAP];                  //   and which of the pass's variables
+    uint16_t qmeta[4][IMQ_CAP];                //   the lane (instance) they belong to, and in the
+                                               //   high byte which of the pass's variables
     unsigned long long sum[4][IMQ_VARS][64];
     double sc[4][64], t[4][64], scale[4][64];  // per instance: scale factor, error, fixed-point scale
 };
@@ -315,25 +315,20 @@ __global__ __launch_bounds__(256) void k_alns_impact_batched(int64_t m, int64_t 
     const double sc = (double)scale_q[qc];
     int shift = alns_bits(m) + 24 + alns_bits(n) - 62;
     if (shift < 0) shift = 0;
-    const float pre = (float)(18.0 / alpha * 1.01);
-    const float tf = (float)t, scf = (float)sc;             // exact for fp32 problems
     const bool counts = live && scale != 0.0;               // otherwise every weight of the instance is 1
     L.sc[w][lane] = sc;
     L.t[w][lane] = t;
     L.scale[w][lane] = scale;
     __builtin_amdgcn_wave_barrier();
-    // may the term of matrix entry x and residual rv of this lane's instance count?
-    auto may_count = [&](T x, T rv) -> bool {
-        if constexpr (sizeof(T) == 4) {
-            const float af = __builtin_fabsf(scf * (float)x);
-            const float slack = tf - __builtin_fabsf((float)rv);
-            return !(slack > af * pre);
-        } else {
-            const double a = __builtin_fabs(sc * (double)x);
-            const double slack = t - __builtin_fabs((double)rv);
-            return a != 0.0 && !(slack > a * (18.0 / alpha));
-        }
-    };
+    // May the term of matrix entry x and a row of slack t - |r_i| count?  The shortcut cuts it off
+    // when slack > |sc x| * 18 / alpha, i.e. when |x| < slack * alpha / (18 sc).  The loop tests
+    // |x| >= lim_i with lim_i = slack_i * cinv, cinv = alpha / (18 * 1.01 * sc), in the working
+    // precision: the 1 % covers the roundings of cinv and of the product, so a term the test
+    // leaves out is one the shortcut cuts off (the reverse need not hold: alns_impact_term
+    // applies the exact shortcut again).  One comparison per term; lim_i is per row.
+    const T tw = (T)t;                                      // exact: t is a value of type T
+    T cinv = (T)(alpha / (18.0 * 1.01)) / (T)sc;
+    if (!(cinv < Limits<T>::inf())) cinv = (T)0;            // a scale so small that this overflows: test nothing
     for (int64_t j0 = (blockIdx.y * 4ll + w) * IMQ_VARS; j0 < n; j0 += 4ll * IMQ_VARS * gridDim.y) {
 #pragma unroll
         for (int v = 0; v < IMQ_VARS; ++v) L.sum[w][v][lane] = 0;
@@ -343,18 +338,19 @@ __global__ __launch_bounds__(256) void k_alns_impact_batched(int64_t m, int64_t 
             __builtin_amdgcn_wave_barrier();
             if (lane < count) {
                 const int e = (head + lane) & (IMQ_CAP - 1);
-                const int owner = L.qlane[w][e];
+                const int meta = L.qmeta[w][e];
+                const int owner = meta & 0xFF;
                 const double a = __builtin_fabs(L.sc[w][owner] * (double)L.qx[w][e]);
                 const uint64_t term = alns_impact_term(a, __builtin_fabs((double)L.qr[w][e]), L.t[w][owner], alpha,
                                                        L.scale[w][owner]);
-                if (term) atomicAdd(&L.sum[w][L.qvar[w][e]][owner], (unsigned long long)term);
+                if (term) atomicAdd(&L.sum[w][meta >> 8][owner], (unsigned long long)term);
             }
             __builtin_amdgcn_wave_barrier();
             head = (head + count) & (IMQ_CAP - 1);
             waiting -= count;
         };
         for (int64_t i0 = 0; i0 < m; i0 += IMQ_ROWS) {
-            T xs[IMQ_ROWS][IMQ_VARS], rs[IMQ_ROWS];
+            T xs[IMQ_ROWS][IMQ_VARS], rs[IMQ_ROWS], lim[IMQ_ROWS];
 #pragma unroll
             for (int u = 0; u < IMQ_ROWS; ++u) {
                 const int64_t i = i0 + u < m ? i0 + u : m - 1;
@@ -363,10 +359,14 @@ __global__ __launch_bounds__(256) void k_alns_impact_batched(int64_t m, int64_t 
                 for (int v = 0; v < IMQ_VARS; ++v) xs[u][v] = Xt[i * n + (j0 + v < n ? j0 + v : n - 1)];
             }
 #pragma unroll
+            for (int u = 0; u < IMQ_ROWS; ++u)              // a lane or a row that does not count takes nothing
+                lim[u] = counts && i0 + u < m ? (tw - dmmv_abs(rs[u])) * cinv : Limits<T>::inf();
+#pragma unroll
             for (int u = 0; u < IMQ_ROWS; ++u) {
 #pragma unroll
                 for (int v = 0; v < IMQ_VARS; ++v) {
-                    const bool take = counts && i0 + u < m && j0 + v < n && may_count(xs[u][v], rs[u]);
+                    if (j0 + v >= n) continue;               // the same for the whole wavefront
+                    const bool take = dmmv_abs(xs[u][v]) >= lim[u];
                     const unsigned long long mask = __ballot(take);
                     if (mask) {                              // the same for the whole wavefront
                         if (take) {
@@ -375,8 +375,7 @@ __global__ __launch_bounds__(256) void k_alns_impact_batched(int64_t m, int64_t 
                             const int e = (head + waiting + before) & (IMQ_CAP - 1);
                             L.qx[w][e] = xs[u][v];
                             L.qr[w][e] = rs[u];
-                            L.qlane[w][e] = (uint8_t)lane;
-                            L.qvar[w][e] = (uint8_t)v;
+                            L.qmeta[w][e] = (uint16_t)(lane | (v << 8));
                         }
                         waiting += __builtin_popcountll(mask);
                         if (waiting >= 64) drain(64);
