@@ -334,8 +334,12 @@ dmmv_status descent_t(Ctx* c, int32_t steps, int32_t iters, dmmv_move* trace, vo
     const size_t lds = bp_lds_bytes(m, n, c->p.nd, sizeof(T));
     const int32_t span = c->o.radius > 0 ? 2 * c->o.radius + 1 : c->p.nd;
     auto launch = [&](auto kernel) -> dmmv_status {
-        DMMV_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)BP_LDS_LIMIT));
+        static bool attr_set = false;                      // per instantiation of this lambda, i.e. per kernel
+        if (!attr_set) {
+            DMMV_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)BP_LDS_LIMIT));
+            attr_set = true;
+        }
         hipLaunchKernelGGL(kernel, dim3((unsigned)R), dim3(BP_BLOCK), lds, c->stream, m, n, c->p.nd, R,
                            (const T*)c->p.A_dense, c->p.lda, (const T*)c->Xt, (const T*)c->D_dev,
                            (const T*)c->scale_dev, (T*)c->r, c->kidx, (InstState<T>*)c->state, c->o.radius,
@@ -347,11 +351,14 @@ dmmv_status descent_t(Ctx* c, int32_t steps, int32_t iters, dmmv_move* trace, vo
         if (c->o.radius > 0) return launch(k_descent_batched_pruned<T, 16, true, uint16_t>);
         return launch(k_descent_batched_pruned<T, 16, false, uint16_t>);
     }
+    // the register tile that wastes least: 4 (a radius of 1, 2-bit codes), 8 (3-bit codes), 16
     if (c->o.radius > 0) {
         if (span <= 4) return launch(k_descent_batched_pruned<T, 4, true, uint8_t>);
+        if (span <= 8) return launch(k_descent_batched_pruned<T, 8, true, uint8_t>);
         return launch(k_descent_batched_pruned<T, 16, true, uint8_t>);
     }
     if (span <= 4) return launch(k_descent_batched_pruned<T, 4, false, uint8_t>);
+    if (span <= 8) return launch(k_descent_batched_pruned<T, 8, false, uint8_t>);
     return launch(k_descent_batched_pruned<T, 16, false, uint8_t>);
 }
 
