@@ -85,19 +85,101 @@ __global__ __launch_bounds__(256) void k_residual_batched(
     T acc[TI];
 #pragma unroll
     for (int u = 0; u < TI; ++u) acc[u] = (T)0;
-    for (int64_t j = 0; j < n; ++j) {
-        const T v = shD[kidx[j * R + qc]];
-        const T* __restrict__ xp = X + ldx * j + i0;
+    // the level indices of RJ variables are fetched together (one memory latency for RJ
+    // variables); the order of the additions stays j ascending
+    constexpr int RJ = 8;
+    for (int64_t j0 = 0; j0 < n; j0 += RJ) {
+        int32_t kk[RJ];
 #pragma unroll
-        for (int u = 0; u < TI; ++u) {
-            const T a = (i0 + u < m) ? xp[u] : (T)0;
-            acc[u] = dmmv_fma(a, v, acc[u]);
+        for (int e = 0; e < RJ; ++e) kk[e] = kidx[(j0 + e < n ? j0 + e : n - 1) * R + qc];
+#pragma unroll
+        for (int e = 0; e < RJ; ++e) {
+            if (j0 + e >= n) break;                          // the same for the whole wavefront
+            const T v = shD[kk[e]];
+            const T* __restrict__ xp = X + ldx * (j0 + e) + i0;
+#pragma unroll
+            for (int u = 0; u < TI; ++u) {
+                const T a = (i0 + u < m) ? xp[u] : (T)0;
+                acc[u] = dmmv_fma(a, v, acc[u]);
+            }
         }
     }
     if (q < R) {
         const T sc = scale[q];
 #pragma unroll
         for (int u = 0; u < TI; ++u)
+            if (i0 + u < m) r[(i0 + u) * R + q] = dmmv_fma(acc[u], sc, -Bt[(i0 + u) * R + q]);
+    }
+}
+
+// The same sums for large batches: the 4 wavefronts of a workgroup take 4 groups of 64 instances
+// and the SAME RT rows, so a tile of X (RC columns x RT rows) is staged once in LDS for all 256
+// instances and read back as broadcasts (every lane of a wavefront needs the same entry), instead
+// of travelling through the scalar cache once per wavefront.  Order over j ascending as above.
+constexpr int RT = 32;                      // rows per lane
+constexpr int RC = 32;                      // columns per staged tile
+
+template <class T>
+__global__ __launch_bounds__(256) void k_residual_batched_tiled(
+    int64_t m, int64_t n, int64_t R, const T* __restrict__ X, int64_t ldx, const T* __restrict__ D,
+    int32_t nd, const int32_t* __restrict__ kidx, const T* __restrict__ scale,
+    const T* __restrict__ Bt, T* __restrict__ r) {
+    extern __shared__ unsigned char smem[];
+    T* shD = reinterpret_cast<T*>(smem);
+    __shared__ __align__(16) T tile[2][RC][RT];
+    for (int k = threadIdx.x; k < nd; k += blockDim.x) shD[k] = D[k];
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t q = (blockIdx.x * 4ll + w) * 64 + lane;
+    const int64_t qc = q < R ? q : R - 1;
+    const int64_t i0 = blockIdx.y * (int64_t)RT;
+    // staging: thread t fetches 4 consecutive rows (t % 8) * 4 .. + 3 of column t / 8 of the tile
+    const int sc_col = threadIdx.x >> 3, sc_row = (threadIdx.x & 7) * 4;
+    T stage[4];
+    auto fetch = [&](int64_t j0) {
+        const int64_t j = j0 + sc_col < n ? j0 + sc_col : n - 1;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int64_t i = i0 + sc_row + u;
+            stage[u] = X[ldx * j + (i < m ? i : m - 1)];     // rows past the end are never stored below
+        }
+    };
+    auto stash = [&](int buf) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) tile[buf][sc_col][sc_row + u] = stage[u];
+    };
+    T acc[RT];
+#pragma unroll
+    for (int u = 0; u < RT; ++u) acc[u] = (T)0;
+    fetch(0);
+    stash(0);
+    __syncthreads();
+    int buf = 0;
+    for (int64_t j0 = 0; j0 < n; j0 += RC, buf ^= 1) {
+        if (j0 + RC < n) fetch(j0 + RC);                     // the next tile travels while this one is used
+        constexpr int RJ = 8;
+        for (int jc0 = 0; jc0 < RC; jc0 += RJ) {
+            int32_t kk[RJ];
+#pragma unroll
+            for (int e = 0; e < RJ; ++e) {
+                const int64_t j = j0 + jc0 + e;
+                kk[e] = kidx[(j < n ? j : n - 1) * R + qc];
+            }
+#pragma unroll
+            for (int e = 0; e < RJ; ++e) {
+                if (j0 + jc0 + e >= n) break;                // the same for the whole workgroup
+                const T v = shD[kk[e]];
+#pragma unroll
+                for (int u = 0; u < RT; ++u) acc[u] = dmmv_fma(tile[buf][jc0 + e][u], v, acc[u]);
+            }
+        }
+        if (j0 + RC < n) stash(buf ^ 1);
+        __syncthreads();
+    }
+    if (q < R) {
+        const T sc = scale[q];
+#pragma unroll
+        for (int u = 0; u < RT; ++u)
             if (i0 + u < m) r[(i0 + u) * R + q] = dmmv_fma(acc[u], sc, -Bt[(i0 + u) * R + q]);
     }
 }
@@ -316,11 +398,24 @@ template <class T>
 static dmmv_status residual_t(Ctx* c) {
     const int64_t m = c->p.m, n = c->p.n, R = c->p.R;
     if (m == 0) return DMMV_OK;
-    constexpr int TI = 8;
-    dim3 grid((unsigned)ceil_div(R, 64), (unsigned)ceil_div(m, 4 * TI));
-    hipLaunchKernelGGL((k_residual_batched<T, TI>), grid, dim3(256), (size_t)c->p.nd * sizeof(T), c->stream,
-                       m, n, R, (const T*)c->p.A_dense, c->p.lda, (const T*)c->D_dev, c->p.nd,
-                       (const int32_t*)c->kidx, (const T*)c->scale_dev, (const T*)c->Bt, (T*)c->r);
+    // rows per lane: every variable's level index is read once per TI rows, so tall matrices take
+    // many rows per lane (as long as the launch still fills the chip)
+    auto launch = [&](auto kernel, int ti) {
+        dim3 grid((unsigned)ceil_div(R, 64), (unsigned)ceil_div(m, 4 * ti));
+        hipLaunchKernelGGL(kernel, grid, dim3(256), (size_t)c->p.nd * sizeof(T), c->stream,
+                           m, n, R, (const T*)c->p.A_dense, c->p.lda, (const T*)c->D_dev, c->p.nd,
+                           (const int32_t*)c->kidx, (const T*)c->scale_dev, (const T*)c->Bt, (T*)c->r);
+    };
+    if (R >= 256 && ceil_div(R, 256) * ceil_div(m, RT) >= 512) {
+        dim3 grid((unsigned)ceil_div(R, 256), (unsigned)ceil_div(m, RT));
+        hipLaunchKernelGGL(k_residual_batched_tiled<T>, grid, dim3(256), (size_t)c->p.nd * sizeof(T), c->stream,
+                           m, n, R, (const T*)c->p.A_dense, c->p.lda, (const T*)c->D_dev, c->p.nd,
+                           (const int32_t*)c->kidx, (const T*)c->scale_dev, (const T*)c->Bt, (T*)c->r);
+    } else if (ceil_div(R, 64) * ceil_div(m, 4 * 32) >= 512) {
+        launch(k_residual_batched<T, 32>, 32);
+    } else {
+        launch(k_residual_batched<T, 8>, 8);
+    }
     DMMV_LAUNCH_CHECK();
     return DMMV_OK;
 }

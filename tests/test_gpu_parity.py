@@ -351,6 +351,25 @@ def test_batched_f64_and_integer_ties():
     batched_check(random_batched(9, 30, 10, 70, 4, dtype=np.float32, integer=True), 15)
 
 
+@pytest.mark.parametrize("shape,dtype", [((8200, 7, 515, 5), np.float32), ((8195, 37, 600, 9), np.float32),
+                                         ((8200, 6, 512, 4), np.float64), ((2100, 33, 600, 8), np.float32)])
+def test_batched_residual_kernels_for_large_batches(shape, dtype):
+    """Enough instances and rows for the residual kernels that large batches take (the LDS-tiled
+    one from 256 instances and 512 workgroups on, the 32-rows-per-lane one below that): every
+    element equals the oracle's sequential-order sum bit for bit, ragged edges included."""
+    m = dmmv()
+    mm, nn, R, nd = shape
+    inst = random_batched(3000 + nn, mm, nn, R, nd, dtype=dtype)
+    with m.from_instance(inst, DEV) as h:
+        m.dmmv_set_x(h, T(inst.x0))
+        r = N(m.dmmv_residual(h))
+        x, r2, t = m.dmmv_get_state(h)
+        assert np.array_equal(np.abs(r).max(axis=1), N(t))
+    for q in list(range(0, R, 41)) + [R - 1]:
+        rq = orc.residual_dense(inst.A, inst.b[q], inst.D, inst.x0[q], scale=inst.scale[q])
+        assert np.array_equal(r[q], rq), q
+
+
 def test_batched_stepwise_tables():
     m = dmmv()
     inst = random_batched(66, 75, 21, 67, 16, dtype=np.float32)
