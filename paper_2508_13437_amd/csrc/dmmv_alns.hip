@@ -268,7 +268,34 @@ __global__ __launch_bounds__(256) void k_alns_impact_dense(int64_t m, int64_t n,
     }
 }
 
-// batched: lane = instance (r coalesced, X through the scalar unit); grid.x = group of 64
+// batched: the instances whose destroy operator of this iteration is worst-remove, in ascending
+// order (single workgroup); their number goes to flags[FLAG_WORST].  The impact kernel works on
+// this list, so that its wavefronts are full of instances that need weights.
+__global__ __launch_bounds__(1024) void k_alns_worst_list(int64_t R, const AlnsState* __restrict__ S,
+                                                          int32_t* __restrict__ list, int32_t* flags) {
+    __shared__ int32_t sh_cnt[16];
+    __shared__ int32_t sh_base;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    if (threadIdx.x == 0) sh_base = 0;
+    __syncthreads();
+    for (int64_t b0 = 0; b0 < R; b0 += 1024) {
+        const int64_t q = b0 + threadIdx.x;
+        const bool on = q < R && S[q].d_op == 1;
+        const unsigned long long bal = __ballot(on);
+        if (lane == 0) sh_cnt[w] = __popcll(bal);
+        __syncthreads();
+        int32_t before = 0, all = 0;
+        for (int u = 0; u < 16; ++u) { if (u < w) before += sh_cnt[u]; all += sh_cnt[u]; }
+        const int32_t base = sh_base;
+        if (on) list[base + before + __popcll(bal & ((1ull << lane) - 1ull))] = (int32_t)q;
+        __syncthreads();
+        if (threadIdx.x == 0) sh_base = base + all;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) flags[FLAG_WORST] = sh_base;
+}
+
+// batched: lane = listed instance (X through the scalar unit); grid.x = group of 64 of them
 // instances, each of the 4 wavefronts takes the variables blockIdx.y*4 + w, +4*gridDim.y, ...
 //
 // Only a few per cent of the terms are not cut off by the shortcut of alns_impact_term (slack >
@@ -302,14 +329,18 @@ __global__ __launch_bounds__(256) void k_alns_impact_batched(int64_t m, int64_t 
                                                              const T* __restrict__ scale_q,
                                                              const T* __restrict__ r,
                                                              const InstState<T>* st, double alpha,
-                                                             uint64_t* __restrict__ weight, const AlnsState* S) {
+                                                             uint64_t* __restrict__ weight,
+                                                             const int32_t* __restrict__ list,
+                                                             const int32_t* __restrict__ flags) {
     __shared__ ImpactShared<T> L;
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t q = blockIdx.x * 64ll + lane;
-    const bool live = q < R && S[q < R ? q : 0].d_op == 1;
-    if (__ballot(live) == 0ull) return;
-    const int64_t qc = q < R ? q : R - 1;
+    const int64_t count = flags[FLAG_WORST];                // instances on the list (k_alns_worst_list)
+    const int64_t slot = blockIdx.x * 64ll + lane;
+    if (blockIdx.x * 64ll >= count) return;                 // the same for the whole workgroup
+    const bool live = slot < count;
+    const int64_t q = list[live ? slot : count - 1];
+    const int64_t qc = q;
     const double t = (double)st[qc].t;
     const double scale = alns_impact_scale(t);
     const double sc = (double)scale_q[qc];
@@ -547,10 +578,13 @@ static dmmv_status destroy_repair_t(Ctx* c, const dmmv_alns_params& prm, int32_t
     } else if (c->kind == KIND_BATCHED) {
         int64_t ny = (c->p.n + 4 * IMQ_VARS - 1) / (4 * IMQ_VARS);     // a wavefront takes IMQ_VARS variables per pass
         if (ny > 2048) ny = 2048;
+        // (the list shares the buffer of the descent's list of running instances: never both at once)
+        hipLaunchKernelGGL(k_alns_worst_list, dim3(1), dim3(1024), 0, c->stream, R, (const AlnsState*)S,
+                           c->cmp_orig, c->flags);
         hipLaunchKernelGGL(k_alns_impact_batched<T>, dim3(blocks_for(R, 64), (unsigned)ny), dim3(256), 0,
                            c->stream, c->p.m, c->p.n, R, (const T*)c->Xt, (const T*)c->scale_dev,
                            (const T*)c->r, (const InstState<T>*)c->state, prm.alpha, c->alns_weight,
-                           (const AlnsState*)S);
+                           (const int32_t*)c->cmp_orig, (const int32_t*)c->flags);
     } else {
         DMMV_TRY(csc_alns_impact(c, prm.alpha));
     }

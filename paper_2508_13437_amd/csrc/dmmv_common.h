@@ -76,7 +76,7 @@ struct alignas(16) Partial {
 };
 
 // device flag slots
-enum { FLAG_ERROR = 0, FLAG_ACTIVE = 1, FLAG_PLANES = 2, FLAG_MAXROW = 3, FLAG_MAXCOL = 4, FLAG_COUNT = 8 };
+enum { FLAG_ERROR = 0, FLAG_ACTIVE = 1, FLAG_PLANES = 2, FLAG_MAXROW = 3, FLAG_MAXCOL = 4, FLAG_WORST = 5, FLAG_COUNT = 8 };
 // error bits set by kernels
 enum { ERRBIT_X_NOT_IN_D = 1, ERRBIT_CSR_RANGE = 2, ERRBIT_CSR_DUP = 4, ERRBIT_MOVE_RANGE = 8 };
 
