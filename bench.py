@@ -13,9 +13,10 @@ Prints ONE JSON line.  `value` = candidate moves evaluated per second over the w
 region.  `roofline` describes the dominant kernel (the evaluation kernel that streams all of
 A), timed with HIP events on the library's stream.  `cpu_baseline` is the CPU oracle timed on
 a bounded sample of the same workload on this host.  Further objects of the same line:
-`other_workloads` (the same measurements for the other four workloads), `descent` (sparse: the
-real descent with and without pruning), `alns` (wall time of the ALNS outer loop), `residual`
-(batched: the sequential-order and the matrix-core residual).
+`other_workloads` (the same measurements for the other four workloads), `descent` (sparse and
+batched: the real descent with and without exact pruning), `alns` (wall time of the ALNS outer
+loop; batched also `alns_full_evaluation`, dense `alns_value_search`), `swap` (one search of the
+swap move), `residual` (batched: the sequential-order and the matrix-core residual).
 """
 from __future__ import annotations
 
