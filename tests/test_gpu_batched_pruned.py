@@ -112,3 +112,24 @@ def test_pruned_and_full_descent_agree_on_the_full_size_layer():
             out.append((N(res.x), N(res.max_violation), N(res.iters_done), N(res.trace), N(res.trace_t)))
     for a, b in zip(out[0], out[1]):
         assert np.array_equal(a, b)
+
+
+def test_pruned_descent_of_the_full_size_layer_follows_the_oracle_to_the_local_optimum():
+    """Config 4 at full size with pruning, up to 100 iterations (every instance but a few reaches
+    its local optimum); four seeded instances are replayed by the oracle's full enumeration and
+    must show the same moves, errors and solutions."""
+    m = dmmv()
+    inst = make_config(4)
+    iters = 100
+    with m.from_instance(inst, DEV, prune=True) as h:
+        res = m.dmmv_solve(h, T(inst.x0), iters, trace=True)
+        x, t, done = N(res.x), N(res.max_violation), N(res.iters_done)
+        tr, tt = N(res.trace), N(res.trace_t)
+    sel = np.sort(np.random.default_rng(44).choice(inst.R, size=4, replace=False))
+    print("oracle replay of instances", sel, flush=True)
+    o = orc.solve_batched(inst.A, inst.b[sel], inst.D, inst.scale[sel], inst.x0[sel], iters)
+    assert np.array_equal(done[sel], o.iters_done)
+    assert np.array_equal(tr[sel][:, :, 0], o.trace_j) and np.array_equal(tr[sel][:, :, 1], o.trace_k)
+    assert np.array_equal(tt[sel], o.trace_t)
+    assert np.array_equal(x[sel], o.x) and np.array_equal(t[sel], o.t)
+    assert o.iters_done.min() >= 10
