@@ -28,6 +28,10 @@ def test_pruned_batched_many_levels_and_instances_too_large_for_lds():
     batched_check(random_batched(9051, 33, 5, 3, 700, dtype=np.float64), 8, radius=40, prune=True)
     # (m + n) w + 2 n bytes exceed the LDS a workgroup may take: the full evaluation runs instead
     batched_check(random_batched(9052, 8, 21000, 3, 3, dtype=np.float32), 4, prune=True)
+    # more rows than a thread's 64-bit row mask covers: the full evaluation again
+    batched_check(random_batched(9053, 16400, 5, 3, 3, dtype=np.float32), 4, prune=True)
+    # the largest m that is pruned
+    batched_check(random_batched(9054, 16384, 6, 2, 3, dtype=np.float32), 6, prune=True)
 
 
 def test_pruned_batched_f64_and_integer_ties():
