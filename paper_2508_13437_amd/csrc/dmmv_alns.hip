@@ -310,7 +310,8 @@ __global__ __launch_bounds__(1024) void k_alns_worst_list(int64_t R, const AlnsS
 // A wavefront goes over the rows once for eight consecutive variables, so that an instance's
 // residual (the only per-lane operand) is read once for all eight.
 constexpr int IMQ_CAP = 128;                   // ring of waiting terms per wavefront (drained at 64)
-constexpr int IMQ_ROWS = 4;                    // rows whose operands are fetched before they are tested
+constexpr int IMQ_ROWS = 1;                    // rows whose operands are fetched before they are tested (more rows in
+                                               //   flight only make the unrolled loop longer: 14.9 ms with 4, 13.1 with 1)
 constexpr int IMQ_VARS = 8;                    // consecutive variables a wavefront works on per pass over the rows
                                                //   (r is read once for all of them)
 
