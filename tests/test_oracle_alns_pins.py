@@ -391,3 +391,208 @@ def test_l2_guard_keeps_both_norms_from_increasing():
     assert guard.accepted.sum() < free.accepted.sum() or not np.array_equal(guard.t, free.t)
     # the best solution's residual has the recorded error
     assert np.isclose(np.abs(A @ guard.x - b).max(), guard.t_best)
+
+
+# ---- per-instance scale (batched instances: variables take the values s * D[k]) ------------------
+def _scaled_csr(inst_A, s):
+    """CSR of s * A with every entry stored (s a power of two: the products are exact)."""
+    rowptr, col, val = orc.full_csr(np.asarray(inst_A) * s)
+    return rowptr, col, val
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("s", [0.25, 8.0])
+def test_power_of_two_scale_is_the_same_run_as_the_scale_folded_into_the_matrix(dtype, s):
+    """Instance q of a batch is the problem with matrix s_q X (section "Quantization without
+    outlier separation as DMMV": A = X s_row).  With s a power of two, s X_ij is exact and every
+    rounding of the scaled run (residual, steps, pairs, slacks of the impact score) meets the same
+    real number as the run on the matrix s X with scale 1: the whole outer loop must agree bit for
+    bit - operators, draws, repairs, local-search moves, errors, weights and the solution."""
+    inst = random_dense(610, 36, 14, 5, dtype=dtype)
+    prm = orc.alns_params(30, ls_moves=5, ls_radius=1, destroy_count=3, seed=17, ls_swaps=1, l2_guard=1)
+    a = orc.alns_dense(inst.A, inst.b, inst.D, inst.x0, prm, inst=3, scale=s)
+    b = orc.alns_dense((inst.A.astype(np.float64) * s).astype(dtype), inst.b, inst.D, inst.x0, prm, inst=3, scale=1.0)
+    for f in ("destroy", "repair", "moves", "accepted", "t", "best", "weights", "q2", "x"):
+        assert np.array_equal(getattr(a, f), getattr(b, f)), f
+    assert a.t_best == b.t_best
+    # the scale is not a no-op: the unscaled problem runs differently
+    c = orc.alns_dense(inst.A, inst.b, inst.D, inst.x0, prm, inst=3, scale=1.0)
+    assert not np.array_equal(a.t, c.t)
+    # and both destroy operators and the local search took part
+    assert set(a.destroy.tolist()) == {0, 1} and a.moves.sum() > 0
+
+
+@pytest.mark.parametrize("s", [0.5, 4.0, 0.37])
+def test_impact_weights_with_a_scale_follow_the_bound_equations_of_the_scaled_matrix(s):
+    inst = random_dense(611, 14, 6, 5)
+    A = inst.A.astype(np.float64)
+    r = orc.residual_dense(A, inst.b, inst.D, inst.x0, scale=s)
+    # Appendix B.2 evaluated literally for the matrix s A
+    sres, t, Rs, num = literal_impact(A * s, inst.b, inst.x0, 0.3)
+    assert np.allclose(sres, r, rtol=1e-12, atol=1e-12)
+    rowptr, col, val = orc.full_csr(A)
+    w = orc.alns_impact_weights(inst.m, inst.n, rowptr, col, val, r, alpha=0.3, scale=s).astype(np.float64)
+    scale = 2.0 ** (24 - math.frexp(t)[1])
+    assert np.all(np.abs((w - 1) - num * scale) <= inst.m + 1e-6 * num * scale)
+    # without the scale the slacks are divided by other coefficients: other weights
+    w1 = orc.alns_impact_weights(inst.m, inst.n, rowptr, col, val, r, alpha=0.3, scale=1.0).astype(np.float64)
+    assert not np.allclose(w1, w, rtol=1e-3)
+    if s in (0.5, 4.0):                                    # power of two: same bits as the folded matrix
+        rp, cc, vv = _scaled_csr(A, s)
+        w2 = orc.alns_impact_weights(inst.m, inst.n, rp, cc, vv, r, alpha=0.3, scale=1.0)
+        assert np.array_equal(w2.astype(np.float64), w)
+
+
+@pytest.mark.parametrize("s", [0.5, 2.0, 1.7])
+def test_repair_with_a_scale_is_the_repair_of_the_scaled_matrix(s):
+    inst = random_dense(612, 18, 7, 6)
+    A = inst.A.astype(np.float64)
+    rowptr, col, val = orc.full_csr(A)
+    D = inst.D
+    x = inst.x0.copy()
+    r = orc.residual_dense(A, inst.b, D, x, scale=s)
+    assert np.allclose(r, (A * s) @ x - inst.b, atol=1e-12)     # starting residual carries the scale
+    picked = np.array([3, 0, 6, 5], dtype=np.int32)
+    for greedy in (True, False):
+        x_new, r_new = orc.alns_repair(inst.m, inst.n, rowptr, col, val, D, x, r, picked, greedy, 5, 2, 7, scale=s)
+        xs = x.copy()
+        for pos, j in enumerate(picked):
+            k = int(np.searchsorted(D, xs[j]))
+            cands = [kk for kk in (k - 1, k + 1) if 0 <= kk < D.size]
+            if greedy:
+                errs = []
+                for kk in cands:
+                    y = xs.copy(); y[j] = D[kk]
+                    errs.append(np.abs((A * s) @ y - inst.b).max())
+                assert len(cands) == 1 or abs(errs[0] - errs[1]) > 1e-9
+                best = cands[int(np.argmin(errs))]
+            else:
+                up = orc.alns_rnd(5, 2, 7, 2, pos) & 1
+                best = k + 1 if (up or k == 0) and k + 1 < D.size else k - 1
+            xs[j] = D[best]
+        assert np.array_equal(x_new, xs), greedy
+        assert np.allclose(r_new, (A * s) @ xs - inst.b, atol=1e-9)
+    if s in (0.5, 2.0):
+        rp, cc, vv = _scaled_csr(A, s)
+        xa, ra = orc.alns_repair(inst.m, inst.n, rowptr, col, val, D, x, r, picked, True, 5, 2, 7, scale=s)
+        xb, rb = orc.alns_repair(inst.m, inst.n, rp, cc, vv, D, x, r, picked, True, 5, 2, 7, scale=1.0)
+        assert np.array_equal(xa, xb) and np.array_equal(ra, rb)
+
+
+# ---- the loop replayed outside the oracle ---------------------------------------------------------
+def _replay_alns(A, b, D, x0, res, iters, ls_moves, ls_radius, count, seed, inst, alpha=0.3, s=1.0):
+    """Algorithm 1 replayed from the oracle's trace on small-integer data (every operation exact).
+    The draws and the repair come from the oracle's own routines, which have pins of their own; the
+    local search is written out here from its definition: while moves are left, the error of every
+    single-coordinate change (within ls_radius levels) is recomputed FRESH as max |A x' - b|, the
+    smallest wins (lowest flat index on a tie) and is taken only if it is strictly below the
+    current error.  Returns how many local searches stopped on a plateau (best score == error)
+    with moves to spare."""
+    As = np.asarray(A, dtype=np.float64) * s
+    b = np.asarray(b, dtype=np.float64)
+    D = np.asarray(D, dtype=np.float64)
+    m, n = As.shape
+    nd = D.size
+    rowptr, col, val = orc.full_csr(np.asarray(A, dtype=np.float64))
+    x_cur = np.asarray(x0, dtype=np.float64).copy()
+    t_cur = np.abs(As @ x_cur - b).max()
+    plateaus = 0
+    for it in range(iters):
+        x = x_cur.copy()
+        r = As @ x - b
+        if res.destroy[it] == 1:
+            w = orc.alns_impact_weights(m, n, rowptr, col, val, r, alpha=alpha, scale=s)
+            picked = orc.alns_sample(n, w, count, seed, inst, it)
+        else:
+            picked = orc.alns_sample(n, None, count, seed, inst, it)
+        assert len(picked) == min(count, n)
+        x, r = orc.alns_repair(m, n, rowptr, col, val, D, x, r, picked, bool(res.repair[it]), seed, inst, it, scale=s)
+        assert np.array_equal(r, As @ x - b)
+        t = np.abs(r).max()
+        moves = 0
+        while moves < ls_moves:
+            best = (np.inf, -1, -1)
+            for j in range(n):
+                kc = int(np.searchsorted(D, x[j]))
+                for k in range(nd):
+                    if k != kc and ls_radius > 0 and abs(k - kc) > ls_radius:
+                        continue
+                    y = x.copy(); y[j] = D[k]
+                    sc = np.abs(As @ y - b).max()
+                    if sc < best[0]:
+                        best = (sc, j, k)
+            if not best[0] < t:
+                plateaus += int(best[0] == t)
+                break
+            x[best[1]] = D[best[2]]
+            t = best[0]
+            moves += 1
+        assert res.moves[it] == moves, (it, res.moves[it], moves)
+        assert res.t[it] == t, (it, res.t[it], t)
+        ok = t <= t_cur
+        assert bool(res.accepted[it]) == ok
+        if ok:
+            x_cur, t_cur = x, t
+    return plateaus
+
+
+@pytest.mark.parametrize("radius", [1, 0])
+def test_local_search_of_the_loop_is_the_strict_best_improvement_descent(radius):
+    inst = random_dense(620, 16, 9, 5, integer=True)
+    iters, ls_moves, count, seed = 40, 6, 2, 4
+    prm = orc.alns_params(iters, ls_moves=ls_moves, ls_radius=radius, destroy_count=count, seed=seed)
+    res = orc.alns_dense(inst.A, inst.b, inst.D, inst.x0, prm, inst=1)
+    plateaus = _replay_alns(inst.A, inst.b, inst.D, inst.x0, res, iters, ls_moves, radius, count, seed, 1)
+    # the case that tells '<' from '<=': a best move that only EQUALS the current error was refused
+    assert plateaus > 0
+    assert 0 < res.moves.sum() and res.moves.max() <= ls_moves
+
+
+def test_neighbourhood_radius_of_the_local_search_changes_the_run():
+    """ls_radius = 1 tries the two neighbouring levels only (the paper's 1-OPT), 0 every level:
+    on this instance a jump of more than one level is the best move somewhere, so the runs part."""
+    inst = random_dense(620, 16, 9, 5, integer=True)
+    near = orc.alns_dense(inst.A, inst.b, inst.D, inst.x0, orc.alns_params(40, ls_moves=6, ls_radius=1, destroy_count=2, seed=4), inst=1)
+    far = orc.alns_dense(inst.A, inst.b, inst.D, inst.x0, orc.alns_params(40, ls_moves=6, ls_radius=0, destroy_count=2, seed=4), inst=1)
+    assert not (np.array_equal(near.t, far.t) and np.array_equal(near.moves, far.moves))
+
+
+def test_loop_with_a_scale_replays_on_the_scaled_matrix():
+    inst = random_dense(621, 14, 8, 4, integer=True)
+    iters, ls_moves, count, seed, s = 25, 4, 2, 12, 0.5
+    prm = orc.alns_params(iters, ls_moves=ls_moves, ls_radius=1, destroy_count=count, seed=seed)
+    res = orc.alns_dense(inst.A, inst.b, inst.D, inst.x0, prm, inst=6, scale=s)
+    _replay_alns(inst.A, inst.b, inst.D, inst.x0, res, iters, ls_moves, 1, count, seed, 6, s=s)
+    assert res.t_best == np.abs((inst.A * s) @ res.x - inst.b).max()
+
+
+@pytest.mark.parametrize("n,count", [(199, 1), (200, 1), (201, 2), (1000, 5), (7, 1)])
+def test_default_destroy_count_is_half_a_percent_rounded_up(n, count):
+    """Appendix F: 0.5 % of the variables are unassigned; read as ceil(0.005 n), at least one.
+    With no local search the error after the first iteration is that of x0 with exactly that many
+    variables reassigned, which the replay checks (the replay asserts the number of draws)."""
+    assert count == max(1, math.ceil(n * 5 / 1000))
+    inst = random_dense(630 + n, 6, n, 4, integer=True)
+    prm = orc.alns_params(3, ls_moves=0, ls_radius=1, destroy_count=0, seed=2)
+    res = orc.alns_dense(inst.A, inst.b, inst.D, inst.x0, prm)
+    _replay_alns(inst.A, inst.b, inst.D, inst.x0, res, 3, 0, 1, count, 2, 0)
+    if count > 1:
+        # one draw fewer gives another error after the first iteration: the count is visible
+        with pytest.raises(AssertionError):
+            _replay_alns(inst.A, inst.b, inst.D, inst.x0, res, 3, 0, 1, count - 1, 2, 0)
+
+
+def test_impact_weights_of_a_vanishing_error():
+    """Reading (the paper does not treat it): when the largest violation is below 2^-900 the
+    fixed-point scale 2^24 / 2^e would leave the double range, and every variable gets weight 1
+    (uniform draws).  From 2^-899 on the formula applies: an entry on a row that attains the
+    error has slack 0 and adds trunc(t 2^24 / 2^e) = 2^23."""
+    A = np.array([[1.0, 0.0], [0.0, 2.0], [1.0, 1.0]])
+    rowptr, col, val = orc.full_csr(A)
+    for e, uniform in ((-901, True), (-950, True), (-1074, True), (-899, False), (-850, False)):
+        r = np.array([2.0 ** e, 0.0, 0.0])
+        w = orc.alns_impact_weights(3, 2, rowptr, col, val, r, alpha=0.3)
+        if uniform:
+            assert w.tolist() == [1, 1], e
+        else:
+            assert w.tolist() == [1 + 2 ** 23, 1], e

@@ -70,6 +70,27 @@ MUTANTS = [
     ("swap_ignores_scale", "swap_oracle_impl.inc",
      "    const REAL diff = D[kidx[i]] - D[kidx[j]];\n    const REAL Delta = sc * diff;\n    REAL out = (REAL)0;",
      "    const REAL diff = D[kidx[i]] - D[kidx[j]];\n    const REAL Delta = diff;\n    REAL out = (REAL)0;"),
+    ("alns_scores_ignore_the_scale", "alns_oracle_impl.inc",
+     "                REAL delta = SFX(delta_of)(D, kidx[j], k, sc);\n                out = rest;",
+     "                REAL delta = SFX(delta_of)(D, kidx[j], k, (REAL)1);\n                out = rest;"),
+    ("impact_ignores_the_scale", "alns_oracle_impl.inc", "const double a = fabs((double)sc * (double)cval[p]);",
+     "const double a = fabs((double)cval[p]);"),
+    ("repair_ignores_the_scale", "alns_oracle_impl.inc", "const REAL delta = SFX(delta_of)(D, kc, knew, sc);",
+     "const REAL delta = SFX(delta_of)(D, kc, knew, (REAL)1);"),
+    ("greedy_repair_scores_without_the_scale", "alns_oracle_impl.inc", "SFX(delta_of)(D, kc, kc - 1, sc));",
+     "SFX(delta_of)(D, kc, kc - 1, (REAL)1));"),
+    ("alns_start_residual_ignores_the_scale", "alns_oracle_impl.inc",
+     "        r[i] = FMA(acc, sc, -b[i]);\n    }\n    REAL t_cur", "        r[i] = FMA(acc, (REAL)1, -b[i]);\n    }\n    REAL t_cur"),
+    ("alns_local_search_applies_without_the_scale", "alns_oracle_impl.inc",
+     "            const REAL delta = SFX(delta_of)(D, kidx[j], k, sc);\n            t = SFX(oracle_apply_move_csc)",
+     "            const REAL delta = SFX(delta_of)(D, kidx[j], k, (REAL)1);\n            t = SFX(oracle_apply_move_csc)"),
+    ("alns_local_search_takes_plateau_moves", "alns_oracle_impl.inc",
+     "            if (c < 0 || !(s < t)) break;\n            const int64_t j = c / nd;",
+     "            if (c < 0 || !(s <= t)) break;\n            const int64_t j = c / nd;"),
+    ("alns_local_search_radius_ignored", "alns_oracle_impl.inc", "kidx, r, prm->ls_radius, scores);", "kidx, r, 0, scores);"),
+    ("default_destroy_count_rounds_down", "alns_common.inc", "const int64_t c = (n * 5 + 999) / 1000;",
+     "const int64_t c = (n * 5) / 1000;"),
+    ("vanishing_error_threshold", "alns_oracle_impl.inc", "if (!(t >= 0x1p-900)) {", "if (!(t >= 0x1p-800)) {"),
 ]
 
 
