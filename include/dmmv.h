@@ -209,6 +209,22 @@ dmmv_status dmmv_solve(dmmv_handle h, const void* x0, int32_t iters, void* x_out
                        void* max_violation_out, int32_t* iters_done, dmmv_move* trace,
                        void* trace_t);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture around the call,
+ * tight serving loops, harnesses that forbid hipMalloc): the whole of dmmv_create + dmmv_solve +
+ * dmmv_destroy in one call that allocates nothing, on the device or on the heap.  The workspace is
+ * an array of DMMV_STATIC_SCRATCH_BYTES inside the library's device image (every GPU the library
+ * runs on holds its own copy until the process ends); the handle lives on the stack.  Arguments as
+ * for dmmv_create (problem, options, hip_stream) and dmmv_solve (the rest); x0 must not be NULL.
+ * The device of hip_stream must be the current device.  Fails with DMMV_ERR_WORKSPACE, before any
+ * GPU work, when dmmv_workspace_bytes(problem, options) exceeds DMMV_STATIC_SCRATCH_BYTES.
+ * Every call on a GPU uses that GPU's one array, so calls that overlap in time on one GPU race
+ * (also from different streams or threads); what a call needs cleared it clears itself.  Waits for
+ * the stream before returning. */
+#define DMMV_STATIC_SCRATCH_BYTES (16u << 20)
+dmmv_status dmmv_solve_static(const dmmv_problem* problem, const dmmv_options* options, const void* x0,
+                              int32_t iters, void* x_out, void* max_violation_out, int32_t* iters_done,
+                              dmmv_move* trace, void* trace_t, void* hip_stream);
+
 /* Measurement hook: enqueue the fused evaluation kernel of the descent (the kernel that
  * streams all of A: the "evaluate all candidates in bulk" step of the paper's section
  * "GPU Acceleration") `reps` times back to back between two HIP events on the handle's

@@ -6,6 +6,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 
 #include "dmmv_common.h"
@@ -650,29 +651,10 @@ static dmmv_status alns_run(dmmv_ctx* c, const void* x0, const dmmv_alns_params&
     return DMMV_OK;
 }
 
-}  // namespace dmmv
-
-// ========================================================================================
-// C ABI
-// ========================================================================================
-using namespace dmmv;
-
-extern "C" {
-
-const char* dmmv_last_error(void) { return g_err; }
-const char* dmmv_version(void) { return "libdmmv 0.1 (gfx950)"; }
-
-size_t dmmv_workspace_bytes(const dmmv_problem* problem, const dmmv_options* options) {
-    if (validate_problem(problem) != DMMV_OK) return 0;
-    dmmv_options o{};
-    if (options) o = *options;
-    return workspace_layout(*problem, o, nullptr, nullptr);
-}
-
-dmmv_status dmmv_create(dmmv_handle* out, const dmmv_problem* problem, const dmmv_options* options,
-                        void* workspace, size_t workspace_bytes, void* hip_stream) {
-    if (!out) return fail(DMMV_ERR_NULL, "out handle pointer is NULL");
-    *out = nullptr;
+// ----------------------------------------------------------------------------------------
+// options and context set-up shared by dmmv_create and dmmv_solve_static
+// ----------------------------------------------------------------------------------------
+static dmmv_status resolve_options(const dmmv_problem* problem, const dmmv_options* options, dmmv_options* out) {
     DMMV_TRY(validate_problem(problem));
     dmmv_options o{};
     o.poll_every = 64;
@@ -698,16 +680,17 @@ dmmv_status dmmv_create(dmmv_handle* out, const dmmv_problem* problem, const dmm
                 return fail(DMMV_ERR_UNSUPPORTED, "options.residual_mfma: D[%d] is not exactly representable in bf16", k);
         }
     }
-    const size_t need = workspace_layout(*problem, o, nullptr, nullptr);
-    if (!workspace) return fail(DMMV_ERR_WORKSPACE, "workspace is NULL (%zu bytes needed)", need);
-    if (((uintptr_t)workspace & 255) != 0) return fail(DMMV_ERR_WORKSPACE, "workspace must be 256-byte aligned");
-    if (workspace_bytes < need) return fail(DMMV_ERR_WORKSPACE, "workspace too small: %zu bytes given, %zu needed", workspace_bytes, need);
+    *out = o;
+    return DMMV_OK;
+}
 
-    dmmv_ctx* c = new (std::nothrow) dmmv_ctx();
-    if (!c) return fail(DMMV_ERR_STATE, "out of host memory");
+// Fill *c for a validated problem and build the internal layouts in `workspace` (large enough,
+// 256-byte aligned).  Waits for the stream.
+static dmmv_status ctx_setup(dmmv_ctx* c, const dmmv_problem* problem, const dmmv_options& o, void* workspace,
+                             hipStream_t stream) {
     c->p = *problem;
     c->o = o;
-    c->stream = (hipStream_t)hip_stream;
+    c->stream = stream;
     c->esz = problem->dtype == DMMV_F64 ? 8 : 4;
     const bool sparse = problem->csr_rowptr != nullptr;
     c->kind = sparse ? KIND_CSC : ((problem->R > 1 || problem->scale) ? KIND_BATCHED : KIND_DENSE);
@@ -717,47 +700,127 @@ dmmv_status dmmv_create(dmmv_handle* out, const dmmv_problem* problem, const dmm
     c->p.D = nullptr;       // host arrays are copied below and not referenced afterwards
     c->p.scale = nullptr;
 
-    dmmv_status st = [&]() -> dmmv_status {
-        hipLaunchKernelGGL(k_zero_flags, dim3(1), dim3(64), 0, c->stream, c->flags);
-        DMMV_HIP_CHECK(hipMemcpyAsync(c->D_dev, problem->D, (size_t)problem->nd * c->esz, hipMemcpyHostToDevice, c->stream));
-        if (problem->scale) {
-            DMMV_HIP_CHECK(hipMemcpyAsync(c->scale_dev, problem->scale, (size_t)problem->R * c->esz, hipMemcpyHostToDevice, c->stream));
-        } else if (problem->dtype == DMMV_F64) {
-            const double one = 1.0;
-            DMMV_HIP_CHECK(hipMemcpyAsync(c->scale_dev, &one, sizeof(one), hipMemcpyHostToDevice, c->stream));
-        } else {
-            const float one = 1.0f;
-            DMMV_HIP_CHECK(hipMemcpyAsync(c->scale_dev, &one, sizeof(one), hipMemcpyHostToDevice, c->stream));
-        }
-        // the host copies above read caller memory: finish them before returning
-        if (problem->dtype == DMMV_F64)
-            hipLaunchKernelGGL(k_init_state<double>, grid1(problem->R, 256), dim3(256), 0, c->stream, (InstState<double>*)c->state, problem->R);
-        else
-            hipLaunchKernelGGL(k_init_state<float>, grid1(problem->R, 256), dim3(256), 0, c->stream, (InstState<float>*)c->state, problem->R);
-        DMMV_LAUNCH_CHECK();
-        c->csc_max_row = 0;
-        c->csc_max_col = 0;
-        if (c->kind == KIND_CSC) {
-            DMMV_TRY(csc_build(c));
-            DMMV_HIP_CHECK(hipMemcpyAsync(&c->csc_max_row, &c->flags[FLAG_MAXROW], sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
-            DMMV_HIP_CHECK(hipMemcpyAsync(&c->csc_max_col, &c->flags[FLAG_MAXCOL], sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
-            DMMV_HIP_CHECK(hipStreamSynchronize(c->stream));
-            if (c->csc_max_row > c->p.n) c->csc_max_row = (int32_t)c->p.n;   // duplicates are an error anyway
-        }
-        if (c->kind == KIND_BATCHED) DMMV_TRY(batched_build(c));
-        c->mfma_planes = 1;
-        if (o.residual_mfma) {
-            DMMV_TRY(batched_mfma_build(c));
-            int32_t lower = 0;
-            DMMV_HIP_CHECK(hipMemcpyAsync(&lower, &c->flags[FLAG_PLANES], sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
-            DMMV_HIP_CHECK(hipStreamSynchronize(c->stream));
-            c->mfma_planes |= lower & 6;
-        }
-        return check_device_errors(c);
-    }();
+    hipLaunchKernelGGL(k_zero_flags, dim3(1), dim3(64), 0, c->stream, c->flags);
+    DMMV_HIP_CHECK(hipMemcpyAsync(c->D_dev, problem->D, (size_t)problem->nd * c->esz, hipMemcpyHostToDevice, c->stream));
+    if (problem->scale) {
+        DMMV_HIP_CHECK(hipMemcpyAsync(c->scale_dev, problem->scale, (size_t)problem->R * c->esz, hipMemcpyHostToDevice, c->stream));
+    } else {
+        static const double one_d = 1.0;     // static: the copy may read them after this block
+        static const float one_f = 1.0f;
+        const void* one = problem->dtype == DMMV_F64 ? (const void*)&one_d : (const void*)&one_f;
+        DMMV_HIP_CHECK(hipMemcpyAsync(c->scale_dev, one, c->esz, hipMemcpyHostToDevice, c->stream));
+    }
+    // the host copies above read caller memory: they are finished before returning (the
+    // stream is waited for below)
+    if (problem->dtype == DMMV_F64)
+        hipLaunchKernelGGL(k_init_state<double>, grid1(problem->R, 256), dim3(256), 0, c->stream, (InstState<double>*)c->state, problem->R);
+    else
+        hipLaunchKernelGGL(k_init_state<float>, grid1(problem->R, 256), dim3(256), 0, c->stream, (InstState<float>*)c->state, problem->R);
+    DMMV_LAUNCH_CHECK();
+    c->csc_max_row = 0;
+    c->csc_max_col = 0;
+    if (c->kind == KIND_CSC) {
+        DMMV_TRY(csc_build(c));
+        DMMV_HIP_CHECK(hipMemcpyAsync(&c->csc_max_row, &c->flags[FLAG_MAXROW], sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
+        DMMV_HIP_CHECK(hipMemcpyAsync(&c->csc_max_col, &c->flags[FLAG_MAXCOL], sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
+        DMMV_HIP_CHECK(hipStreamSynchronize(c->stream));
+        if (c->csc_max_row > c->p.n) c->csc_max_row = (int32_t)c->p.n;   // duplicates are an error anyway
+    }
+    if (c->kind == KIND_BATCHED) DMMV_TRY(batched_build(c));
+    c->mfma_planes = 1;
+    if (o.residual_mfma) {
+        DMMV_TRY(batched_mfma_build(c));
+        int32_t lower = 0;
+        DMMV_HIP_CHECK(hipMemcpyAsync(&lower, &c->flags[FLAG_PLANES], sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
+        DMMV_HIP_CHECK(hipStreamSynchronize(c->stream));
+        c->mfma_planes |= lower & 6;
+    }
+    return check_device_errors(c);
+}
+
+}  // namespace dmmv
+
+// ========================================================================================
+// C ABI
+// ========================================================================================
+using namespace dmmv;
+
+extern "C" {
+
+const char* dmmv_last_error(void) { return g_err; }
+const char* dmmv_version(void) { return "libdmmv 0.1 (gfx950)"; }
+
+size_t dmmv_workspace_bytes(const dmmv_problem* problem, const dmmv_options* options) {
+    if (validate_problem(problem) != DMMV_OK) return 0;
+    dmmv_options o{};
+    if (options) o = *options;
+    return workspace_layout(*problem, o, nullptr, nullptr);
+}
+
+dmmv_status dmmv_create(dmmv_handle* out, const dmmv_problem* problem, const dmmv_options* options,
+                        void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!out) return fail(DMMV_ERR_NULL, "out handle pointer is NULL");
+    *out = nullptr;
+    dmmv_options o{};
+    DMMV_TRY(resolve_options(problem, options, &o));
+    const size_t need = workspace_layout(*problem, o, nullptr, nullptr);
+    if (!workspace) return fail(DMMV_ERR_WORKSPACE, "workspace is NULL (%zu bytes needed)", need);
+    if (((uintptr_t)workspace & 255) != 0) return fail(DMMV_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+    if (workspace_bytes < need) return fail(DMMV_ERR_WORKSPACE, "workspace too small: %zu bytes given, %zu needed", workspace_bytes, need);
+
+    dmmv_ctx* c = new (std::nothrow) dmmv_ctx();
+    if (!c) return fail(DMMV_ERR_STATE, "out of host memory");
+    const dmmv_status st = ctx_setup(c, problem, o, workspace, (hipStream_t)hip_stream);
     if (st != DMMV_OK) { delete c; return st; }
     *out = c;
     return DMMV_OK;
+}
+
+// ---- one-shot descent for callers that cannot allocate device memory ----------------------
+// The workspace is an array in the library's own device image.  In host code the array's name is
+// only a stand-in for the symbol: its device address is looked up once per device and kept.
+static __device__ __align__(256) unsigned char scratch[DMMV_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int SCRATCH_MAX_DEVICES = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[SCRATCH_MAX_DEVICES] = {};
+
+// device address of `scratch` on the current device
+dmmv_status scratch_of_current_device(void** out) {
+    int dev = -1;
+    DMMV_HIP_CHECK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= SCRATCH_MAX_DEVICES) return fail(DMMV_ERR_UNSUPPORTED, "device ordinal %d outside [0, %d)", dev, SCRATCH_MAX_DEVICES);
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        DMMV_HIP_CHECK(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr || ((uintptr_t)ptr & 255) != 0) return fail(DMMV_ERR_HIP, "hipGetSymbolAddress gave an unusable address %p", ptr);
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return DMMV_OK;
+}
+}  // namespace
+
+dmmv_status dmmv_solve_static(const dmmv_problem* problem, const dmmv_options* options, const void* x0,
+                              int32_t iters, void* x_out, void* max_violation_out, int32_t* iters_done,
+                              dmmv_move* trace, void* trace_t, void* hip_stream) {
+    if (iters < 0) return fail(DMMV_ERR_SHAPE, "iters must be >= 0");
+    dmmv_options o{};
+    DMMV_TRY(resolve_options(problem, options, &o));
+    if (!x0 && problem->n > 0) return fail(DMMV_ERR_NULL, "dmmv_solve_static: x0 is NULL");
+    const size_t need = workspace_layout(*problem, o, nullptr, nullptr);
+    if (need > (size_t)DMMV_STATIC_SCRATCH_BYTES)
+        return fail(DMMV_ERR_WORKSPACE, "dmmv_solve_static: this problem needs %zu bytes of workspace, the built-in scratch holds %zu "
+                    "(use dmmv_create with a workspace of your own)", need, (size_t)DMMV_STATIC_SCRATCH_BYTES);
+    void* ws = nullptr;
+    DMMV_TRY(scratch_of_current_device(&ws));
+    dmmv_ctx c;                                            // on the stack: nothing is allocated
+    DMMV_TRY(ctx_setup(&c, problem, o, ws, (hipStream_t)hip_stream));
+    const dmmv_status st = dmmv_solve(&c, x0, iters, x_out, max_violation_out, iters_done, trace, trace_t);
+    if (st != DMMV_OK) (void)hipStreamSynchronize(c.stream);   // nothing of this call may still use the scratch
+    return st;
 }
 
 dmmv_status dmmv_destroy(dmmv_handle h) {

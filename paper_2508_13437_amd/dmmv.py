@@ -26,7 +26,8 @@ STATUS_NAMES = {0: "DMMV_OK", -1: "DMMV_ERR_NULL", -2: "DMMV_ERR_SHAPE", -3: "DM
 
 EXPORTS = ("dmmv_workspace_bytes", "dmmv_create", "dmmv_destroy", "dmmv_set_x",
            "dmmv_set_residual", "dmmv_residual", "dmmv_eval_moves", "dmmv_argmin_move",
-           "dmmv_apply_move", "dmmv_get_state", "dmmv_solve", "dmmv_alns", "dmmv_swap_move", "dmmv_time_eval",
+           "dmmv_apply_move", "dmmv_get_state", "dmmv_solve", "dmmv_solve_static", "dmmv_alns", "dmmv_swap_move",
+           "dmmv_time_eval",
            "dmmv_last_error",
            "dmmv_version")
 
@@ -87,6 +88,9 @@ def load() -> C.CDLL:
     lib.dmmv_solve.restype = C.c_int
     lib.dmmv_solve.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
                                C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.dmmv_solve_static.restype = C.c_int
+    lib.dmmv_solve_static.argtypes = [C.POINTER(Problem), C.POINTER(Options), C.c_void_p, C.c_int32, C.c_void_p,
+                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.dmmv_alns.restype = C.c_int
     lib.dmmv_alns.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(AlnsParams), C.c_void_p, C.c_void_p,
                               C.c_void_p, C.c_void_p]
@@ -133,7 +137,7 @@ class Handle:
                  keep_going: bool = False, poll_every: int = 64, var_mask=None,
                  sparse_partition_rows: int = 0, residual_mfma: bool = False, prune: bool = False,
                  alns: bool = False, value_search: bool = False, batched_eval: int = 0,
-                 stream: Optional[torch.cuda.Stream] = None, device=None):
+                 stream: Optional[torch.cuda.Stream] = None, device=None, _create: bool = True):
         lib = load()
         self._h = C.c_void_p(None)
         dev = torch.device(device) if device is not None else (
@@ -198,6 +202,8 @@ class Handle:
         self._var_mask = var_mask
         self._problem, self._options = p, o
         self.stream = stream if stream is not None else torch.cuda.current_stream(dev)
+        if not _create:        # marshalled description only (dmmv_solve_static)
+            return
         nbytes = lib.dmmv_workspace_bytes(C.byref(p), C.byref(o))
         if nbytes == 0:       # invalid problem: let dmmv_create name the status
             _check(lib.dmmv_create(C.byref(self._h), C.byref(p), C.byref(o), None, 0, None))
@@ -321,6 +327,31 @@ def dmmv_solve(h: Handle, x0: Optional[torch.Tensor], iters: int, trace: bool = 
     tt = h._new((h.R, max(iters, 1))) if trace else None
     _check(load().dmmv_solve(h._h, _ptr(x0), C.c_int32(iters), _ptr(x), _ptr(t), _ptr(done),
                              _ptr(tr), _ptr(tt)))
+    if trace and iters == 0:
+        tr, tt = tr[:, :0], tt[:, :0]
+    return SolveResult(x, t, done, tr, tt)
+
+
+STATIC_SCRATCH_BYTES = 16 << 20
+
+
+def dmmv_solve_static(x0: torch.Tensor, iters: int, trace: bool = False, **problem_and_options) -> SolveResult:
+    """dmmv_create + dmmv_solve + dmmv_destroy in one C call that allocates nothing: the library's
+    built-in scratch array is the workspace (problems that need more are refused).  Keyword
+    arguments as for Handle (D, b, A or csr/m/n, scale, options)."""
+    d = Handle(_create=False, **problem_and_options)       # argument marshalling only
+    x0 = x0.to(d.dtype).contiguous()
+    if x0.numel() != d.R * d.n:
+        raise DmmvError(-2, "x0 must have R*n entries")
+    x = d._new(d._xshape())
+    t = d._new((d.R,))
+    done = d._new((d.R,), dtype=torch.int32)
+    tr = d._new((d.R, max(iters, 1), 2), dtype=torch.int32) if trace else None
+    tt = d._new((d.R, max(iters, 1))) if trace else None
+    with torch.cuda.device(d.device):
+        _check(load().dmmv_solve_static(C.byref(d._problem), C.byref(d._options), _ptr(x0), C.c_int32(iters),
+                                        _ptr(x), _ptr(t), _ptr(done), _ptr(tr), _ptr(tt),
+                                        C.c_void_p(d.stream.cuda_stream)))
     if trace and iters == 0:
         tr, tt = tr[:, :0], tt[:, :0]
     return SolveResult(x, t, done, tr, tt)
