@@ -8,6 +8,8 @@
 
 #include <mutex>
 #include <new>
+#include <utility>
+#include <vector>
 
 #include "dmmv_common.h"
 
@@ -24,6 +26,21 @@ dmmv_status fail(dmmv_status st, const char* fmt, ...) {
     vsnprintf(g_err, sizeof(g_err), fmt, ap);
     va_end(ap);
     return st;
+}
+
+// The attribute belongs to the kernel ON ONE DEVICE, so what has been done is remembered per
+// (device, kernel); the list stays short (a few kernels per device).
+dmmv_status ensure_dynamic_lds(const void* kernel, int bytes) {
+    static std::mutex mu;
+    static std::vector<std::pair<int, const void*>> done;
+    int dev = -1;
+    DMMV_HIP_CHECK(hipGetDevice(&dev));
+    std::lock_guard<std::mutex> lock(mu);
+    for (const auto& e : done)
+        if (e.first == dev && e.second == kernel) return DMMV_OK;
+    DMMV_HIP_CHECK(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
+    done.emplace_back(dev, kernel);
+    return DMMV_OK;
 }
 
 // ----------------------------------------------------------------------------------------
@@ -52,6 +69,17 @@ int32_t batched_chunk_cols(const dmmv_problem& p) {
     cols = ceil_div(cols, 32) * 32;
     if (cols < 32) cols = 32;
     return (int32_t)cols;
+}
+
+// sparse matrices: rows per LDS-resident partition of r (what fits the LDS budget, addressable by
+// a 16-bit offset) and the number of partitions
+static void sparse_partitions(const dmmv_problem& p, const dmmv_options& o, int64_t* mp_out, int64_t* P_out) {
+    const int64_t esz = p.dtype == DMMV_F64 ? 8 : 4;
+    int64_t mp = o.sparse_partition_rows > 0 ? o.sparse_partition_rows : (int64_t)(CSC_LDS_BYTES / esz);
+    if (mp > 65535) mp = 65535;          // offset mp itself marks a pad
+    if (mp * esz > CSC_LDS_BYTES) mp = CSC_LDS_BYTES / esz;
+    *mp_out = mp;
+    *P_out = p.m > 0 ? ceil_div(p.m, mp) : 1;
 }
 
 size_t workspace_layout(const dmmv_problem& p, const dmmv_options& o, Ctx* c, char* base) {
@@ -98,12 +126,10 @@ size_t workspace_layout(const dmmv_problem& p, const dmmv_options& o, Ctx* c, ch
         b.take(&c->swap_skip, (size_t)p.R * sizeof(int32_t));
     }
     if (sparse) {
-        // rows per partition: what fits the LDS budget, addressable by a 16-bit offset
-        int64_t mp = o.sparse_partition_rows > 0 ? o.sparse_partition_rows : (int64_t)(CSC_LDS_BYTES / esz);
-        if (mp > 65535) mp = 65535;          // offset mp itself marks a pad
-        if (mp * (int64_t)esz > CSC_LDS_BYTES) mp = CSC_LDS_BYTES / esz;
+        int64_t mp, P;
+        sparse_partitions(p, o, &mp, &P);
         c->csc_mp = (int32_t)mp;
-        c->csc_P = (int32_t)(p.m > 0 ? ceil_div(p.m, mp) : 1);
+        c->csc_P = (int32_t)P;
         int64_t gb = 512 / c->csc_P;         // about two workgroups per compute unit in all
         if (gb > ceil_div(p.n, 16)) gb = ceil_div(p.n, 16);
         if (gb < 1) gb = 1;
@@ -181,10 +207,6 @@ static dmmv_status validate_problem(const dmmv_problem* p) {
         if (p->nnz < 0 || p->nnz > INT32_MAX - 1) return fail(DMMV_ERR_SHAPE, "nnz must be in [0, 2^31-2]");
         if (p->nnz > 0 && (!p->csr_col || !p->csr_val)) return fail(DMMV_ERR_NULL, "csr_col / csr_val is NULL");
         if (p->R != 1 || p->scale) return fail(DMMV_ERR_UNSUPPORTED, "sparse matrices support a single unscaled instance (R = 1, scale = NULL)");
-        // every (row partition, column) segment is padded to a multiple of four entries and
-        // holds at least four
-        const int64_t parts = p->m / 16384 + 1;
-        if (p->nnz + 4 * parts * p->n > INT32_MAX - 1) return fail(DMMV_ERR_UNSUPPORTED, "sparse matrix too large for 32-bit segment offsets");
     }
     if (p->m > 0 && !p->b) return fail(DMMV_ERR_NULL, "b is NULL");
     if (p->scale) {
@@ -663,6 +685,18 @@ static dmmv_status resolve_options(const dmmv_problem* problem, const dmmv_optio
         return fail(DMMV_ERR_SHAPE, "options: radius, poll_every and sparse_partition_rows must be >= 0");
     if (o.batched_eval < 0 || o.batched_eval > 2)
         return fail(DMMV_ERR_SHAPE, "options.batched_eval must be 0, 1 or 2");
+    if (problem->csr_rowptr) {
+        // the partition count the layout will really use decides whether the matrix fits: every
+        // (row partition, column) segment is padded to a multiple of four entries and holds at
+        // least four, segment offsets are 32-bit, and the partitions are one grid dimension
+        int64_t mp, P;
+        sparse_partitions(*problem, o, &mp, &P);
+        if (P > CSC_MAX_PARTITIONS)
+            return fail(DMMV_ERR_UNSUPPORTED, "sparse path: %lld row partitions of %lld rows exceed the limit of %d (raise sparse_partition_rows)",
+                        (long long)P, (long long)mp, CSC_MAX_PARTITIONS);
+        if (problem->nnz + 4 * P * problem->n + 4 > (int64_t)INT32_MAX - 1)
+            return fail(DMMV_ERR_UNSUPPORTED, "sparse matrix too large for 32-bit segment offsets (nnz + 4 * partitions * n must stay below 2^31)");
+    }
     if (o.batched_eval == 2) {
         const bool is_batched = !problem->csr_rowptr && (problem->R > 1 || problem->scale);
         if (!is_batched || !batched_eval_mfma_applicable(*problem))
@@ -751,9 +785,8 @@ const char* dmmv_last_error(void) { return g_err; }
 const char* dmmv_version(void) { return "libdmmv 0.1 (gfx950)"; }
 
 size_t dmmv_workspace_bytes(const dmmv_problem* problem, const dmmv_options* options) {
-    if (validate_problem(problem) != DMMV_OK) return 0;
     dmmv_options o{};
-    if (options) o = *options;
+    if (resolve_options(problem, options, &o) != DMMV_OK) return 0;
     return workspace_layout(*problem, o, nullptr, nullptr);
 }
 

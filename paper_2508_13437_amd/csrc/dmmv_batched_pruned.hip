@@ -334,12 +334,7 @@ dmmv_status descent_t(Ctx* c, int32_t steps, int32_t iters, dmmv_move* trace, vo
     const size_t lds = bp_lds_bytes(m, n, c->p.nd, sizeof(T));
     const int32_t span = c->o.radius > 0 ? 2 * c->o.radius + 1 : c->p.nd;
     auto launch = [&](auto kernel) -> dmmv_status {
-        static bool attr_set = false;                      // per instantiation of this lambda, i.e. per kernel
-        if (!attr_set) {
-            DMMV_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)BP_LDS_LIMIT));
-            attr_set = true;
-        }
+        DMMV_TRY(ensure_dynamic_lds(reinterpret_cast<const void*>(kernel), (int)BP_LDS_LIMIT));
         hipLaunchKernelGGL(kernel, dim3((unsigned)R), dim3(BP_BLOCK), lds, c->stream, m, n, c->p.nd, R,
                            (const T*)c->p.A_dense, c->p.lda, (const T*)c->Xt, (const T*)c->D_dev,
                            (const T*)c->scale_dev, (T*)c->r, c->kidx, (InstState<T>*)c->state, c->o.radius,

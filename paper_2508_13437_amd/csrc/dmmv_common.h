@@ -15,6 +15,9 @@ namespace dmmv {
 // ----------------------------------------------------------------------------------------
 dmmv_status fail(dmmv_status st, const char* fmt, ...);
 
+// Raise a kernel's dynamic-LDS limit on the CURRENT device, once per (device, kernel); thread-safe.
+dmmv_status ensure_dynamic_lds(const void* kernel, int bytes);
+
 #define DMMV_HIP_CHECK(expr)                                                              \
     do {                                                                                  \
         hipError_t e__ = (expr);                                                          \

@@ -535,12 +535,7 @@ static dmmv_status stream_launch(Ctx* c, bool honor_done) {
     if (c->csc_P > CSC_MAX_PARTITIONS)
         return fail(DMMV_ERR_UNSUPPORTED, "sparse path: %d row partitions exceed the limit of %d (raise sparse_partition_rows)", c->csc_P, CSC_MAX_PARTITIONS);
     const size_t lds = ((size_t)c->csc_mp + 1) * sizeof(T);
-    static bool attr_set = false;
-    if (!attr_set) {
-        DMMV_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_eval_stream<T, KT>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, CSC_LDS_BYTES + 256));
-        attr_set = true;
-    }
+    DMMV_TRY(ensure_dynamic_lds(reinterpret_cast<const void*>(&k_eval_stream<T, KT>), CSC_LDS_BYTES + 256));
     dim3 grid((unsigned)c->csc_gb, (unsigned)c->csc_P);
     hipLaunchKernelGGL((k_eval_stream<T, KT>), grid, dim3(ST_BLOCK), lds, c->stream, c->p.m, c->p.n,
                        c->p.nd, c->csc_mp, (const int32_t*)c->segptr, (const uint16_t*)c->row16,

@@ -343,14 +343,8 @@ dmmv_status swap_t(Ctx* c, int32_t k_eps, int32_t apply, bool use_skip, dmmv_swa
         hipLaunchKernelGGL(k_swap_top<T>, dim3((unsigned)R), dim3(SW_BLOCK), 0, c->stream, m, R, K, (const T*)c->r,
                            (const int32_t*)skip, c->swap_rows);
     const dim3 grid((unsigned)R, (unsigned)nb);
-    static bool attr_set = false;                          // per instantiation of this function
-    if (!attr_set) {
-        DMMV_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_swap_eval<T, true>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)SW_LDS_BUDGET));
-        DMMV_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_swap_eval<T, false>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)SW_LDS_BUDGET));
-        attr_set = true;
-    }
+    DMMV_TRY(ensure_dynamic_lds(reinterpret_cast<const void*>(&k_swap_eval<T, true>), (int)SW_LDS_BUDGET));
+    DMMV_TRY(ensure_dynamic_lds(reinterpret_cast<const void*>(&k_swap_eval<T, false>), (int)SW_LDS_BUDGET));
 #define DMMV_SWAP_LAUNCH(DV)                                                                               \
     hipLaunchKernelGGL((k_swap_eval<T, DV>), grid, dim3(SWE_BLOCK), used, c->stream, m, n, R, nb, K,       \
                        (int32_t)L, (const T*)c->p.A_dense, c->p.lda,                                       \

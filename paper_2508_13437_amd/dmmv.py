@@ -245,6 +245,16 @@ class Handle:
         return (self.R, self.m) if self.batched else (self.m,)
 
 
+def _arg(h: "Handle", t: torch.Tensor, dtype) -> torch.Tensor:
+    """An input tensor in the layout the C call expects.  The call only enqueues work on the
+    handle's stream; a converted temporary is therefore tied to that stream, so that the caching
+    allocator does not hand its memory to another tensor before the work has run."""
+    c = t.to(h.device, dtype).contiguous()
+    if c.is_cuda:
+        c.record_stream(h.stream)
+    return c
+
+
 # ---- the C entry points, same names -----------------------------------------------------------
 def dmmv_create(**kw) -> Handle:
     return Handle(**kw)
@@ -255,14 +265,14 @@ def dmmv_destroy(h: Handle):
 
 
 def dmmv_set_x(h: Handle, x: torch.Tensor):
-    x = x.to(h.dtype).contiguous()
+    x = _arg(h, x, h.dtype)
     if x.numel() != h.R * h.n:
         raise DmmvError(-2, "x must have R*n entries")
     _check(load().dmmv_set_x(h._h, _ptr(x)))
 
 
 def dmmv_set_residual(h: Handle, r: torch.Tensor):
-    r = r.to(h.dtype).contiguous()
+    r = _arg(h, r, h.dtype)
     if r.numel() != h.R * h.m:
         raise DmmvError(-2, "r must have R*m entries")
     _check(load().dmmv_set_residual(h._h, _ptr(r)))
@@ -284,7 +294,7 @@ def dmmv_eval_moves(h: Handle) -> torch.Tensor:
 def dmmv_argmin_move(h: Handle, scores: Optional[torch.Tensor] = None):
     """Returns (moves [R][2] int32 = (j, k), best_score [R])."""
     if scores is not None:
-        scores = scores.to(h.dtype).contiguous()
+        scores = _arg(h, scores, h.dtype)
         if scores.numel() != h.R * h.n * h.nd:
             raise DmmvError(-2, "scores must have R*n*nd entries")
     best = h._new((h.R, 2), dtype=torch.int32)
@@ -294,7 +304,7 @@ def dmmv_argmin_move(h: Handle, scores: Optional[torch.Tensor] = None):
 
 
 def dmmv_apply_move(h: Handle, moves: torch.Tensor):
-    moves = moves.to(torch.int32).contiguous()
+    moves = _arg(h, moves, torch.int32)
     if moves.numel() != 2 * h.R:
         raise DmmvError(-2, "moves must be [R][2] (j, k)")
     _check(load().dmmv_apply_move(h._h, _ptr(moves)))
@@ -317,7 +327,7 @@ def dmmv_get_x(h: Handle) -> torch.Tensor:
 
 def dmmv_solve(h: Handle, x0: Optional[torch.Tensor], iters: int, trace: bool = False) -> SolveResult:
     if x0 is not None:
-        x0 = x0.to(h.dtype).contiguous()
+        x0 = _arg(h, x0, h.dtype)
         if x0.numel() != h.R * h.n:
             raise DmmvError(-2, "x0 must have R*n entries")
     x = h._new(h._xshape())
@@ -340,7 +350,7 @@ def dmmv_solve_static(x0: torch.Tensor, iters: int, trace: bool = False, **probl
     built-in scratch array is the workspace (problems that need more are refused).  Keyword
     arguments as for Handle (D, b, A or csr/m/n, scale, options)."""
     d = Handle(_create=False, **problem_and_options)       # argument marshalling only
-    x0 = x0.to(d.dtype).contiguous()
+    x0 = _arg(d, x0, d.dtype)
     if x0.numel() != d.R * d.n:
         raise DmmvError(-2, "x0 must have R*n entries")
     x = d._new(d._xshape())
@@ -375,7 +385,7 @@ def dmmv_alns(h: Handle, x0: Optional[torch.Tensor], iters: int, ls_moves: int =
                      float(lambda_), float(sigma1), float(sigma2), float(sigma3), int(seed),
                      int(ls_swaps), int(k_eps), 1 if l2_guard else 0, 0)
     if x0 is not None:
-        x0 = x0.to(h.device, h.dtype).contiguous()
+        x0 = _arg(h, x0, h.dtype)
     x_best = h._new(h._xshape())
     t_best = h._new((h.R,))
     trace = torch.full((h.R, max(iters, 1), 4), -1, dtype=torch.int32, device=h.device)

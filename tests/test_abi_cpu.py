@@ -165,3 +165,39 @@ def test_workspace_grows_with_the_options_that_need_buffers(mod):
     o = mod.Options()
     o.alns = 1
     assert lib.dmmv_workspace_bytes(C.byref(pb), C.byref(o)) > base
+
+
+def test_sparse_matrix_that_needs_too_many_partitions_is_refused_before_any_gpu_work(mod):
+    """The partition count the layout will use (rows / sparse_partition_rows) is checked on the host:
+    more than 1024 partitions, or padded segments that overflow 32-bit offsets, fail in
+    dmmv_workspace_bytes, dmmv_create and dmmv_solve_static alike, with no GPU call made."""
+    lib = mod.load()
+    ps, keep = _problem(mod, dtype=np.float32, m=5000, n=50, sparse=True)
+    o = mod.Options()
+    assert lib.dmmv_workspace_bytes(C.byref(ps), C.byref(o)) > 0
+    o.sparse_partition_rows = 4                            # 1250 partitions
+    assert lib.dmmv_workspace_bytes(C.byref(ps), C.byref(o)) == 0
+    assert b"partitions" in lib.dmmv_last_error()
+    h = C.c_void_p(None)
+    assert lib.dmmv_create(C.byref(h), C.byref(ps), C.byref(o), C.c_void_p(4096), 1 << 30, None) == -8
+    assert lib.dmmv_solve_static(C.byref(ps), C.byref(o), C.c_void_p(4096), 1, None, None, None, None, None, None) == -8
+    # fp64 partitions hold 8192 rows: 2^27 rows would need 16384 partitions
+    pl, keepl = _problem(mod, dtype=np.float64, m=1 << 27, n=8, sparse=True)
+    assert lib.dmmv_workspace_bytes(C.byref(pl), C.byref(mod.Options())) == 0
+    # 4 * partitions * n pads beyond 2^31 entries
+    pw, keepw = _problem(mod, dtype=np.float32, m=16 * 16384, n=40_000_000, sparse=True)
+    assert lib.dmmv_workspace_bytes(C.byref(pw), C.byref(mod.Options())) == 0
+    assert b"32-bit" in lib.dmmv_last_error()
+
+
+def test_static_scratch_entry_point_refuses_large_problems_on_the_host(mod):
+    lib = mod.load()
+    p, keep = _problem(mod, dtype=np.float32, m=600, n=300, R=4000, scale=np.ones(4000))
+    need = lib.dmmv_workspace_bytes(C.byref(p), None)
+    assert need > mod.STATIC_SCRATCH_BYTES
+    hdr = open(os.path.join(ROOT, "include", "dmmv.h")).read()
+    assert re.search(r"#define DMMV_STATIC_SCRATCH_BYTES \((\d+)u << 20\)", hdr).group(1) == str(mod.STATIC_SCRATCH_BYTES >> 20)
+    assert lib.dmmv_solve_static(C.byref(p), None, C.c_void_p(4096), 3, None, None, None, None, None, None) == -5
+    assert b"scratch" in lib.dmmv_last_error()
+    assert lib.dmmv_solve_static(C.byref(p), None, None, 3, None, None, None, None, None, None) == -1
+    assert lib.dmmv_solve_static(C.byref(p), None, C.c_void_p(4096), -1, None, None, None, None, None, None) == -2
