@@ -145,6 +145,14 @@ typedef struct {
                                 rounded once like the vector instruction, so both kernels give the
                                 same bits; on MI355X it is the slower of the two (the maximum over
                                 the rows stays on the vector unit and does not overlap)           */
+    int32_t sparse_eval;     /* sparse matrices: which kernels score the moves.  0 = automatic;
+                                1 = two kernels: workgroups own (row partition, column range) pairs and
+                                write per-partition maxima, a second kernel combines them (residual
+                                traffic independent of n: for matrices with very many rows);
+                                2 = one kernel: a workgroup owns 256 columns and walks every row
+                                partition, its maxima never leave the registers (every workgroup
+                                reads all of r: taken automatically when (n / 256) m w bytes do not
+                                exceed the matrix).  Same scores, records and moves either way    */
 } dmmv_options;
 
 /* Bytes of device workspace dmmv_create needs for this problem (0 on invalid input, with
@@ -225,9 +233,9 @@ dmmv_status dmmv_solve_static(const dmmv_problem* problem, const dmmv_options* o
                               int32_t iters, void* x_out, void* max_violation_out, int32_t* iters_done,
                               dmmv_move* trace, void* trace_t, void* hip_stream);
 
-/* Measurement hook: enqueue the fused evaluation kernel of the descent (the kernel that
- * streams all of A: the "evaluate all candidates in bulk" step of the paper's section
- * "GPU Acceleration") `reps` times back to back between two HIP events on the handle's
+/* Measurement hook: enqueue the evaluation step of the descent (every kernel of it: the step
+ * that streams all of A and leaves the arg-min records, the "evaluate all candidates in bulk"
+ * step of the paper's section "GPU Acceleration") `reps` times back to back between two HIP events on the handle's
  * stream and return the elapsed time in milliseconds in *ms_out (HOST).  The state is not
  * changed.  Needs a residual.  Waits for the stream. */
 dmmv_status dmmv_time_eval(dmmv_handle h, int32_t reps, float* ms_out);

@@ -134,6 +134,14 @@ size_t workspace_layout(const dmmv_problem& p, const dmmv_options& o, Ctx* c, ch
         if (gb > ceil_div(p.n, 16)) gb = ceil_div(p.n, 16);
         if (gb < 1) gb = 1;
         c->csc_gb = (int32_t)gb;
+        // One-kernel evaluation: each of its ceil(n / 256) workgroups reads all of r, so it is
+        // taken when that traffic does not exceed the matrix itself (about w + 2 bytes an entry)
+        {
+            const double r_traffic = (double)ceil_div(p.n, 256) * (double)p.m * (double)esz;
+            const double a_traffic = ((double)p.nnz + 2.0 * (double)c->csc_P * (double)p.n) * (double)(esz + 2);
+            // (fp64: its registers do not fit without spills, the two-kernel path is the faster one)
+            c->csc_fused = c->csc_P <= 16 && (o.sparse_eval == 2 || (o.sparse_eval == 0 && p.dtype == DMMV_F32 && r_traffic <= a_traffic));
+        }
         const int64_t nseg = (int64_t)c->csc_P * p.n;
         c->csc_nnzp = p.nnz + 4 * nseg + 4;  // padding bound (an empty segment holds four pads), plus spare entries
         c->n_partials = ceil_div(p.n, CSC_FIN_BLOCK);
@@ -685,6 +693,13 @@ static dmmv_status resolve_options(const dmmv_problem* problem, const dmmv_optio
         return fail(DMMV_ERR_SHAPE, "options: radius, poll_every and sparse_partition_rows must be >= 0");
     if (o.batched_eval < 0 || o.batched_eval > 2)
         return fail(DMMV_ERR_SHAPE, "options.batched_eval must be 0, 1 or 2");
+    if (o.sparse_eval < 0 || o.sparse_eval > 2)
+        return fail(DMMV_ERR_SHAPE, "options.sparse_eval must be 0, 1 or 2");
+    if (o.sparse_eval == 2 && problem->csr_rowptr) {
+        int64_t mp, P;
+        sparse_partitions(*problem, o, &mp, &P);
+        if (P > 16) return fail(DMMV_ERR_UNSUPPORTED, "options.sparse_eval = 2 takes at most 16 row partitions (%lld here)", (long long)P);
+    }
     if (problem->csr_rowptr) {
         // the partition count the layout will really use decides whether the matrix fits: every
         // (row partition, column) segment is padded to a multiple of four entries and holds at
@@ -1022,8 +1037,8 @@ dmmv_status dmmv_time_eval(dmmv_handle h, int32_t reps, float* ms_out) {
     hipEvent_t e0, e1;
     DMMV_HIP_CHECK(hipEventCreate(&e0));
     DMMV_HIP_CHECK(hipEventCreate(&e1));
-    // sparse: the streaming kernel alone (the finalize pass reads its output, not the matrix)
-    auto once = [&]() { return h->kind == KIND_CSC ? csc_eval_stream_only(h) : eval_any(h, nullptr, true, false); };
+    // the whole evaluation step as the descent runs it (sparse, two-kernel path: both kernels)
+    auto once = [&]() { return eval_any(h, nullptr, true, false); };
     dmmv_status st = h->p.n > 0 ? once() : DMMV_OK;       // warm-up launch, not timed
     if (st == DMMV_OK) {
         (void)hipEventRecord(e0, h->stream);

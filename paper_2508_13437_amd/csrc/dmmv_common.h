@@ -105,6 +105,7 @@ struct Ctx {
 
     // sparse: rows cut into csc_P partitions of csc_mp rows; segment s = p*n + j
     int32_t csc_P, csc_mp, csc_gb;  // partitions, rows per partition, workgroups per partition
+    bool csc_fused;       // the one-kernel evaluation (a workgroup walks every partition) scores the moves
     int64_t csc_nnzp;     // stored entries including segment padding (upper bound)
     int32_t* segptr;      // [P*n + 1] padded start of every segment
     uint16_t* row16;      // [nnzp] row offset inside the partition (pad = csc_mp)
@@ -225,7 +226,6 @@ dmmv_status csc_build(Ctx* c);
 dmmv_status csc_residual(Ctx* c);
 dmmv_status csc_reservoir(Ctx* c);      // rebuild the reservoir of largest |r| from r
 dmmv_status csc_eval(Ctx* c, void* scores_out, bool want_partials, bool honor_done);
-dmmv_status csc_eval_stream_only(Ctx* c);   // just the kernel that streams the matrix
 dmmv_status csc_apply(Ctx* c);          // staged move only; caller refreshes t and the reservoir
 dmmv_status csc_select_apply(Ctx* c, int32_t iters, dmmv_move* trace, void* trace_t, bool pruned);
 dmmv_status csc_eval_pruned(Ctx* c, bool honor_done);   // records of the columns of the worst row only

@@ -16,6 +16,8 @@
 // rows OUTSIDE the column (first reservoir row the column does not contain; rare columns that
 // contain every inline-checked row walk the rest of the reservoir, then scan all rows),
 // apply the neighbourhood mask, write scores and one arg-min record per workgroup.
+#include <type_traits>
+
 #include "dmmv_sparse_common.h"
 
 namespace dmmv {
@@ -205,6 +207,309 @@ __global__ __launch_bounds__(ST_BLOCK, 4) void k_eval_stream(   // 4 waves per S
                 }
             }
         }
+    }
+}
+
+// =========================================================================================
+// one-kernel evaluation: every partition inside one workgroup
+// =========================================================================================
+// For matrices whose residual is a few partitions long, cutting the work by (partition, column
+// range) costs a second kernel that only combines the partitions.  Here a workgroup of sixteen
+// wavefronts owns FZ_COLS = 256 columns (two groups of eight per wavefront, eight lanes per
+// column as above) and walks the partitions itself: the running maxima of its columns stay in
+// registers from the first partition to the last.  The kernel lives on memory latency, so
+// everything is requested early and nothing is spilled (a reload from scratch memory would queue
+// behind every load in flight): the entries of a group for partition p + 1 are requested the
+// moment its registers for partition p are folded, partition p + 1 of r travels from memory to
+// the second LDS buffer (through registers) while the lanes fold partition p, and nothing waits
+// at the barrier between two partitions but the barrier itself.  A lane takes two aligned groups
+// of four entries of its column per partition (64 entries per column).  A group of eight columns
+// with a segment longer than that (one in fourteen for the projection matrices this is written
+// for) gets a third group of four per lane from a spare set of registers of the wavefront; what
+// is longer still, or finds the spare set taken, goes on with loads that are waited for.  After
+// the last partition the lanes add the maximum over the rows outside their column, apply the
+// neighbourhood and reduce to ONE arg-min record per workgroup: no per-partition maxima leave
+// the chip.  Every workgroup reads all of r (256 columns share one copy), which is why this
+// kernel serves matrices with (n / 256) m w bytes of residual traffic not above the matrix
+// itself; the two-kernel path serves the others.
+constexpr int FZ_BLOCK = 1024;
+constexpr int FZ_WAVES = FZ_BLOCK / 64;
+constexpr int FZ_GROUPS = 2;                               // column groups per wavefront
+constexpr int FZ_COLS = FZ_WAVES * ST_CPW * FZ_GROUPS;
+constexpr int FZ_NQ = 2;                                   // aligned groups of four entries per lane per partition
+constexpr int FZ_QSTEP = SEG_ALIGN * ST_LPC;               // entries of a column one such group covers over its lanes (32)
+constexpr int FZ_RV = CSC_LDS_BYTES / 16 / FZ_BLOCK;       // 16-byte pieces of a partition of r per thread
+constexpr int FZ_MAX_P = 16;                               // partitions whose segment bounds fit the LDS table
+typedef uint32_t fz_piece __attribute__((ext_vector_type(4)));   // one such piece, a plain vector of registers
+static_assert(FZ_COLS == CSC_FIN_BLOCK, "one arg-min record per 256 columns, as the two-kernel path writes");
+
+// one aligned group of four entries: the lane's own, or the segment's last group when the lane's
+// would lie past the segment (a repeated entry changes neither a maximum nor a mask)
+template <class T>
+__device__ __forceinline__ void fz_load_quad(uint2& ix, typename Vec4<T>::type& av,
+                                             const uint16_t* __restrict__ row16, const T* __restrict__ cval,
+                                             int32_t eg, int32_t s1) {
+    const int32_t ec = eg < s1 ? eg : s1 - SEG_ALIGN;
+    ix = *reinterpret_cast<const uint2*>(row16 + ec);
+    av = *reinterpret_cast<const typename Vec4<T>::type*>(cval + ec);
+}
+
+// dk[q] - dcur is the step of value q (the unscaled instance: the factor 1 of step_of is exact)
+template <class T, int KT>
+__device__ __forceinline__ void fz_fold_quad(const uint2 ix, const typename Vec4<T>::type av, const T* lds_r,
+                                             const T (&dk)[KT], T dcur, T (&acc)[KT], uint32_t& mask, bool first_tile,
+                                             T thr, int32_t nfast, const int32_t* sh_rr, int64_t row0,
+                                             int32_t rows_here) {
+    const uint32_t i0 = ix.x & 0xFFFFu, i1 = ix.x >> 16, i2 = ix.y & 0xFFFFu, i3 = ix.y >> 16;
+    const T r0 = lds_r[i0], r1 = lds_r[i1], r2 = lds_r[i2], r3 = lds_r[i3];
+    if (first_tile) {
+        const T big = dmmv_max(dmmv_max(dmmv_abs(r0), dmmv_abs(r1)), dmmv_max(dmmv_abs(r2), dmmv_abs(r3)));
+        if (big >= thr) {      // uncommon: one of these rows may be among the listed ones
+            for (int32_t q = 0; q < nfast; ++q) {
+                const int64_t d = (int64_t)sh_rr[q] - row0;
+                const uint32_t l = (d >= 0 && d < (int64_t)rows_here) ? (uint32_t)d : ~0u;
+                if (i0 == l || i1 == l || i2 == l || i3 == l) mask |= 1u << q;
+            }
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < KT; ++q) {
+        const T delta = step_of(dk[q], dcur, (T)1);
+        T a = acc[q];
+        a = dmmv_max(a, dmmv_abs(dmmv_fma(delta, av.x, r0)));
+        a = dmmv_max(a, dmmv_abs(dmmv_fma(delta, av.y, r1)));
+        a = dmmv_max(a, dmmv_abs(dmmv_fma(delta, av.z, r2)));
+        a = dmmv_max(a, dmmv_abs(dmmv_fma(delta, av.w, r3)));
+        acc[q] = a;
+    }
+}
+
+template <class T, int KT>
+__global__ __launch_bounds__(FZ_BLOCK) void k_eval_fused(
+    int64_t m, int32_t n, int32_t nd, int32_t mp, int32_t P, const int32_t* __restrict__ segptr,
+    const uint16_t* __restrict__ row16, const T* __restrict__ cval, const T* __restrict__ D,
+    const int32_t* __restrict__ kidx, const T* __restrict__ r, const T* __restrict__ res_val,
+    const int32_t* __restrict__ res_row, const int32_t* __restrict__ res_meta,
+    const InstState<T>* __restrict__ st, int32_t honor_done, int32_t radius,
+    const uint8_t* __restrict__ var_mask, T* __restrict__ scores, Partial<T>* __restrict__ part) {
+    extern __shared__ __align__(32) unsigned char smem[];
+    const int32_t buf_bytes = (int32_t)((((size_t)mp + 1) * sizeof(T) + 15) / 16 * 16);
+    T* const buf0 = reinterpret_cast<T*>(smem);
+    T* const buf1 = reinterpret_cast<T*>(smem + buf_bytes);
+    int32_t* const sh_seg = reinterpret_cast<int32_t*>(smem + 2 * buf_bytes);   // [P][FZ_COLS + 1] segment bounds
+    __shared__ T sh_rv[RES_CAP];
+    __shared__ int32_t sh_rr[RES_CAP];
+    __shared__ T sh_s[FZ_WAVES];
+    __shared__ int64_t sh_c[FZ_WAVES];
+    __shared__ T sh_out[FZ_COLS];          // largest |r| outside each column (found with the first value tile)
+    // loads that depend on nothing go out first
+    const int32_t done = st[0].done;
+    const int32_t cnt = res_meta[RES_CNT];
+    T rv_in = (T)-1;
+    int32_t rr_in = -1;
+    if (threadIdx.x < RES_CAP) { rv_in = res_val[threadIdx.x]; rr_in = res_row[threadIdx.x]; }
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int sub = lane & (ST_LPC - 1);
+    const int rowid = lane / ST_LPC;
+    const int32_t c0 = blockIdx.x * FZ_COLS;               // n < 2^31
+    const int32_t ncol = n - c0 < FZ_COLS ? n - c0 : FZ_COLS;
+    // the bounds of this workgroup's segments in every partition: one trip to memory for all of them
+    for (int32_t t = threadIdx.x; t < P * (FZ_COLS + 1); t += FZ_BLOCK) {
+        const int32_t p = t / (FZ_COLS + 1), cc = t - p * (FZ_COLS + 1);
+        sh_seg[t] = cc <= ncol ? segptr[(int64_t)p * n + c0 + cc] : 0;
+    }
+    int32_t slot[FZ_GROUPS];               // column of the workgroup this lane works on, per group
+    int32_t kcur[FZ_GROUPS];
+    uint32_t flags = 0;                    // bit u: the column exists; bit 4 + u: it may move
+#pragma unroll
+    for (int u = 0; u < FZ_GROUPS; ++u) {
+        slot[u] = (w + u * FZ_WAVES) * ST_CPW + rowid;
+        const bool ok = slot[u] < ncol;
+        const int32_t j = ok ? c0 + slot[u] : n - 1;
+        kcur[u] = kidx[j];
+        const bool vok = var_mask ? var_mask[j] != 0 : true;
+        flags |= (ok ? 1u : 0u) << u | (vok ? 1u : 0u) << (4 + u);
+    }
+    if (honor_done && done) return;
+    T dcur[FZ_GROUPS];
+#pragma unroll
+    for (int u = 0; u < FZ_GROUPS; ++u) dcur[u] = D[kcur[u]];
+    if (threadIdx.x < RES_CAP) {
+        sh_rv[threadIdx.x] = (int32_t)threadIdx.x < cnt ? rv_in : (T)-1;
+        sh_rr[threadIdx.x] = (int32_t)threadIdx.x < cnt ? rr_in : -1;
+    }
+    if (threadIdx.x == 0) { buf0[mp] = (T)0; buf1[mp] = (T)0; }      // what a pad's offset reads
+    const int32_t nfast = cnt < RES_FAST ? cnt : RES_FAST;
+    const T thr = nfast > 0 ? res_val[nfast - 1] : Limits<T>::inf();
+    const bool aligned = (((size_t)mp * sizeof(T)) & 15) == 0;       // partitions start on 16 bytes
+    __syncthreads();                                                 // the bounds are in place
+
+    T bs = (T)0;                 // this lane's best candidate so far (lanes with sub != 0 stay empty)
+    int64_t bc = -1;
+
+    for (int32_t k0 = 0; k0 < nd; k0 += KT) {
+        T dk[KT], acc[FZ_GROUPS][KT];
+        uint32_t mask[FZ_GROUPS];
+#pragma unroll
+        for (int q = 0; q < KT; ++q) dk[q] = D[k0 + q < nd ? k0 + q : nd - 1];
+#pragma unroll
+        for (int u = 0; u < FZ_GROUPS; ++u) {
+            mask[u] = 0;
+#pragma unroll
+            for (int q = 0; q < KT; ++q) acc[u][q] = (T)0;
+        }
+        // Per group: the two groups of four of the partition about to be folded (ix, av), this
+        // lane's first entry of that segment and the segment's end (qe, qs1).  One spare group of
+        // four per wavefront (`ext`), owned by group ext_owner (-1: free).
+        uint2 ix[FZ_GROUPS][FZ_NQ];
+        typename Vec4<T>::type av[FZ_GROUPS][FZ_NQ];
+        int32_t qe[FZ_GROUPS], qs1[FZ_GROUPS];
+        uint2 ext_ix;
+        typename Vec4<T>::type ext_av;
+        int32_t ext_owner = -1;
+        // request the entries of group u in partition pp (a column that does not exist: entries 0..3, unused)
+#define FZ_REQUEST(u, pp)                                                                              \
+        do {                                                                                           \
+            const bool ok_ = (flags >> (u)) & 1u;                                                      \
+            const int32_t b0_ = ok_ ? sh_seg[(pp) * (FZ_COLS + 1) + slot[u]] : 0;                      \
+            const int32_t b1_ = ok_ ? sh_seg[(pp) * (FZ_COLS + 1) + slot[u] + 1] : SEG_ALIGN;          \
+            qe[u] = b0_ + sub * SEG_ALIGN;                                                             \
+            qs1[u] = b1_;                                                                              \
+            fz_load_quad<T>(ix[u][0], av[u][0], row16, cval, qe[u], b1_);                              \
+            fz_load_quad<T>(ix[u][1], av[u][1], row16, cval, qe[u] + FZ_QSTEP, b1_);                   \
+            if (ext_owner < 0 && __any(b1_ - b0_ > FZ_NQ * FZ_QSTEP)) {                                \
+                ext_owner = (u);                                                                       \
+                fz_load_quad<T>(ext_ix, ext_av, row16, cval, qe[u] + FZ_NQ * FZ_QSTEP, b1_);           \
+            }                                                                                          \
+        } while (0)
+        // ---- prologue: entries of partition 0, r of partition 0
+#pragma unroll
+        for (int u = 0; u < FZ_GROUPS; ++u) FZ_REQUEST(u, 0);
+        {
+            const int32_t rows0 = (int32_t)(m < mp ? m : mp);
+            const int32_t npiece0 = aligned ? (int32_t)(((size_t)rows0 * sizeof(T)) / 16) : 0;
+            for (int32_t i = threadIdx.x; i < npiece0; i += FZ_BLOCK)
+                reinterpret_cast<fz_piece*>(buf0)[i] = reinterpret_cast<const fz_piece*>(r)[i];
+            for (int32_t i = npiece0 * (int32_t)(16 / sizeof(T)) + threadIdx.x; i < rows0; i += FZ_BLOCK) buf0[i] = r[i];
+        }
+        __syncthreads();
+        for (int32_t p = 0; p < P; ++p) {
+            T* const cur = (p & 1) ? buf1 : buf0;
+            T* const nxt = (p & 1) ? buf0 : buf1;
+            const int64_t row0 = (int64_t)p * mp;
+            const int32_t rows_here = (int32_t)((m - row0) < mp ? (m - row0) : mp);
+            const int64_t row0n = row0 + mp;
+            const int32_t rows_next = p + 1 < P ? (int32_t)((m - row0n) < mp ? (m - row0n) : mp) : 0;
+            // partition p + 1 of r: requested now, written to the other buffer after the folds
+            // (unconditional loads: a piece past the end repeats piece 0; no next partition: r itself)
+            const int32_t npiece = aligned ? (int32_t)(((size_t)rows_next * sizeof(T)) / 16) : 0;
+            fz_piece rvp[FZ_RV];
+            {
+                const fz_piece* __restrict__ src = reinterpret_cast<const fz_piece*>(npiece > 0 ? r + row0n : r);
+#pragma unroll
+                for (int v = 0; v < FZ_RV; ++v) {
+                    const int32_t i = threadIdx.x + v * FZ_BLOCK;
+                    rvp[v] = src[i < npiece ? i : 0];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < FZ_GROUPS; ++u) {
+                fz_fold_quad<T, KT>(ix[u][0], av[u][0], cur, dk, dcur[u], acc[u], mask[u], k0 == 0, thr, nfast, sh_rr, row0, rows_here);
+                fz_fold_quad<T, KT>(ix[u][1], av[u][1], cur, dk, dcur[u], acc[u], mask[u], k0 == 0, thr, nfast, sh_rr, row0, rows_here);
+                int32_t e = qe[u] + FZ_NQ * FZ_QSTEP;
+                if (ext_owner == u) {
+                    fz_fold_quad<T, KT>(ext_ix, ext_av, cur, dk, dcur[u], acc[u], mask[u], k0 == 0, thr, nfast, sh_rr, row0, rows_here);
+                    e += FZ_QSTEP;
+                    ext_owner = -1;
+                }
+                // what is left of long segments: loads that are waited for (the columns diverge here)
+                const int32_t seg_end = qs1[u];
+                for (; e - sub * SEG_ALIGN < seg_end; e += FZ_QSTEP) {
+                    uint2 lix;
+                    typename Vec4<T>::type lav;
+                    fz_load_quad<T>(lix, lav, row16, cval, e, seg_end);
+                    fz_fold_quad<T, KT>(lix, lav, cur, dk, dcur[u], acc[u], mask[u], k0 == 0, thr, nfast, sh_rr, row0, rows_here);
+                }
+                if (p + 1 < P) FZ_REQUEST(u, p + 1);       // these registers take the next partition
+            }
+            if (p + 1 < P) {
+#pragma unroll
+                for (int v = 0; v < FZ_RV; ++v) {
+                    const int32_t i = threadIdx.x + v * FZ_BLOCK;
+                    if (i < npiece) reinterpret_cast<fz_piece*>(nxt)[i] = rvp[v];
+                }
+                for (int32_t i = npiece * (int32_t)(16 / sizeof(T)) + threadIdx.x; i < rows_next; i += FZ_BLOCK) nxt[i] = r[row0n + i];
+            }
+            __syncthreads();                  // partition p consumed by all, partition p + 1 in place
+        }
+#undef FZ_REQUEST
+        // ---- the columns' scores: partition maxima are complete, add the rows outside the column
+#pragma unroll
+        for (int u = 0; u < FZ_GROUPS; ++u) {
+#pragma unroll
+            for (int q = 0; q < KT; ++q) acc[u][q] = lanes_max_nonneg<ST_LPC>(acc[u][q]);
+            const bool ok = (flags >> u) & 1u;
+            const int64_t j = ok ? (int64_t)c0 + slot[u] : (int64_t)n - 1;
+            T outside_u;
+            if (k0 == 0) {
+                outside_u = (T)0;
+                const uint32_t cm = lanes_or<ST_LPC>(mask[u]);
+                const uint32_t full = (1u << nfast) - 1u;          // RES_FAST < 32
+                const uint32_t missing = full & ~cm;
+                bool need_walk = false;
+                if (missing) outside_u = sh_rv[__builtin_ctz(missing)];
+                else if ((int64_t)nfast >= m) outside_u = (T)0;    // the column holds every row
+                else need_walk = ok;
+                // rare: the column contains every inline-checked reservoir row; the wavefront helps
+                unsigned long long todo = __ballot(need_walk && sub == 0);
+                while (todo) {
+                    const int src = __builtin_ctzll(todo);
+                    todo &= todo - 1;
+                    const int64_t jj = __shfl(j, src, 64);
+                    int32_t first = INT32_MAX;
+                    for (int32_t base = RES_FAST; base < cnt && first == INT32_MAX; base += 64) {
+                        const int32_t q = base + lane;
+                        const bool absent = q < cnt && !column_has_row<T>(segptr, row16, n, mp, jj, sh_rr[q]);
+                        const unsigned long long bal = __ballot(absent);
+                        if (bal) first = base + __builtin_ctzll(bal);
+                    }
+                    T o;
+                    if (first != INT32_MAX) {
+                        o = sh_rv[first];
+                    } else if ((int64_t)cnt >= m) {
+                        o = (T)0;
+                    } else {                                       // exact scan over all rows
+                        o = (T)0;
+                        for (int64_t i = lane; i < m; i += 64)
+                            if (!column_has_row<T>(segptr, row16, n, mp, jj, (int32_t)i)) o = dmmv_max(o, dmmv_abs(r[i]));
+                        o = wave_max(o);
+                    }
+                    if ((lane & ~(ST_LPC - 1)) == (src & ~(ST_LPC - 1))) outside_u = o;   // the column's lanes
+                }
+                if (sub == 0 && nd > KT) sh_out[slot[u]] = outside_u;   // later value tiles read it back (same lane)
+            } else {
+                outside_u = sh_out[slot[u]];
+            }
+            if (sub == 0 && ok) {
+                const bool vok = (flags >> (4 + u)) & 1u;
+#pragma unroll
+                for (int q = 0; q < KT; ++q) {
+                    const int32_t k = k0 + q;
+                    if (k < nd) {
+                        T v = dmmv_max(outside_u, acc[u][q]);
+                        if (!cand_allowed(kcur[u], k, radius, vok)) v = Limits<T>::inf();
+                        const int64_t cidx = j * (int64_t)nd + k;
+                        if (scores) scores[cidx] = v;
+                        if (rec_less(v, cidx, bs, bc)) { bs = v; bc = cidx; }
+                    }
+                }
+            }
+        }
+    }
+    if (part) {
+        block_argmin(bs, bc, sh_s, sh_c);
+        if (threadIdx.x == 0) { Partial<T> pr; pr.s = bs; pr.c = bc; part[blockIdx.x] = pr; }
     }
 }
 
@@ -556,8 +861,33 @@ static dmmv_status stream_t(Ctx* c, bool honor_done) {
     return stream_launch<T, 8>(c, honor_done);
 }
 
+template <class T, int KT>
+static dmmv_status fused_launch(Ctx* c, void* scores, bool want_partials, bool honor_done) {
+    const size_t buf = (((size_t)c->csc_mp + 1) * sizeof(T) + 15) / 16 * 16;
+    const size_t lds = 2 * buf + (size_t)c->csc_P * (FZ_COLS + 1) * sizeof(int32_t);
+    if (c->csc_P > FZ_MAX_P) return fail(DMMV_ERR_STATE, "one-kernel sparse evaluation chosen for %d partitions (at most %d)", c->csc_P, FZ_MAX_P);
+    DMMV_TRY(ensure_dynamic_lds(reinterpret_cast<const void*>(&k_eval_fused<T, KT>),
+                                2 * CSC_LDS_BYTES + 64 + FZ_MAX_P * (FZ_COLS + 1) * (int)sizeof(int32_t)));
+    const unsigned blocks = (unsigned)ceil_div(c->p.n, FZ_COLS);
+    if ((int64_t)blocks != c->n_partials) return fail(DMMV_ERR_STATE, "sparse evaluation grid does not match the partial-record buffer");
+    hipLaunchKernelGGL((k_eval_fused<T, KT>), dim3(blocks), dim3(FZ_BLOCK), lds, c->stream, c->p.m, (int32_t)c->p.n,
+                       c->p.nd, c->csc_mp, c->csc_P, (const int32_t*)c->segptr, (const uint16_t*)c->row16,
+                       (const T*)c->cval, (const T*)c->D_dev, (const int32_t*)c->kidx, (const T*)c->r,
+                       (const T*)c->res_val, (const int32_t*)c->res_row, (const int32_t*)c->res_meta,
+                       (const InstState<T>*)c->state, (int32_t)honor_done, c->o.radius, c->o.var_mask,
+                       (T*)scores, want_partials ? (Partial<T>*)c->partials : nullptr);
+    DMMV_LAUNCH_CHECK();
+    return DMMV_OK;
+}
+
 template <class T>
 static dmmv_status eval_t(Ctx* c, void* scores, bool want_partials, bool honor_done) {
+    if (c->csc_fused) {
+        if (c->p.nd <= 2) return fused_launch<T, 2>(c, scores, want_partials, honor_done);
+        if (c->p.nd == 3) return fused_launch<T, 3>(c, scores, want_partials, honor_done);
+        if (c->p.nd <= 4) return fused_launch<T, 4>(c, scores, want_partials, honor_done);
+        return fused_launch<T, 8>(c, scores, want_partials, honor_done);
+    }
     DMMV_TRY(stream_t<T>(c, honor_done));
     const unsigned blocks = (unsigned)ceil_div(c->p.n, FIN_BLOCK);
     if ((int64_t)blocks != c->n_partials) return fail(DMMV_ERR_STATE, "sparse finalize grid does not match the partial-record buffer");
@@ -592,9 +922,6 @@ static dmmv_status eval_pruned_t(Ctx* c, bool honor_done) {
 }
 dmmv_status csc_eval_pruned(Ctx* c, bool honor_done) {
     return c->p.dtype == DMMV_F64 ? eval_pruned_t<double>(c, honor_done) : eval_pruned_t<float>(c, honor_done);
-}
-dmmv_status csc_eval_stream_only(Ctx* c) {
-    return c->p.dtype == DMMV_F64 ? stream_t<double>(c, false) : stream_t<float>(c, false);
 }
 
 }  // namespace dmmv

@@ -49,7 +49,7 @@ class Options(C.Structure):
     _fields_ = [("radius", C.c_int32), ("keep_going", C.c_int32), ("poll_every", C.c_int32),
                 ("sparse_partition_rows", C.c_int32), ("var_mask", C.c_void_p),
                 ("residual_mfma", C.c_int32), ("prune", C.c_int32), ("alns", C.c_int32),
-                ("value_search", C.c_int32), ("batched_eval", C.c_int32)]
+                ("value_search", C.c_int32), ("batched_eval", C.c_int32), ("sparse_eval", C.c_int32)]
 
 
 class AlnsParams(C.Structure):
@@ -136,7 +136,7 @@ class Handle:
     def __init__(self, *, D, b, A=None, csr=None, m=None, n=None, scale=None, radius: int = 0,
                  keep_going: bool = False, poll_every: int = 64, var_mask=None,
                  sparse_partition_rows: int = 0, residual_mfma: bool = False, prune: bool = False,
-                 alns: bool = False, value_search: bool = False, batched_eval: int = 0,
+                 alns: bool = False, value_search: bool = False, batched_eval: int = 0, sparse_eval: int = 0,
                  stream: Optional[torch.cuda.Stream] = None, device=None, _create: bool = True):
         lib = load()
         self._h = C.c_void_p(None)
@@ -193,6 +193,7 @@ class Handle:
         o.prune = int(bool(prune))
         o.alns = int(bool(alns))
         o.batched_eval = int(batched_eval)
+        o.sparse_eval = int(sparse_eval)
         o.value_search = int(bool(value_search))
         if var_mask is not None:
             var_mask = var_mask.to(torch.uint8).contiguous()

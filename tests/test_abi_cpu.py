@@ -145,7 +145,7 @@ def test_options_block_of_the_binding_has_the_layout_of_the_header(mod):
     for decl in re.findall(r"^\s+(?:const\s+)?(?:int32_t|uint8_t\*)\s+\*?([a-z0-9_]+);", body, flags=re.M):
         names.append(decl)
     assert names == [f[0] for f in mod.Options._fields_], (names, [f[0] for f in mod.Options._fields_])
-    # four int32, one pointer (8-byte aligned already), six int32 -> padded to the pointer's alignment
+    # four int32, one pointer (8-byte aligned already), six int32: 48 bytes, no padding
     assert C.sizeof(mod.Options) == 48
 
 

@@ -68,8 +68,9 @@ def stepwise_check(inst, steps=4, **opt):
     vm = opt.get("var_mask")
     hopt = dict(radius=opt.pop("radius", 0))
     opt["radius"] = hopt["radius"]
-    if "sparse_partition_rows" in opt:
-        hopt["sparse_partition_rows"] = opt.pop("sparse_partition_rows")
+    for key in ("sparse_partition_rows", "sparse_eval"):
+        if key in opt:
+            hopt[key] = opt.pop(key)
     if vm is not None:
         hopt["var_mask"] = T(vm)
     with m.from_instance(inst, DEV, **hopt) as h:
@@ -269,6 +270,60 @@ def test_sparse_long_descent_reservoir_maintenance():
             assert np.array_equal(N(r), o.r)
             # the table of the final state still matches (reservoir consistent with r)
             assert np.array_equal(N(dmmv().dmmv_eval_moves(h)), oracle_table(inst, o.x, o.r))
+
+
+@pytest.mark.parametrize("mode", [1, 2])
+def test_sparse_both_evaluation_kernels(mode):
+    """options.sparse_eval forces the two-kernel path (1: per-partition maxima + combine) or the
+    one-kernel path (2: a workgroup walks every partition): each must give the oracle's tables,
+    arg-min records and traces on its own, whatever the automatic choice would be - ragged shapes,
+    forced and misaligned partition sizes, several value tiles, long columns, columns that hold
+    every large row, masks and radius, both precisions."""
+    m = dmmv()
+    for mm, nn, nd, dens, dtype in [(1, 1, 2, 1.0, np.float32), (20, 9, 3, 0.3, np.float64), (33, 12, 3, 0.9, np.float32),
+                                    (200, 150, 3, 0.05, np.float32), (129, 31, 11, 0.2, np.float64),
+                                    (2100, 300, 3, 0.02, np.float32), (300, 700, 20, 0.03, np.float32)]:
+        stepwise_check(random_sparse(20 + mm, mm, nn, nd, density=dens, dtype=dtype), steps=2, sparse_eval=mode)
+    # the one-kernel path takes at most 16 partitions; 10 and 13 rows also give partitions that
+    # do not start on 16 bytes
+    for rows in ((1, 7, 64, 1000) if mode == 1 else (10, 13, 64, 1000)):
+        inst = random_sparse(555, 150, 60, 4, density=0.2, dtype=np.float32)
+        stepwise_check(inst, steps=2, sparse_partition_rows=rows, sparse_eval=mode)
+        inst = random_sparse(556, 90, 25, 3, density=0.5, dtype=np.float64, integer=True)
+        stepwise_check(inst, steps=2, sparse_partition_rows=rows, sparse_eval=mode)
+        with m.from_instance(inst, DEV, sparse_partition_rows=rows, sparse_eval=mode) as h:
+            res = m.dmmv_solve(h, T(inst.x0), 30, trace=True)
+        check_single_trace(res, oracle_solve(inst, 30), 30)
+    inst = random_sparse(557, 5000, 20, 3, density=0.3, dtype=np.float32)          # long columns
+    stepwise_check(inst, steps=2, sparse_eval=mode)
+    stepwise_check(inst, steps=2, sparse_partition_rows=700, sparse_eval=mode)
+    stepwise_check(random_sparse(558, 70000, 12, 3, density=0.01, dtype=np.float32), steps=2, sparse_eval=mode)
+    for seed in range(2):                                                           # ties, full columns
+        inst = random_sparse(300 + seed, 45, 14, 3, density=0.85, dtype=np.float32, integer=True, explicit_zeros=True)
+        stepwise_check(inst, steps=3, sparse_eval=mode)
+    for density, nn in [(1.0, 5), (1.0, 100), (0.97, 70)]:                          # columns holding all large rows
+        inst = random_sparse(900 + nn, 333, nn, 3, density=density, dtype=np.float32)
+        stepwise_check(inst, steps=2, sparse_eval=mode)
+        stepwise_check(inst, steps=2, sparse_partition_rows=100, sparse_eval=mode)
+    inst = random_sparse(910, 260, 90, 9, density=0.1, dtype=np.float32)            # mask and radius
+    vm = (np.random.default_rng(3).uniform(size=inst.n) < 0.6).astype(np.uint8)
+    stepwise_check(inst, steps=2, radius=1, var_mask=vm, sparse_eval=mode)
+    inst = random_sparse(977, 6000, 400, 5, density=0.02, dtype=np.float32)         # long descent
+    x0 = np.random.default_rng(5).choice(inst.D, size=inst.n).astype(np.float32)
+    o = oracle_solve(inst, 400, x0=x0)
+    for rows, keep in ((0, False), (2500, True)):
+        with m.from_instance(inst, DEV, sparse_partition_rows=rows, sparse_eval=mode, keep_going=keep) as h:
+            res = m.dmmv_solve(h, T(x0), 400, trace=True)
+            check_single_trace(res, o, 400)
+            assert np.array_equal(N(m.dmmv_eval_moves(h)), oracle_table(inst, o.x, o.r))
+    inst = make_config(3, "small")
+    with m.from_instance(inst, DEV, sparse_eval=mode) as h:
+        res = m.dmmv_solve(h, T(inst.x0), inst.iters, trace=True)
+    check_single_trace(res, oracle_solve(inst, inst.iters), inst.iters)
+    if mode == 2:
+        with pytest.raises(m.DmmvError) as e:                 # 150 partitions: refused, not mis-run
+            m.from_instance(random_sparse(555, 150, 60, 4, density=0.2), DEV, sparse_partition_rows=1, sparse_eval=2)
+        assert e.value.status == -8
 
 
 def test_sparse_solve_small_tomography():
