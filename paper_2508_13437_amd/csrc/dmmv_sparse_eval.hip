@@ -345,7 +345,7 @@ __global__ __launch_bounds__(FZ_BLOCK) void k_eval_fused(
     const bool aligned = (((size_t)mp * sizeof(T)) & 15) == 0;       // partitions start on 16 bytes
     __syncthreads();                                                 // the bounds are in place
 
-    T bs = (T)0;                 // this lane's best candidate so far (lanes with sub != 0 stay empty)
+    T bs = (T)0;                 // this lane's best candidate so far
     int64_t bc = -1;
 
     for (int32_t k0 = 0; k0 < nd; k0 += KT) {
@@ -450,7 +450,7 @@ __global__ __launch_bounds__(FZ_BLOCK) void k_eval_fused(
 #pragma unroll
             for (int q = 0; q < KT; ++q) acc[u][q] = lanes_max_nonneg<ST_LPC>(acc[u][q]);
             const bool ok = (flags >> u) & 1u;
-            const int64_t j = ok ? (int64_t)c0 + slot[u] : (int64_t)n - 1;
+            const int32_t j = ok ? c0 + slot[u] : n - 1;
             T outside_u;
             if (k0 == 0) {
                 outside_u = (T)0;
@@ -491,19 +491,19 @@ __global__ __launch_bounds__(FZ_BLOCK) void k_eval_fused(
             } else {
                 outside_u = sh_out[slot[u]];
             }
-            if (sub == 0 && ok) {
-                const bool vok = (flags >> (4 + u)) & 1u;
+            // every lane of the column holds the column's maxima: lane `sub` scores value k0 + sub
+            static_assert(KT <= ST_LPC, "one lane of the column per value of the tile");
+            T mine = acc[u][0];
 #pragma unroll
-                for (int q = 0; q < KT; ++q) {
-                    const int32_t k = k0 + q;
-                    if (k < nd) {
-                        T v = dmmv_max(outside_u, acc[u][q]);
-                        if (!cand_allowed(kcur[u], k, radius, vok)) v = Limits<T>::inf();
-                        const int64_t cidx = j * (int64_t)nd + k;
-                        if (scores) scores[cidx] = v;
-                        if (rec_less(v, cidx, bs, bc)) { bs = v; bc = cidx; }
-                    }
-                }
+            for (int q = 1; q < KT; ++q) mine = sub == q ? acc[u][q] : mine;
+            const int32_t k = k0 + sub;
+            if (ok && sub < KT && k < nd) {
+                const bool vok = (flags >> (4 + u)) & 1u;
+                T v = dmmv_max(outside_u, mine);
+                if (!cand_allowed(kcur[u], k, radius, vok)) v = Limits<T>::inf();
+                const int64_t cidx = (int64_t)j * nd + k;
+                if (scores) scores[cidx] = v;
+                if (rec_less(v, cidx, bs, bc)) { bs = v; bc = cidx; }
             }
         }
     }
