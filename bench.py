@@ -35,11 +35,18 @@ import numpy as np  # noqa: E402
 HBM_PEAK_GBS = 8000.0
 ALU_PEAK_TFLOPS = {"f32": 157.3, "f64": 78.6}
 FLOPS_PER_PAIR = 3          # multiply + add of the fma, and the max; |.| is an operand modifier
-# HBM bytes per launch of the evaluation kernel, from rocprofv3 FETCH_SIZE + WRITE_SIZE runs
-# calibrated against a plain copy (summaries under profiles/hbm_traffic_*.md)
-MEASURED_TRAFFIC_BYTES = {
-    "tomography_256x256_180x363_csr_f32": 100.2e6,
-}
+PROFILES = os.path.join(ROOT, "profiles")
+
+
+def measured_traffic(workload: str):
+    """HBM-side bytes per launch of the evaluation kernel, as `--traffic-summary` wrote them from two
+    rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE) calibrated against a plain copy; None when
+    no such summary has been made for this workload."""
+    path = os.path.join(PROFILES, f"hbm_traffic_{workload}.json")
+    if not os.path.exists(path):
+        return None
+    with open(path) as f:
+        return json.load(f)
 
 
 def algorithmic_bytes_per_eval(inst) -> float:
@@ -59,15 +66,36 @@ def pairs_per_eval(inst) -> float:
     return float(inst.R) * inst.n * (inst.nd - 1) * rows
 
 
-def roofline_for(inst, eval_ms: float) -> dict:
+def roofline_for(inst, eval_ms: float, iter_us=None, cold_ms=None) -> dict:
     dt = "f64" if inst.dtype == np.float64 else "f32"
     if inst.kind == "csr":
         b = algorithmic_bytes_per_eval(inst)
         ach = b / (eval_ms * 1e-3) / 1e9
-        return {"bound": "hbm", "kernel": "k_eval_stream", "achieved": ach, "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
-                "traffic": MEASURED_TRAFFIC_BYTES.get(inst.name),
-                "algorithmic_bytes_per_launch": b, "avg_launch_ms": eval_ms}
+        tr = measured_traffic(inst.name)
+        out = {"bound": "hbm", "kernel": "k_eval_fused", "achieved": ach, "peak": HBM_PEAK_GBS,
+               "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+               "traffic": None if tr is None else tr["bytes_per_launch"],
+               "algorithmic_bytes_per_launch": b, "avg_launch_ms": eval_ms,
+               "covers": "the whole evaluation step (one kernel: stream every row partition, add the rows "
+                         "outside each column, reduce to the arg-min records), launches back to back"}
+        if tr is not None:
+            out["measured_GBs"] = tr["bytes_per_launch"] / (eval_ms * 1e-3) / 1e9
+            out["frac_measured"] = out["measured_GBs"] / HBM_PEAK_GBS
+            out["traffic_source"] = tr.get("source")
+        if iter_us is not None:
+            # the same bytes over a whole iteration of the loop (evaluation + select/apply)
+            out["iteration_us"] = iter_us
+            out["frac_iteration"] = b / (iter_us * 1e-6) / 1e9 / HBM_PEAK_GBS
+        if cold_ms is not None:
+            # every launch preceded by a flush of the 256 MB Infinity Cache and the L2s (a 1 GiB
+            # device-to-device copy, or a 1 GiB read): nothing of the matrix is left on the chip, so
+            # these are rates out of HBM itself; after the copy the reads also push written lines out
+            out["cold_launch_ms"], out["cold_after_read_ms"] = cold_ms
+            out["cold_GBs"] = b / (cold_ms[0] * 1e-3) / 1e9
+            out["frac_cold"] = out["cold_GBs"] / HBM_PEAK_GBS
+            out["cold_after_read_GBs"] = b / (cold_ms[1] * 1e-3) / 1e9
+            out["frac_cold_after_read"] = out["cold_after_read_GBs"] / HBM_PEAK_GBS
+        return out
     flops = pairs_per_eval(inst) * FLOPS_PER_PAIR
     ach = flops / (eval_ms * 1e-3) / 1e12
     peak = ALU_PEAK_TFLOPS[dt]
@@ -101,17 +129,27 @@ def cpu_baseline(inst, budget_s: float) -> dict:
     per_iter = inst.nnz * inst.nd
     # the oracle scores about 1e9 pairs/s on one core; only used to size the sample
     iters = int(max(1, min(inst.iters, budget_s * 1.0e9 / max(per_iter, 1))))
+    def once():
+        if inst.kind == "csr":
+            return orc.solve_csr(inst.m, inst.n, inst.csr_rowptr, inst.csr_col, inst.csr_val, inst.b,
+                                 inst.D, inst.x0, iters)
+        return orc.solve_dense(inst.A, inst.b, inst.D, inst.x0, iters)
+
+    # a descent that stalls after a move or two is over in milliseconds: repeat it until the clock
+    # has something to measure (the same evaluations every time)
     t0 = time.perf_counter()
-    if inst.kind == "csr":
-        res = orc.solve_csr(inst.m, inst.n, inst.csr_rowptr, inst.csr_col, inst.csr_val, inst.b,
-                            inst.D, inst.x0, iters)
-    else:
-        res = orc.solve_dense(inst.A, inst.b, inst.D, inst.x0, iters)
-    dt = time.perf_counter() - t0
+    runs = 0
+    while True:
+        res = once()
+        runs += 1
+        dt = time.perf_counter() - t0
+        if dt >= min(0.5, budget_s) or runs >= 1000:
+            break
     evals = min(res.iters_done + 1, iters)
-    moves = evals * inst.n * (inst.nd - 1)
+    moves = runs * evals * inst.n * (inst.nd - 1)
     return {"value": moves / dt, "unit": "moves/s", "cores": 1, "kind": "oracle",
-            "sample": f"{evals} evaluations from the configured start (of {inst.iters}), {dt:.1f} s",
+            "sample": f"{runs} run(s) of {evals} evaluations from the configured start (of {inst.iters} "
+                      f"iterations), {dt:.1f} s",
             "host_cores_visible": cores}
 
 
@@ -148,6 +186,7 @@ def run_config(idx: int, steps: int, warmup: int, iters_override, device: str, d
         dt = time.perf_counter() - t0
         reps = max(3, min(200, int(0.5 / max(dt / (steps * iters), 1e-6))))
         eval_ms = dmmv.dmmv_time_eval(h, reps) / reps
+        cold_ms = cold_eval_ms(h, device) if inst.kind == "csr" else None
     moves = float(steps) * iters * inst.moves_per_iter()
     out.update({
         "workload": inst.name, "kind": inst.kind, "m": inst.m, "n": inst.n, "nd": inst.nd,
@@ -159,7 +198,7 @@ def run_config(idx: int, steps: int, warmup: int, iters_override, device: str, d
         "descent_until_local_optimum_ms": normal_s * 1e3,
         "final_max_violation": float(t_final.max()),
         "dtype": "f64" if inst.dtype == np.float64 else "f32",
-        "roofline": roofline_for(inst, eval_ms), "input_gen_s": round(t_gen, 2),
+        "roofline": roofline_for(inst, eval_ms, dt / (steps * iters) * 1e6, cold_ms), "input_gen_s": round(t_gen, 2),
     })
     if inst.kind == "batched":
         out["residual"] = residual_timing(inst, device, x0)
@@ -184,6 +223,28 @@ def run_config(idx: int, steps: int, warmup: int, iters_override, device: str, d
     if do_cpu:
         out["cpu_baseline"] = cpu_baseline(inst, cpu_budget)
     return out
+
+
+def cold_eval_ms(h, device: str, reps: int = 8):
+    """One evaluation launch timed right after the caches were flushed on the same stream, averaged over
+    `reps` such launches.  Two flushes: a 1 GiB device-to-device copy (it leaves the Infinity Cache
+    full of written lines, which the evaluation's reads then push out to HBM), and a read of 1 GiB
+    (clean lines only).  Either is long enough for the launch to be enqueued behind it."""
+    import torch
+    from paper_2508_13437_amd import dmmv
+
+    src = torch.empty(1 << 28, dtype=torch.int32, device=device).fill_(1)
+    dst = torch.empty_like(src)
+    after_copy = after_read = 0.0
+    with torch.cuda.stream(h.stream):
+        for _ in range(reps):
+            dst.copy_(src)
+            after_copy += dmmv.dmmv_time_eval(h, -1)
+        for _ in range(reps):
+            src.max()
+            after_read += dmmv.dmmv_time_eval(h, -1)
+    del src, dst
+    return after_copy / reps, after_read / reps
 
 
 def descent_timing(inst, device: str, x0, iters: int) -> dict:
@@ -336,6 +397,60 @@ def traffic_probe(idx: int, device: str, reps: int) -> None:
                       "algorithmic_bytes_per_launch": algorithmic_bytes_per_eval(inst)}))
 
 
+def traffic_summary(idx: int, fetch_dir: str, write_dir: str) -> None:
+    """Turn the counter CSVs of the two --traffic-probe runs into profiles/hbm_traffic_<workload>.json.
+    Both counters are read in KiB per dispatch; each is scaled by what it reads for the probe's plain
+    256 MiB copy (whose bytes are known).  Runs on the CPU."""
+    import csv
+    import glob
+
+    def per_kernel(d, counter):
+        files = glob.glob(os.path.join(d, "**", "*counter_collection.csv"), recursive=True)
+        if not files:
+            raise SystemExit(f"no *counter_collection.csv under {d}")
+        acc = {}
+        for path in files:
+            with open(path, newline="") as f:
+                for row in csv.DictReader(f):
+                    if row.get("Counter_Name") != counter:
+                        continue
+                    name = row["Kernel_Name"].split("(")[0]
+                    acc.setdefault(name, []).append((int(row["Grid_Size"]), float(row["Counter_Value"])))
+        return acc
+
+    from workloads import CONFIG_NAMES
+    fetch, write = per_kernel(fetch_dir, "FETCH_SIZE"), per_kernel(write_dir, "WRITE_SIZE")
+
+    def pick(acc, needle):
+        hits = [k for k in acc if needle in k]
+        if len(hits) != 1:
+            raise SystemExit(f"expected one kernel matching {needle!r}, found {hits}")
+        return hits[0], acc[hits[0]]
+
+    copy_bytes = 256 << 20
+    # the probe's 256 MiB copy is the largest dispatch of the copy kernel (uploads use it too)
+    cf = max(pick(fetch, "copyBuffer")[1])[1]
+    cw = max(pick(write, "copyBuffer")[1])[1]
+    f_scale = copy_bytes / 1024.0 / cf
+    w_scale = copy_bytes / 1024.0 / cw
+    kname, kf = pick(fetch, "k_eval_")
+    _, kw = pick(write, "k_eval_")
+    kf, kw = [v for _, v in kf], [v for _, v in kw]
+    fetched = sum(kf) / len(kf) * 1024.0 * f_scale
+    written = sum(kw) / len(kw) * 1024.0 * w_scale
+    out = {"workload": CONFIG_NAMES[idx], "kernel": kname, "launches": len(kf),
+           "fetch_KiB_raw": sum(kf) / len(kf), "write_KiB_raw": sum(kw) / len(kw),
+           "fetch_scale": f_scale, "write_scale": w_scale,
+           "bytes_fetched": fetched, "bytes_written": written, "bytes_per_launch": fetched + written,
+           "source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on `bench.py --traffic-probe`, scaled by the "
+                     "same counters' reading for a 256 MiB device-to-device copy"}
+    path = os.path.join(PROFILES, f"hbm_traffic_{CONFIG_NAMES[idx]}.json")
+    with open(path, "w") as f:
+        json.dump(out, f, indent=1)
+        f.write("\n")
+    print(json.dumps(out))
+
+
 def residual_probe(idx: int, device: str, reps: int) -> None:
     """For `rocprofv3 --pmc` runs on the matrix-core residual: `reps` calls of dmmv_residual
     with options.residual_mfma on batched workload idx, nothing else."""
@@ -385,6 +500,11 @@ def main():
                          "line ('' for none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget", type=float, default=15.0)
+    ap.add_argument("--cpu-budget-others", type=float, default=4.0,
+                    help="seconds of oracle time per workload of --others")
+    ap.add_argument("--traffic-summary", nargs=2, metavar=("FETCH_DIR", "WRITE_DIR"), default=None,
+                    help="no GPU: read the counter CSVs of two `rocprofv3 --pmc` runs of --traffic-probe "
+                         "(FETCH_SIZE, WRITE_SIZE) and write profiles/hbm_traffic_<workload>.json")
     ap.add_argument("--traffic-probe", type=int, default=0, metavar="REPS",
                     help="only launch the evaluation kernel REPS times plus a calibration copy "
                          "(for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs)")
@@ -393,6 +513,9 @@ def main():
     ap.add_argument("--descent-probe", type=int, default=0, metavar="REPS",
                     help="only run the pruned batched descent REPS times (for rocprofv3 --pmc runs)")
     args = ap.parse_args()
+    if args.traffic_summary:
+        traffic_summary(args.config, *args.traffic_summary)
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
               "--gpus must be 1", file=sys.stderr)
@@ -449,7 +572,9 @@ def main():
     if others:
         line["other_workloads"] = []
         for idx in others:
-            o = run_config(idx, default_steps[idx], 1 if idx < 4 else 0, None, device, False, 0)
+            # the oracle on a small bounded sample of each (a few seconds): a reported baseline
+            o = run_config(idx, default_steps[idx], 1 if idx < 4 else 0, None, device,
+                           not args.no_cpu_baseline, args.cpu_budget_others)
             line["other_workloads"].append(o)
     print(json.dumps(line))
 

@@ -233,13 +233,6 @@ dmmv_status dmmv_solve_static(const dmmv_problem* problem, const dmmv_options* o
                               int32_t iters, void* x_out, void* max_violation_out, int32_t* iters_done,
                               dmmv_move* trace, void* trace_t, void* hip_stream);
 
-/* Measurement hook: enqueue the evaluation step of the descent (every kernel of it: the step
- * that streams all of A and leaves the arg-min records, the "evaluate all candidates in bulk"
- * step of the paper's section "GPU Acceleration") `reps` times back to back between two HIP events on the handle's
- * stream and return the elapsed time in milliseconds in *ms_out (HOST).  The state is not
- * changed.  Needs a residual.  Waits for the stream. */
-dmmv_status dmmv_time_eval(dmmv_handle h, int32_t reps, float* ms_out);
-
 /* Parameters of the ALNS outer loop (Algorithm 1 of the paper).  What the paper leaves open is
  * fixed as stated at each field. */
 typedef struct {

@@ -1,0 +1,27 @@
+/*
+ * libdmmv - measurement hooks.  Not part of the library's functional surface (include/dmmv.h):
+ * the benchmark uses them to time a kernel of the hot path in isolation with HIP events on the
+ * handle's own stream.
+ */
+#ifndef DMMV_BENCH_H
+#define DMMV_BENCH_H
+
+#include "dmmv.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Enqueue the evaluation step of the descent (every kernel of it: the step that streams all of A
+ * and leaves the arg-min records, the "evaluate all candidates in bulk" step of the paper's
+ * section "GPU Acceleration") `reps` times back to back between two HIP events on the handle's
+ * stream and return the elapsed time in milliseconds in *ms_out (HOST).  One untimed launch
+ * precedes the timed ones.  reps < 0: -reps timed launches WITHOUT the untimed one, for a
+ * measurement that starts from whatever the caller left in the caches (say, after a large copy).
+ * The state is not changed.  Needs a residual.  Waits for the stream. */
+dmmv_status dmmv_time_eval(dmmv_handle h, int32_t reps, float* ms_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DMMV_BENCH_H */

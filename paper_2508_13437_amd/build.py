@@ -13,7 +13,8 @@ SOURCES = ["dmmv_api.hip", "dmmv_dense.hip", "dmmv_dense_search.hip", "dmmv_spar
            "dmmv_batched.hip", "dmmv_batched_pruned.hip", "dmmv_batched_mfma.hip", "dmmv_batched_eval_mfma.hip", "dmmv_alns.hip", "dmmv_swap.hip", "dmmv_swap_sparse.hip"]
 HEADERS = [os.path.join(CSRC, "dmmv_common.h"), os.path.join(CSRC, "dmmv_sparse_common.h"),
            os.path.join(CSRC, "dmmv_alns_common.h"),
-           os.path.join(os.path.dirname(HERE), "include", "dmmv.h")]
+           os.path.join(os.path.dirname(HERE), "include", "dmmv.h"),
+           os.path.join(os.path.dirname(HERE), "include", "dmmv_bench.h")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

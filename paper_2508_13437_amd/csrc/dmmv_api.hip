@@ -12,6 +12,7 @@
 #include <vector>
 
 #include "dmmv_common.h"
+#include "../../include/dmmv_bench.h"
 
 namespace dmmv {
 
@@ -1028,7 +1029,9 @@ dmmv_status dmmv_swap_move(dmmv_handle h, int32_t k_eps, int32_t apply, dmmv_swa
 dmmv_status dmmv_time_eval(dmmv_handle h, int32_t reps, float* ms_out) {
     if (!h) return fail(DMMV_ERR_NULL, "handle is NULL");
     if (!ms_out) return fail(DMMV_ERR_NULL, "ms_out is NULL");
-    if (reps < 1) return fail(DMMV_ERR_SHAPE, "reps must be >= 1");
+    if (reps == 0) return fail(DMMV_ERR_SHAPE, "reps must not be 0");
+    const bool warm = reps > 0;
+    if (!warm) reps = -reps;
     if (!h->r_valid) return fail(DMMV_ERR_STATE, "dmmv_time_eval needs a residual");
     if (h->p.dtype == DMMV_F64)
         hipLaunchKernelGGL(k_clear_done<double>, grid1(h->p.R, 256), dim3(256), 0, h->stream, (InstState<double>*)h->state, h->p.R);
@@ -1039,7 +1042,7 @@ dmmv_status dmmv_time_eval(dmmv_handle h, int32_t reps, float* ms_out) {
     DMMV_HIP_CHECK(hipEventCreate(&e1));
     // the whole evaluation step as the descent runs it (sparse, two-kernel path: both kernels)
     auto once = [&]() { return eval_any(h, nullptr, true, false); };
-    dmmv_status st = h->p.n > 0 ? once() : DMMV_OK;       // warm-up launch, not timed
+    dmmv_status st = (warm && h->p.n > 0) ? once() : DMMV_OK;       // warm-up launch, not timed
     if (st == DMMV_OK) {
         (void)hipEventRecord(e0, h->stream);
         for (int32_t q = 0; q < reps && st == DMMV_OK && h->p.n > 0; ++q) st = once();
