@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB = os.path.join(HERE, "liboracle.so")
 SOURCES = [os.path.join(HERE, f) for f in ("dmmv_oracle.c", "dmmv_oracle_impl.inc", "alns_common.inc",
-                                           "alns_oracle_impl.inc", "swap_oracle_impl.inc")]
+                                           "alns_oracle_impl.inc", "swap_oracle_impl.inc", "l2_oracle_impl.inc")]
 
 
 def _cpu_has_fma() -> bool:

@@ -19,6 +19,9 @@
  * The swap move (swap_oracle_impl.inc) is pinned by fresh recomputation of ||A x' - b||_inf for
  * the exchanged x', by Proposition 1 and Corollary 1 evaluated in rational arithmetic, and by
  * the A = I closed form.
+ * The l2 changes (l2_oracle_impl.inc) are pinned by fresh recomputation of ||A x' - b||_2^2 -
+ * ||A x - b||_2^2 on integer data (exact), by numpy for real data, and the selection rule by
+ * brute force over constructed ties.
  */
 #include <math.h>
 #include <stdint.h>
@@ -34,6 +37,7 @@
 #include "dmmv_oracle_impl.inc"
 #include "swap_oracle_impl.inc"
 #include "alns_oracle_impl.inc"
+#include "l2_oracle_impl.inc"
 #undef REAL
 #undef SFX
 #undef FMA
@@ -46,6 +50,7 @@
 #include "dmmv_oracle_impl.inc"
 #include "swap_oracle_impl.inc"
 #include "alns_oracle_impl.inc"
+#include "l2_oracle_impl.inc"
 #undef REAL
 #undef SFX
 #undef FMA

@@ -515,3 +515,74 @@ def apply_swap_dense(A, D, x, r, i, j, scale=1.0):
     A = np.asarray(A, dtype=np.asarray(D).dtype)
     rowptr, col, val = full_csr(A)
     return apply_swap_csr(A.shape[0], A.shape[1], rowptr, col, val, D, x, r, i, j, scale)
+
+
+# ------------------------------------------------------------------------------ l2 changes
+def l2_column_sums(m, n, rowptr, col, val, r):
+    """(g, c): g_j = a_j . r and c_j = ||a_j||^2, chains of fused multiply-adds by ascending row."""
+    dt = np.asarray(val).dtype
+    colptr, rowidx, cval = _csc_of(m, n, rowptr, col, val, dt)
+    r = np.ascontiguousarray(r, dtype=dt)
+    g = np.empty(max(n, 1), dtype=dt)
+    c = np.empty(max(n, 1), dtype=dt)
+    _fn("oracle_l2_column_sums", dt)(C.c_int64(n), _p(colptr), _p(rowidx), _p(cval), _p(r), _p(g), _p(c))
+    return g[:n], c[:n]
+
+
+def l2_changes_csr(m, n, rowptr, col, val, D, x, r, scale=1.0) -> np.ndarray:
+    """dq[j*nd + k] = ||r + delta a_j||^2 - ||r||^2 for every single-coordinate move."""
+    dt = np.asarray(D).dtype
+    D = np.ascontiguousarray(D)
+    colptr, rowidx, cval = _csc_of(m, n, rowptr, col, val, dt)
+    k = values_to_index(x, D)
+    r = np.ascontiguousarray(r, dtype=dt)
+    dq = np.empty(max(n * D.size, 1), dtype=dt)
+    _fn("oracle_l2_changes", dt)(C.c_int64(n), C.c_int32(D.size), _p(colptr), _p(rowidx), _p(cval), _p(D),
+                                 _real(dt)(scale), _p(k), _p(r), _p(dq))
+    return dq[:n * D.size]
+
+
+def l2_changes_dense(A, D, x, r, scale=1.0) -> np.ndarray:
+    A = np.asarray(A, dtype=np.asarray(D).dtype)
+    rowptr, col, val = full_csr(A)
+    return l2_changes_csr(A.shape[0], A.shape[1], rowptr, col, val, D, x, r, scale)
+
+
+def argmin_move_l2(scores, dq, rule=1):
+    """(flat index, score) of the best move: smallest score, then smallest dq, then lowest index;
+    rule 2 considers only candidates with dq <= 0."""
+    scores = np.ascontiguousarray(scores)
+    dq = np.ascontiguousarray(dq, dtype=scores.dtype)
+    c = C.c_int64(-1)
+    s = _real(scores.dtype)(0)
+    _fn("oracle_argmin_move_l2", scores.dtype)(C.c_int64(scores.size), _p(scores), _p(dq), C.c_int32(rule),
+                                               C.byref(c), C.byref(s))
+    return int(c.value), scores.dtype.type(s.value)
+
+
+def solve_l2_csr(m, n, rowptr, col, val, b, D, x0, iters, rule=1, scale=1.0, radius=0) -> SolveResult:
+    """The descent with the l2 change as second criterion (rule 1) or as a guard too (rule 2)."""
+    dt = np.asarray(D).dtype
+    rowptr = np.ascontiguousarray(rowptr, dtype=np.int64)
+    col = np.ascontiguousarray(col, dtype=np.int32)
+    val = np.ascontiguousarray(val, dtype=dt)
+    b = np.ascontiguousarray(b, dtype=dt)
+    D = np.ascontiguousarray(D)
+    k = values_to_index(x0, D)
+    it = max(int(iters), 1)
+    tj, tk = np.full(it, -1, dtype=np.int32), np.full(it, -1, dtype=np.int32)
+    tt = np.zeros(it, dtype=dt)
+    t = _real(dt)(0)
+    r = np.empty(max(m, 1), dtype=dt)
+    f = _fn("oracle_solve_l2", dt)
+    f.restype = C.c_int32
+    done = int(f(C.c_int64(m), C.c_int64(n), C.c_int32(D.size), _p(rowptr), _p(col), _p(val), _p(b), _p(D),
+                 _real(dt)(scale), _p(k), C.c_int32(iters), C.c_int32(radius), C.c_int32(rule), C.byref(t),
+                 _p(r), _p(tj), _p(tk), _p(tt)))
+    return SolveResult(D[k], dt.type(t.value), done, r[:m], tj[:done], tk[:done], tt[:done])
+
+
+def solve_l2_dense(A, b, D, x0, iters, rule=1, scale=1.0, radius=0) -> SolveResult:
+    A = np.asarray(A, dtype=np.asarray(D).dtype)
+    rowptr, col, val = full_csr(A)
+    return solve_l2_csr(A.shape[0], A.shape[1], rowptr, col, val, b, D, x0, iters, rule, scale, radius)

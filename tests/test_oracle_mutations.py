@@ -11,7 +11,8 @@ import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 ORACLE = os.path.join(ROOT, "oracle")
-PIN_TESTS = ["tests/test_oracle_pins.py", "tests/test_oracle_alns_pins.py", "tests/test_oracle_swap_pins.py"]
+PIN_TESTS = ["tests/test_oracle_pins.py", "tests/test_oracle_alns_pins.py", "tests/test_oracle_swap_pins.py",
+             "tests/test_oracle_l2_pins.py"]
 
 # (name, file, correct text, planted mistake)
 MUTANTS = [
@@ -91,6 +92,21 @@ MUTANTS = [
     ("default_destroy_count_rounds_down", "alns_common.inc", "const int64_t c = (n * 5 + 999) / 1000;",
      "const int64_t c = (n * 5) / 1000;"),
     ("vanishing_error_threshold", "alns_oracle_impl.inc", "if (!(t >= 0x1p-900)) {", "if (!(t >= 0x1p-800)) {"),
+    ("l2_cross_term_sign", "l2_oracle_impl.inc", "const REAL twog = (REAL)2 * g[j];", "const REAL twog = (REAL)-2 * g[j];"),
+    ("l2_square_term_dropped", "l2_oracle_impl.inc", "dq[j * nd + k] = delta * FMA(delta, csq[j], twog);", "dq[j * nd + k] = delta * twog;"),
+    ("l2_key_prefers_the_larger_change", "l2_oracle_impl.inc", "(scores[e] == s && dq[e] < q)", "(scores[e] == s && dq[e] > q)"),
+    ("l2_guard_ignored", "l2_oracle_impl.inc", "if (rule == 2 && !(dq[e] <= (REAL)0)) continue;", "if (0) continue;"),
+    ("l2_guard_drops_unchanged_norm", "l2_oracle_impl.inc", "if (rule == 2 && !(dq[e] <= (REAL)0)) continue;",
+     "if (rule == 2 && !(dq[e] < (REAL)0)) continue;"),
+    ("l2_changes_ignore_the_scale", "l2_oracle_impl.inc",
+     "            const REAL delta = SFX(delta_of)(D, kidx[j], k, sc);\n            const REAL twog",
+     "            const REAL delta = SFX(delta_of)(D, kidx[j], k, (REAL)1);\n            const REAL twog"),
+    ("l2_column_sum_reads_the_wrong_row", "l2_oracle_impl.inc", "acc = FMA(cval[e], r[rowidx[e]], acc);",
+     "acc = FMA(cval[e], r[e - colptr[j]], acc);"),
+    ("l2_descent_takes_plateau_moves", "l2_oracle_impl.inc",
+     "        if (c < 0 || !(s < t)) break;\n        const int64_t j = c / nd; const int32_t k = (int32_t)(c % nd);\n        const REAL delta = SFX(delta_of)(D, kidx[j], k, sc);\n        t = SFX(oracle_apply_move_csc)",
+     "        if (c < 0 || !(s <= t)) break;\n        const int64_t j = c / nd; const int32_t k = (int32_t)(c % nd);\n        const REAL delta = SFX(delta_of)(D, kidx[j], k, sc);\n        t = SFX(oracle_apply_move_csc)"),
+    ("l2_descent_scores_without_the_untouched_rows", "l2_oracle_impl.inc", "                        else v = FABS(r[i]);", "                        else v = (REAL)0;"),
 ]
 
 
