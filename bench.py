@@ -209,6 +209,7 @@ def run_config(idx: int, steps: int, warmup: int, iters_override, device: str, d
                 dmmv.dmmv_residual(h)
                 out["eval_matrix_core_ms"] = dmmv.dmmv_time_eval(h, 3) / 3
                 out["eval_vector_unit_ms"] = eval_ms
+        out["l2"] = l2_timing(inst, device, x0)
     if inst.kind == "csr":
         out["descent"] = descent_timing(inst, device, x0, iters)
     if inst.kind == "batched":
@@ -344,6 +345,33 @@ def alns_timing(inst, device: str, x0, **hopt) -> dict:
             "accepted": int(tr[:, 3].sum()), "local_search_moves": int(tr[:, 2].sum()),
             "worst_remove_used": int(tr[:, 0].sum()), "greedy_repair_used": int(tr[:, 1].sum()),
             "instances": int(inst.R), "max_t_best": float(res.t_best.cpu().max())}
+
+
+def l2_timing(inst, device: str, x0) -> dict:
+    """The l2 change of every candidate (options.l2_rule): G = X^T R_mat for the whole batch, on the
+    matrix cores with one row of the contraction per instruction (fp32), timed with events on the
+    library's stream; and one iteration of the descent with the l2 change as second criterion."""
+    import torch
+    from paper_2508_13437_amd import dmmv
+
+    flops = 2.0 * inst.m * inst.n * inst.R
+    with dmmv.from_instance(inst, device, l2_rule=1) as h:
+        dmmv.dmmv_set_x(h, x0)
+        dmmv.dmmv_residual(h)
+        ms = dmmv.dmmv_time_l2(h, 5) / 5
+        dmmv.dmmv_solve(h, x0, 1)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        dmmv.dmmv_solve(h, x0, 3)
+        torch.cuda.synchronize()
+        it_ms = (time.perf_counter() - t0) / 3 * 1e3
+    peak = 157.3
+    return {"kernel": "k_l2_g_mfma" if inst.dtype == np.float32 else "k_l2_g_batched", "flops": flops, "ms": ms,
+            "TFLOPs": flops / (ms * 1e-3) / 1e12, "peak_TFLOPs_fp32_matrix": peak,
+            "frac": flops / (ms * 1e-3) / 1e12 / peak,
+            "ms_per_iteration_with_l2_rule": it_ms,
+            "note": "ms_per_iteration_with_l2_rule: dmmv_solve with options.l2_rule = 1 (residual included, 3 "
+                    "iterations): score table written, G recomputed, arg-min over (score, l2 change, index)"}
 
 
 def residual_timing(inst, device: str, x0) -> dict:
@@ -553,6 +581,8 @@ def main():
     }
     if "residual" in head:
         line["residual"] = head["residual"]
+    if "l2" in head:
+        line["l2"] = head["l2"]
     for key in ("eval_matrix_core_ms", "eval_vector_unit_ms"):
         if key in head:
             line[key] = head[key]

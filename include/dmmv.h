@@ -153,6 +153,17 @@ typedef struct {
                                 partition, its maxima never leave the registers (every workgroup
                                 reads all of r: taken automatically when (n / 256) m w bytes do not
                                 exceed the matrix).  Same scores, records and moves either way    */
+    int32_t l2_rule;         /* the change of the squared l2 norm of the residual, dq = ||r + delta a_j||^2 -
+                                ||r||^2, beside the score (paper: the l-infinity and l2 changes of the
+                                candidates are evaluated together; the quantisation use case keeps the
+                                l2 norm from increasing).  0 = not used (default: lowest index among
+                                equal scores).  1 = second criterion of every arg-min of the handle
+                                (dmmv_argmin_move, dmmv_solve, the local search of dmmv_alns): smallest
+                                score, then smallest dq, then lowest index.  2 = the same among the
+                                candidates with dq <= 0 only, so that no move raises the l2 norm.
+                                3 = reserve the workspace of dmmv_l2_changes only.  With 1 and 2 the
+                                evaluation writes its whole score table every iteration (R n nd more
+                                elements of workspace) and options.prune / value_search do not apply  */
 } dmmv_options;
 
 /* Bytes of device workspace dmmv_create needs for this problem (0 on invalid input, with
@@ -288,6 +299,16 @@ typedef struct {
  * are [R][n], t_best_out [R], trace [R][iters][4], trace_t [R][iters][2]. */
 dmmv_status dmmv_alns(dmmv_handle h, const void* x0, const dmmv_alns_params* params, void* x_best_out,
                       void* t_best_out, int32_t* trace, void* trace_t);
+
+/* dq_out[q][j*nd + k] = change of the squared l2 norm of the residual under the move x_j -> D[k]
+ * (handles created with options.l2_rule != 0), in the fixed arithmetic
+ *     g_j = chain over the stored entries of column j by ascending row of fma(A_ij, r_i, .)
+ *     c_j = the same chain of fma(A_ij, A_ij, .)         dq = delta * fma(delta, c_j, 2 g_j)
+ * with delta the step of the score table.  For an fp32 batch G = X^T R_mat is computed on the matrix
+ * cores with one row of the contraction per instruction, which keeps that chain bit for bit.
+ * Needs a residual.
+ * Paper: section "GPU Acceleration" (l-infinity and l2 changes of the candidates); Appendix A. */
+dmmv_status dmmv_l2_changes(dmmv_handle h, void* dq_out);
 
 /* A swap: variables i and j exchange their values (x_i > x_j before).  i = -1: none. */
 typedef struct { int64_t i, j; } dmmv_swap;

@@ -21,6 +21,11 @@ extern "C" {
  * The state is not changed.  Needs a residual.  Waits for the stream. */
 dmmv_status dmmv_time_eval(dmmv_handle h, int32_t reps, float* ms_out);
 
+/* The same for the contraction g = A^T r behind dmmv_l2_changes (for a batch G = X^T R_mat, on the
+ * matrix cores for fp32): `reps` launches between two events after one untimed launch.  The handle
+ * must have been created with options.l2_rule != 0 and needs a residual.  Waits for the stream. */
+dmmv_status dmmv_time_l2(dmmv_handle h, int32_t reps, float* ms_out);
+
 #ifdef __cplusplus
 }
 #endif

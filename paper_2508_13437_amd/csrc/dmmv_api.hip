@@ -120,6 +120,11 @@ size_t workspace_layout(const dmmv_problem& p, const dmmv_options& o, Ctx* c, ch
         b.take(&c->alns_q2, (size_t)p.R * sizeof(double));
         b.take(&c->alns_q2_blocks, (size_t)(ceil_div(p.m, 256) + 1) * sizeof(double));
     }
+    if (o.l2_rule) {
+        b.take(&c->l2_g, (size_t)p.n * p.R * esz);
+        b.take(&c->l2_c, (size_t)p.n * esz);
+        if (o.l2_rule != 3) b.take(&c->l2_scores, (size_t)p.n * p.R * p.nd * esz);
+    }
     if (!sparse) {
         c->swap_nb = swap_blocks_per_instance(p);
         b.take(&c->swap_rows, (size_t)p.R * SWAP_KMAX * sizeof(int32_t));
@@ -518,7 +523,22 @@ static dmmv_status select_apply_any(Ctx* c, int32_t iters, dmmv_move* trace, voi
     return apply_any(c, true, iters, trace, trace_t);
 }
 
+// One step with the l2 change as second criterion: the evaluation writes the whole score table,
+// g = A^T r follows the residual, the selection reads both.  (The exact prunings drop candidates
+// that cannot win on the score alone, so they do not apply here.)
+static dmmv_status loop_step_l2(Ctx* c, int32_t iters, dmmv_move* trace, void* trace_t) {
+    if (c->p.n == 0) return DMMV_OK;
+    DMMV_TRY(eval_any(c, c->l2_scores, false, true));
+    DMMV_TRY(l2_update_g(c));
+    DMMV_TRY(l2_select(c, c->l2_scores, c->o.keep_going, nullptr, nullptr));
+    if (c->kind != KIND_CSC) return apply_any(c, true, iters, trace, trace_t);
+    DMMV_TRY(csc_apply(c));
+    DMMV_TRY(l2_after_apply_csc(c, iters, trace, trace_t));
+    return csc_reservoir(c);
+}
+
 static dmmv_status loop_step(Ctx* c, int32_t iters, dmmv_move* trace, void* trace_t) {
+    if (c->o.l2_rule == 1 || c->o.l2_rule == 2) return loop_step_l2(c, iters, trace, trace_t);
     if (batched_pruned_applicable(c)) return batched_descent_pruned(c, 1, iters, trace, trace_t);
     if (c->kind == KIND_CSC && c->o.prune && !c->o.keep_going && c->p.n > 0) {
         DMMV_TRY(csc_eval_pruned(c, true));
@@ -593,7 +613,8 @@ static dmmv_status solve_t(dmmv_ctx* c, const void* x0, int32_t iters, void* x_o
     // a batch drops its stopped instances at the polling points (their wavefronts would
     // otherwise keep running for the sake of a few neighbours), so it polls more often
     const bool pruned_batch = batched_pruned_applicable(c);
-    const bool compacting = c->kind == KIND_BATCHED && poll > 0 && !c->o.var_mask && !pruned_batch;
+    const bool l2_on = c->o.l2_rule == 1 || c->o.l2_rule == 2;
+    const bool compacting = c->kind == KIND_BATCHED && poll > 0 && !c->o.var_mask && !pruned_batch && !l2_on;
     if (compacting && poll > 8) poll = 8;
     dmmv_status loop_st = [&]() -> dmmv_status {
         // a pruned batch runs all its iterations in one launch; every instance stops by itself
@@ -694,6 +715,8 @@ static dmmv_status resolve_options(const dmmv_problem* problem, const dmmv_optio
         return fail(DMMV_ERR_SHAPE, "options: radius, poll_every and sparse_partition_rows must be >= 0");
     if (o.batched_eval < 0 || o.batched_eval > 2)
         return fail(DMMV_ERR_SHAPE, "options.batched_eval must be 0, 1 or 2");
+    if (o.l2_rule < 0 || o.l2_rule > 3)
+        return fail(DMMV_ERR_SHAPE, "options.l2_rule must be 0, 1, 2 or 3");
     if (o.sparse_eval < 0 || o.sparse_eval > 2)
         return fail(DMMV_ERR_SHAPE, "options.sparse_eval must be 0, 1 or 2");
     if (o.sparse_eval == 2 && problem->csr_rowptr) {
@@ -777,6 +800,7 @@ static dmmv_status ctx_setup(dmmv_ctx* c, const dmmv_problem* problem, const dmm
         if (c->csc_max_row > c->p.n) c->csc_max_row = (int32_t)c->p.n;   // duplicates are an error anyway
     }
     if (c->kind == KIND_BATCHED) DMMV_TRY(batched_build(c));
+    if (o.l2_rule) DMMV_TRY(l2_build(c));
     c->mfma_planes = 1;
     if (o.residual_mfma) {
         DMMV_TRY(batched_mfma_build(c));
@@ -925,6 +949,23 @@ dmmv_status dmmv_eval_moves(dmmv_handle h, void* scores_out) {
 dmmv_status dmmv_argmin_move(dmmv_handle h, const void* scores, dmmv_move* best, void* best_score) {
     if (!h) return fail(DMMV_ERR_NULL, "handle is NULL");
     if (!best && !best_score) return fail(DMMV_ERR_NULL, "best and best_score are both NULL");
+    const bool l2_on = h->o.l2_rule == 1 || h->o.l2_rule == 2;
+    if (l2_on) {
+        // the second criterion is a function of the current residual: the table given (or the
+        // evaluation made here) is reduced together with the l2 changes of the current state
+        if (!h->r_valid) return fail(DMMV_ERR_STATE, "dmmv_argmin_move with options.l2_rule needs a residual");
+        if (h->p.n == 0) {
+            if (best) DMMV_HIP_CHECK(hipMemsetAsync(best, 0xFF, (size_t)h->p.R * sizeof(dmmv_move), h->stream));
+            return DMMV_OK;
+        }
+        if (h->p.dtype == DMMV_F64)
+            hipLaunchKernelGGL(k_clear_done<double>, grid1(h->p.R, 256), dim3(256), 0, h->stream, (InstState<double>*)h->state, h->p.R);
+        else
+            hipLaunchKernelGGL(k_clear_done<float>, grid1(h->p.R, 256), dim3(256), 0, h->stream, (InstState<float>*)h->state, h->p.R);
+        if (!scores) DMMV_TRY(eval_any(h, h->l2_scores, false, false));
+        DMMV_TRY(l2_update_g(h));
+        return l2_select(h, scores ? scores : h->l2_scores, 1, best, best_score);
+    }
     if (scores) {
         const int64_t ntab = h->p.n * (int64_t)h->p.nd;
         if (h->p.dtype == DMMV_F64)
@@ -1019,6 +1060,15 @@ dmmv_status dmmv_alns(dmmv_handle h, const void* x0, const dmmv_alns_params* par
     return alns_run(h, x0, *params, x_best_out, t_best_out, trace, trace_t);
 }
 
+dmmv_status dmmv_l2_changes(dmmv_handle h, void* dq_out) {
+    if (!h) return fail(DMMV_ERR_NULL, "handle is NULL");
+    if (!dq_out && h->p.n > 0) return fail(DMMV_ERR_NULL, "dq_out is NULL");
+    if (!h->o.l2_rule) return fail(DMMV_ERR_STATE, "dmmv_l2_changes needs a handle created with options.l2_rule != 0 (workspace for g and the column norms)");
+    if (!h->r_valid) return fail(DMMV_ERR_STATE, "dmmv_l2_changes needs a residual (call dmmv_residual or dmmv_set_residual)");
+    DMMV_TRY(l2_update_g(h));
+    return l2_table(h, dq_out);
+}
+
 dmmv_status dmmv_swap_move(dmmv_handle h, int32_t k_eps, int32_t apply, dmmv_swap* best, void* best_t) {
     if (!h) return fail(DMMV_ERR_NULL, "dmmv_swap_move: handle is NULL");
     if (k_eps < 0) return fail(DMMV_ERR_SHAPE, "dmmv_swap_move: k_eps < 0");
@@ -1046,6 +1096,29 @@ dmmv_status dmmv_time_eval(dmmv_handle h, int32_t reps, float* ms_out) {
     if (st == DMMV_OK) {
         (void)hipEventRecord(e0, h->stream);
         for (int32_t q = 0; q < reps && st == DMMV_OK && h->p.n > 0; ++q) st = once();
+        (void)hipEventRecord(e1, h->stream);
+        hipError_t e = hipEventSynchronize(e1);
+        if (e != hipSuccess) st = fail(DMMV_ERR_HIP, "hipEventSynchronize failed: %s", hipGetErrorString(e));
+        else (void)hipEventElapsedTime(ms_out, e0, e1);
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    return st;
+}
+
+dmmv_status dmmv_time_l2(dmmv_handle h, int32_t reps, float* ms_out) {
+    if (!h) return fail(DMMV_ERR_NULL, "handle is NULL");
+    if (!ms_out) return fail(DMMV_ERR_NULL, "ms_out is NULL");
+    if (reps < 1) return fail(DMMV_ERR_SHAPE, "reps must be >= 1");
+    if (!h->o.l2_rule) return fail(DMMV_ERR_STATE, "dmmv_time_l2 needs a handle created with options.l2_rule != 0");
+    if (!h->r_valid) return fail(DMMV_ERR_STATE, "dmmv_time_l2 needs a residual");
+    hipEvent_t e0, e1;
+    DMMV_HIP_CHECK(hipEventCreate(&e0));
+    DMMV_HIP_CHECK(hipEventCreate(&e1));
+    dmmv_status st = l2_update_g(h);                       // warm-up launch, not timed
+    if (st == DMMV_OK) {
+        (void)hipEventRecord(e0, h->stream);
+        for (int32_t q = 0; q < reps && st == DMMV_OK; ++q) st = l2_update_g(h);
         (void)hipEventRecord(e1, h->stream);
         hipError_t e = hipEventSynchronize(e1);
         if (e != hipSuccess) st = fail(DMMV_ERR_HIP, "hipEventSynchronize failed: %s", hipGetErrorString(e));

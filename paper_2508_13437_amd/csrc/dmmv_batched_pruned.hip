@@ -361,6 +361,7 @@ dmmv_status descent_t(Ctx* c, int32_t steps, int32_t iters, dmmv_move* trace, vo
 
 bool batched_pruned_applicable(const Ctx* c) {
     if (c->kind != KIND_BATCHED || !c->o.prune || c->o.keep_going || c->cmp_on) return false;
+    if (c->o.l2_rule == 1 || c->o.l2_rule == 2) return false;      // a bound on the score alone does not order (score, l2 change)
     const int64_t m = c->p.m, n = c->p.n;
     if (n <= 0 || c->p.R > INT32_MAX) return false;
     if (m > (int64_t)BP_BLOCK * BP_MAX_RPT) return false;

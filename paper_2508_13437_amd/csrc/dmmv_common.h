@@ -161,6 +161,10 @@ struct Ctx {
     void* swap_part;          // Partial<T>[R][swap_nb]; sparse: one per evaluation workgroup
     int32_t* swap_skip;       // [R] 1: the last search of this ALNS iteration found no swap
     unsigned long long* swap_gbest;   // sparse: order bits of the best t' found so far by any workgroup
+    // l2 change of every candidate (options.l2_rule)
+    void* l2_g;           // T[n][R] g = A^T r of the current residual (instances contiguous)
+    void* l2_c;           // T[n] squared column norms
+    void* l2_scores;      // T[R][n*nd] score table the arg-min with the second criterion reads
     // batched evaluation on the matrix cores
     bool eval_mfma;       // the matrix-core kernel scores the moves
     void* rT;             // float[R][m64] instance-major copy of r, rows padded with zeros to a multiple of 64
@@ -221,6 +225,14 @@ dmmv_status swap_clear_skip(Ctx* c);
 dmmv_status swap_move(Ctx* c, int32_t k_eps, int32_t apply, bool use_skip, dmmv_swap* best, void* best_t);
 int64_t swap_csc_records(const dmmv_problem& p);
 dmmv_status swap_move_csc(Ctx* c, int32_t apply, bool use_skip, dmmv_swap* best, void* best_t);
+
+dmmv_status l2_build(Ctx* c);            // squared column norms, once per handle
+dmmv_status l2_update_g(Ctx* c);         // g = A^T r for the current residual
+dmmv_status l2_table(Ctx* c, void* dq_out);
+// arg-min of a score table [R][n*nd] with the l2 change as second criterion (options.l2_rule 1, 2);
+// stages the move in the loop state like the other selection kernels
+dmmv_status l2_select(Ctx* c, const void* scores, int32_t keep_going, dmmv_move* best_out, void* best_score_out);
+dmmv_status l2_after_apply_csc(Ctx* c, int32_t iters, dmmv_move* trace, void* trace_t);
 
 dmmv_status csc_build(Ctx* c);
 dmmv_status csc_residual(Ctx* c);

@@ -27,7 +27,8 @@ STATUS_NAMES = {0: "DMMV_OK", -1: "DMMV_ERR_NULL", -2: "DMMV_ERR_SHAPE", -3: "DM
 EXPORTS = ("dmmv_workspace_bytes", "dmmv_create", "dmmv_destroy", "dmmv_set_x",
            "dmmv_set_residual", "dmmv_residual", "dmmv_eval_moves", "dmmv_argmin_move",
            "dmmv_apply_move", "dmmv_get_state", "dmmv_solve", "dmmv_solve_static", "dmmv_alns", "dmmv_swap_move",
-           "dmmv_time_eval",
+           "dmmv_l2_changes",
+           "dmmv_time_eval", "dmmv_time_l2",
            "dmmv_last_error",
            "dmmv_version")
 
@@ -49,7 +50,8 @@ class Options(C.Structure):
     _fields_ = [("radius", C.c_int32), ("keep_going", C.c_int32), ("poll_every", C.c_int32),
                 ("sparse_partition_rows", C.c_int32), ("var_mask", C.c_void_p),
                 ("residual_mfma", C.c_int32), ("prune", C.c_int32), ("alns", C.c_int32),
-                ("value_search", C.c_int32), ("batched_eval", C.c_int32), ("sparse_eval", C.c_int32)]
+                ("value_search", C.c_int32), ("batched_eval", C.c_int32), ("sparse_eval", C.c_int32),
+                ("l2_rule", C.c_int32)]
 
 
 class AlnsParams(C.Structure):
@@ -81,7 +83,7 @@ def load() -> C.CDLL:
     lib.dmmv_destroy.argtypes = [C.c_void_p]
     for name, nargs in (("dmmv_set_x", 2), ("dmmv_set_residual", 2), ("dmmv_residual", 2),
                         ("dmmv_eval_moves", 2), ("dmmv_argmin_move", 4), ("dmmv_apply_move", 2),
-                        ("dmmv_get_state", 4)):
+                        ("dmmv_get_state", 4), ("dmmv_l2_changes", 2)):
         fn = getattr(lib, name)
         fn.restype = C.c_int
         fn.argtypes = [C.c_void_p] * nargs
@@ -98,6 +100,8 @@ def load() -> C.CDLL:
     lib.dmmv_swap_move.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
     lib.dmmv_time_eval.restype = C.c_int
     lib.dmmv_time_eval.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_float)]
+    lib.dmmv_time_l2.restype = C.c_int
+    lib.dmmv_time_l2.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_float)]
     lib.dmmv_last_error.restype = C.c_char_p
     lib.dmmv_version.restype = C.c_char_p
     _lib = lib
@@ -137,6 +141,7 @@ class Handle:
                  keep_going: bool = False, poll_every: int = 64, var_mask=None,
                  sparse_partition_rows: int = 0, residual_mfma: bool = False, prune: bool = False,
                  alns: bool = False, value_search: bool = False, batched_eval: int = 0, sparse_eval: int = 0,
+                 l2_rule: int = 0,
                  stream: Optional[torch.cuda.Stream] = None, device=None, _create: bool = True):
         lib = load()
         self._h = C.c_void_p(None)
@@ -194,6 +199,7 @@ class Handle:
         o.alns = int(bool(alns))
         o.batched_eval = int(batched_eval)
         o.sparse_eval = int(sparse_eval)
+        o.l2_rule = int(l2_rule)
         o.value_search = int(bool(value_search))
         if var_mask is not None:
             var_mask = var_mask.to(torch.uint8).contiguous()
@@ -290,6 +296,15 @@ def dmmv_eval_moves(h: Handle) -> torch.Tensor:
     scores = h._new(shape)
     _check(load().dmmv_eval_moves(h._h, _ptr(scores)))
     return scores
+
+
+def dmmv_l2_changes(h: Handle) -> torch.Tensor:
+    """Change of the squared l2 norm of the residual under every move, [R][n*nd] (handles created
+    with l2_rule != 0)."""
+    shape = (h.R, h.n * h.nd) if h.batched else (h.n * h.nd,)
+    dq = h._new(shape)
+    _check(load().dmmv_l2_changes(h._h, _ptr(dq)))
+    return dq
 
 
 def dmmv_argmin_move(h: Handle, scores: Optional[torch.Tensor] = None):
@@ -418,6 +433,13 @@ def dmmv_time_eval(h: Handle, reps: int) -> float:
     """Milliseconds for `reps` back-to-back launches of the fused evaluation kernel."""
     ms = C.c_float(0.0)
     _check(load().dmmv_time_eval(h._h, C.c_int32(reps), C.byref(ms)))
+    return float(ms.value)
+
+
+def dmmv_time_l2(h: Handle, reps: int) -> float:
+    """Milliseconds for `reps` back-to-back launches of the contraction g = A^T r (l2 changes)."""
+    ms = C.c_float(0.0)
+    _check(load().dmmv_time_l2(h._h, C.c_int32(reps), C.byref(ms)))
     return float(ms.value)
 
 
