@@ -210,6 +210,8 @@ def run_config(idx: int, steps: int, warmup: int, iters_override, device: str, d
                 out["eval_matrix_core_ms"] = dmmv.dmmv_time_eval(h, 3) / 3
                 out["eval_vector_unit_ms"] = eval_ms
         out["l2"] = l2_timing(inst, device, x0)
+    if inst.kind == "dense":
+        out["descent"] = descent_timing_dense(inst, device, iters)
     if inst.kind == "csr":
         out["descent"] = descent_timing(inst, device, x0, iters)
     if inst.kind == "batched":
@@ -220,6 +222,8 @@ def run_config(idx: int, steps: int, warmup: int, iters_override, device: str, d
     if inst.kind == "dense":
         # same loop, the local search finding each variable's best value by bisection over D
         out["alns_value_search"] = alns_timing(inst, device, x0, value_search=True)
+        # and with the pruned local search, one launch per outer iteration (small instances only)
+        out["alns_pruned_local_search"] = alns_timing(inst, device, x0, prune=True)
     out["swap"] = swap_timing(inst, device, x0, iters)
     if do_cpu:
         out["cpu_baseline"] = cpu_baseline(inst, cpu_budget)
@@ -268,6 +272,34 @@ def descent_timing(inst, device: str, x0, iters: int) -> dict:
         res[key] = {"ms": dt * 1e3, "moves_applied": moves, "final_max_violation": float(out.max_violation.cpu()[0])}
     res["note"] = ("wall time of dmmv_solve until the local optimum; the host polls every 64 iterations, "
                    "so up to 63 iterations past the last move are enqueued")
+    return res
+
+
+def descent_timing_dense(inst, device: str, iters: int) -> dict:
+    """The real descent of a dense single instance from a seeded RANDOM starting point (the
+    configured one is a local optimum already): the loop of launches with the full evaluation, and
+    options.prune, which runs every iteration inside one workgroup and one launch (bounds on 16 rows,
+    full scores best-first) and applies the same moves.  An EFFECTIVE rate, apart from `value`."""
+    import torch
+    from paper_2508_13437_amd import dmmv
+
+    x0 = torch.from_numpy(np.random.default_rng(7).choice(inst.D, size=inst.n)).to(device)
+    res = {}
+    for key, opt in (("full", {}), ("pruned_one_launch", {"prune": True})):
+        with dmmv.from_instance(inst, device, poll_every=64, **opt) as h:
+            dmmv.dmmv_solve(h, x0, iters)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            out = dmmv.dmmv_solve(h, x0, iters)
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t0
+        moves = int(out.iters_done.cpu()[0])
+        res[key] = {"ms": dt * 1e3, "moves_applied": moves, "us_per_move": dt * 1e6 / max(moves, 1),
+                    "final_max_violation": float(out.max_violation.cpu()[0])}
+    res["same_moves_and_error"] = (res["full"]["moves_applied"] == res["pruned_one_launch"]["moves_applied"] and
+                                   res["full"]["final_max_violation"] == res["pruned_one_launch"]["final_max_violation"])
+    res["note"] = ("wall time of dmmv_solve from a random starting point until the local optimum or the configured "
+                   "iteration count; full: the host polls every 64 iterations")
     return res
 
 
@@ -592,6 +624,8 @@ def main():
         line["alns"] = head["alns"]
     if "alns_value_search" in head:
         line["alns_value_search"] = head["alns_value_search"]
+    if "alns_pruned_local_search" in head:
+        line["alns_pruned_local_search"] = head["alns_pruned_local_search"]
     if "alns_full_evaluation" in head:
         line["alns_full_evaluation"] = head["alns_full_evaluation"]
     if "swap" in head:

@@ -124,7 +124,11 @@ typedef struct {
                                 beat the best score found; same moves again, all iterations of a
                                 call in one launch (used when the instance's r and x fit in
                                 96 KiB of LDS: (m + n) w + 2 n bytes, 4 n if nd > 256, and
-                                m <= 16384; otherwise the full evaluation runs).  Dense single instances ignore it.
+                                m <= 16384; otherwise the full evaluation runs).  A dense single instance is
+                                taken as a batch of one (one workgroup, all iterations in one launch)
+                                when it is small - at most 64 levels and 2^24 (row, move) pairs per
+                                table - so that a launch per step costs more than the step; larger
+                                dense instances keep the chip-wide full evaluation.
                                 dmmv_eval_moves and dmmv_argmin_move always score all             */
     int32_t alns;            /* batched problems: 1 = reserve the workspace dmmv_alns needs (current
                                 and best solution, sampling weights and draws per instance, about

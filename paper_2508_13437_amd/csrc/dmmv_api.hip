@@ -191,6 +191,7 @@ size_t workspace_layout(const dmmv_problem& p, const dmmv_options& o, Ctx* c, ch
         c->n_partials = dense_num_partials(p);
         b.take(&c->partials, (size_t)(c->n_partials > 0 ? c->n_partials : 1) * part_sz);
         if (o.value_search) b.take(&c->search_part, (size_t)(p.n > 0 ? p.n : 1) * part_sz);
+        if (o.prune) b.take(&c->Xt, (size_t)p.m * p.n * esz);     // the pruned descent reads rows of A
     }
     return (b.off + 255) / 256 * 256;
 }
@@ -800,6 +801,7 @@ static dmmv_status ctx_setup(dmmv_ctx* c, const dmmv_problem* problem, const dmm
         if (c->csc_max_row > c->p.n) c->csc_max_row = (int32_t)c->p.n;   // duplicates are an error anyway
     }
     if (c->kind == KIND_BATCHED) DMMV_TRY(batched_build(c));
+    if (c->kind == KIND_DENSE && o.prune) DMMV_TRY(batched_build_xt(c));
     if (o.l2_rule) DMMV_TRY(l2_build(c));
     c->mfma_planes = 1;
     if (o.residual_mfma) {
@@ -889,7 +891,7 @@ dmmv_status dmmv_solve_static(const dmmv_problem* problem, const dmmv_options* o
                     "(use dmmv_create with a workspace of your own)", need, (size_t)DMMV_STATIC_SCRATCH_BYTES);
     void* ws = nullptr;
     DMMV_TRY(scratch_of_current_device(&ws));
-    dmmv_ctx c;                                            // on the stack: nothing is allocated
+    dmmv_ctx c{};                                          // on the stack: nothing is allocated
     DMMV_TRY(ctx_setup(&c, problem, o, ws, (hipStream_t)hip_stream));
     const dmmv_status st = dmmv_solve(&c, x0, iters, x_out, max_violation_out, iters_done, trace, trace_t);
     if (st != DMMV_OK) (void)hipStreamSynchronize(c.stream);   // nothing of this call may still use the scratch

@@ -602,6 +602,17 @@ dmmv_status batched_compact_end(Ctx* c) {
     return st;
 }
 
+// row-major copy of a column-major matrix alone (a dense single instance that uses the batch's
+// pruned descent needs nothing else of the batched layouts)
+dmmv_status batched_build_xt(Ctx* c) {
+    if (c->p.dtype == DMMV_F64)
+        launch_transpose<double>(c->stream, (const double*)c->p.A_dense, c->p.n, c->p.m, c->p.lda, (double*)c->Xt, c->p.n);
+    else
+        launch_transpose<float>(c->stream, (const float*)c->p.A_dense, c->p.n, c->p.m, c->p.lda, (float*)c->Xt, c->p.n);
+    DMMV_LAUNCH_CHECK();
+    return DMMV_OK;
+}
+
 dmmv_status batched_build(Ctx* c) {
     if (c->eval_mfma) DMMV_TRY(batched_eval_mfma_build(c));
     return c->p.dtype == DMMV_F64 ? build_t<double>(c) : build_t<float>(c);

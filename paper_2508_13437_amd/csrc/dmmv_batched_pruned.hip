@@ -360,7 +360,15 @@ dmmv_status descent_t(Ctx* c, int32_t steps, int32_t iters, dmmv_move* trace, vo
 }  // namespace
 
 bool batched_pruned_applicable(const Ctx* c) {
-    if (c->kind != KIND_BATCHED || !c->o.prune || c->o.keep_going || c->cmp_on) return false;
+    // a batch, or a dense single instance (a batch of one: r [m][1], x [n][1], scale 1, with the
+    // row-major copy of A that dmmv_create makes for options.prune)
+    // - only a small one: one workgroup scores it, so a table of more than 2^24 pairs, or more than
+    // 64 levels per variable (a thread walks the levels of its variable), is left to the chip-wide
+    // full evaluation
+    const bool small_dense = c->kind == KIND_DENSE && c->Xt != nullptr && c->p.nd <= 64 &&
+                             c->p.m * c->p.n * (int64_t)c->p.nd <= ((int64_t)1 << 24);
+    const bool kind_ok = c->kind == KIND_BATCHED || small_dense;
+    if (!kind_ok || !c->o.prune || c->o.keep_going || c->cmp_on) return false;
     if (c->o.l2_rule == 1 || c->o.l2_rule == 2) return false;      // a bound on the score alone does not order (score, l2 change)
     const int64_t m = c->p.m, n = c->p.n;
     if (n <= 0 || c->p.R > INT32_MAX) return false;

@@ -247,6 +247,7 @@ int64_t batched_eval_mfma_rt_elems(const dmmv_problem& p);
 dmmv_status batched_eval_mfma_build(Ctx* c);
 dmmv_status batched_eval_mfma(Ctx* c, void* scores_out, bool want_partials);
 dmmv_status batched_build(Ctx* c);
+dmmv_status batched_build_xt(Ctx* c);    // the row-major copy of X only
 dmmv_status batched_residual(Ctx* c);
 dmmv_status batched_eval(Ctx* c, void* scores_out, bool want_partials);
 dmmv_status batched_apply(Ctx* c, bool t_from_score, int32_t iters, dmmv_move* trace, void* trace_t);

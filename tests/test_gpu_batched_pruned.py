@@ -137,3 +137,55 @@ def test_pruned_descent_of_the_full_size_layer_follows_the_oracle_to_the_local_o
     assert np.array_equal(tt[sel], o.trace_t)
     assert np.array_equal(x[sel], o.x) and np.array_equal(t[sel], o.t)
     assert o.iters_done.min() >= 10
+
+
+# ---- a dense single instance as a batch of one ----------------------------------------------------
+def dense_pruned_check(inst, iters, **opt):
+    """dmmv_solve with options.prune on a dense single instance (one workgroup, all iterations in one
+    launch) against the oracle's full enumeration: traces, x, residual, error, bit for bit."""
+    from test_gpu_parity import check_single_trace, oracle_solve
+    m = dmmv()
+    hopt = dict(opt)
+    if "var_mask" in hopt:
+        hopt["var_mask"] = T(hopt["var_mask"])
+    with m.from_instance(inst, DEV, prune=True, **hopt) as h:
+        res = m.dmmv_solve(h, T(inst.x0), iters, trace=True)
+        x, r, t = m.dmmv_get_state(h)
+        o = oracle_solve(inst, iters, **opt)
+        check_single_trace(res, o, iters)
+        assert np.array_equal(N(r), o.r) and N(t)[0] == o.t
+        # the handle still serves the other entry points (full table, standalone arg-min)
+        want = orc.eval_moves_dense(inst.A, inst.D, o.x, o.r, **{k: v for k, v in opt.items() if k in ("radius", "var_mask")})
+        assert np.array_equal(N(m.dmmv_eval_moves(h)), want)
+    return o.iters_done
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_pruned_dense_single_instance(dtype):
+    from workloads import random_dense
+    moved = 0
+    for shape in [(1, 1, 2), (5, 3, 2), (65, 5, 5), (257, 13, 9), (300, 40, 16), (1000, 6, 37), (130, 4, 300), (700, 48, 16)]:
+        print("pruned dense case", shape, dtype, flush=True)
+        moved += dense_pruned_check(random_dense(9600 + shape[0], *shape, dtype=dtype), 60)
+    for seed in range(3):
+        moved += dense_pruned_check(random_dense(9650 + seed, 37, 11, 5, dtype=dtype, integer=True), 40)
+    inst = random_dense(9660, 90, 17, 9, dtype=dtype)
+    vm = (np.random.default_rng(3).uniform(size=inst.n) < 0.5).astype(np.uint8)
+    for radius in (1, 2):
+        moved += dense_pruned_check(inst, 30, radius=radius, var_mask=vm)
+    assert moved > 100
+
+
+def test_pruned_dense_configs_and_outer_loop():
+    from test_gpu_alns import alns_check
+    from workloads import random_dense
+    dense_pruned_check(make_config(1), 50)
+    dense_pruned_check(make_config(2, "small"), 80)
+    dense_pruned_check(make_config(2), 20)
+    # from a poor starting point the toy workload has a long descent
+    inst = make_config(1)
+    inst.x0 = np.random.default_rng(11).choice(inst.D, size=inst.n)
+    assert dense_pruned_check(inst, 200) > 30
+    # the local search of the outer loop in one launch per outer iteration
+    alns_check(random_dense(9670, 60, 30, 5), 12, ls_moves=4, destroy_count=4, seed=5, prune=1)
+    alns_check(make_config(1), 10, ls_moves=8, seed=6, prune=1)
