@@ -171,7 +171,7 @@ struct Ctx {
     // batched residual on the matrix cores (options.residual_mfma)
     void* Xp;             // bf16[3][m][mfma_ldk] planes whose sum is X
     void* Qt;             // bf16[R][mfma_ldk] current codes D[k_j] per instance
-    int64_t mfma_ldk;     // n rounded up to the K step, zero-filled
+    int64_t mfma_ldk;     // row stride of Xp and Qt: n rounded up to an odd number of K steps, zero-filled
     int32_t mfma_planes;  // bit s set: plane s of Xp is not all zero (bit 0 always)
 };
 

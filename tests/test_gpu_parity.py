@@ -650,7 +650,9 @@ def mfma_residual_check(inst):
 
 
 @pytest.mark.parametrize("shape", [(1, 1, 1, 2), (17, 5, 3, 3), (64, 64, 64, 4), (100, 33, 65, 8),
-                                   (130, 70, 130, 16), (257, 129, 200, 16), (300, 200, 129, 8)])
+                                   (130, 70, 130, 16), (257, 129, 200, 16), (300, 200, 129, 8),
+                                   # several 256 x 256 tiles: a ragged band of row tiles, more tiles than XCDs
+                                   (520, 100, 515, 4), (1100, 70, 300, 3), (256, 64, 2305, 2)])
 def test_batched_mfma_residual_random(shape):
     mm, nn, R, nd = shape
     print("mfma residual", shape, flush=True)
