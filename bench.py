@@ -186,11 +186,12 @@ def run_config(idx: int, steps: int, warmup: int, iters_override, device: str, d
         dt = time.perf_counter() - t0
         reps = max(3, min(200, int(0.5 / max(dt / (steps * iters), 1e-6))))
         eval_ms = dmmv.dmmv_time_eval(h, reps) / reps
+        loop = "all iterations in one launch" if dmmv.dmmv_loop_in_use(h) == 2 else "launches per iteration"
         cold_ms = cold_eval_ms(h, device) if inst.kind == "csr" else None
     moves = float(steps) * iters * inst.moves_per_iter()
     out.update({
         "workload": inst.name, "kind": inst.kind, "m": inst.m, "n": inst.n, "nd": inst.nd,
-        "R": inst.R, "nnz": inst.nnz, "iters_per_step": iters,
+        "R": inst.R, "nnz": inst.nnz, "iters_per_step": iters, "loop": loop,
         "moves_per_sec": moves / dt, "iters_per_sec": steps * iters / dt,
         "instance_iters_per_sec": steps * iters * inst.R / dt,
         "ms_per_step": dt / steps * 1e3, "us_per_iter": dt / (steps * iters) * 1e6,
@@ -276,16 +277,42 @@ def descent_timing(inst, device: str, x0, iters: int) -> dict:
 
 
 def descent_timing_dense(inst, device: str, iters: int) -> dict:
-    """The real descent of a dense single instance from a seeded RANDOM starting point (the
-    configured one is a local optimum already): the loop of launches with the full evaluation, and
-    options.prune, which runs every iteration inside one workgroup and one launch (bounds on 16 rows,
-    full scores best-first) and applies the same moves.  An EFFECTIVE rate, apart from `value`."""
+    """A dense single instance, three ways to iterate, the same moves from each: a launch of the
+    evaluation and one of selection + apply per iteration (options.dense_loop = 1); all iterations
+    in one launch of a fixed grid of workgroups that exchange one arg-min record per iteration
+    (dense_loop = 2, when the instance fits); options.prune, one workgroup and one launch (bounds on
+    16 rows, full scores best-first; small instances).  Two figures each: the time per iteration in
+    fixed-work mode (every iteration scores all moves, nothing improves at the configured start),
+    and the wall time of the real descent from a seeded RANDOM starting point (the configured one is
+    a local optimum already).  EFFECTIVE rates, apart from `value`."""
     import torch
     from paper_2508_13437_amd import dmmv
 
+    x_cfg = torch.from_numpy(np.ascontiguousarray(inst.x0)).to(device)
     x0 = torch.from_numpy(np.random.default_rng(7).choice(inst.D, size=inst.n)).to(device)
     res = {}
-    for key, opt in (("full", {}), ("pruned_one_launch", {"prune": True})):
+    for key, opt in (("launch_per_step", {"dense_loop": 1}), ("one_launch", {"dense_loop": 2}),
+                     ("pruned_one_launch", {"prune": True})):
+        try:
+            h_fixed = dmmv.from_instance(inst, device, keep_going=True, poll_every=0, **opt)
+        except dmmv.DmmvError as e:
+            res[key] = {"skipped": str(e)}
+            continue
+        entry = {}
+        if key != "pruned_one_launch":          # the pruned descent has no fixed-work mode: it stops by itself
+            with h_fixed as h:
+                fixed = []
+                for n_it in (200, 2200):
+                    dmmv.dmmv_solve(h, x_cfg, n_it)
+                    torch.cuda.synchronize()
+                    t0 = time.perf_counter()
+                    dmmv.dmmv_solve(h, x_cfg, n_it)
+                    torch.cuda.synchronize()
+                    fixed.append(time.perf_counter() - t0)
+                entry["fixed_work_us_per_iter"] = (fixed[1] - fixed[0]) / 2000 * 1e6
+                entry["fixed_work_iters_per_sec"] = 2000 / (fixed[1] - fixed[0])
+        else:
+            h_fixed.close()
         with dmmv.from_instance(inst, device, poll_every=64, **opt) as h:
             dmmv.dmmv_solve(h, x0, iters)
             torch.cuda.synchronize()
@@ -294,12 +321,16 @@ def descent_timing_dense(inst, device: str, iters: int) -> dict:
             torch.cuda.synchronize()
             dt = time.perf_counter() - t0
         moves = int(out.iters_done.cpu()[0])
-        res[key] = {"ms": dt * 1e3, "moves_applied": moves, "us_per_move": dt * 1e6 / max(moves, 1),
-                    "final_max_violation": float(out.max_violation.cpu()[0])}
-    res["same_moves_and_error"] = (res["full"]["moves_applied"] == res["pruned_one_launch"]["moves_applied"] and
-                                   res["full"]["final_max_violation"] == res["pruned_one_launch"]["final_max_violation"])
-    res["note"] = ("wall time of dmmv_solve from a random starting point until the local optimum or the configured "
-                   "iteration count; full: the host polls every 64 iterations")
+        entry.update({"descent_ms": dt * 1e3, "moves_applied": moves, "us_per_move": dt * 1e6 / max(moves, 1),
+                      "final_max_violation": float(out.max_violation.cpu()[0])})
+        res[key] = entry
+    ran = [v for v in res.values() if "moves_applied" in v]
+    res["same_moves_and_error"] = all(v["moves_applied"] == ran[0]["moves_applied"] and
+                                      v["final_max_violation"] == ran[0]["final_max_violation"] for v in ran)
+    res["note"] = ("fixed_work: time of 2000 further iterations inside one dmmv_solve call (a 2200-iteration call "
+                   "minus a 200-iteration call); descent: wall time of dmmv_solve from a random starting point until "
+                   "the local optimum or the configured iteration count (launch_per_step: the host polls every 64 "
+                   "iterations)")
     return res
 
 
@@ -605,7 +636,7 @@ def main():
         "vs_baseline": None, "dtype": head["dtype"], "data": "synthetic",
         "config": {"workload": head["workload"], "m": head["m"], "n": head["n"], "nd": head["nd"],
                    "R": head["R"], "nnz": head["nnz"], "iters_per_step": head["iters_per_step"],
-                   "mode": "fixed-work (keep_going): every iteration scores all moves"},
+                   "mode": "fixed-work (keep_going): every iteration scores all moves", "loop": head["loop"]},
         "iters_per_sec": head["iters_per_sec"], "us_per_iter": head["us_per_iter"],
         "improving_moves_applied": head["improving_moves_applied"],
         "final_max_violation": head["final_max_violation"],

@@ -168,6 +168,23 @@ typedef struct {
                                 3 = reserve the workspace of dmmv_l2_changes only.  With 1 and 2 the
                                 evaluation writes its whole score table every iteration (R n nd more
                                 elements of workspace) and options.prune / value_search do not apply  */
+    int32_t dense_loop;      /* one dense instance: how dmmv_solve iterates (paper: the iteration is not to
+                                pay for host-side stepping and synchronisation).  1 = a launch of the
+                                evaluation and one of selection + apply per iteration.  2 = all
+                                iterations in ONE launch: a fixed grid of at most 256 workgroups shares
+                                the moves, each keeps r, its columns of A, D and x in LDS, and they
+                                exchange one arg-min record per iteration through memory (needs r, D, x
+                                and one column to fit 156 KiB of LDS; dmmv_create fails with
+                                DMMV_ERR_UNSUPPORTED otherwise).  0 = automatic: 2 when the instance is
+                                so small that the launches would dominate an iteration, else 1.  Same
+                                scores, moves, traces and residual either way.  With 2 the workgroups
+                                wait for one another, so all must be resident on the device at once;
+                                if another kernel keeps some from starting, the wait ends after
+                                wait_limit polls and dmmv_solve returns DMMV_ERR_STATE with the handle
+                                still at its starting point.  options.prune and value_search (without
+                                keep_going) and l2_rule 1 / 2 keep their own loops                    */
+    int32_t wait_limit;      /* dense_loop = 2: polls of another workgroup's arrival word before the
+                                kernel gives up; 0 = default (2^22, a few seconds)                    */
 } dmmv_options;
 
 /* Bytes of device workspace dmmv_create needs for this problem (0 on invalid input, with

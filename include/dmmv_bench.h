@@ -26,6 +26,12 @@ dmmv_status dmmv_time_eval(dmmv_handle h, int32_t reps, float* ms_out);
  * must have been created with options.l2_rule != 0 and needs a residual.  Waits for the stream. */
 dmmv_status dmmv_time_l2(dmmv_handle h, int32_t reps, float* ms_out);
 
+/* Which loop dmmv_solve runs on this handle: 1 = launches per iteration, 2 = all iterations in one
+ * launch (options.dense_loop, resolved: the automatic choice depends on the instance and on the
+ * device's number of compute units; a handle on a batch with options.prune in effect also
+ * answers 2).  HOST query, no GPU work. */
+int32_t dmmv_loop_in_use(dmmv_handle h);
+
 #ifdef __cplusplus
 }
 #endif

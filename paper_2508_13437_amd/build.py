@@ -10,7 +10,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libdmmv.so")
 SOURCES = ["dmmv_api.hip", "dmmv_dense.hip", "dmmv_dense_search.hip", "dmmv_sparse.hip", "dmmv_sparse_eval.hip",
-           "dmmv_batched.hip", "dmmv_batched_pruned.hip", "dmmv_batched_mfma.hip", "dmmv_batched_eval_mfma.hip", "dmmv_alns.hip", "dmmv_swap.hip", "dmmv_swap_sparse.hip", "dmmv_l2.hip"]
+           "dmmv_batched.hip", "dmmv_batched_pruned.hip", "dmmv_batched_mfma.hip", "dmmv_batched_eval_mfma.hip", "dmmv_alns.hip", "dmmv_swap.hip", "dmmv_swap_sparse.hip", "dmmv_l2.hip", "dmmv_dense_persistent.hip"]
 HEADERS = [os.path.join(CSRC, "dmmv_common.h"), os.path.join(CSRC, "dmmv_sparse_common.h"),
            os.path.join(CSRC, "dmmv_alns_common.h"),
            os.path.join(os.path.dirname(HERE), "include", "dmmv.h"),

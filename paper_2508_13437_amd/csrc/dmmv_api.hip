@@ -125,6 +125,7 @@ size_t workspace_layout(const dmmv_problem& p, const dmmv_options& o, Ctx* c, ch
         b.take(&c->l2_c, (size_t)p.n * esz);
         if (o.l2_rule != 3) b.take(&c->l2_scores, (size_t)p.n * p.R * p.nd * esz);
     }
+    if (!sparse && !batched) b.take(&c->persist_exchange, dense_persistent_exchange_bytes());
     if (!sparse) {
         c->swap_nb = swap_blocks_per_instance(p);
         b.take(&c->swap_rows, (size_t)p.R * SWAP_KMAX * sizeof(int32_t));
@@ -587,6 +588,9 @@ static dmmv_status check_device_errors(Ctx* c) {
         if (host_flag & ERRBIT_CSR_RANGE) return fail(DMMV_ERR_SHAPE, "CSR column index out of range or row pointers not ascending");
         if (host_flag & ERRBIT_CSR_DUP) return fail(DMMV_ERR_SHAPE, "CSR matrix stores the same (row, column) entry twice");
         if (host_flag & ERRBIT_MOVE_RANGE) return fail(DMMV_ERR_SHAPE, "move with j >= n or k outside [0, nd)");
+        if (host_flag & ERRBIT_WAIT_LIMIT)
+            return fail(DMMV_ERR_STATE, "one-launch descent: a workgroup waited options.wait_limit polls for another one "
+                        "(is another kernel holding compute units?); the state is that of the starting point");
         return fail(DMMV_ERR_STATE, "device error flag %d", host_flag);
     }
     return DMMV_OK;
@@ -620,6 +624,11 @@ static dmmv_status solve_t(dmmv_ctx* c, const void* x0, int32_t iters, void* x_o
     dmmv_status loop_st = [&]() -> dmmv_status {
         // a pruned batch runs all its iterations in one launch; every instance stops by itself
         if (pruned_batch) return batched_descent_pruned(c, iters, iters, trace, trace_t);
+        // a small dense instance too; the wait between its workgroups is bounded and reports here
+        if (iters > 0 && dense_persistent_applicable(c)) {
+            DMMV_TRY(dense_descent_persistent(c, iters, trace, trace_t));
+            return check_device_errors(c);
+        }
         for (int32_t it = 0; it < iters; ++it) {
             DMMV_TRY(loop_step(c, iters, trace, trace_t));
             if (poll > 0 && (it + 1) % poll == 0 && it + 1 < iters) {
@@ -720,6 +729,11 @@ static dmmv_status resolve_options(const dmmv_problem* problem, const dmmv_optio
         return fail(DMMV_ERR_SHAPE, "options.l2_rule must be 0, 1, 2 or 3");
     if (o.sparse_eval < 0 || o.sparse_eval > 2)
         return fail(DMMV_ERR_SHAPE, "options.sparse_eval must be 0, 1 or 2");
+    if (o.dense_loop < 0 || o.dense_loop > 2 || o.wait_limit < 0)
+        return fail(DMMV_ERR_SHAPE, "options.dense_loop must be 0, 1 or 2 and wait_limit >= 0");
+    if (o.dense_loop == 2 && !dense_persistent_fits(*problem))
+        return fail(DMMV_ERR_UNSUPPORTED, "options.dense_loop = 2 needs one dense instance whose r, D, x and one column of A "
+                    "fit 156 KiB of LDS");
     if (o.sparse_eval == 2 && problem->csr_rowptr) {
         int64_t mp, P;
         sparse_partitions(*problem, o, &mp, &P);
@@ -1076,6 +1090,11 @@ dmmv_status dmmv_swap_move(dmmv_handle h, int32_t k_eps, int32_t apply, dmmv_swa
     if (k_eps < 0) return fail(DMMV_ERR_SHAPE, "dmmv_swap_move: k_eps < 0");
     if (!h->r_valid) return fail(DMMV_ERR_STATE, "dmmv_swap_move: no residual (call dmmv_residual or dmmv_solve first)");
     return swap_move(h, k_eps, apply, false, best, best_t);
+}
+
+int32_t dmmv_loop_in_use(dmmv_handle h) {
+    if (!h) return 0;
+    return (batched_pruned_applicable(h) || dense_persistent_applicable(h)) ? 2 : 1;
 }
 
 dmmv_status dmmv_time_eval(dmmv_handle h, int32_t reps, float* ms_out) {

@@ -81,7 +81,7 @@ struct alignas(16) Partial {
 // device flag slots
 enum { FLAG_ERROR = 0, FLAG_ACTIVE = 1, FLAG_PLANES = 2, FLAG_MAXROW = 3, FLAG_MAXCOL = 4, FLAG_WORST = 5, FLAG_COUNT = 8 };
 // error bits set by kernels
-enum { ERRBIT_X_NOT_IN_D = 1, ERRBIT_CSR_RANGE = 2, ERRBIT_CSR_DUP = 4, ERRBIT_MOVE_RANGE = 8 };
+enum { ERRBIT_X_NOT_IN_D = 1, ERRBIT_CSR_RANGE = 2, ERRBIT_CSR_DUP = 4, ERRBIT_MOVE_RANGE = 8, ERRBIT_WAIT_LIMIT = 16 };
 
 struct Ctx {
     dmmv_problem p;
@@ -100,6 +100,7 @@ struct Ctx {
     void* partials;       // Partial<T>: single [n_partials]; batched [n_partials][R]
     int64_t n_partials;
     int32_t* flags;       // [FLAG_COUNT]
+    void* persist_exchange; // dense single instance: arg-min records and arrival words of the one-launch descent
     void* red;            // T[red_elems] partial maxima of the max-|r| reduction
     int64_t red_elems;
 
@@ -259,6 +260,13 @@ dmmv_status batched_get_r(Ctx* c, void* r);
 dmmv_status batched_maxabs(Ctx* c);     // state[q].t = max_i |r[i][q]|
 dmmv_status batched_compact(Ctx* c, int32_t* active_out);   // polling point of the descent
 dmmv_status batched_compact_end(Ctx* c);
+// dense single instance: all iterations of the descent in one launch (a fixed grid of workgroups
+// that exchange one arg-min record per iteration); same moves as evaluation + selection + apply
+size_t dense_persistent_exchange_bytes();
+bool dense_persistent_fits(const dmmv_problem& p);
+bool dense_persistent_applicable(const Ctx* c);
+dmmv_status dense_descent_persistent(Ctx* c, int32_t iters, dmmv_move* trace, void* trace_t);
+
 // options.prune on a batch: `steps` iterations of the descent for every instance in one launch,
 // same moves as evaluation + selection + apply (an instance stops at its local optimum)
 bool batched_pruned_applicable(const Ctx* c);

@@ -28,7 +28,7 @@ EXPORTS = ("dmmv_workspace_bytes", "dmmv_create", "dmmv_destroy", "dmmv_set_x",
            "dmmv_set_residual", "dmmv_residual", "dmmv_eval_moves", "dmmv_argmin_move",
            "dmmv_apply_move", "dmmv_get_state", "dmmv_solve", "dmmv_solve_static", "dmmv_alns", "dmmv_swap_move",
            "dmmv_l2_changes",
-           "dmmv_time_eval", "dmmv_time_l2",
+           "dmmv_time_eval", "dmmv_time_l2", "dmmv_loop_in_use",
            "dmmv_last_error",
            "dmmv_version")
 
@@ -51,7 +51,7 @@ class Options(C.Structure):
                 ("sparse_partition_rows", C.c_int32), ("var_mask", C.c_void_p),
                 ("residual_mfma", C.c_int32), ("prune", C.c_int32), ("alns", C.c_int32),
                 ("value_search", C.c_int32), ("batched_eval", C.c_int32), ("sparse_eval", C.c_int32),
-                ("l2_rule", C.c_int32)]
+                ("l2_rule", C.c_int32), ("dense_loop", C.c_int32), ("wait_limit", C.c_int32)]
 
 
 class AlnsParams(C.Structure):
@@ -98,6 +98,8 @@ def load() -> C.CDLL:
                               C.c_void_p, C.c_void_p]
     lib.dmmv_swap_move.restype = C.c_int
     lib.dmmv_swap_move.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+    lib.dmmv_loop_in_use.restype = C.c_int32
+    lib.dmmv_loop_in_use.argtypes = [C.c_void_p]
     lib.dmmv_time_eval.restype = C.c_int
     lib.dmmv_time_eval.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_float)]
     lib.dmmv_time_l2.restype = C.c_int
@@ -141,7 +143,7 @@ class Handle:
                  keep_going: bool = False, poll_every: int = 64, var_mask=None,
                  sparse_partition_rows: int = 0, residual_mfma: bool = False, prune: bool = False,
                  alns: bool = False, value_search: bool = False, batched_eval: int = 0, sparse_eval: int = 0,
-                 l2_rule: int = 0,
+                 l2_rule: int = 0, dense_loop: int = 0, wait_limit: int = 0,
                  stream: Optional[torch.cuda.Stream] = None, device=None, _create: bool = True):
         lib = load()
         self._h = C.c_void_p(None)
@@ -200,6 +202,8 @@ class Handle:
         o.batched_eval = int(batched_eval)
         o.sparse_eval = int(sparse_eval)
         o.l2_rule = int(l2_rule)
+        o.dense_loop = int(dense_loop)
+        o.wait_limit = int(wait_limit)
         o.value_search = int(bool(value_search))
         if var_mask is not None:
             var_mask = var_mask.to(torch.uint8).contiguous()
@@ -427,6 +431,10 @@ def dmmv_swap_move(h: Handle, k_eps: int = 0, apply: bool = True) -> SwapResult:
     _check(load().dmmv_swap_move(h._h, C.c_int32(int(k_eps)), C.c_int32(1 if apply else 0), _ptr(best),
                                  _ptr(best_t)))
     return SwapResult(best[:, 0], best[:, 1], best_t)
+
+
+def dmmv_loop_in_use(h: Handle) -> int:
+    return int(load().dmmv_loop_in_use(h._h))
 
 
 def dmmv_time_eval(h: Handle, reps: int) -> float:

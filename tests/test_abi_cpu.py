@@ -149,8 +149,8 @@ def test_options_block_of_the_binding_has_the_layout_of_the_header(mod):
     for decl in re.findall(r"^\s+(?:const\s+)?(?:int32_t|uint8_t\*)\s+\*?([a-z0-9_]+);", body, flags=re.M):
         names.append(decl)
     assert names == [f[0] for f in mod.Options._fields_], (names, [f[0] for f in mod.Options._fields_])
-    # four int32, one pointer (8-byte aligned already), seven int32 -> padded to the pointer's alignment
-    assert C.sizeof(mod.Options) == 56
+    # four int32, one pointer (8-byte aligned already), nine int32 -> padded to the pointer's alignment
+    assert C.sizeof(mod.Options) == 64
 
 
 def test_workspace_grows_with_the_options_that_need_buffers(mod):
@@ -192,6 +192,30 @@ def test_sparse_matrix_that_needs_too_many_partitions_is_refused_before_any_gpu_
     pw, keepw = _problem(mod, dtype=np.float32, m=16 * 16384, n=40_000_000, sparse=True)
     assert lib.dmmv_workspace_bytes(C.byref(pw), C.byref(mod.Options())) == 0
     assert b"32-bit" in lib.dmmv_last_error()
+
+
+def test_one_launch_dense_descent_is_refused_on_the_host_when_it_cannot_fit(mod):
+    """options.dense_loop = 2 needs r, D, x and one column of A in 156 KiB of LDS, and one dense
+    instance; anything else fails in dmmv_workspace_bytes / dmmv_create with no GPU call made."""
+    lib = mod.load()
+    small, keep = _problem(mod, dtype=np.float64, m=300, n=40)
+    o = mod.Options()
+    o.dense_loop = 2
+    assert lib.dmmv_workspace_bytes(C.byref(small), C.byref(o)) > 0
+    tall, keept = _problem(mod, dtype=np.float64, m=30000, n=4)       # r alone: 234 KiB
+    assert lib.dmmv_workspace_bytes(C.byref(tall), C.byref(o)) == 0
+    assert b"dense_loop" in lib.dmmv_last_error()
+    h = C.c_void_p(None)
+    assert lib.dmmv_create(C.byref(h), C.byref(tall), C.byref(o), C.c_void_p(4096), 1 << 30, None) == -8
+    sp, keeps = _problem(mod, dtype=np.float32, m=500, n=50, sparse=True)
+    assert lib.dmmv_workspace_bytes(C.byref(sp), C.byref(o)) == 0
+    pb, keepb = _problem(mod, dtype=np.float32, m=100, n=50, R=3, scale=(1.0, 2.0, 0.5))
+    assert lib.dmmv_workspace_bytes(C.byref(pb), C.byref(o)) == 0
+    o.dense_loop = 3
+    assert lib.dmmv_workspace_bytes(C.byref(small), C.byref(o)) == 0
+    o.dense_loop = 0
+    o.wait_limit = -1
+    assert lib.dmmv_workspace_bytes(C.byref(small), C.byref(o)) == 0
 
 
 def test_static_scratch_entry_point_refuses_large_problems_on_the_host(mod):
