@@ -560,6 +560,24 @@ def residual_probe(idx: int, device: str, reps: int) -> None:
                       "useful_flops_per_call": 2.0 * inst.m * inst.n * inst.R}))
 
 
+def l2_probe(idx: int, device: str, reps: int) -> None:
+    """For `rocprofv3 --pmc` runs on the contraction behind the l2 changes: `reps` launches of
+    g = A^T r (a batch: G = X^T R_mat on the matrix cores) on workload idx, nothing else timed."""
+    import torch
+    from paper_2508_13437_amd import dmmv
+    from workloads import make_config
+
+    inst = make_config(idx)
+    x0 = torch.from_numpy(np.ascontiguousarray(inst.x0)).to(device)
+    with dmmv.from_instance(inst, device, l2_rule=3) as h:
+        dmmv.dmmv_set_x(h, x0)
+        dmmv.dmmv_residual(h)
+        ms = dmmv.dmmv_time_l2(h, reps) / reps
+        torch.cuda.synchronize()
+    print(json.dumps({"probe": inst.name, "l2_launches": reps + 1, "ms_per_launch": ms,
+                      "multiply_adds_per_launch": float(inst.m) * inst.n * inst.R}))
+
+
 def descent_probe(idx: int, device: str, reps: int) -> None:
     """For `rocprofv3 --pmc` runs on the pruned batched descent: `reps` calls of dmmv_solve with
     options.prune on batched workload idx (one launch of k_descent_batched_pruned each)."""
@@ -601,6 +619,8 @@ def main():
                          "(for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs)")
     ap.add_argument("--residual-probe", type=int, default=0, metavar="REPS",
                     help="only run the matrix-core batched residual REPS times (for rocprofv3 --pmc runs)")
+    ap.add_argument("--l2-probe", type=int, default=0, metavar="REPS",
+                    help="only launch the contraction g = A^T r of the l2 changes REPS times on --config (for rocprofv3 --pmc)")
     ap.add_argument("--descent-probe", type=int, default=0, metavar="REPS",
                     help="only run the pruned batched descent REPS times (for rocprofv3 --pmc runs)")
     args = ap.parse_args()
@@ -621,6 +641,9 @@ def main():
         return
     if args.residual_probe > 0:
         residual_probe(args.config, device, args.residual_probe)
+        return
+    if args.l2_probe > 0:
+        l2_probe(args.config, device, args.l2_probe)
         return
     if args.descent_probe > 0:
         descent_probe(args.config, device, args.descent_probe)

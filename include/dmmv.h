@@ -242,6 +242,9 @@ dmmv_status dmmv_get_state(dmmv_handle h, void* x_values, void* r, void* max_vio
  *   x_out [R][n], max_violation_out [R], iters_done [R] (moves applied)   - any may be NULL
  *   trace [R][iters] applied moves in order (j = -1 past the end), trace_t [R][iters]
  *   the max violation after each                                            - may be NULL
+ * x0 = NULL continues from the handle's current x.  r is recomputed from x at the start of
+ * every call and maintained by rank-1 updates inside it, so calling dmmv_solve(h, NULL, k)
+ * repeatedly is a descent whose residual is refreshed every k moves.
  * Waits for the stream before returning.
  * Paper: Algorithm 1 local-search step restricted to single-coordinate moves; strict
  * improvement as in Proposition 1 / Algorithm 2. */
