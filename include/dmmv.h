@@ -180,8 +180,9 @@ typedef struct {
                                 scores, moves, traces and residual either way.  With 2 the workgroups
                                 wait for one another, so all must be resident on the device at once;
                                 if another kernel keeps some from starting, the wait ends after
-                                wait_limit polls and dmmv_solve returns DMMV_ERR_STATE with the handle
-                                still at its starting point.  options.prune and value_search (without
+                                wait_limit polls; x, r and the loop state are then untouched, and
+                                dmmv_solve returns DMMV_ERR_STATE (dense_loop = 2) or runs the same
+                                descent with launches (dense_loop = 0).  options.prune and value_search (without
                                 keep_going) and l2_rule 1 / 2 keep their own loops                    */
     int32_t wait_limit;      /* dense_loop = 2: polls of another workgroup's arrival word before the
                                 kernel gives up; 0 = default (2^22, a few seconds)                    */

@@ -577,10 +577,11 @@ static dmmv_status residual_any(Ctx* c) {
 }
 
 // read and clear the device error flag (waits for the stream)
-static dmmv_status check_device_errors(Ctx* c) {
+static dmmv_status check_device_errors(Ctx* c, int32_t* raw = nullptr) {
     int32_t host_flag = 0;
     DMMV_HIP_CHECK(hipMemcpyAsync(&host_flag, &c->flags[FLAG_ERROR], sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
     DMMV_HIP_CHECK(hipStreamSynchronize(c->stream));
+    if (raw) *raw = host_flag;
     if (host_flag) {
         hipLaunchKernelGGL(k_zero_flags, dim3(1), dim3(64), 0, c->stream, c->flags);
         DMMV_HIP_CHECK(hipStreamSynchronize(c->stream));
@@ -627,7 +628,14 @@ static dmmv_status solve_t(dmmv_ctx* c, const void* x0, int32_t iters, void* x_o
         // a small dense instance too; the wait between its workgroups is bounded and reports here
         if (iters > 0 && dense_persistent_applicable(c)) {
             DMMV_TRY(dense_descent_persistent(c, iters, trace, trace_t));
-            return check_device_errors(c);
+            int32_t raw = 0;
+            const dmmv_status one = check_device_errors(c, &raw);
+            // An automatic choice must not add a way to fail: if the workgroups could not all be
+            // resident (the device is shared), the attempt has left x, r and the loop state alone,
+            // and the loop of launches below does the same descent.
+            if (!(one != DMMV_OK && raw == ERRBIT_WAIT_LIMIT && c->o.dense_loop == 0)) return one;
+            if (trace || trace_t)
+                hipLaunchKernelGGL(k_fill_trace<T>, grid1(R * (int64_t)iters, 256), dim3(256), 0, c->stream, trace, (T*)trace_t, R * (int64_t)iters);
         }
         for (int32_t it = 0; it < iters; ++it) {
             DMMV_TRY(loop_step(c, iters, trace, trace_t));

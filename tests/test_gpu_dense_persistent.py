@@ -146,6 +146,15 @@ def test_one_launch_descent_bounded_wait_reports_instead_of_hanging():
         else:
             print("bounded wait: every arrival was already there", flush=True)
             assert int(res.iters_done[0]) == o.iters_done and N(res.max_violation)[0] == o.t
+    # the automatic choice falls back to the loop of launches instead of failing
+    with m.from_instance(inst, DEV, wait_limit=1) as h:
+        assert m.dmmv_loop_in_use(h) == 2
+        res = m.dmmv_solve(h, T(x0), 50, trace=True)
+        d = int(res.iters_done[0])
+        assert d == o.iters_done and N(res.max_violation)[0] == o.t
+        tr = N(res.trace)[0]
+        assert np.array_equal(tr[:d, 0], o.trace_j) and np.array_equal(tr[:d, 1], o.trace_k) and np.all(tr[d:] == -1)
+        assert np.array_equal(N(res.trace_t)[0, :d], o.trace_t)
     # the default limit on the same problem
     with m.from_instance(inst, DEV, dense_loop=2) as h:
         res = m.dmmv_solve(h, T(x0), 50, trace=True)
