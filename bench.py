@@ -90,7 +90,8 @@ def roofline_for(inst, eval_ms: float, iter_us=None, cold_ms=None) -> dict:
             # every launch preceded by a flush of the 256 MB Infinity Cache and the L2s (a 1 GiB
             # device-to-device copy, or a 1 GiB read): nothing of the matrix is left on the chip, so
             # these are rates out of HBM itself; after the copy the reads also push written lines out
-            out["cold_launch_ms"], out["cold_after_read_ms"] = cold_ms
+            out["cold_launch_ms"], out["cold_after_read_ms"] = cold_ms[0], cold_ms[1]
+            out["device_copy_GBs_measured"] = cold_ms[2]
             out["cold_GBs"] = b / (cold_ms[0] * 1e-3) / 1e9
             out["frac_cold"] = out["cold_GBs"] / HBM_PEAK_GBS
             out["cold_after_read_GBs"] = b / (cold_ms[1] * 1e-3) / 1e9
@@ -249,8 +250,18 @@ def cold_eval_ms(h, device: str, reps: int = 8):
         for _ in range(reps):
             src.max()
             after_read += dmmv.dmmv_time_eval(h, -1)
+    # what a plain device-to-device copy of 1 GiB reaches on this device (read + written bytes per second)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    with torch.cuda.stream(h.stream):
+        dst.copy_(src)
+        e0.record(h.stream)
+        for _ in range(4):
+            dst.copy_(src)
+        e1.record(h.stream)
+    e1.synchronize()
+    copy_gbs = 4 * 2.0 * src.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9
     del src, dst
-    return after_copy / reps, after_read / reps
+    return after_copy / reps, after_read / reps, copy_gbs
 
 
 def descent_timing(inst, device: str, x0, iters: int) -> dict:
@@ -665,6 +676,12 @@ def main():
         "final_max_violation": head["final_max_violation"],
         "roofline": head["roofline"],
     }
+    import torch
+    prop = torch.cuda.get_device_properties(device)
+    line["device"] = {"name": prop.name, "compute_units": prop.multi_processor_count,
+                      "memory_GiB": round(prop.total_memory / 2**30, 1),
+                      "gcn_arch": getattr(prop, "gcnArchName", None),
+                      "peaks_used": {"hbm_GBs": HBM_PEAK_GBS, "fp32_TFLOPs": 157.3, "fp64_TFLOPs": 78.6}}
     if "residual" in head:
         line["residual"] = head["residual"]
     if "l2" in head:
