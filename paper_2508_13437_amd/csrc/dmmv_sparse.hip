@@ -202,8 +202,18 @@ __device__ void reservoir_publish(ResLds<T>& L, int32_t c, bool set_floor_from_l
     for (int32_t u = threadIdx.x; u < c; u += blockDim.x) {
         const T a = L.v[u];
         const int32_t row = L.r[u];
-        int32_t rank = 0;
-        for (int32_t q = 0; q < c; ++q) rank += key_before(L.v[q], L.r[q], a, row);
+        // eight entries per step, so that their LDS reads are in flight together (one at a time
+        // the loop runs at the LDS latency: 4.5 us for 150 entries)
+        int32_t rank = 0, q = 0;
+        for (; q + 8 <= c; q += 8) {
+            T v8[8];
+            int32_t r8[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) { v8[e] = L.v[q + e]; r8[e] = L.r[q + e]; }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) rank += key_before(v8[e], r8[e], a, row);
+        }
+        for (; q < c; ++q) rank += key_before(L.v[q], L.r[q], a, row);
         if (rank < RES_CAP) { L.ov[rank] = a; L.orow[rank] = row; }
     }
     __syncthreads();
@@ -323,8 +333,17 @@ __global__ __launch_bounds__(SA_BLOCK) void k_select_apply_cscp(
     __shared__ T sh_sval[SA_MAXCOL];            // their new |r|
     __shared__ int32_t sh_ns, sh_j, sh_k;
     __shared__ T sh_delta, sh_best;
-    // the loop state and the records are fetched together (one memory latency, not two)
+    __shared__ int32_t sh_e0[CSC_MAX_PARTITIONS], sh_len[CSC_MAX_PARTITIONS];   // column j's segments
+    // Everything that depends on nothing is fetched together (one memory latency, not one per
+    // use): the loop state, the records, and the reservoir this kernel will update.  From one
+    // workgroup every dependent access to memory costs about a microsecond.
     const InstState<T> z0 = st[0];
+    const int32_t cnt = res_meta[RES_CNT];
+    const int32_t fr = res_meta[RES_FLOOR_ROW];
+    const T fv = floor_val[0];
+    int32_t my_row = -1;
+    T my_val = (T)0;
+    if (threadIdx.x < RES_CAP) { my_row = res_row[threadIdx.x]; my_val = res_val[threadIdx.x]; }
     T s = (T)0;
     int64_t c = -1;
     for (int64_t q = threadIdx.x; q < n_part; q += SA_BLOCK) {
@@ -363,12 +382,18 @@ __global__ __launch_bounds__(SA_BLOCK) void k_select_apply_cscp(
     if (j < 0) return;
     const T delta = sh_delta;
     // ---- rank-1 update of the rows of column j; remember them (ascending by row) ----
+    for (int32_t p = threadIdx.x; p < P; p += SA_BLOCK) {
+        const int32_t e0 = segptr[(int64_t)p * n + j], e1 = segptr[(int64_t)p * n + j + 1];
+        sh_e0[p] = e0;
+        sh_len[p] = e1 - e0;
+    }
+    __syncthreads();
     int32_t col_len = 0;
-    for (int32_t p = 0; p < P; ++p) col_len += segptr[(int64_t)p * n + j + 1] - segptr[(int64_t)p * n + j];
+    for (int32_t p = 0; p < P; ++p) col_len += sh_len[p];
     const bool incremental = col_len <= SA_MAXCOL && m > RES_CAP;
     int32_t base = 0;
     for (int32_t p = 0; p < P; ++p) {
-        const int32_t e0 = segptr[(int64_t)p * n + j], e1 = segptr[(int64_t)p * n + j + 1];
+        const int32_t e0 = sh_e0[p], e1 = e0 + sh_len[p];
         for (int32_t e = e0 + threadIdx.x; e < e1; e += SA_BLOCK) {
             const uint32_t loc = row16[e];
             const bool pad = loc == (uint32_t)mp;
@@ -392,18 +417,15 @@ __global__ __launch_bounds__(SA_BLOCK) void k_select_apply_cscp(
     // ---- incremental reservoir update ----
     // (pads make sh_srow non-monotone across partitions only at segment ends; membership
     //  below therefore searches each partition's slice separately)
-    const int32_t cnt = res_meta[RES_CNT];
-    const T fv = floor_val[0];
-    const int32_t fr = res_meta[RES_FLOOR_ROW];
     if (threadIdx.x == 0) L.count = 0;
     __syncthreads();
     // survivors: reservoir rows that the move did not touch
     if (threadIdx.x < cnt) {
-        const int32_t row = res_row[threadIdx.x];
+        const int32_t row = my_row;
         const int32_t p = row / mp;
         int32_t lo = 0;
-        for (int32_t pp = 0; pp < p; ++pp) lo += segptr[(int64_t)pp * n + j + 1] - segptr[(int64_t)pp * n + j];
-        int32_t hi = lo + (segptr[(int64_t)p * n + j + 1] - segptr[(int64_t)p * n + j]);
+        for (int32_t pp = 0; pp < p; ++pp) lo += sh_len[pp];
+        int32_t hi = lo + sh_len[p];
         const int32_t end = hi;
         while (lo < hi) {
             const int32_t mid = (lo + hi) >> 1;
@@ -412,7 +434,7 @@ __global__ __launch_bounds__(SA_BLOCK) void k_select_apply_cscp(
         const bool touched = lo < end && sh_srow[lo] == row;
         if (!touched) {
             const int32_t pos = atomicAdd(&L.count, 1);
-            L.v[pos] = res_val[threadIdx.x];
+            L.v[pos] = my_val;
             L.r[pos] = row;
         }
     }
@@ -431,7 +453,7 @@ __global__ __launch_bounds__(SA_BLOCK) void k_select_apply_cscp(
     const int32_t cnew = L.count;
     __syncthreads();
     reservoir_publish(L, cnew, false, res_val, res_row, res_meta, floor_val);
-    if (res_meta[RES_CNT] < RES_MIN) {
+    if ((cnew < RES_CAP ? cnew : RES_CAP) < RES_MIN) {      // what publish left in meta[RES_CNT]
         __threadfence_block();
         reservoir_rebuild(L, m, r, res_val, res_row, res_meta, floor_val);
     }
