@@ -244,11 +244,22 @@ __device__ void reservoir_rebuild(ResLds<T>& L, int64_t m, const T* r, T* res_va
     // strided maxima of the first RES_SEL threads propose a floor with about `target` rows above it
     T mv = (T)-1;
     int32_t mr = INT32_MAX;
-    if (threadIdx.x < RES_SEL)
-        for (int64_t i = threadIdx.x; i < m; i += RES_SEL) {
+    // (eight rows per step, so that their loads are in flight together)
+    if (threadIdx.x < RES_SEL) {
+        int64_t i = threadIdx.x;
+        for (; i + 7 * RES_SEL < m; i += 8 * RES_SEL) {
+            T a8[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) a8[e] = dmmv_abs(ld_coherent(r + i + e * RES_SEL));
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (key_before(a8[e], (int32_t)(i + e * RES_SEL), mv, mr)) { mv = a8[e]; mr = (int32_t)(i + e * RES_SEL); }
+        }
+        for (; i < m; i += RES_SEL) {
             const T a = dmmv_abs(ld_coherent(r + i));
             if (key_before(a, (int32_t)i, mv, mr)) { mv = a; mr = (int32_t)i; }
         }
+    }
     int32_t target = RES_CAP / 2;
     for (;;) {
         __syncthreads();
@@ -257,18 +268,41 @@ __device__ void reservoir_rebuild(ResLds<T>& L, int64_t m, const T* r, T* res_va
         __syncthreads();
         if (threadIdx.x < RES_SEL) {
             int32_t rank = 0;
-            for (int32_t q = 0; q < RES_SEL; ++q) rank += key_before(L.v[q], L.r[q], mv, mr);
+            static_assert(RES_SEL % 8 == 0, "ranking loop step");
+            for (int32_t q = 0; q < RES_SEL; q += 8) {
+                T v8[8];
+                int32_t r8[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) { v8[e] = L.v[q + e]; r8[e] = L.r[q + e]; }
+#pragma unroll
+                for (int e = 0; e < 8; ++e) rank += key_before(v8[e], r8[e], mv, mr);
+            }
             if (rank == target - 1) { L.fv = mv; L.fr = mr; }
         }
         __syncthreads();
         const T fv = L.fv;
         const int32_t fr = L.fr;
         __syncthreads();
-        for (int64_t i = threadIdx.x; i < m; i += blockDim.x) {
-            const T a = dmmv_abs(ld_coherent(r + i));
-            if (!key_before(fv, fr, a, (int32_t)i)) {          // key(i) before-or-equal floor
-                const int32_t pos = atomicAdd(&L.count, 1);
-                if (pos < RES_COLLECT) { L.v[pos] = a; L.r[pos] = (int32_t)i; }
+        {
+            const int64_t step = blockDim.x;
+            int64_t i = threadIdx.x;
+            for (; i + 7 * step < m; i += 8 * step) {
+                T a8[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) a8[e] = dmmv_abs(ld_coherent(r + i + e * step));
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (!key_before(fv, fr, a8[e], (int32_t)(i + e * step))) {      // key before-or-equal floor
+                        const int32_t pos = atomicAdd(&L.count, 1);
+                        if (pos < RES_COLLECT) { L.v[pos] = a8[e]; L.r[pos] = (int32_t)(i + e * step); }
+                    }
+            }
+            for (; i < m; i += step) {
+                const T a = dmmv_abs(ld_coherent(r + i));
+                if (!key_before(fv, fr, a, (int32_t)i)) {
+                    const int32_t pos = atomicAdd(&L.count, 1);
+                    if (pos < RES_COLLECT) { L.v[pos] = a; L.r[pos] = (int32_t)i; }
+                }
             }
         }
         __syncthreads();
