@@ -314,6 +314,19 @@ __global__ __launch_bounds__(FZ_BLOCK) void k_eval_fused(
     const int rowid = lane / ST_LPC;
     const int32_t c0 = blockIdx.x * FZ_COLS;               // n < 2^31
     const int32_t ncol = n - c0 < FZ_COLS ? n - c0 : FZ_COLS;
+    // The first trip to memory carries everything whose address is known now: partition 0 of r
+    // (into registers; it is written to LDS below), this lane's segment bounds in partition 0
+    // (straight into registers, so that its first entries can be requested without waiting for
+    // the LDS table and a barrier), the table of all bounds, x and the reservoir.
+    const bool aligned = (((size_t)mp * sizeof(T)) & 15) == 0;       // partitions start on 16 bytes
+    const int32_t rows0 = (int32_t)(m < mp ? m : mp);
+    const int32_t npiece0 = aligned ? (int32_t)(((size_t)rows0 * sizeof(T)) / 16) : 0;
+    fz_piece rvp0[FZ_RV];
+#pragma unroll
+    for (int v = 0; v < FZ_RV; ++v) {
+        const int32_t i = threadIdx.x + v * FZ_BLOCK;
+        rvp0[v] = reinterpret_cast<const fz_piece*>(r)[i < npiece0 ? i : 0];
+    }
     // the bounds of this workgroup's segments in every partition: one trip to memory for all of them
     for (int32_t t = threadIdx.x; t < P * (FZ_COLS + 1); t += FZ_BLOCK) {
         const int32_t p = t / (FZ_COLS + 1), cc = t - p * (FZ_COLS + 1);
@@ -321,6 +334,7 @@ __global__ __launch_bounds__(FZ_BLOCK) void k_eval_fused(
     }
     int32_t slot[FZ_GROUPS];               // column of the workgroup this lane works on, per group
     int32_t kcur[FZ_GROUPS];
+    int32_t first_b0[FZ_GROUPS], first_b1[FZ_GROUPS];
     uint32_t flags = 0;                    // bit u: the column exists; bit 4 + u: it may move
 #pragma unroll
     for (int u = 0; u < FZ_GROUPS; ++u) {
@@ -328,6 +342,8 @@ __global__ __launch_bounds__(FZ_BLOCK) void k_eval_fused(
         const bool ok = slot[u] < ncol;
         const int32_t j = ok ? c0 + slot[u] : n - 1;
         kcur[u] = kidx[j];
+        first_b0[u] = ok ? segptr[c0 + slot[u]] : 0;                 // partition 0
+        first_b1[u] = ok ? segptr[c0 + slot[u] + 1] : SEG_ALIGN;
         const bool vok = var_mask ? var_mask[j] != 0 : true;
         flags |= (ok ? 1u : 0u) << u | (vok ? 1u : 0u) << (4 + u);
     }
@@ -341,12 +357,49 @@ __global__ __launch_bounds__(FZ_BLOCK) void k_eval_fused(
     }
     if (threadIdx.x == 0) { buf0[mp] = (T)0; buf1[mp] = (T)0; }      // what a pad's offset reads
     const int32_t nfast = cnt < RES_FAST ? cnt : RES_FAST;
-    const T thr = nfast > 0 ? res_val[nfast - 1] : Limits<T>::inf();
-    const bool aligned = (((size_t)mp * sizeof(T)) & 15) == 0;       // partitions start on 16 bytes
-    __syncthreads();                                                 // the bounds are in place
+    // partition 0 of r goes to LDS as soon as it arrives (its loads were the first issued, so
+    // nothing requested later is held up by waiting for them, and their registers are free again)
+#pragma unroll
+    for (int v = 0; v < FZ_RV; ++v) {
+        const int32_t i = threadIdx.x + v * FZ_BLOCK;
+        if (i < npiece0) reinterpret_cast<fz_piece*>(buf0)[i] = rvp0[v];
+    }
 
     T bs = (T)0;                 // this lane's best candidate so far
     int64_t bc = -1;
+
+    // Per group: the two groups of four of the partition about to be folded (ix, av), this
+    // lane's first entry of that segment and the segment's end (qe, qs1).  One spare group of
+    // four per wavefront (`ext`), owned by group ext_owner (-1: free).
+    uint2 ix[FZ_GROUPS][FZ_NQ];
+    typename Vec4<T>::type av[FZ_GROUPS][FZ_NQ];
+    int32_t qe[FZ_GROUPS], qs1[FZ_GROUPS];
+    uint2 ext_ix;
+    typename Vec4<T>::type ext_av;
+    int32_t ext_owner = -1;
+    // request the entries of group u in partition pp (a column that does not exist: entries 0..3, unused)
+#define FZ_REQUEST(u, pp)                                                                              \
+    do {                                                                                           \
+        const bool ok_ = (flags >> (u)) & 1u;                                                      \
+        FZ_REQUEST_B(u, ok_ ? sh_seg[(pp) * (FZ_COLS + 1) + slot[u]] : 0,                          \
+                     ok_ ? sh_seg[(pp) * (FZ_COLS + 1) + slot[u] + 1] : SEG_ALIGN);                \
+    } while (0)
+#define FZ_REQUEST_B(u, lo_, hi_)                                                                      \
+    do {                                                                                           \
+        const int32_t b0_ = (lo_);                                                                 \
+        const int32_t b1_ = (hi_);                                                                 \
+        qe[u] = b0_ + sub * SEG_ALIGN;                                                             \
+        qs1[u] = b1_;                                                                              \
+        fz_load_quad<T>(ix[u][0], av[u][0], row16, cval, qe[u], b1_);                              \
+        fz_load_quad<T>(ix[u][1], av[u][1], row16, cval, qe[u] + FZ_QSTEP, b1_);                   \
+        if (ext_owner < 0 && __any(b1_ - b0_ > FZ_NQ * FZ_QSTEP)) {                                \
+            ext_owner = (u);                                                                       \
+            fz_load_quad<T>(ext_ix, ext_av, row16, cval, qe[u] + FZ_NQ * FZ_QSTEP, b1_);           \
+        }                                                                                          \
+    } while (0)
+    // first value tile: its bounds were requested at the top of the kernel
+#pragma unroll
+    for (int u = 0; u < FZ_GROUPS; ++u) FZ_REQUEST_B(u, first_b0[u], first_b1[u]);
 
     for (int32_t k0 = 0; k0 < nd; k0 += KT) {
         T dk[KT], acc[FZ_GROUPS][KT];
@@ -359,41 +412,16 @@ __global__ __launch_bounds__(FZ_BLOCK) void k_eval_fused(
 #pragma unroll
             for (int q = 0; q < KT; ++q) acc[u][q] = (T)0;
         }
-        // Per group: the two groups of four of the partition about to be folded (ix, av), this
-        // lane's first entry of that segment and the segment's end (qe, qs1).  One spare group of
-        // four per wavefront (`ext`), owned by group ext_owner (-1: free).
-        uint2 ix[FZ_GROUPS][FZ_NQ];
-        typename Vec4<T>::type av[FZ_GROUPS][FZ_NQ];
-        int32_t qe[FZ_GROUPS], qs1[FZ_GROUPS];
-        uint2 ext_ix;
-        typename Vec4<T>::type ext_av;
-        int32_t ext_owner = -1;
-        // request the entries of group u in partition pp (a column that does not exist: entries 0..3, unused)
-#define FZ_REQUEST(u, pp)                                                                              \
-        do {                                                                                           \
-            const bool ok_ = (flags >> (u)) & 1u;                                                      \
-            const int32_t b0_ = ok_ ? sh_seg[(pp) * (FZ_COLS + 1) + slot[u]] : 0;                      \
-            const int32_t b1_ = ok_ ? sh_seg[(pp) * (FZ_COLS + 1) + slot[u] + 1] : SEG_ALIGN;          \
-            qe[u] = b0_ + sub * SEG_ALIGN;                                                             \
-            qs1[u] = b1_;                                                                              \
-            fz_load_quad<T>(ix[u][0], av[u][0], row16, cval, qe[u], b1_);                              \
-            fz_load_quad<T>(ix[u][1], av[u][1], row16, cval, qe[u] + FZ_QSTEP, b1_);                   \
-            if (ext_owner < 0 && __any(b1_ - b0_ > FZ_NQ * FZ_QSTEP)) {                                \
-                ext_owner = (u);                                                                       \
-                fz_load_quad<T>(ext_ix, ext_av, row16, cval, qe[u] + FZ_NQ * FZ_QSTEP, b1_);           \
-            }                                                                                          \
-        } while (0)
         // ---- prologue: entries of partition 0, r of partition 0
+        if (k0 > 0) {                     // (the first tile's requests went out before the loop)
 #pragma unroll
-        for (int u = 0; u < FZ_GROUPS; ++u) FZ_REQUEST(u, 0);
-        {
-            const int32_t rows0 = (int32_t)(m < mp ? m : mp);
-            const int32_t npiece0 = aligned ? (int32_t)(((size_t)rows0 * sizeof(T)) / 16) : 0;
+            for (int u = 0; u < FZ_GROUPS; ++u) FZ_REQUEST(u, 0);
             for (int32_t i = threadIdx.x; i < npiece0; i += FZ_BLOCK)
                 reinterpret_cast<fz_piece*>(buf0)[i] = reinterpret_cast<const fz_piece*>(r)[i];
-            for (int32_t i = npiece0 * (int32_t)(16 / sizeof(T)) + threadIdx.x; i < rows0; i += FZ_BLOCK) buf0[i] = r[i];
         }
-        __syncthreads();
+        for (int32_t i = npiece0 * (int32_t)(16 / sizeof(T)) + threadIdx.x; i < rows0; i += FZ_BLOCK) buf0[i] = r[i];
+        __syncthreads();                  // partition 0 of r, the table of bounds and the reservoir are in place
+        const T thr = nfast > 0 ? sh_rv[nfast - 1] : Limits<T>::inf();
         for (int32_t p = 0; p < P; ++p) {
             T* const cur = (p & 1) ? buf1 : buf0;
             T* const nxt = (p & 1) ? buf0 : buf1;
@@ -444,6 +472,7 @@ __global__ __launch_bounds__(FZ_BLOCK) void k_eval_fused(
             __syncthreads();                  // partition p consumed by all, partition p + 1 in place
         }
 #undef FZ_REQUEST
+#undef FZ_REQUEST_B
         // ---- the columns' scores: partition maxima are complete, add the rows outside the column
 #pragma unroll
         for (int u = 0; u < FZ_GROUPS; ++u) {
