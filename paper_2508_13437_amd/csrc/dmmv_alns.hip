@@ -87,32 +87,51 @@ __global__ void k_alns_begin(AlnsState* S, int64_t R, uint64_t seed, int32_t it)
     S[q].r_op = (ur * (S[q].w[2] + S[q].w[3]) < S[q].w[2]) ? 0 : 1;
 }
 
-// inclusive prefix sums of the weights (one workgroup per instance); only for worst-remove
+// Inclusive prefix sums of the weights (one workgroup per instance); only for worst-remove.
+// The weights are integers, so the sums are the same in any order: a thread sums SC_E
+// consecutive weights in registers, the wavefronts scan the threads' totals, and the total of a
+// tile of 1024 * SC_E weights is carried into the next.
+constexpr int SC_E = 8;
 __global__ __launch_bounds__(1024) void k_alns_scan(int64_t n, const uint64_t* __restrict__ weight_all,
                                                     uint64_t* __restrict__ prefix_all, const AlnsState* S) {
-    __shared__ uint64_t sh[1024];
-    __shared__ uint64_t carry;
+    __shared__ uint64_t sh_w[16];
     const int64_t q = blockIdx.x;
     if (S[q].d_op != 1) return;
     const uint64_t* __restrict__ weight = weight_all + q * n;
     uint64_t* __restrict__ prefix = prefix_all + q * n;
-    if (threadIdx.x == 0) carry = 0;
-    __syncthreads();
-    for (int64_t base = 0; base < n; base += 1024) {
-        const int64_t j = base + threadIdx.x;
-        sh[threadIdx.x] = j < n ? weight[j] : 0;
-        __syncthreads();
-        for (int off = 1; off < 1024; off <<= 1) {
-            const uint64_t t = threadIdx.x >= off ? sh[threadIdx.x - off] : 0;
-            __syncthreads();
-            sh[threadIdx.x] += t;
-            __syncthreads();
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    uint64_t carry = 0;                                     // the same in every thread
+    for (int64_t base = 0; base < n; base += 1024 * SC_E) {
+        const int64_t j0 = base + (int64_t)threadIdx.x * SC_E;
+        uint64_t v[SC_E];
+#pragma unroll
+        for (int u = 0; u < SC_E; ++u) v[u] = weight[j0 + u < n ? j0 + u : n - 1];   // clamped: the loads go out together
+#pragma unroll
+        for (int u = 0; u < SC_E; ++u) v[u] = j0 + u < n ? v[u] : 0;
+#pragma unroll
+        for (int u = 1; u < SC_E; ++u) v[u] += v[u - 1];
+        const uint64_t tot = v[SC_E - 1];
+        uint64_t inc = tot;                                 // inclusive over the wavefront's threads
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const uint64_t t = (uint64_t)__shfl_up((long long)inc, off, 64);
+            if (lane >= off) inc += t;
         }
-        const uint64_t incl = sh[threadIdx.x] + carry;
-        if (j < n) prefix[j] = incl;
+        if (lane == 63) sh_w[w] = inc;
         __syncthreads();
-        if (threadIdx.x == 1023) carry = incl;
-        __syncthreads();
+        uint64_t before = 0, all = 0;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            const uint64_t x = sh_w[k];
+            if (k < w) before += x;
+            all += x;
+        }
+        const uint64_t ex = carry + before + (inc - tot);   // everything ahead of this thread
+#pragma unroll
+        for (int u = 0; u < SC_E; ++u)
+            if (j0 + u < n) prefix[j0 + u] = v[u] + ex;
+        carry += all;
+        __syncthreads();                                    // sh_w is written again
     }
 }
 

@@ -319,17 +319,28 @@ __device__ __forceinline__ double dpp_mov(double v) {
 
 // Maximum over the 64 lanes of a wavefront, result in every lane.  max is idempotent, so a
 // butterfly of DPP permutations inside each row of 16 lanes (quad xor 1, quad xor 2, half-row
-// mirror, row mirror) followed by two cross-row exchanges is enough.  All 64 lanes must be
-// active.
+// mirror, row mirror) leaves every row with its maximum in all its lanes; the four row results
+// are then read through the scalar unit (no trip through the LDS crossbar, whose latency a
+// chain of reductions would pay once per exchange).  All 64 lanes must be active.
+__device__ __forceinline__ float read_lane(float v, int l) {
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l));
+}
+__device__ __forceinline__ double read_lane(double v, int l) {
+    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), l),
+                            __builtin_amdgcn_readlane(__double2loint(v), l));
+}
+__device__ __forceinline__ int64_t read_lane(int64_t v, int l) {
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, l);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)((uint64_t)v >> 32), l);
+    return (int64_t)(((uint64_t)hi << 32) | lo);
+}
 template <class T>
 __device__ __forceinline__ T wave_max(T v) {
     v = dmmv_max(v, dpp_mov<DPP_QUAD_XOR1>(v));
     v = dmmv_max(v, dpp_mov<DPP_QUAD_XOR2>(v));
     v = dmmv_max(v, dpp_mov<DPP_ROW_HALF_MIRROR>(v));
     v = dmmv_max(v, dpp_mov<DPP_ROW_MIRROR>(v));
-    v = dmmv_max(v, __shfl_xor(v, 16, 64));
-    v = dmmv_max(v, __shfl_xor(v, 32, 64));
-    return v;
+    return dmmv_max(dmmv_max(read_lane(v, 0), read_lane(v, 16)), dmmv_max(read_lane(v, 32), read_lane(v, 48)));
 }
 
 __device__ __forceinline__ uint32_t wave_or(uint32_t v) {
@@ -352,18 +363,6 @@ __device__ __forceinline__ bool rec_less(T s1, int64_t c1, T s2, int64_t c2) {
 __device__ __forceinline__ float dmmv_min(float a, float b) { return __builtin_fminf(a, b); }
 __device__ __forceinline__ double dmmv_min(double a, double b) { return __builtin_fmin(a, b); }
 
-__device__ __forceinline__ float read_lane(float v, int l) {
-    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l));
-}
-__device__ __forceinline__ double read_lane(double v, int l) {
-    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), l),
-                            __builtin_amdgcn_readlane(__double2loint(v), l));
-}
-__device__ __forceinline__ int64_t read_lane(int64_t v, int l) {
-    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, l);
-    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)((uint64_t)v >> 32), l);
-    return (int64_t)(((uint64_t)hi << 32) | lo);
-}
 template <int CTRL>
 __device__ __forceinline__ int64_t dpp_mov(int64_t v) {
     const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)v, CTRL, 0xF, 0xF, true);

@@ -683,23 +683,32 @@ __global__ __launch_bounds__(1024) void k_alns_repair_cscp_general(int64_t m, in
 }
 
 // Repair without the chain of dependent loads.  From one workgroup every dependent access to
-// memory costs about a microsecond, and the general kernel needs three to five per picked
+// memory costs about half a microsecond, and the general kernel needs three to five per picked
 // variable (segment bounds, entries, residuals, ...).  Here the entries of all picked columns are
 // first gathered, by many workgroups, into a scratch array with a fixed stride per column
 // (k_alns_gather: global row and value, row -1 for padding), so the repair kernel knows the
-// address of a pick's entries without loading anything, fetches the next pick's entries while
-// it works on the current one, and is left with the residuals themselves: one dependent access
-// per pick for the random operator, two for the greedy one.
+// address of a pick's entries without loading anything and fetches the next pick's entries, pick
+// number and level index while it works on the current one; the levels sit in LDS.  What is left
+// per pick is one trip for the residuals and one for the acknowledgement of their stores.
 // Greedy: a thread keeps one entry (row, value, residual) in registers for the whole step; the
-// column's rows are marked in an LDS bitmap; the maxima of |r| over chunks of 64 rows live in LDS,
+// column's rows are marked in an LDS bitmap; the maxima of |r| over chunks of 16 rows live in LDS,
 // so "the largest |r| outside the column" is the kept maximum of the chunks the column does not
-// touch and a row-by-row look (one wavefront per chunk, loads issued together) at those it
-// does; the touched chunks get their new maxima from that look and from the new residuals.
+// touch and a row-by-row look at those it does - one row of 16 lanes per chunk, all loads of a
+// pass issued together on clamped indices (a load inside a branch is waited for inside it);
+// the touched chunks get their new maxima from that look and from the new residuals.
+// One workgroup of 1024 threads issues one wavefront instruction per clock at best, so the
+// step is written for few instructions: 32-bit indices, reductions as a DPP pass over 16 lanes
+// plus one LDS atomic per row of lanes (|.| >= 0: the bit patterns order like the values).
 // Maxima are exact in any order, so the choices are those of the general kernel.
-constexpr int RP_CHUNK = 64;
-constexpr int RP_MAXCHUNKS = 2048;        // rows up to 131072
+constexpr int RP_CHUNK = 16;              // rows per chunk = lanes of a DPP row
+constexpr int RP_CMAX_BYTES = 32768;      // LDS for the chunk maxima: 131072 rows in fp32, 65536 in fp64
 constexpr int RP_BLOCK = 1024;            // longest column (padding included) the kernel takes
+constexpr int RP_DCAP = 1024;             // levels kept in LDS (more are read from memory)
+constexpr int RP_LOOK = 4;                // passes of 64 touched chunks whose loads are in flight together
 constexpr int64_t RP_GATHER_CAP = 1 << 20;   // entries of the scratch array
+
+template <class T>
+constexpr int rp_max_chunks() { return RP_CMAX_BYTES / (int)sizeof(T); }
 
 template <class T>
 __global__ void k_alns_gather(int64_t n, int32_t mp, int32_t P, int32_t stride, const int32_t* __restrict__ segptr,
@@ -722,149 +731,182 @@ __global__ void k_alns_gather(int64_t n, int32_t mp, int32_t P, int32_t stride, 
     for (int32_t t = base + threadIdx.x; t < stride; t += blockDim.x) { g_row[q * stride + t] = -1; g_val[q * stride + t] = (T)0; }
 }
 
+// LDS maximum of values >= 0
+__device__ __forceinline__ void lds_max_nonneg(float* p, float v) {
+    atomicMax(reinterpret_cast<unsigned int*>(p), __float_as_uint(v));
+}
+__device__ __forceinline__ void lds_max_nonneg(double* p, double v) {
+    atomicMax(reinterpret_cast<unsigned long long*>(p), (unsigned long long)__double_as_longlong(v));
+}
+
 template <class T>
 __global__ __launch_bounds__(RP_BLOCK) void k_alns_repair_gathered(
-    int64_t m, int32_t nd, int32_t stride, const int32_t* __restrict__ g_row, const T* __restrict__ g_val,
+    int32_t m, int32_t nd, int32_t stride, const int32_t* __restrict__ g_row, const T* __restrict__ g_val,
     const T* __restrict__ D, T* r, int32_t* kidx, int32_t count, const int32_t* __restrict__ picked,
     InstState<T>* st, const AlnsState* S, uint64_t seed, uint64_t inst) {
+    constexpr int MAXCH = rp_max_chunks<T>();
     __shared__ T sh[16];
-    __shared__ T sh_pair[16][2];
-    __shared__ T sh_cmax[RP_MAXCHUNKS];                       // max |r| of every chunk
-    __shared__ unsigned int sh_rowbit[RP_MAXCHUNKS * RP_CHUNK / 32];   // rows of the current column
-    __shared__ int32_t sh_dirty[RP_BLOCK];                    // chunks the column touches, each once
-    __shared__ unsigned int sh_isdirty[RP_MAXCHUNKS];
+    __shared__ __align__(32) T sh_cmax[MAXCH];                 // max |r| of every chunk
+    __shared__ unsigned int sh_rowbit[MAXCH * RP_CHUNK / 32];  // rows of the current column
+    __shared__ unsigned int sh_dirtybit[MAXCH / 32];           // chunks the column touches
+    __shared__ int32_t sh_dirty[RP_BLOCK];                     // the same as a list, each once
     __shared__ int32_t sh_ndirty;
+    __shared__ T sh_red[2][4];                                 // per pick parity: outside, column low, column high
+    __shared__ T sh_D[RP_DCAP];                                // the levels, when they fit
     const int32_t it = S->it;
     const bool greedy = S->r_op == 1;
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    constexpr int NW = RP_BLOCK / 64;
-    const int64_t nch = (m + RP_CHUNK - 1) / RP_CHUNK;
+    const int32_t tid = threadIdx.x;
+    const int lane = tid & 63, w = tid >> 6, sub = lane & 15;
+    const int32_t nch = (m + RP_CHUNK - 1) / RP_CHUNK;
+    const int32_t nch4 = (nch + 3) & ~3;
+    const bool d_lds = nd <= RP_DCAP;
+    if (d_lds)
+        for (int32_t k = tid; k < nd; k += RP_BLOCK) sh_D[k] = D[k];
+#define RP_LEVEL(k) (d_lds ? sh_D[k] : D[k])
     if (greedy) {
-        for (int64_t c0 = w; c0 < nch; c0 += 8 * NW) {
+        // rows i0 + tid: the 16 lanes of a DPP row hold one chunk
+        for (int32_t i0 = 0; i0 < nch4 * RP_CHUNK; i0 += 8 * RP_BLOCK) {
             T v[8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int64_t i = (c0 + (int64_t)u * NW) * RP_CHUNK + lane;
-                v[u] = i < m ? dmmv_abs(r[i]) : (T)0;
-            }
+            for (int u = 0; u < 8; ++u) v[u] = r[min(i0 + u * RP_BLOCK + tid, m - 1)];
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
-                const int64_t c = c0 + (int64_t)u * NW;
-                if (c < nch) {
-                    const T cm = wave_max(v[u]);
-                    if (lane == 0) { sh_cmax[c] = cm; sh_isdirty[c] = 0u; }
-                }
+                const int32_t i = i0 + u * RP_BLOCK + tid;
+                const T cm = row16_max(i < m ? dmmv_abs(v[u]) : (T)0);
+                if (sub == 0 && i < nch4 * RP_CHUNK) sh_cmax[i / RP_CHUNK] = cm;
             }
         }
-        for (int64_t q = threadIdx.x; q < (nch * RP_CHUNK + 31) / 32; q += RP_BLOCK) sh_rowbit[q] = 0u;
-        if (threadIdx.x == 0) sh_ndirty = 0;
-        __syncthreads();
+        for (int32_t q = tid; q < nch4 * RP_CHUNK / 32; q += RP_BLOCK) sh_rowbit[q] = 0u;
+        for (int32_t q = tid; q < (nch4 + 31) / 32; q += RP_BLOCK) sh_dirtybit[q] = 0u;
+        if (tid < 8) sh_red[tid >> 2][tid & 3] = (T)0;
+        if (tid == 0) sh_ndirty = 0;
     }
-    const bool mine = (int32_t)threadIdx.x < stride;
-    // entry of the first pick
+    const bool mine = tid < stride;
+    const bool entry_wave = w * 64 < stride;                 // wavefronts that hold entries
+    // entry of the first pick; picks two ahead, level index one ahead: no load of the chain
+    // picked -> kidx is waited for inside a step (the picks are distinct, so kidx[j] of a later
+    // pick is final already)
     int32_t row_n = -1;
     T a_n = (T)0;
-    if (mine && count > 0) { row_n = g_row[threadIdx.x]; a_n = g_val[threadIdx.x]; }
-    int32_t kc_n = count > 0 ? kidx[picked[0]] : 0;
+    if (mine && count > 0) { row_n = g_row[tid]; a_n = g_val[tid]; }
+    int32_t j_cur = count > 0 ? picked[0] : 0;
+    int32_t j_n = count > 1 ? picked[1] : 0;
+    int32_t j_nn = 0;
+    int32_t kc_n = count > 0 ? kidx[j_cur] : 0;
+    __syncthreads();                                         // the LDS tables
     for (int32_t pos = 0; pos < count; ++pos) {
-        const int64_t j = picked[pos];
+        const int32_t j = j_cur;
         const int32_t kc = kc_n;
         const int32_t row = row_n;
         const T a = a_n;
+        const int par = pos & 1;
         const bool real = row >= 0;
         const bool has_lo = kc > 0, has_hi = kc < nd - 1;
         const bool evaluate = greedy && has_lo && has_hi;
-        const T ri = real ? r[row] : (T)0;
-        if (greedy && real) {
-            atomicOr(&sh_rowbit[row >> 5], 1u << (row & 31));
-            const int32_t c = row / RP_CHUNK;
-            if (atomicExch(&sh_isdirty[c], 1u) == 0u) sh_dirty[atomicAdd(&sh_ndirty, 1)] = c;
+        if (greedy) {
+            if (real) {
+                atomicOr(&sh_rowbit[row >> 5], 1u << (row & 31));
+                const int32_t c = row / RP_CHUNK;
+                const unsigned int bit = 1u << (c & 31);
+                if ((atomicOr(&sh_dirtybit[c >> 5], bit) & bit) == 0u) {   // first to touch the chunk: list it, restart its maximum
+                    sh_dirty[atomicAdd(&sh_ndirty, 1)] = c;
+                    sh_cmax[c] = (T)0;
+                }
+            }
+            __syncthreads();
         }
-        if (greedy) __syncthreads();
-        // largest |r| outside the column: row-by-row look at the chunks it touches
+        // the entry's residual and the look at the touched chunks are requested together
+        const T ri = real ? r[row] : (T)0;
         T rest = (T)0;
         if (greedy) {
             const int32_t ndirty = sh_ndirty;
-            for (int32_t d0 = w; d0 < ndirty; d0 += 8 * NW) {
-                T v[8];
+            for (int32_t d0 = 0; d0 < ndirty; d0 += 64 * RP_LOOK) {
+                T v[RP_LOOK];
+                int32_t row_u[RP_LOOK];
+                unsigned int bits[RP_LOOK];
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const int32_t d = d0 + u * NW;
-                    T val = (T)0;
-                    if (d < ndirty) {
-                        const int64_t i = (int64_t)sh_dirty[d] * RP_CHUNK + lane;
-                        const bool in_col = (sh_rowbit[i >> 5] >> (i & 31)) & 1u;
-                        if (i < m && !in_col) val = dmmv_abs(r[i]);
-                    }
-                    v[u] = val;
+                for (int u = 0; u < RP_LOOK; ++u)
+                    row_u[u] = sh_dirty[min(d0 + u * 64 + 4 * w + (lane >> 4), ndirty - 1)] * RP_CHUNK + sub;
+#pragma unroll
+                for (int u = 0; u < RP_LOOK; ++u) {
+                    const int32_t ic = min(row_u[u], m - 1);
+                    bits[u] = sh_rowbit[ic >> 5];
+                    v[u] = r[ic];
                 }
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const int32_t d = d0 + u * NW;
-                    if (d < ndirty) {                       // uniform per wavefront
-                        const T um = wave_max(v[u]);
-                        rest = dmmv_max(rest, um);
-                        if (lane == 0) sh_cmax[sh_dirty[d]] = um;   // the column's rows join below
-                    }
+                for (int u = 0; u < RP_LOOK; ++u) {
+                    const bool valid = d0 + u * 64 + 4 * w + (lane >> 4) < ndirty;
+                    const bool in_col = (bits[u] >> (row_u[u] & 31)) & 1u;
+                    const T val = (valid && row_u[u] < m && !in_col) ? dmmv_abs(v[u]) : (T)0;
+                    rest = dmmv_max(rest, val);
+                    // the chunk's maximum restarts from its rows outside the column; the
+                    // column's rows join below
+                    const T rm = row16_max(val);
+                    if (valid && sub == 0) lds_max_nonneg(&sh_cmax[row_u[u] / RP_CHUNK], rm);
                 }
             }
-        }
-        // the next pick's entries: requested after the loads this step waits for
-        if (pos + 1 < count) {
-            if (mine) { row_n = g_row[(int64_t)(pos + 1) * stride + threadIdx.x]; a_n = g_val[(int64_t)(pos + 1) * stride + threadIdx.x]; }
-            kc_n = kidx[picked[pos + 1]];
         }
         int32_t knew;
         if (evaluate) {
-            for (int64_t c = threadIdx.x; c < nch; c += RP_BLOCK)
-                if (sh_isdirty[c] == 0u) rest = dmmv_max(rest, sh_cmax[c]);
-            const T dlo = step_of(D[kc - 1], D[kc], (T)1), dhi = step_of(D[kc + 1], D[kc], (T)1);
-            T elo = rest, ehi = rest;
-            if (real) {
-                elo = dmmv_max(elo, dmmv_abs(dmmv_fma(dlo, a, ri)));
-                ehi = dmmv_max(ehi, dmmv_abs(dmmv_fma(dhi, a, ri)));
+            // untouched chunks: four kept maxima per thread
+            for (int32_t g = tid; 4 * g < nch4; g += RP_BLOCK) {
+                const unsigned int db = sh_dirtybit[g >> 3] >> ((g & 7) * 4);
+                const typename Vec4<T>::type c4 = *reinterpret_cast<const typename Vec4<T>::type*>(&sh_cmax[4 * g]);
+                rest = dmmv_max(rest, (db & 1u) ? (T)0 : c4.x);
+                rest = dmmv_max(rest, (db & 2u) ? (T)0 : c4.y);
+                rest = dmmv_max(rest, (db & 4u) ? (T)0 : c4.z);
+                rest = dmmv_max(rest, (db & 8u) ? (T)0 : c4.w);
             }
-            elo = wave_max(elo);
-            ehi = wave_max(ehi);
-            if (lane == 0) { sh_pair[w][0] = elo; sh_pair[w][1] = ehi; }
+            const T rm = row16_max(rest);
+            if (sub == 0) lds_max_nonneg(&sh_red[par][0], rm);
+            if (entry_wave) {
+                const T dlo = step_of(RP_LEVEL(kc - 1), RP_LEVEL(kc), (T)1), dhi = step_of(RP_LEVEL(kc + 1), RP_LEVEL(kc), (T)1);
+                const T lo = row16_max(real ? dmmv_abs(dmmv_fma(dlo, a, ri)) : (T)0);
+                const T hi = row16_max(real ? dmmv_abs(dmmv_fma(dhi, a, ri)) : (T)0);
+                if (sub == 0) { lds_max_nonneg(&sh_red[par][1], lo); lds_max_nonneg(&sh_red[par][2], hi); }
+            }
             __syncthreads();
-            elo = sh_pair[0][0];
-            ehi = sh_pair[0][1];
-#pragma unroll
-            for (int u = 1; u < NW; ++u) { elo = dmmv_max(elo, sh_pair[u][0]); ehi = dmmv_max(ehi, sh_pair[u][1]); }
+            const T outside = sh_red[par][0];
+            const T elo = dmmv_max(outside, sh_red[par][1]), ehi = dmmv_max(outside, sh_red[par][2]);
             knew = ehi < elo ? kc + 1 : kc - 1;
         } else {
             if (has_lo && has_hi) knew = (alns_rnd(seed, inst, (uint64_t)it, 2, (uint64_t)pos) & 1) ? kc + 1 : kc - 1;
             else knew = has_lo ? kc - 1 : kc + 1;
-            if (greedy) __syncthreads();                    // the chunk maxima written above are in place
+            if (greedy) __syncthreads();                    // the look's chunk maxima are in place
+        }
+        // the next pick: requested here, so that only the step's last barrier waits for it
+        if (pos + 1 < count) {
+            if (mine) { row_n = g_row[(int64_t)(pos + 1) * stride + tid]; a_n = g_val[(int64_t)(pos + 1) * stride + tid]; }
+            kc_n = kidx[j_n];
+            if (pos + 2 < count) j_nn = picked[pos + 2];
         }
         // reassign: r follows; greedy: the touched chunks take in the new residuals, the marks go
-        const T delta = step_of(D[knew], D[kc], (T)1);
+        const T delta = step_of(RP_LEVEL(knew), RP_LEVEL(kc), (T)1);
         if (real) {
             const T nv = dmmv_fma(delta, a, ri);
             r[row] = nv;
             if (greedy) {
                 const int32_t c = row / RP_CHUNK;
-                // |.| >= 0: the bit patterns order like the values
-                if constexpr (sizeof(T) == 4)
-                    atomicMax(reinterpret_cast<unsigned int*>(&sh_cmax[c]), __float_as_uint(dmmv_abs(nv)));
-                else
-                    atomicMax(reinterpret_cast<unsigned long long*>(&sh_cmax[c]), (unsigned long long)__double_as_longlong(dmmv_abs(nv)));
+                lds_max_nonneg(&sh_cmax[c], dmmv_abs(nv));
                 atomicAnd(&sh_rowbit[row >> 5], ~(1u << (row & 31)));
-                sh_isdirty[c] = 0u;
+                atomicAnd(&sh_dirtybit[c >> 5], ~(1u << (c & 31)));
             }
         }
-        if (threadIdx.x == 0) { kidx[j] = knew; sh_ndirty = 0; }
+        if (tid == 0) { kidx[j] = knew; sh_ndirty = 0; }
+        if (tid < 4) sh_red[par ^ 1][tid] = (T)0;            // last read before the previous step's end
+        j_cur = j_n;
+        j_n = j_nn;
         __syncthreads();                                     // r, kidx and the tables are settled
     }
+#undef RP_LEVEL
     T tmax = (T)0;
     if (greedy) {
-        for (int64_t c = threadIdx.x; c < nch; c += RP_BLOCK) tmax = dmmv_max(tmax, sh_cmax[c]);
+        for (int32_t c = tid; c < nch; c += RP_BLOCK) tmax = dmmv_max(tmax, sh_cmax[c]);
     } else {
-        for (int64_t i = threadIdx.x; i < m; i += RP_BLOCK) tmax = dmmv_max(tmax, dmmv_abs(r[i]));
+        for (int32_t i = tid; i < m; i += RP_BLOCK) tmax = dmmv_max(tmax, dmmv_abs(r[i]));
     }
     tmax = block_max(tmax, sh);
-    if (threadIdx.x == 0) { st[0].t = tmax; st[0].done = 0; st[0].moves = 0; }
+    if (tid == 0) { st[0].t = tmax; st[0].done = 0; st[0].moves = 0; }
 }
 
 // after a rejected iteration r was restored: the reservoir has to follow
@@ -897,14 +939,14 @@ static dmmv_status alns_repair_t(Ctx* c, int32_t count, uint64_t seed) {
     // where the tables and the scratch array fit: gather the picked columns, then the kernel
     // without dependent loads; else the general kernel
     const int32_t stride = (int32_t)(ceil_div(c->csc_max_col > 0 ? c->csc_max_col : 1, 64) * 64);
-    const bool fast = ceil_div(c->p.m, RP_CHUNK) <= RP_MAXCHUNKS && stride <= RP_BLOCK &&
+    const bool fast = c->p.m >= 1 && ceil_div(c->p.m, RP_CHUNK) <= rp_max_chunks<T>() && stride <= RP_BLOCK &&
                       (int64_t)count * stride <= RP_GATHER_CAP && c->alns_g_row && c->alns_g_val;
     if (fast) {
         if (count > 0)
             hipLaunchKernelGGL(k_alns_gather<T>, dim3((unsigned)count), dim3(128), 0, c->stream, c->p.n, c->csc_mp,
                                c->csc_P, stride, (const int32_t*)c->segptr, (const uint16_t*)c->row16,
                                (const T*)c->cval, (const int32_t*)c->alns_picked, c->alns_g_row, (T*)c->alns_g_val);
-        hipLaunchKernelGGL(k_alns_repair_gathered<T>, dim3(1), dim3(RP_BLOCK), 0, c->stream, c->p.m, c->p.nd, stride,
+        hipLaunchKernelGGL(k_alns_repair_gathered<T>, dim3(1), dim3(RP_BLOCK), 0, c->stream, (int32_t)c->p.m, c->p.nd, stride,
                            (const int32_t*)c->alns_g_row, (const T*)c->alns_g_val, (const T*)c->D_dev, (T*)c->r,
                            c->kidx, count, (const int32_t*)c->alns_picked, (InstState<T>*)c->state,
                            (const AlnsState*)c->alns_state, seed, (uint64_t)0);

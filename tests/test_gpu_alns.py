@@ -227,9 +227,20 @@ def test_alns_batched_with_the_matrix_core_evaluation():
                        batched_eval=2)
 
 
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_alns_sparse_gathered_repair_paths(dtype):
+    # the gathered repair kernel beyond its common case: columns touching more chunks of rows than
+    # one pass of its look takes (several hundred entries spread over 12007 rows, a row count that
+    # ends inside a chunk), more levels than it keeps in LDS, and a row count that needs the second
+    # round of its scan over the chunk maxima (fp32; in fp64 that many rows go to the general kernel)
+    alns_check(random_sparse(7960, 12007, 30, 3, density=0.05, dtype=dtype), 8, ls_moves=2, destroy_count=6, seed=6)
+    alns_check(random_sparse(7961, 900, 40, 1500, density=0.1, dtype=dtype), 8, ls_moves=2, destroy_count=5, seed=7)
+    alns_check(random_sparse(7962, 70001, 24, 4, density=0.003, dtype=dtype), 6, ls_moves=2, destroy_count=6, seed=8)
+
+
 def test_alns_sparse_general_repair_kernel():
     # a column longer than the gathered kernel takes (1024 entries), and more rows than its tables
-    # hold (131072): both fall back to the general repair kernel
+    # hold (131072 in fp32): both fall back to the general repair kernel
     alns_check(random_sparse(7950, 1400, 20, 3, density=0.9), 8, ls_moves=2, destroy_count=5, seed=4)
     alns_check(random_sparse(7951, 140000, 24, 4, density=0.002), 6, ls_moves=2, destroy_count=6, seed=5)
 
