@@ -343,12 +343,6 @@ __device__ __forceinline__ T wave_max(T v) {
     return dmmv_max(dmmv_max(read_lane(v, 0), read_lane(v, 16)), dmmv_max(read_lane(v, 32), read_lane(v, 48)));
 }
 
-__device__ __forceinline__ uint32_t wave_or(uint32_t v) {
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) v |= (uint32_t)__shfl_xor((int)v, off, 64);
-    return v;
-}
-
 // Lexicographic minimum of (score, index) over the wavefront, result in every lane.
 // Records with c < 0 are empty and lose against everything.
 template <class T>

@@ -209,29 +209,44 @@ __global__ __launch_bounds__(DP_THREADS) void k_descent_dense_persistent(
             uint32_t fail = 0;
             for (int q = lane; q < G; q += 64) {
                 const uint64_t* slot = rec + ((int64_t)(it & 1) * G + q) * DP_REC_WORDS;
+                // Two reads of the record are kept in flight (loads return in order): a read
+                // samples memory half a round trip after it was issued, so with one read at a
+                // time a record that lands just after the sample costs a whole further round
+                // trip; the second read halves that.
+                const uint64_t hi = 0xffffffff00000000ull;
+                uint64_t a0, a1, a2, a3, b0, b1, b2, b3;
+#define DP_READ(x0, x1, x2, x3)                                                              \
+    x0 = __hip_atomic_load(&slot[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);             \
+    x1 = __hip_atomic_load(&slot[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);             \
+    x2 = __hip_atomic_load(&slot[2], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);             \
+    x3 = __hip_atomic_load(&slot[3], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#define DP_THERE(x0, x1, x2, x3) (((x0) & hi) == tag && ((x1) & hi) == tag && ((x2) & hi) == tag && ((x3) & hi) == tag)
                 int32_t polls = 0;
-                uint64_t b0, b1, b2, b3;
-                bool there;
+                bool there = false;
+                DP_READ(a0, a1, a2, a3)
                 do {
-                    b0 = __hip_atomic_load(&slot[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    b1 = __hip_atomic_load(&slot[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    b2 = __hip_atomic_load(&slot[2], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    b3 = __hip_atomic_load(&slot[3], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    const uint64_t hi = 0xffffffff00000000ull;
-                    there = (b0 & hi) == tag && (b1 & hi) == tag && (b2 & hi) == tag && (b3 & hi) == tag;
+                    DP_READ(b0, b1, b2, b3)
+                    there = DP_THERE(a0, a1, a2, a3);
+                    if (there) break;
+                    DP_READ(a0, a1, a2, a3)
+                    there = DP_THERE(b0, b1, b2, b3);
+                    if (there) { a0 = b0; a1 = b1; a2 = b2; a3 = b3; break; }
+                    polls += 2;
                     // somebody else has given up already: no point in waiting out the limit
-                    if (!there && (polls & 255) == 255 &&
+                    if ((polls & 254) == 254 &&
                         __hip_atomic_load(&flags[FLAG_ERROR], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)
                         polls = wait_limit;
-                } while (!there && ++polls < wait_limit);
+                } while (polls < wait_limit);
+#undef DP_READ
+#undef DP_THERE
                 if (!there) { fail = 1; break; }
                 T s;
-                score_from((b0 << 32) | (b1 & 0xffffffffull), s);
-                const int64_t c = (int64_t)((b2 << 32) | (b3 & 0xffffffffull));
+                score_from((a0 << 32) | (a1 & 0xffffffffull), s);
+                const int64_t c = (int64_t)((a2 << 32) | (a3 & 0xffffffffull));
                 if (rec_less(s, c, gs, gc)) { gs = s; gc = c; }
             }
             wave_argmin(gs, gc);
-            fail = wave_or(fail);
+            fail = __ballot(fail != 0) != 0ull;
             if (lane == 0) {
                 sh_bs = gs;
                 sh_bc = gc;
