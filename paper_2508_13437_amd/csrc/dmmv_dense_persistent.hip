@@ -52,7 +52,7 @@ struct Plan {
 
 // Picks the grid: more workgroups shorten the scoring and lengthen the exchange.  Measured on
 // MI355X: the exchange takes about 2 us + 16 ns per workgroup, the rest of an iteration outside
-// the scoring 2.2 us; 64 (row, move) pairs cost a wavefront about 18 cycles in fp64 (the
+// the scoring 1.6 us; 64 (row, move) pairs cost a wavefront about 18 cycles in fp64 (the
 // maximum is not a full-rate instruction) and 10 in fp32; the reduction of a unit's 16 x 64
 // lane maxima about 400.
 Plan make_plan(const dmmv_problem& p, int cus) {
@@ -76,7 +76,7 @@ Plan make_plan(const dmmv_problem& p, int cus) {
                            (size_t)p.n * 4;
         if (lds <= DP_LDS_LIMIT) {
             const double per_unit = (double)ceil_div(p.m, 64) * DP_KT * (w == 8 ? 18.0 : 10.0) + 400.0;   // cycles
-            const double est = 2.0 + 0.016 * (double)G + (double)ceil_div(upw, DP_WAVES) * per_unit / 2400.0 + 2.2;
+            const double est = 2.0 + 0.016 * (double)G + (double)ceil_div(upw, DP_WAVES) * per_unit / 2400.0 + 1.6;
             if (best.G == 0 || est < best.est_us) {
                 best.G = (int)G; best.upw = (int)upw; best.ncols = (int)ncols; best.lds = lds; best.est_us = est;
             }
@@ -141,6 +141,16 @@ __global__ __launch_bounds__(DP_THREADS) void k_descent_dense_persistent(
     bool stopped = st[0].done != 0, failed = false;
     __syncthreads();
 
+    // A wavefront with a single unit keeps that unit's level index and steps in registers; they
+    // change only when a move lands on its variable (the chain level index -> levels -> steps is
+    // three LDS latencies that nothing hides with one wavefront per SIMD).
+    const bool one_unit = upw <= DP_WAVES;
+    bool steps_stale = true;
+    int32_t kcur_keep = 0;
+    T delta_keep[KT];
+#pragma unroll
+    for (int q = 0; q < KT; ++q) delta_keep[q] = (T)0;
+
     for (int32_t it = 0; it < iters && !stopped; ++it) {
         // ---- score this wavefront's units ------------------------------------------------
         T ws = (T)0;
@@ -149,19 +159,38 @@ __global__ __launch_bounds__(DP_THREADS) void k_descent_dense_persistent(
             const int64_t j = u / tiles;
             const int32_t kbase = (int32_t)(u % tiles) * KT;
             const T* __restrict__ col = sh_cols + (j - j_lo) * m;
-            const int32_t kcur = sh_kidx[j];
-            const T dcur = sh_D[kcur];
             T delta[KT], acc[KT];
+            int32_t kcur;
+            if (!one_unit || steps_stale) {
+                kcur = sh_kidx[j];
+                const T dcur = sh_D[kcur];
 #pragma unroll
-            for (int q = 0; q < KT; ++q) {
-                const int32_t k = kbase + q < nd ? kbase + q : nd - 1;
-                delta[q] = step_of(sh_D[k], dcur, (T)1);
-                acc[q] = (T)0;
+                for (int q = 0; q < KT; ++q) {
+                    const int32_t k = kbase + q < nd ? kbase + q : nd - 1;
+                    delta[q] = step_of(sh_D[k], dcur, (T)1);
+                }
+                if (one_unit) {
+                    kcur_keep = kcur;
+#pragma unroll
+                    for (int q = 0; q < KT; ++q) delta_keep[q] = delta[q];
+                    steps_stale = false;
+                }
+            } else {
+                kcur = kcur_keep;
+#pragma unroll
+                for (int q = 0; q < KT; ++q) delta[q] = delta_keep[q];
             }
-            for (int64_t i = lane; i < m; i += 64) {
-                const T a = col[i], ri = sh_r[i];
+#pragma unroll
+            for (int q = 0; q < KT; ++q) acc[q] = (T)0;
+            // two rows per pass, both requested before the first is used (a row past the end
+            // is replaced by the pass's first row: a maximum does not mind the repeat)
+            for (int64_t i = lane; i < m; i += 128) {
+                const int64_t i2 = i + 64 < m ? i + 64 : i;
+                const T a = col[i], ri = sh_r[i], a2 = col[i2], ri2 = sh_r[i2];
 #pragma unroll
                 for (int q = 0; q < KT; ++q) acc[q] = dmmv_max(acc[q], dmmv_abs(dmmv_fma(delta[q], a, ri)));
+#pragma unroll
+                for (int q = 0; q < KT; ++q) acc[q] = dmmv_max(acc[q], dmmv_abs(dmmv_fma(delta[q], a2, ri2)));
             }
             // 16 x 64 lane maxima -> 16 scores: lane folds a quarter of value lane / 4, two DPP steps join
             T* sc = sh_sc + w * KT * DP_SKEW;
@@ -175,16 +204,21 @@ __global__ __launch_bounds__(DP_THREADS) void k_descent_dense_persistent(
             __builtin_amdgcn_wave_barrier();
             v = dmmv_max(v, dpp_mov<DPP_QUAD_XOR1>(v));
             v = dmmv_max(v, dpp_mov<DPP_QUAD_XOR2>(v));
+            // the unit's candidates sit in lanes 0, 4, 8, ... in ascending k: the smallest score,
+            // then the first lane that holds it
             const int32_t k = kbase + q;
-            T cs = (T)0;
-            int64_t cc = -1;
-            if (quarter == 0 && k < nd) {
+            const bool cand = quarter == 0 && k < nd;
+            T cs = Limits<T>::inf();
+            if (cand) {
                 const bool var_ok = var_mask ? var_mask[j] != 0 : true;
-                cs = cand_allowed(kcur, k, radius, var_ok) ? v : Limits<T>::inf();
-                cc = j * (int64_t)nd + k;
+                if (cand_allowed(kcur, k, radius, var_ok)) cs = v;
             }
-            wave_argmin(cs, cc);
-            if (rec_less(cs, cc, ws, wc)) { ws = cs; wc = cc; }
+            const T smin = wave_min(cs);
+            const unsigned long long hit = __ballot(cand && cs == smin);
+            if (hit) {
+                const int64_t cc = j * (int64_t)nd + kbase + (__builtin_ctzll(hit) >> 2);
+                if (rec_less(smin, cc, ws, wc)) { ws = smin; wc = cc; }
+            }
         }
         if (lane == 0) { sh_ws[w] = ws; sh_wc[w] = wc; }
         __syncthreads();
@@ -270,6 +304,7 @@ __global__ __launch_bounds__(DP_THREADS) void k_descent_dense_persistent(
             for (int64_t i = tid; i < m; i += DP_THREADS) sh_r[i] = dmmv_fma(delta, colg[i], sh_r[i]);
             __syncthreads();                                  // every thread has read sh_kidx[j]
             if (tid == 0) sh_kidx[j] = k;
+            if (one_unit && u0 + w < u1 && (u0 + w) / tiles == j) steps_stale = true;
             t = s;
             moves += 1;
         } else if (!keep_going) {
