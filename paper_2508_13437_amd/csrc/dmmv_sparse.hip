@@ -176,6 +176,7 @@ __global__ void k_residual_csr(int64_t m, const int64_t* __restrict__ rowptr,
 // =========================================================================================
 constexpr int RES_SEL = 256;     // threads whose strided maxima choose the floor at a rebuild
 constexpr int RES_COLLECT = 1024;
+constexpr int RES_BATCH = 8;     // rows a thread requests before it waits, in the scans of a rebuild (16: slower)
 
 // r may have been written earlier in the same kernel by other wavefronts: read past the L1
 template <class T>
@@ -241,23 +242,36 @@ __device__ void reservoir_rebuild(ResLds<T>& L, int64_t m, const T* r, T* res_va
         __syncthreads();
         return;
     }
-    // strided maxima of the first RES_SEL threads propose a floor with about `target` rows above it
+    // The maxima of the RES_SEL residue classes of the row number propose a floor with about
+    // `target` rows above it.  Every thread scans (the workgroup's size is a multiple of RES_SEL,
+    // so a thread's rows t, t + blockDim, ... belong to one class), RES_BATCH rows per step so that
+    // their loads are in flight together; the partial maxima of a class are joined through LDS.
     T mv = (T)-1;
     int32_t mr = INT32_MAX;
-    // (eight rows per step, so that their loads are in flight together)
-    if (threadIdx.x < RES_SEL) {
+    {
+        const int64_t step = blockDim.x;
         int64_t i = threadIdx.x;
-        for (; i + 7 * RES_SEL < m; i += 8 * RES_SEL) {
-            T a8[8];
+        for (; i + (RES_BATCH - 1) * step < m; i += RES_BATCH * step) {
+            T a8[RES_BATCH];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) a8[e] = dmmv_abs(ld_coherent(r + i + e * RES_SEL));
+            for (int e = 0; e < RES_BATCH; ++e) a8[e] = dmmv_abs(ld_coherent(r + i + e * step));
 #pragma unroll
-            for (int e = 0; e < 8; ++e)
-                if (key_before(a8[e], (int32_t)(i + e * RES_SEL), mv, mr)) { mv = a8[e]; mr = (int32_t)(i + e * RES_SEL); }
+            for (int e = 0; e < RES_BATCH; ++e)
+                if (key_before(a8[e], (int32_t)(i + e * step), mv, mr)) { mv = a8[e]; mr = (int32_t)(i + e * step); }
         }
-        for (; i < m; i += RES_SEL) {
+        for (; i < m; i += step) {
             const T a = dmmv_abs(ld_coherent(r + i));
             if (key_before(a, (int32_t)i, mv, mr)) { mv = a; mr = (int32_t)i; }
+        }
+    }
+    L.v[threadIdx.x] = mv;
+    L.r[threadIdx.x] = mr;
+    __syncthreads();
+    if (threadIdx.x < RES_SEL) {
+        for (int32_t o = threadIdx.x + RES_SEL; o < (int32_t)blockDim.x; o += RES_SEL) {
+            const T ov = L.v[o];
+            const int32_t orow = L.r[o];
+            if (key_before(ov, orow, mv, mr)) { mv = ov; mr = orow; }
         }
     }
     int32_t target = RES_CAP / 2;
@@ -286,12 +300,12 @@ __device__ void reservoir_rebuild(ResLds<T>& L, int64_t m, const T* r, T* res_va
         {
             const int64_t step = blockDim.x;
             int64_t i = threadIdx.x;
-            for (; i + 7 * step < m; i += 8 * step) {
-                T a8[8];
+            for (; i + (RES_BATCH - 1) * step < m; i += RES_BATCH * step) {
+                T a8[RES_BATCH];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) a8[e] = dmmv_abs(ld_coherent(r + i + e * step));
+                for (int e = 0; e < RES_BATCH; ++e) a8[e] = dmmv_abs(ld_coherent(r + i + e * step));
 #pragma unroll
-                for (int e = 0; e < 8; ++e)
+                for (int e = 0; e < RES_BATCH; ++e)
                     if (!key_before(fv, fr, a8[e], (int32_t)(i + e * step))) {      // key before-or-equal floor
                         const int32_t pos = atomicAdd(&L.count, 1);
                         if (pos < RES_COLLECT) { L.v[pos] = a8[e]; L.r[pos] = (int32_t)(i + e * step); }
