@@ -137,3 +137,48 @@ def test_random_sweep_of_the_outer_loop_and_the_swap_move(seed):
             ran += attempt(f"outer loop batched {kw}", lambda: ta.batched_alns_check(inst, 6, **kw))
             ran += attempt("swap batched", lambda: ts.chain_check(inst, 2, descend=descend))
     assert ran >= 60
+
+
+@pytest.mark.parametrize("seed", [31])
+def test_random_sweep_of_the_l2_changes_and_the_matrix_core_residual(seed):
+    import test_gpu_l2 as tl
+
+    rng = np.random.default_rng(seed)
+    ran = 0
+    for _ in range(90):
+        kind = int(rng.integers(0, 3))
+        s = int(rng.integers(1, 1 << 30))
+        dt = [np.float32, np.float64][int(rng.integers(0, 2))]
+        integer = bool(rng.integers(0, 2))
+        rule = int(rng.choice([1, 2]))
+        if kind == 0:
+            mm, nn = int(rng.integers(1, 600)), int(rng.integers(1, 60))
+            nd = int(rng.integers(2, 13 if integer else 30))
+            radius = int(rng.choice([0, 1]))
+            inst = random_dense(s, mm, nn, nd, dtype=dt, integer=integer)
+            ran += attempt(f"l2 tables dense {mm}x{nn} nd{nd} {dt.__name__} integer={integer}", lambda: tl.check_tables(inst))
+            ran += attempt(f"l2 descent dense rule {rule} radius {radius}", lambda: tl.check_descent(inst, 20, rule, radius=radius))
+        elif kind == 1:
+            mm, nn = int(rng.integers(1, 3000)), int(rng.integers(1, 200))
+            nd = int(rng.integers(2, 7))
+            dens = min(float(rng.choice([0.01, 0.05, 0.2, 0.6])), 2e5 / (mm * nn))
+            inst = random_sparse(s, mm, nn, nd, density=dens, dtype=dt, integer=integer)
+            opt = {}
+            part = int(rng.choice([0, 0, 64, 500]))
+            if part:
+                opt["sparse_partition_rows"] = part
+            ran += attempt(f"l2 tables sparse {mm}x{nn} nd{nd} density={dens:.3f} {dt.__name__} integer={integer}",
+                           lambda: tl.check_tables(inst))
+            ran += attempt(f"l2 descent sparse rule {rule} {opt}", lambda: tl.check_descent(inst, 20, rule, **opt))
+        else:
+            mm, nn, R = int(rng.integers(1, 300)), int(rng.integers(1, 200)), int(rng.integers(1, 150))
+            nd = int(rng.integers(2, 13 if integer else 17))
+            dtb = np.float32 if rng.integers(0, 4) else np.float64
+            inst = random_batched(s, mm, nn, R, nd, dtype=dtb, integer=integer)
+            ran += attempt(f"l2 tables batched {mm}x{nn} R={R} nd{nd} {dtb.__name__} integer={integer}",
+                           lambda: tl.check_tables(inst, steps=1))
+            if mm * nn * R < 4e5:
+                ran += attempt(f"l2 descent batched rule {rule}", lambda: tl.check_descent(inst, 8, rule))
+            if dtb == np.float32:
+                ran += attempt(f"matrix-core residual {mm}x{nn} R={R}", lambda: tp.mfma_residual_check(inst))
+    assert ran >= 150
