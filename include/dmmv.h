@@ -175,8 +175,8 @@ typedef struct {
                                 the moves, each keeps r, its columns of A, D and x in LDS, and they
                                 exchange one arg-min record per iteration through memory (needs r, D, x
                                 and one column to fit 156 KiB of LDS; dmmv_create fails with
-                                DMMV_ERR_UNSUPPORTED otherwise).  0 = automatic: 2 when the instance is
-                                so small that the launches would dominate an iteration, else 1.  Same
+                                DMMV_ERR_UNSUPPORTED otherwise).  0 = automatic: 2 when it fits and a model
+                                of both loops says its iteration is the shorter one, else 1.  Same
                                 scores, moves, traces and residual either way.  With 2 the workgroups
                                 wait for one another, so all must be resident on the device at once;
                                 if another kernel keeps some from starting, the wait ends after

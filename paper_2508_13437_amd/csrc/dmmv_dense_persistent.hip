@@ -27,15 +27,17 @@
 namespace dmmv {
 
 constexpr int DP_KT = 16;                 // values of D per unit
-constexpr int DP_WAVES = 4;
-constexpr int DP_THREADS = 64 * DP_WAVES;
+constexpr int DP_MAX_WAVES = 8;            // wavefronts per workgroup: 4 (one per SIMD) or 8, chosen with the grid
+constexpr int DP_MAX_THREADS = 64 * DP_MAX_WAVES;
 constexpr int DP_SKEW = 65;               // row stride of the per-wavefront transpose scratch
 constexpr int DP_MAX_G = 256;
 constexpr size_t DP_LDS_LIMIT = 156 * 1024;
 constexpr int32_t DP_WAIT_DEFAULT = 1 << 22;
-// modelled iteration time up to which one launch is taken by default: the two launches of a
-// step in the other loop take 8 us before any work is done
-constexpr double DP_AUTO_MAX_US = 7.5;
+// The loop of launches, for the automatic choice: its two launches take 8.1 us before any work
+// is done, and the chip-wide evaluation kernel then needs about 81 ns per million (row, move)
+// pairs in fp64 and 40 in fp32 (fitted to the measured iterations of small and large instances).
+constexpr double DP_LAUNCH_LOOP_US = 8.1;
+constexpr double DP_LAUNCH_LOOP_US_PER_PAIR_F64 = 8.1e-8, DP_LAUNCH_LOOP_US_PER_PAIR_F32 = 4.0e-8;
 
 constexpr int DP_REC_WORDS = 4;
 size_t dense_persistent_exchange_bytes() { return (size_t)2 * DP_MAX_G * DP_REC_WORDS * sizeof(uint64_t); }
@@ -46,15 +48,19 @@ struct Plan {
     int G = 0;            // workgroups (0: not applicable)
     int upw = 0;          // units per workgroup
     int ncols = 0;        // columns of A a workgroup keeps in LDS
+    int waves = 0;        // wavefronts per workgroup
     size_t lds = 0;
     double est_us = 0;    // modelled time of one iteration
 };
 
-// Picks the grid: more workgroups shorten the scoring and lengthen the exchange.  Measured on
-// MI355X: the exchange takes about 2 us + 16 ns per workgroup, the rest of an iteration outside
-// the scoring 1.6 us; 64 (row, move) pairs cost a wavefront about 18 cycles in fp64 (the
-// maximum is not a full-rate instruction) and 10 in fp32; the reduction of a unit's 16 x 64
-// lane maxima about 400.
+// Picks the grid and the workgroup size: more workgroups shorten the scoring and lengthen the
+// exchange; eight wavefronts per workgroup instead of four put two on every SIMD, which share its
+// arithmetic but hide each other's latencies (better when a wavefront would otherwise take
+// several units in a row, worse for a single short unit).  Measured on MI355X: the exchange
+// takes about 2 us + 4 ns per workgroup, the rest of an iteration outside the scoring 1.6 us;
+// 64 (row, move) pairs cost a wavefront about 18 cycles in fp64 (the maximum is not a full-rate
+// instruction) and 10 in fp32 when it has its SIMD to itself, 32 and 16 when it shares it; the
+// reduction of a unit's 16 x 64 lane maxima about 400.
 Plan make_plan(const dmmv_problem& p, int cus) {
     Plan best;
     if (p.csr_rowptr || p.R != 1 || p.scale || p.m < 1 || p.n < 1 || p.nd < 1) return best;
@@ -63,25 +69,29 @@ Plan make_plan(const dmmv_problem& p, int cus) {
     const int64_t U = p.n * tiles;
     if (p.m > (int64_t)(DP_LDS_LIMIT / w) || p.n > (1 << 20) || p.nd > (1 << 16)) return best;
     const int gmax = cus < DP_MAX_G ? (cus > 0 ? cus : 1) : DP_MAX_G;
-    for (int want = 1;; want = want * 2 < gmax ? want * 2 : gmax) {
-        const int64_t upw = ceil_div(U, want);
-        const int64_t G = ceil_div(U, upw);
-        int64_t ncols = 1;
-        for (int64_t g = 0; g < G; ++g) {
-            const int64_t u0 = g * upw, u1 = (g + 1) * upw < U ? (g + 1) * upw : U;
-            const int64_t span = (u1 - 1) / tiles - u0 / tiles + 1;
-            if (span > ncols) ncols = span;
-        }
-        const size_t lds = (size_t)(1 + ncols) * p.m * w + (size_t)DP_WAVES * DP_KT * DP_SKEW * w + (size_t)p.nd * w +
-                           (size_t)p.n * 4;
-        if (lds <= DP_LDS_LIMIT) {
-            const double per_unit = (double)ceil_div(p.m, 64) * DP_KT * (w == 8 ? 18.0 : 10.0) + 400.0;   // cycles
-            const double est = 2.0 + 0.016 * (double)G + (double)ceil_div(upw, DP_WAVES) * per_unit / 2400.0 + 1.6;
-            if (best.G == 0 || est < best.est_us) {
-                best.G = (int)G; best.upw = (int)upw; best.ncols = (int)ncols; best.lds = lds; best.est_us = est;
+    for (int waves = 4; waves <= DP_MAX_WAVES; waves *= 2) {
+        for (int want = 1;; want = want * 2 < gmax ? want * 2 : gmax) {
+            const int64_t upw = ceil_div(U, want);
+            const int64_t G = ceil_div(U, upw);
+            int64_t ncols = 1;
+            for (int64_t g = 0; g < G; ++g) {
+                const int64_t u0 = g * upw, u1 = (g + 1) * upw < U ? (g + 1) * upw : U;
+                const int64_t span = (u1 - 1) / tiles - u0 / tiles + 1;
+                if (span > ncols) ncols = span;
             }
+            const size_t lds = (size_t)(1 + ncols) * p.m * w + (size_t)waves * DP_KT * DP_SKEW * w + (size_t)p.nd * w +
+                               (size_t)p.n * 4;
+            if (lds <= DP_LDS_LIMIT) {
+                const double per_64 = waves == 4 ? (w == 8 ? 18.0 : 10.0) : (w == 8 ? 32.0 : 16.0);
+                const double per_unit = (double)ceil_div(p.m, 64) * DP_KT * per_64 + 400.0;     // cycles
+                const double est = 2.0 + 0.004 * (double)G + (double)ceil_div(upw, waves) * per_unit / 2400.0 + 1.6;
+                if (best.G == 0 || est < best.est_us) {
+                    best.G = (int)G; best.upw = (int)upw; best.ncols = (int)ncols; best.waves = waves; best.lds = lds;
+                    best.est_us = est;
+                }
+            }
+            if (want == gmax) break;
         }
-        if (want == gmax) break;
     }
     return best;
 }
@@ -103,8 +113,8 @@ __global__ void k_zero_words(uint32_t* p, int n) {
     if (i < n) p[i] = 0;
 }
 
-template <class T>
-__global__ __launch_bounds__(DP_THREADS) void k_descent_dense_persistent(
+template <class T, int NWAVES>
+__global__ __launch_bounds__(64 * NWAVES) void k_descent_dense_persistent(
     int64_t m, int64_t n, int32_t nd, const T* __restrict__ A, int64_t lda, const T* __restrict__ D,
     T* r, int32_t* kidx, int32_t radius, const uint8_t* __restrict__ var_mask, InstState<T>* st,
     int32_t keep_going, int32_t iters, dmmv_move* trace, T* trace_t, int32_t tiles, int32_t upw,
@@ -113,11 +123,12 @@ __global__ __launch_bounds__(DP_THREADS) void k_descent_dense_persistent(
     extern __shared__ __align__(16) unsigned char smem[];
     T* sh_r = reinterpret_cast<T*>(smem);                   // [m]
     T* sh_cols = sh_r + m;                                  // [ncols][m]
-    T* sh_sc = sh_cols + (int64_t)ncols * m;                // [DP_WAVES][KT * DP_SKEW]
-    T* sh_D = sh_sc + DP_WAVES * KT * DP_SKEW;              // [nd]
+    constexpr int nthreads = 64 * NWAVES, nwaves = NWAVES;
+    T* sh_sc = sh_cols + (int64_t)ncols * m;                // [nwaves][KT * DP_SKEW]
+    T* sh_D = sh_sc + nwaves * KT * DP_SKEW;                // [nd]
     int32_t* sh_kidx = reinterpret_cast<int32_t*>(sh_D + nd);   // [n]
-    __shared__ T sh_ws[DP_WAVES];
-    __shared__ int64_t sh_wc[DP_WAVES];
+    __shared__ T sh_ws[NWAVES];
+    __shared__ int64_t sh_wc[NWAVES];
     __shared__ T sh_bs;
     __shared__ int64_t sh_bc;
     __shared__ int32_t sh_fail;
@@ -129,11 +140,11 @@ __global__ __launch_bounds__(DP_THREADS) void k_descent_dense_persistent(
     const int64_t u0 = (int64_t)g * upw, u1 = u0 + upw < U ? u0 + upw : U;
     const int64_t j_lo = u0 / tiles, j_hi = (u1 - 1) / tiles;
 
-    for (int64_t i = tid; i < m; i += DP_THREADS) sh_r[i] = r[i];
+    for (int64_t i = tid; i < m; i += nthreads) sh_r[i] = r[i];
     for (int64_t j = j_lo; j <= j_hi; ++j)
-        for (int64_t i = tid; i < m; i += DP_THREADS) sh_cols[(j - j_lo) * m + i] = A[lda * j + i];
-    for (int64_t j = tid; j < n; j += DP_THREADS) sh_kidx[j] = kidx[j];
-    for (int32_t k = tid; k < nd; k += DP_THREADS) sh_D[k] = D[k];
+        for (int64_t i = tid; i < m; i += nthreads) sh_cols[(j - j_lo) * m + i] = A[lda * j + i];
+    for (int64_t j = tid; j < n; j += nthreads) sh_kidx[j] = kidx[j];
+    for (int32_t k = tid; k < nd; k += nthreads) sh_D[k] = D[k];
     if (tid == 0) sh_fail = 0;
     T t = st[0].t;
     int32_t moves = st[0].moves;
@@ -144,7 +155,7 @@ __global__ __launch_bounds__(DP_THREADS) void k_descent_dense_persistent(
     // A wavefront with a single unit keeps that unit's level index and steps in registers; they
     // change only when a move lands on its variable (the chain level index -> levels -> steps is
     // three LDS latencies that nothing hides with one wavefront per SIMD).
-    const bool one_unit = upw <= DP_WAVES;
+    const bool one_unit = upw <= nwaves;
     bool steps_stale = true;
     int32_t kcur_keep = 0;
     T delta_keep[KT];
@@ -155,7 +166,7 @@ __global__ __launch_bounds__(DP_THREADS) void k_descent_dense_persistent(
         // ---- score this wavefront's units ------------------------------------------------
         T ws = (T)0;
         int64_t wc = -1;
-        for (int64_t u = u0 + w; u < u1; u += DP_WAVES) {
+        for (int64_t u = u0 + w; u < u1; u += nwaves) {
             const int64_t j = u / tiles;
             const int32_t kbase = (int32_t)(u % tiles) * KT;
             const T* __restrict__ col = sh_cols + (j - j_lo) * m;
@@ -227,8 +238,13 @@ __global__ __launch_bounds__(DP_THREADS) void k_descent_dense_persistent(
         if (tid == 0) {
             T bs = (T)0;
             int64_t bc = -1;
-            for (int x = 0; x < DP_WAVES; ++x)
-                if (rec_less(sh_ws[x], sh_wc[x], bs, bc)) { bs = sh_ws[x]; bc = sh_wc[x]; }
+            T xs[NWAVES];
+            int64_t xc[NWAVES];
+#pragma unroll
+            for (int x = 0; x < NWAVES; ++x) { xs[x] = sh_ws[x]; xc[x] = sh_wc[x]; }
+#pragma unroll
+            for (int x = 0; x < NWAVES; ++x)
+                if (rec_less(xs[x], xc[x], bs, bc)) { bs = xs[x]; bc = xc[x]; }
             uint64_t* slot = rec + ((int64_t)(it & 1) * G + g) * DP_REC_WORDS;
             const uint64_t sb = score_bits(bs), cb = (uint64_t)bc;
             __hip_atomic_store(&slot[0], tag | (sb >> 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -301,7 +317,7 @@ __global__ __launch_bounds__(DP_THREADS) void k_descent_dense_persistent(
                 if (trace_t) trace_t[moves] = s;
             }
             const T* __restrict__ colg = A + lda * (int64_t)j;
-            for (int64_t i = tid; i < m; i += DP_THREADS) sh_r[i] = dmmv_fma(delta, colg[i], sh_r[i]);
+            for (int64_t i = tid; i < m; i += nthreads) sh_r[i] = dmmv_fma(delta, colg[i], sh_r[i]);
             __syncthreads();                                  // every thread has read sh_kidx[j]
             if (tid == 0) sh_kidx[j] = k;
             if (one_unit && u0 + w < u1 && (u0 + w) / tiles == j) steps_stale = true;
@@ -314,8 +330,8 @@ __global__ __launch_bounds__(DP_THREADS) void k_descent_dense_persistent(
     }
     // ---- workgroup 0 hands the state back (after a failed wait the state is not written) ---
     if (g != 0 || failed) return;
-    for (int64_t i = tid; i < m; i += DP_THREADS) r[i] = sh_r[i];
-    for (int64_t j = tid; j < n; j += DP_THREADS) kidx[j] = sh_kidx[j];
+    for (int64_t i = tid; i < m; i += nthreads) r[i] = sh_r[i];
+    for (int64_t j = tid; j < n; j += nthreads) kidx[j] = sh_kidx[j];
     if (tid == 0) {
         InstState<T> z = st[0];
         z.t = t;
@@ -333,9 +349,10 @@ dmmv_status run_t(Ctx* c, const Plan& pl, int32_t iters, dmmv_move* trace, void*
     uint64_t* rec = (uint64_t*)c->persist_exchange;
     const int words = 2 * DP_MAX_G * DP_REC_WORDS * 2;       // as 32-bit words
     hipLaunchKernelGGL(k_zero_words, dim3((unsigned)ceil_div(words, 256)), dim3(256), 0, c->stream, (uint32_t*)rec, words);
-    DMMV_TRY(ensure_dynamic_lds((const void*)k_descent_dense_persistent<T>, (int)DP_LDS_LIMIT));
     const int32_t wait_limit = c->o.wait_limit > 0 ? c->o.wait_limit : DP_WAIT_DEFAULT;
-    hipLaunchKernelGGL(k_descent_dense_persistent<T>, dim3((unsigned)pl.G), dim3(DP_THREADS), pl.lds, c->stream,
+    auto kernel = pl.waves == 8 ? k_descent_dense_persistent<T, 8> : k_descent_dense_persistent<T, 4>;
+    DMMV_TRY(ensure_dynamic_lds((const void*)kernel, (int)DP_LDS_LIMIT));
+    hipLaunchKernelGGL(kernel, dim3((unsigned)pl.G), dim3(64 * pl.waves), pl.lds, c->stream,
                        c->p.m, c->p.n, c->p.nd, (const T*)c->p.A_dense, c->p.lda, (const T*)c->D_dev, (T*)c->r,
                        c->kidx, c->o.radius, c->o.var_mask, (InstState<T>*)c->state, c->o.keep_going, iters, trace,
                        (T*)trace_t, (int32_t)ceil_div(c->p.nd, DP_KT), (int32_t)pl.upw, (int32_t)pl.ncols, rec,
@@ -346,9 +363,9 @@ dmmv_status run_t(Ctx* c, const Plan& pl, int32_t iters, dmmv_move* trace, void*
 
 }  // namespace
 
-// options.dense_loop: 0 = one launch when the model says an iteration is short enough that the
-// launches of a step would dominate it, 1 = always a launch per step, 2 = one launch whenever
-// the instance fits (dmmv_create refuses the option otherwise).
+// options.dense_loop: 0 = one launch when the model says its iteration is shorter than that of
+// the loop of launches, 1 = always a launch per step, 2 = one launch whenever the instance fits
+// (dmmv_create refuses the option otherwise).
 bool dense_persistent_fits(const dmmv_problem& p) { return make_plan(p, DP_MAX_G).G > 0; }
 
 bool dense_persistent_applicable(const Ctx* c) {
@@ -357,7 +374,11 @@ bool dense_persistent_applicable(const Ctx* c) {
     if (!c->o.keep_going && (c->o.value_search || c->o.prune)) return false;      // those have loops of their own
     const Plan pl = make_plan(c->p, device_cus());
     if (pl.G == 0) return false;
-    return c->o.dense_loop == 2 || pl.est_us <= DP_AUTO_MAX_US;
+    if (c->o.dense_loop == 2) return true;
+    const double pairs = (double)c->p.m * (double)c->p.n * (double)c->p.nd;
+    const double launches_us = DP_LAUNCH_LOOP_US + pairs * (c->p.dtype == DMMV_F64 ? DP_LAUNCH_LOOP_US_PER_PAIR_F64
+                                                                                   : DP_LAUNCH_LOOP_US_PER_PAIR_F32);
+    return pl.est_us < launches_us;
 }
 
 dmmv_status dense_descent_persistent(Ctx* c, int32_t iters, dmmv_move* trace, void* trace_t) {
