@@ -439,22 +439,24 @@ __global__ __launch_bounds__(SA_BLOCK) void k_select_apply_cscp(
     int32_t col_len = 0;
     for (int32_t p = 0; p < P; ++p) col_len += sh_len[p];
     const bool incremental = col_len <= SA_MAXCOL && m > RES_CAP;
-    int32_t base = 0;
-    for (int32_t p = 0; p < P; ++p) {
-        const int32_t e0 = sh_e0[p], e1 = e0 + sh_len[p];
-        for (int32_t e = e0 + threadIdx.x; e < e1; e += SA_BLOCK) {
-            const uint32_t loc = row16[e];
-            const bool pad = loc == (uint32_t)mp;
-            const int64_t i = (int64_t)p * mp + loc;
-            T nv = (T)0;
-            if (!pad) { nv = dmmv_fma(delta, cval[e], r[i]); r[i] = nv; }
-            if (incremental) {
-                // pads sit at the end of a segment: give them row INT32_MAX-ish keys past the real ones
-                sh_srow[base + (e - e0)] = pad ? INT32_MAX : (int32_t)i;
-                sh_sval[base + (e - e0)] = dmmv_abs(nv);
-            }
+    // The segments of all partitions are taken as one list (position u = entries of the earlier
+    // partitions + offset in its own), one entry per thread: the entries of the whole column are
+    // requested together and so are its rows of r - two trips to memory, not two per partition.
+    for (int32_t u = threadIdx.x; u < col_len; u += SA_BLOCK) {
+        int32_t p = 0, lo = 0, len = sh_len[0];
+        while (u >= lo + len) { lo += len; len = sh_len[++p]; }       // u < col_len: ends inside the table
+        const int32_t e = sh_e0[p] + (u - lo);
+        const uint32_t loc = row16[e];
+        const T a = cval[e];
+        const bool pad = loc == (uint32_t)mp;
+        const int64_t i = (int64_t)p * mp + loc;
+        T nv = (T)0;
+        if (!pad) { nv = dmmv_fma(delta, a, r[i]); r[i] = nv; }
+        if (incremental) {
+            // pads sit at the end of a segment: give them row INT32_MAX-ish keys past the real ones
+            sh_srow[u] = pad ? INT32_MAX : (int32_t)i;
+            sh_sval[u] = dmmv_abs(nv);
         }
-        base += e1 - e0;
     }
     __syncthreads();
     if (!incremental) {
