@@ -769,6 +769,10 @@ __global__ __launch_bounds__(64) void k_eval_pruned_csc_reg(
     const int32_t cnt = res_meta[RES_CNT];
     const int32_t rr0 = res_row[lane], rr1 = res_row[lane + 64];      // RES_CAP = 128 entries exist
     const T rv0 = res_val[lane], rv1 = res_val[lane + 64];
+    // the levels travel with these loads when they fit the lanes (lane k holds D[k]); later reads
+    // of a level are lane reads, not trips to memory
+    const bool d_in_lanes = nd <= 64;
+    const T d_lane = D[lane < nd ? lane : nd - 1];
     if (honor_done && done) return;
     Partial<T> rec; rec.s = (T)0; rec.c = -1;
     int64_t j = -1;
@@ -782,14 +786,28 @@ __global__ __launch_bounds__(64) void k_eval_pruned_csc_reg(
         return;
     }
     // 4: the segment bounds and the current value; a lane's slots are entries lane, lane + 64, ...
-    const int32_t kcur = kidx[j];
+    // (up to 64 partitions: lane p fetches the bounds of partition p, all in one trip)
+    const int32_t kcur = __builtin_amdgcn_readfirstlane(kidx[j]);
     int32_t ent[PR_SLOTS], part_of[PR_SLOTS];
 #pragma unroll
     for (int u = 0; u < PR_SLOTS; ++u) { ent[u] = -1; part_of[u] = 0; }
     {
+        const bool by_lane = P <= 64;
+        int32_t my_e0 = 0, my_len = 0;
+        if (by_lane && lane < P) {
+            my_e0 = segptr[(int64_t)lane * n + j];
+            my_len = segptr[(int64_t)lane * n + j + 1] - my_e0;
+        }
         int32_t base = 0;
         for (int32_t p = 0; p < P; ++p) {
-            const int32_t e0 = segptr[(int64_t)p * n + j], len = segptr[(int64_t)p * n + j + 1] - e0;
+            int32_t e0, len;
+            if (by_lane) {
+                e0 = __builtin_amdgcn_readlane(my_e0, p);
+                len = __builtin_amdgcn_readlane(my_len, p);
+            } else {
+                e0 = segptr[(int64_t)p * n + j];
+                len = segptr[(int64_t)p * n + j + 1] - e0;
+            }
 #pragma unroll
             for (int u = 0; u < PR_SLOTS; ++u) {
                 const int32_t t = lane + 64 * u - base;
@@ -810,7 +828,7 @@ __global__ __launch_bounds__(64) void k_eval_pruned_csc_reg(
             if (loc != (uint32_t)mp) { row[u] = part_of[u] * mp + (int32_t)loc; a[u] = cval[ent[u]]; }
         }
     }
-    const T dcur = D[kcur];
+    const T dcur = d_in_lanes ? read_lane(d_lane, kcur) : D[kcur];
 #pragma unroll
     for (int u = 0; u < PR_SLOTS; ++u) ri[u] = row[u] >= 0 ? r[row[u]] : (T)0;
     // maximum over the rows outside column j: first reservoir row the column does not hold
@@ -838,7 +856,8 @@ __global__ __launch_bounds__(64) void k_eval_pruned_csc_reg(
         T delta[KT], acc[KT];
 #pragma unroll
         for (int q = 0; q < KT; ++q) {
-            delta[q] = step_of(D[k0 + q < nd ? k0 + q : nd - 1], dcur, (T)1);
+            const int32_t kq = k0 + q < nd ? k0 + q : nd - 1;
+            delta[q] = step_of(d_in_lanes ? read_lane(d_lane, kq) : D[kq], dcur, (T)1);
             acc[q] = (T)0;
         }
 #pragma unroll
