@@ -366,6 +366,7 @@ __global__ void k_apply_cscp(int64_t n, int32_t mp, int32_t P, const int32_t* __
 // and x, and update the reservoir for the rows that changed.  One workgroup.
 constexpr int SA_BLOCK = 1024;
 constexpr int SA_MAXCOL = RES_COLLECT - RES_CAP;   // changed rows handled incrementally
+constexpr int SA_DCAP = SA_BLOCK;                  // levels kept in LDS: one per thread
 
 template <class T>
 __global__ __launch_bounds__(SA_BLOCK) void k_select_apply_cscp(
@@ -382,6 +383,7 @@ __global__ __launch_bounds__(SA_BLOCK) void k_select_apply_cscp(
     __shared__ int32_t sh_ns, sh_j, sh_k;
     __shared__ T sh_delta, sh_best;
     __shared__ int32_t sh_e0[CSC_MAX_PARTITIONS], sh_len[CSC_MAX_PARTITIONS];   // column j's segments
+    __shared__ T sh_D[SA_DCAP];                 // the levels, when they fit: requested with the first loads
     // Everything that depends on nothing is fetched together (one memory latency, not one per
     // use): the loop state, the records, and the reservoir this kernel will update.  From one
     // workgroup every dependent access to memory costs about a microsecond.
@@ -392,6 +394,9 @@ __global__ __launch_bounds__(SA_BLOCK) void k_select_apply_cscp(
     int32_t my_row = -1;
     T my_val = (T)0;
     if (threadIdx.x < RES_CAP) { my_row = res_row[threadIdx.x]; my_val = res_val[threadIdx.x]; }
+    const bool d_lds = nd <= SA_DCAP;
+    T my_d = (T)0;
+    if (d_lds && (int32_t)threadIdx.x < nd) my_d = D[threadIdx.x];
     T s = (T)0;
     int64_t c = -1;
     for (int64_t q = threadIdx.x; q < n_part; q += SA_BLOCK) {
@@ -399,6 +404,7 @@ __global__ __launch_bounds__(SA_BLOCK) void k_select_apply_cscp(
         if (rec_less(pr.s, pr.c, s, c)) { s = pr.s; c = pr.c; }
     }
     if (z0.done) return;
+    if (d_lds && (int32_t)threadIdx.x < nd) sh_D[threadIdx.x] = my_d;     // (the reduction's barriers order it)
     block_argmin(s, c, sh_s, sh_c);
     if (threadIdx.x == 0) {
         InstState<T> z = z0;
@@ -411,7 +417,8 @@ __global__ __launch_bounds__(SA_BLOCK) void k_select_apply_cscp(
         sh_k = k;
         sh_best = s;
         if (improving) {
-            sh_delta = step_of(D[k], D[kidx[j]], (T)1);
+            const int32_t kc = kidx[j];
+            sh_delta = d_lds ? step_of(sh_D[k], sh_D[kc], (T)1) : step_of(D[k], D[kc], (T)1);
             if (z.moves < iters) {
                 if (trace) { trace[z.moves].j = j; trace[z.moves].k = k; }
                 if (trace_t) trace_t[z.moves] = s;
