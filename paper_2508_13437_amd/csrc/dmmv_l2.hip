@@ -106,7 +106,7 @@ __global__ __launch_bounds__(256) void k_l2_g_batched(int64_t m, int64_t n, int6
 // (variables 32 (v / 16) ...), instance l % 32 and variable row 8 ((v % 16) / 4) + 4 (l / 32) + v % 4
 // of the block.  The operands of the next L2_U rows are loaded before the products of the
 // current ones are issued.
-constexpr int L2_U = 4;
+constexpr int L2_U = 6;
 
 __global__ __launch_bounds__(256, 2) void k_l2_g_mfma(int64_t m, int64_t n, int64_t R, const float* __restrict__ Xt,
                                                       const float* __restrict__ r, float* __restrict__ G) {
@@ -115,40 +115,54 @@ __global__ __launch_bounds__(256, 2) void k_l2_g_mfma(int64_t m, int64_t n, int6
     const int64_t j0 = (blockIdx.x * 2ll + (w & 1)) * 128;
     const int64_t q0 = (blockIdx.y * 2ll + (w >> 1)) * 64;
     if (j0 >= n || q0 >= R) return;                       // whole wavefronts only
-    const int64_t ja = j0 + lane < n ? j0 + lane : n - 1;
-    const int64_t jb = j0 + 64 + lane < n ? j0 + 64 + lane : n - 1;
-    const int64_t qa = q0 + (lane & 31) < R ? q0 + (lane & 31) : R - 1;
-    const int64_t qb = q0 + 32 + (lane & 31) < R ? q0 + 32 + (lane & 31) : R - 1;
+    // Vector instructions do not overlap with the matrix cores' (measured: every one of them adds
+    // its issue time to the loop), so the loop is written to need none: a row's address is a
+    // uniform pointer (scalar unit) plus an unsigned 32-bit lane offset that never changes, and two sets
+    // of operand registers take turns, so nothing is copied.
+    // (byte offsets inside X and r, 32-bit: the host takes this kernel when both are below 4 GiB)
+    const uint32_t ja = 4u * (uint32_t)(j0 + lane < n ? j0 + lane : n - 1);
+    const uint32_t jb = 4u * (uint32_t)(j0 + 64 + lane < n ? j0 + 64 + lane : n - 1);
+    const uint32_t qa = 4u * (uint32_t)(q0 + (lane & 31) < R ? q0 + (lane & 31) : R - 1);
+    const uint32_t qb = 4u * (uint32_t)(q0 + 32 + (lane & 31) < R ? q0 + 32 + (lane & 31) : R - 1);
     floatx32 c00, c01, c10, c11;
 #pragma unroll
     for (int v = 0; v < 32; ++v) { c00[v] = 0.0f; c01[v] = 0.0f; c10[v] = 0.0f; c11[v] = 0.0f; }
-    float a0[L2_U], a1[L2_U], b0[L2_U], b1[L2_U];
-    auto load = [&](int64_t i0) {
-#pragma unroll
-        for (int u = 0; u < L2_U; ++u) {
-            const int64_t i = i0 + u < m ? i0 + u : m - 1;
-            a0[u] = Xt[i * n + ja];
-            a1[u] = Xt[i * n + jb];
-            b0[u] = r[i * R + qa];
-            b1[u] = r[i * R + qb];
-        }
-    };
-    if (m > 0) load(0);
-    for (int64_t i0 = 0; i0 < m; i0 += L2_U) {
-        float x0[L2_U], x1[L2_U], y0[L2_U], y1[L2_U];
-#pragma unroll
-        for (int u = 0; u < L2_U; ++u) { x0[u] = a0[u]; x1[u] = a1[u]; y0[u] = b0[u]; y1[u] = b1[u]; }
-        if (i0 + L2_U < m) load(i0 + L2_U);
-#pragma unroll
-        for (int u = 0; u < L2_U; ++u) {
-            if (i0 + u < m) {                              // uniform
-                c00 = __builtin_amdgcn_mfma_f32_32x32x1f32(x0[u], y0[u], c00, 0, 0, 0);
-                c01 = __builtin_amdgcn_mfma_f32_32x32x1f32(x0[u], y1[u], c01, 0, 0, 0);
-                c10 = __builtin_amdgcn_mfma_f32_32x32x1f32(x1[u], y0[u], c10, 0, 0, 0);
-                c11 = __builtin_amdgcn_mfma_f32_32x32x1f32(x1[u], y1[u], c11, 0, 0, 0);
-            }
-        }
+    const int32_t mrows = (int32_t)m;                       // rows are counted on the scalar unit
+    float pa0[L2_U], pa1[L2_U], pb0[L2_U], pb1[L2_U];       // set P
+    float qa0[L2_U], qa1[L2_U], qb0[L2_U], qb1[L2_U];       // set Q
+    // raw buffer loads: address = descriptor base + scalar row offset + lane offset, no vector
+    // instruction involved (a 64-bit global address would cost one vector add per load)
+    const __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc((void*)Xt, 0, (int)(uint32_t)(m * n * 4), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_r = __builtin_amdgcn_make_buffer_rsrc((void*)r, 0, (int)(uint32_t)(m * R * 4), 0x00020000);
+    const uint32_t xstride = (uint32_t)n * 4u, rstride = (uint32_t)R * 4u;
+#define L2_AT(rs, off, soff) __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs, (int)(off), (int)(soff), 0))
+#define L2_LOAD(A0, A1, B0, B1, I0)                                         \
+    _Pragma("unroll") for (int u = 0; u < L2_U; ++u) {                       \
+        const uint32_t i = (uint32_t)((I0) + u < mrows ? (I0) + u : mrows - 1); \
+        A0[u] = L2_AT(rs_x, ja, i * xstride);                                \
+        A1[u] = L2_AT(rs_x, jb, i * xstride);                                \
+        B0[u] = L2_AT(rs_r, qa, i * rstride);                                \
+        B1[u] = L2_AT(rs_r, qb, i * rstride);                                \
     }
+#define L2_ROWS(A0, A1, B0, B1, I0)                                                      \
+    _Pragma("unroll") for (int u = 0; u < L2_U; ++u) {                                    \
+        if ((I0) + u < mrows) { /* uniform */                                             \
+            c00 = __builtin_amdgcn_mfma_f32_32x32x1f32(A0[u], B0[u], c00, 0, 0, 0);        \
+            c01 = __builtin_amdgcn_mfma_f32_32x32x1f32(A0[u], B1[u], c01, 0, 0, 0);        \
+            c10 = __builtin_amdgcn_mfma_f32_32x32x1f32(A1[u], B0[u], c10, 0, 0, 0);        \
+            c11 = __builtin_amdgcn_mfma_f32_32x32x1f32(A1[u], B1[u], c11, 0, 0, 0);        \
+        }                                                                                 \
+    }
+    if (mrows > 0) { L2_LOAD(pa0, pa1, pb0, pb1, 0) }
+    for (int32_t i0 = 0; i0 < mrows; i0 += 2 * L2_U) {
+        if (i0 + L2_U < mrows) { L2_LOAD(qa0, qa1, qb0, qb1, i0 + L2_U) }
+        L2_ROWS(pa0, pa1, pb0, pb1, i0)
+        if (i0 + 2 * L2_U < mrows) { L2_LOAD(pa0, pa1, pb0, pb1, i0 + 2 * L2_U) }
+        L2_ROWS(qa0, qa1, qb0, qb1, i0 + L2_U)
+    }
+#undef L2_LOAD
+#undef L2_ROWS
+#undef L2_AT
     const int half = lane >> 5, col = lane & 31;
 #pragma unroll
     for (int v = 0; v < 32; ++v) {
@@ -285,7 +299,7 @@ dmmv_status update_g_t(Ctx* c) {
     } else if (c->kind == KIND_DENSE) {
         hipLaunchKernelGGL(k_l2_g_dense<T>, dim3((unsigned)ceil_div(n, 64)), dim3(64), 0, c->stream, m, n,
                            (const T*)c->p.A_dense, c->p.lda, (const T*)c->r, (T*)c->l2_g);
-    } else if (sizeof(T) == 4) {
+    } else if (sizeof(T) == 4 && m * n < (1ll << 30) && m * R < (1ll << 30)) {     // the kernel's 32-bit byte offsets
         const dim3 grid((unsigned)ceil_div(n, 256), (unsigned)ceil_div(R, 128));
         hipLaunchKernelGGL(k_l2_g_mfma, grid, dim3(256), 0, c->stream, m, n, R, (const float*)c->Xt, (const float*)c->r,
                            (float*)c->l2_g);
